@@ -1,0 +1,92 @@
+"""Seeded synthetic inputs and workload shapes.
+
+This module serves both the CPU oracle's tests and the HIP path's tests and
+benchmarks.  It holds no field arithmetic, no sharing, no fixed-point
+encoding: only random draws of plain floats / plain integers below a bound,
+and the table of layer shapes that defines the ResNet-shaped workloads.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Optional
+
+import numpy as np
+
+P61 = (1 << 61) - 1
+
+
+def gaussian(shape, seed: int) -> np.ndarray:
+    """float64 N(0,1) samples of the given shape."""
+    return np.random.default_rng(seed).standard_normal(size=shape)
+
+
+def he_normal(shape, fan_in: int, seed: int) -> np.ndarray:
+    """float64 N(0, 2/fan_in) samples (He-normal initialisation)."""
+    return np.random.default_rng(seed).standard_normal(size=shape) * np.sqrt(2.0 / fan_in)
+
+
+def uniform_below(count: int, bound: int, seed: int) -> np.ndarray:
+    """uint64 samples, uniform on [0, bound)."""
+    return np.random.default_rng(seed).integers(0, bound, size=count, dtype=np.uint64)
+
+
+@dataclass(frozen=True)
+class Layer:
+    """One linear layer of a sequential chain (all convs are square, NCHW)."""
+    kind: str            # "conv" or "fc"
+    cin: int
+    cout: int
+    ksize: int
+    stride: int
+    pad: int
+    hin: int             # input spatial size (square); 1 for fc
+    hout: int
+    post: Optional[str]  # plaintext step applied by the harness after this layer:
+    #                      "relu", "relu+maxpool3s2", "relu+gap", or None (last layer)
+
+    @property
+    def M(self) -> int:
+        return self.hout * self.hout
+
+    @property
+    def K(self) -> int:
+        return self.cin * self.ksize * self.ksize
+
+    @property
+    def N(self) -> int:
+        return self.cout
+
+    @property
+    def macs(self) -> int:
+        return self.M * self.K * self.N
+
+
+def resnet_chain(depth: int, image: int = 224, classes: int = 1000) -> List[Layer]:
+    """Main-path layers of a bottleneck ResNet as one sequential chain.
+
+    conv1 7x7/2 (3->64), 3x3/2 max-pool, four stages of bottleneck blocks
+    (1x1 -> 3x3 -> 1x1 x4; stride 2 sits on the 3x3 of the first block of
+    stages 2-4), global average pool, fully connected layer.  Projection
+    shortcuts and residual additions are left out: the chain is the sequence
+    of conv/FC layers only (50 layers for depth 50, 152 for depth 152).
+    """
+    blocks = {50: (3, 4, 6, 3), 101: (3, 4, 23, 3), 152: (3, 8, 36, 3)}[depth]
+    layers: List[Layer] = []
+    h = image
+    hout = (h + 2 * 3 - 7) // 2 + 1
+    layers.append(Layer("conv", 3, 64, 7, 2, 3, h, hout, "relu+maxpool3s2"))
+    h = (hout + 2 * 1 - 3) // 2 + 1
+    cin = 64
+    for stage, (nblocks, width) in enumerate(zip(blocks, (64, 128, 256, 512))):
+        for b in range(nblocks):
+            stride = 2 if (stage > 0 and b == 0) else 1
+            layers.append(Layer("conv", cin, width, 1, 1, 0, h, h, "relu"))
+            h2 = (h + 2 - 3) // stride + 1
+            layers.append(Layer("conv", width, width, 3, stride, 1, h, h2, "relu"))
+            h = h2
+            last = stage == 3 and b == nblocks - 1
+            layers.append(Layer("conv", width, 4 * width, 1, 1, 0, h, h,
+                                "relu+gap" if last else "relu"))
+            cin = 4 * width
+    layers.append(Layer("fc", cin, classes, 1, 1, 0, 1, 1, None))
+    return layers

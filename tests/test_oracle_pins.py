@@ -1,0 +1,507 @@
+"""Pins for the CPU oracle: what the paper prints, closed forms, invariants and
+brute force over tiny fields.  None of these re-types the oracle's formulas;
+big-integer checks use Python's own arbitrary-precision `%`.
+"""
+import itertools
+import os
+import random
+from fractions import Fraction
+from math import comb
+
+import numpy as np
+import pytest
+
+import oracle as orc
+
+P61 = (1 << 61) - 1
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def frac_mod(fr, p):
+    fr = Fraction(fr)
+    return fr.numerator * pow(fr.denominator, -1, p) % p
+
+
+def read_kv(name):
+    out = {}
+    for line in open(os.path.join(GOLD, name)):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        key, *vals = line.split()
+        out[key] = [int(v) for v in vals]
+    return out
+
+
+# ----------------------------------------------------------------- field
+def test_division_distortion_F11():
+    # Sec. IV-A: 5 * 2^-1 = 8 in F_11
+    assert orc.mul(5, orc.inv(2, 11), 11) == 8
+
+
+def test_inverse_closed_forms_mersenne61():
+    assert orc.inv(2, P61) == 1 << 60                 # 2 * 2^60 = 2^61 = 1 (mod p)
+    assert orc.inv(3, P61) == (2 * P61 + 1) // 3      # 3 * (2p+1)/3 = 2p + 1
+    assert orc.inv(P61 - 1, P61) == P61 - 1           # (-1)^-1 = -1
+
+
+def test_field_ops_against_python_bigints():
+    rnd = random.Random(7)
+    edge = [0, 1, 2, P61 - 1, P61 - 2, (P61 - 1) // 2, (P61 + 1) // 2, 1 << 60, (1 << 60) - 1]
+    vals = edge + [rnd.randrange(P61) for _ in range(200)]
+    for a in vals:
+        for b in vals[:24]:
+            assert orc.add(a, b, P61) == (a + b) % P61
+            assert orc.sub(a, b, P61) == (a - b) % P61
+            assert orc.mul(a, b, P61) == (a * b) % P61
+    for a in vals:
+        if a:
+            assert orc.mul(a, orc.inv(a, P61), P61) == 1
+    for p in (11, 13, 97, 35184372088777):             # the last is the paper's 2^45 - 55
+        for _ in range(50):
+            a, b = rnd.randrange(p), rnd.randrange(1, p)
+            assert orc.mul(a, b, p) == a * b % p
+            assert orc.mul(b, orc.inv(b, p), p) == 1
+
+
+def test_paper_prime_constants():
+    # Sec. VII-A / App. D: p = 2^45 - 55 = 35184372088777 and 2^46 mod p = 110
+    p = 35184372088777
+    assert p == 2 ** 45 - 55
+    assert orc.power(2, 46, p) == 110
+
+
+def test_lift_and_signed_roundtrip():
+    # Sec. II-B: F_11 stands for [-5, 5]
+    assert list(orc.lift(np.arange(11, dtype=np.uint64), 11)) == [0, 1, 2, 3, 4, 5, -5, -4, -3, -2, -1]
+    for v in (-5, -1, 0, 1, 5):
+        assert orc.lift(np.array([orc.from_signed(v, 11)], np.uint64), 11)[0] == v
+    half = (P61 - 1) // 2
+    assert list(orc.lift(np.array([half, half + 1, P61 - 1], np.uint64), P61)) == [half, -half, -1]
+
+
+def test_encode_round_half_even_and_decode():
+    x = np.array([0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 0.49, -0.51, 3.0], dtype=np.float64)
+    enc = orc.encode(x, 0, P61)
+    assert list(orc.lift(enc, P61)) == [0, 2, 2, 0, -2, -2, 0, -1, 3]
+    y = np.array([1.0, -1.0, 0.123456789, -7.75], dtype=np.float64)
+    enc = orc.encode(y, 13, P61)
+    assert list(orc.lift(enc, P61)) == [8192, -8192, round(0.123456789 * 8192), -63488]
+    dec = orc.decode(enc, 13, P61)
+    assert np.max(np.abs(dec - y)) <= 2.0 ** -14
+    with pytest.raises(ValueError):
+        orc.encode(np.array([2.0 ** 30]), 13, P61)
+
+
+# ----------------------------------------------------------------- generator
+def test_generator_core_is_splitmix64():
+    want = [int(l, 16) for l in open(os.path.join(GOLD, "splitmix64.txt")) if l.startswith("0x")]
+    assert [orc.draw(0, e) for e in range(3)] == want
+
+
+def test_keys_separate_streams_and_field_range():
+    keys = {orc.key(s, d, sid, pty, j) for s in (0, 1) for d in range(1, 8) for sid in (0, 1, 2)
+            for pty in range(0, 6) for j in range(0, 3)}
+    assert len(keys) == 2 * 7 * 3 * 6 * 3
+    k = orc.key(42, orc.DOM_SHARE, 0, 0, 1)
+    draws = [orc.draw_field(k, e, P61) for e in range(2000)]
+    assert all(0 <= d < P61 for d in draws) and len(set(draws)) == 2000
+    mean = sum(draws) / len(draws) / P61
+    assert 0.45 < mean < 0.55
+    small = [orc.draw_field(k, e, 11) for e in range(2200)]
+    counts = np.bincount(small, minlength=11)
+    assert counts.min() > 140 and counts.max() < 260
+
+
+# ----------------------------------------------------------------- Lagrange / REC
+def test_lagrange_hand_values():
+    for line in open(os.path.join(GOLD, "lagrange_multipliers.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        ids, vals = line.split("|")
+        ids = [int(v) for v in ids.strip().split(",")]
+        vals = [Fraction(v) for v in vals.split()]
+        assert sum(vals) == 1
+        for p in (11, 13, 97, P61):
+            if any(v.denominator % p == 0 for v in vals):
+                continue
+            got = [int(v) for v in orc.lagrange(ids, p)]
+            assert got == [frac_mod(v, p) for v in vals], (ids, p)
+
+
+def test_lagrange_closed_form_first_m_ids():
+    # for IDs 1..m: lambda_i = (-1)^(i-1) C(m, i)
+    for m in range(1, 9):
+        got = [int(v) for v in orc.lagrange(list(range(1, m + 1)), P61)]
+        assert got == [((-1) ** (i - 1) * comb(m, i)) % P61 for i in range(1, m + 1)]
+
+
+def test_lagrange_sum_is_one_any_subset():
+    for m in (2, 3, 4):
+        for ids in itertools.combinations(range(1, 8), m):
+            assert sum(int(v) for v in orc.lagrange(list(ids), P61)) % P61 == 1
+
+
+@pytest.mark.parametrize("p,t,n", [(11, 1, 3), (13, 1, 3), (11, 2, 5), (13, 2, 5)])
+def test_share_reconstruct_bruteforce_all_polynomials(p, t, n):
+    # every polynomial of degree <= t over F_p: any t+1 shares give the secret
+    # (Sec. II-B property 1) and any t shares are consistent with every secret
+    # (property 2: for each candidate secret the same number of polynomials
+    # produce those t shares)
+    combos = list(itertools.product(range(p), repeat=t + 1))
+    secrets = np.array([c[0] for c in combos], np.uint64)
+    coef = np.array([[c[j] for c in combos] for j in range(1, t + 1)], np.uint64)
+    sh = orc.share_explicit(secrets, coef, n, t, p)
+    # against direct evaluation with Python ints
+    for idx in range(0, len(combos), 7):
+        for i in range(1, n + 1):
+            assert int(sh[i - 1, idx]) == sum(c * i ** j for j, c in enumerate(combos[idx])) % p
+    for ids in itertools.combinations(range(1, n + 1), t + 1):
+        assert np.array_equal(orc.reconstruct(sh, list(ids), p), secrets)
+    for ids in itertools.combinations(range(1, n + 1), t):
+        seen = {}
+        for idx, c in enumerate(combos):
+            view = tuple(int(sh[i - 1, idx]) for i in ids)
+            seen.setdefault(view, []).append(c[0])
+        for view, secs in seen.items():
+            assert sorted(secs) == list(range(p)), "t shares must not narrow down the secret"
+
+
+def test_appendix_B_truncation_case():
+    g = read_kv("appB_truncation.txt")
+    p = g["p"][0]
+    sh = np.array(g["shares"], np.uint64).reshape(3, 1)
+    assert int(orc.reconstruct(sh, [1, 2], p)[0]) == g["rec_first_two"][0] == 5
+    halved = np.array(g["halved_shares"], np.uint64).reshape(3, 1)
+    assert int(orc.reconstruct(halved, [1, 2], p)[0]) == g["rec_halved_first_two"][0] == 8
+
+
+def test_sharing_is_linear():
+    rng = np.random.default_rng(3)
+    a = rng.integers(0, P61, 64, dtype=np.uint64)
+    b = rng.integers(0, P61, 64, dtype=np.uint64)
+    sa = orc.share(a, 5, 2, P61, seed=1, stream_id=0)
+    sb = orc.share(b, 5, 2, P61, seed=1, stream_id=1)
+    ssum = np.array([[(int(x) + int(y)) % P61 for x, y in zip(ra, rb)] for ra, rb in zip(sa, sb)], np.uint64)
+    sdiff = np.array([[(int(x) - int(y)) % P61 for x, y in zip(ra, rb)] for ra, rb in zip(sa, sb)], np.uint64)
+    want_sum = [(int(x) + int(y)) % P61 for x, y in zip(a, b)]
+    want_diff = [(int(x) - int(y)) % P61 for x, y in zip(a, b)]
+    for ids in ([1, 2, 3], [3, 4, 5], [1, 3, 5], [2, 4, 5], [1, 2, 3, 4, 5]):
+        assert [int(v) for v in orc.reconstruct(ssum, ids, P61)] == want_sum
+        assert [int(v) for v in orc.reconstruct(sdiff, ids, P61)] == want_diff
+        assert np.array_equal(orc.reconstruct(sa, ids, P61), a)
+
+
+def test_seeded_share_uses_same_coefficients_for_all_parties():
+    # Eq. 1: a_1..a_t are identical in all shares -> second differences of a
+    # degree-2 sharing at consecutive IDs are constant (= 2 a_2)
+    a = np.arange(10, dtype=np.uint64)
+    sh = orc.share(a, 5, 2, P61, seed=9, stream_id=4)
+    coef = orc.draw_coeffs(9, orc.DOM_SHARE, 4, 0, 2, 10, P61)
+    for e in range(10):
+        s = [int(sh[i, e]) for i in range(5)]
+        d2 = {(s[i + 2] - 2 * s[i + 1] + s[i]) % P61 for i in range(3)}
+        assert d2 == {2 * int(coef[1, e]) % P61}
+        assert (s[0] - int(a[e]) - int(coef[0, e]) - int(coef[1, e])) % P61 == 0
+    # sampled element indices draw the same coefficients as the full call
+    sub = orc.share(a[[2, 7]], 5, 2, P61, seed=9, stream_id=4, eidx=[2, 7])
+    assert np.array_equal(sub, sh[:, [2, 7]])
+
+
+# ----------------------------------------------------------------- products
+def test_fig2_product_needs_all_three_shares():
+    g = read_kv("fig2_example.txt")
+    p = g["p"][0]
+    a, b = g["a_shares"], g["b_shares"]
+    assert int(orc.reconstruct(np.array(a, np.uint64).reshape(3, 1), [1, 2], p)[0]) == 2
+    assert int(orc.reconstruct(np.array(b, np.uint64).reshape(3, 1), [2, 3], p)[0]) == 3
+    prod = np.array([orc.mul(x, y, p) for x, y in zip(a, b)], np.uint64).reshape(3, 1)
+    assert [int(v) for v in prod[:, 0]] == g["product_shares"] == [2, 6, 7]
+    assert int(orc.reconstruct(prod, [1, 2, 3], p)[0]) == g["product"][0] == 6
+    for ids in ([1, 2], [1, 3], [2, 3]):
+        assert int(orc.reconstruct(prod, ids, p)[0]) != 6
+
+
+def test_product_of_sharings_has_degree_2t():
+    rng = np.random.default_rng(5)
+    for n, t in ((3, 1), (5, 2)):
+        a = rng.integers(0, P61, 32, dtype=np.uint64)
+        b = rng.integers(0, P61, 32, dtype=np.uint64)
+        sa = orc.share(a, n, t, P61, 11, 0)
+        sb = orc.share(b, n, t, P61, 11, 1)
+        prod = np.array([[int(x) * int(y) % P61 for x, y in zip(ra, rb)] for ra, rb in zip(sa, sb)], np.uint64)
+        want = np.array([int(x) * int(y) % P61 for x, y in zip(a, b)], np.uint64)
+        assert np.array_equal(orc.reconstruct(prod, list(range(1, 2 * t + 2)), P61), want)
+        short = orc.reconstruct(prod, list(range(1, 2 * t + 1)), P61)
+        assert not np.any(short == want)
+
+
+# ----------------------------------------------------------------- R matrix
+def read_rational_R():
+    mats, cur = {}, None
+    for line in open(os.path.join(GOLD, "reduction_matrix.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        if line.startswith("t="):
+            cur = int(line[2:])
+            mats[cur] = []
+        else:
+            mats[cur].append([Fraction(v) for v in line.split()])
+    return mats
+
+
+@pytest.mark.parametrize("p", [11, 13, 97, P61])
+def test_reduction_matrix_matches_rational_form(p):
+    for t, rows in read_rational_R().items():
+        n = 2 * t + 1
+        if any(v.denominator % p == 0 for r in rows for v in r):
+            continue
+        got = orc.red_matrix(n, t, p)
+        want = [[frac_mod(v, p) for v in r] for r in rows]
+        assert [[int(v) for v in r] for r in got] == want
+
+
+def test_reduction_matrix_mod_11():
+    assert orc.red_matrix(3, 1, 11).tolist() == [[6, 9, 1], [1, 5, 9], [5, 9, 2]]
+
+
+@pytest.mark.parametrize("t", [1, 2, 3])
+def test_reduction_matrix_invariants(t):
+    p, n = P61, 2 * t + 1
+    R = [[int(v) for v in r] for r in orc.red_matrix(n, t, p)]
+    R2 = [[sum(R[i][l] * R[l][j] for l in range(n)) % p for j in range(n)] for i in range(n)]
+    assert R2 == R                                                  # projector
+    # fixes every share vector of degree <= t, drops the monomials above t
+    for deg in range(0, 2 * t + 1):
+        vec = [pow(i, deg, p) for i in range(1, n + 1)]
+        img = [sum(vec[i] * R[i][j] for i in range(n)) % p for j in range(n)]
+        assert img == (vec if deg <= t else [0] * n)
+
+
+def test_reduction_matrix_with_extra_parties():
+    # n > 2t+1: the first 2t+1 parties reduce, the truncated polynomial is
+    # evaluated at all n IDs
+    p, t, n = P61, 1, 5
+    R = [[int(v) for v in r] for r in orc.red_matrix(n, t, p)]
+    assert [r[:3] for r in R] == [[int(v) for v in r] for r in orc.red_matrix(3, t, p)]
+    coeffs = [123456789, 987654321, 555]                             # degree 2t polynomial
+    c = [sum(a * i ** j for j, a in enumerate(coeffs)) % p for i in range(1, 4)]
+    img = [sum(c[i] * R[i][j] for i in range(3)) % p for j in range(n)]
+    assert img == [(coeffs[0] + coeffs[1] * i) % p for i in range(1, n + 1)]
+
+
+# ----------------------------------------------------------------- RED + RERAND
+def test_fig2_degree_reduction_and_rerandomisation():
+    g = read_kv("fig2_example.txt")
+    p = g["p"][0]
+    c = np.array(g["product_shares"], np.uint64).reshape(3, 1)
+    zc = np.array(g["zero_coeff"], np.uint64).reshape(1, 1)
+    for r1, r2, r3 in itertools.product(range(p), repeat=3):        # every reshare randomness
+        rc = np.array([r1, r2, r3], np.uint64).reshape(3, 1, 1)
+        out, msg1, msg2, red = orc.degree_reduce_explicit(c, rc, zc, 3, 1, p, full=True)
+        assert [int(v) for v in red[:, 0]] == g["red_shares"] == [9, 1, 4]
+        assert [int(v) for v in out[:, 0]] == g["final_shares"] == [2, 9, 5]
+    assert [int(v) for v in out[:2, 0]] == [2, 9]                   # Sec. IV-C: "(i.e., 2,9)"
+    for ids in ([1, 2], [1, 3], [2, 3]):
+        assert int(orc.reconstruct(out, ids, p)[0]) == 6
+    zsh = orc.share_explicit(np.zeros(1, np.uint64), zc, 3, 1, p)
+    assert [int(v) for v in zsh[:, 0]] == g["zero_shares"]
+
+
+def test_degree_reduce_messages_are_sharings_of_the_inputs():
+    # step 1 messages of party i reconstruct (from parties 1..k) to c_i;
+    # step 2 messages towards party m reconstruct to the reduced share of m
+    rng = np.random.default_rng(8)
+    n, t, count = 5, 2, 16
+    c = rng.integers(0, P61, (n, count), dtype=np.uint64)
+    out, msg1, msg2, red = orc.degree_reduce(c, n, t, P61, seed=5, stream_id=2, full=True)
+    ids = list(range(1, t + 2))
+    for i in range(2 * t + 1):
+        assert np.array_equal(orc.reconstruct(msg1[i], ids, P61), c[i])
+    for m in range(n):
+        assert np.array_equal(orc.reconstruct(np.ascontiguousarray(msg2[:, m, :]), ids, P61), red[m])
+
+
+@pytest.mark.parametrize("n,t", [(3, 1), (5, 2), (7, 3), (5, 1), (7, 2)])
+def test_degree_reduce_equals_truncated_product_polynomial(n, t):
+    # multiply two degree-t polynomials coefficient-wise with Python ints,
+    # cut above degree t, evaluate at 1..n: RED must give exactly that,
+    # whatever the reshare randomness; RERAND adds a degree-t sharing of 0
+    rnd = random.Random(n * 10 + t)
+    p, count = P61, 6
+    A = [[rnd.randrange(p) for _ in range(t + 1)] for _ in range(count)]
+    Bc = [[rnd.randrange(p) for _ in range(t + 1)] for _ in range(count)]
+    prodc = []
+    for a, b in zip(A, Bc):
+        pc = [0] * (2 * t + 1)
+        for i, x in enumerate(a):
+            for j, y in enumerate(b):
+                pc[i + j] = (pc[i + j] + x * y) % p
+        prodc.append(pc)
+    c = np.array([[sum(co * i ** j for j, co in enumerate(pc)) % p for pc in prodc]
+                  for i in range(1, n + 1)], np.uint64)
+    want_red = [[sum(co * i ** j for j, co in enumerate(pc[:t + 1])) % p for pc in prodc]
+                for i in range(1, n + 1)]
+    outs = []
+    for seed in (1, 2):
+        out, msg1, msg2, red = orc.degree_reduce(c, n, t, p, seed=seed, stream_id=0, full=True)
+        assert [[int(v) for v in r] for r in red] == want_red
+        zc = orc.draw_coeffs(seed, orc.DOM_ZERO, 0, 0, t, count, p)
+        want_out = [[(want_red[i - 1][e] + sum(int(zc[j - 1, e]) * i ** j for j in range(1, t + 1))) % p
+                     for e in range(count)] for i in range(1, n + 1)]
+        assert [[int(v) for v in r] for r in out] == want_out
+        outs.append(out)
+        for ids in itertools.combinations(range(1, n + 1), t + 1):
+            got = orc.reconstruct(out, list(ids), p)
+            assert [int(v) for v in got] == [pc[0] for pc in prodc]
+    assert not np.array_equal(outs[0], outs[1])                      # re-randomised
+    assert not np.array_equal(outs[0], np.array(want_red, np.uint64))
+
+
+# ----------------------------------------------------------------- truncation
+@pytest.mark.parametrize("p,f,n,t", [(97, 1, 3, 1), (97, 2, 3, 1), (251, 2, 5, 2)])
+def test_truncation_bruteforce_small_field(p, f, n, t):
+    # every secret whose masked value stays inside the signed range, every
+    # admissible mask e: the output shares are a degree-t sharing of
+    # floor(x / 2^f) (Sec. VI-B), independent of e
+    r = 1 << f
+    half = (p - 1) // 2
+    rnd = random.Random(p * 10 + f)
+    for e_val in (1, 2, 3):
+        xs = [x for x in range(-half, half + 1) if -half <= x + e_val * r <= half]
+        count = len(xs)
+        secret = np.array([x % p for x in xs], np.uint64)
+        mk = lambda: np.array([[rnd.randrange(p) for _ in range(count)] for _ in range(t)], np.uint64)
+        xsh = orc.share_explicit(secret, mk(), n, t, p)
+        ev = np.full(count, e_val, np.uint64)
+        out, u, wsh = orc.truncate_explicit(xsh, ev, mk(), mk(), mk(), n, t, f, p, full=True)
+        want = [(x // r) % p for x in xs]                           # Python // floors toward -inf
+        for ids in itertools.combinations(range(1, n + 1), t + 1):
+            assert [int(v) for v in orc.reconstruct(out, list(ids), p)] == want
+        # what the elite party sees is x + alpha, and what it re-shares is y + e
+        seen = orc.reconstruct(np.vstack([u, np.zeros((n - t - 1, count), np.uint64)]), list(range(1, t + 2)), p)
+        assert [int(v) for v in seen] == [(x + e_val * r) % p for x in xs]
+        assert [int(v) for v in orc.reconstruct(wsh, list(range(1, t + 2)), p)] == [(x // r + e_val) % p for x in xs]
+
+
+def test_truncation_seeded_mersenne61():
+    rng = np.random.default_rng(12)
+    n, t, f = 5, 2, 13
+    xs = rng.integers(-(1 << 45), 1 << 45, 200, dtype=np.int64)
+    xs[:4] = [0, -1, 8191, -8193]
+    secret = np.array([int(x) % P61 for x in xs], np.uint64)
+    xsh = orc.share(secret, n, t, P61, seed=3, stream_id=0)
+    out, u, wsh = orc.truncate(xsh, n, t, f, P61, seed=3, stream_id=77, full=True)
+    want = [(int(x) >> f) % P61 for x in xs]
+    for ids in ([1, 2, 3], [3, 4, 5], [1, 3, 5]):
+        assert [int(v) for v in orc.reconstruct(out, ids, P61)] == want
+    # masks: alpha in (0, 2^32], a multiple of 2^f
+    masked = orc.reconstruct(np.vstack([u, np.zeros((2, 200), np.uint64)]), [1, 2, 3], P61)
+    alpha = [(int(m) - int(s)) % P61 for m, s in zip(masked, secret)]
+    assert all(0 < a <= 1 << 32 and a % (1 << f) == 0 for a in alpha)
+    assert len(set(alpha)) > 150
+
+
+# ----------------------------------------------------------------- linear / conv
+def test_linear_lazy_equals_strict_and_bigints():
+    rng = np.random.default_rng(21)
+    n, M, K, N = 2, 3, 70, 4
+    x = rng.integers(0, P61, (n, M, K), dtype=np.uint64)
+    w = rng.integers(0, P61, (n, K, N), dtype=np.uint64)
+    x[0, 0, :] = P61 - 1
+    w[0, :, 0] = P61 - 1
+    y = orc.linear(x, w, P61)
+    assert np.array_equal(y, orc.linear(x, w, P61, strict=True))
+    for i in range(n):
+        for m in range(M):
+            for c in range(N):
+                assert int(y[i, m, c]) == sum(int(x[i, m, k]) * int(w[i, k, c]) for k in range(K)) % P61
+
+
+def test_linear_small_prime_against_numpy_matmul():
+    rng = np.random.default_rng(22)
+    for p in (97, 65521):
+        x = rng.integers(0, p, (3, 9, 33), dtype=np.uint64)
+        w = rng.integers(0, p, (3, 33, 7), dtype=np.uint64)
+        want = np.stack([(x[i].astype(np.int64) @ w[i].astype(np.int64)) % p for i in range(3)])
+        assert np.array_equal(orc.linear(x, w, p).astype(np.int64), want)
+    # a transposed operand must fail: non-square, non-symmetric data
+    assert not np.array_equal(orc.linear(x, w, p)[0].astype(np.int64),
+                              (w[0].astype(np.int64).T[:, :9] @ x[0].astype(np.int64).T[:9, :7]) % p)
+
+
+def test_linear_signed_small_values_match_integer_gemm():
+    rng = np.random.default_rng(23)
+    xs = rng.integers(-2 ** 15, 2 ** 15, (1, 8, 64), dtype=np.int64)
+    ws = rng.integers(-2 ** 15, 2 ** 15, (1, 64, 5), dtype=np.int64)
+    x = np.where(xs < 0, xs + P61, xs).astype(np.uint64)
+    w = np.where(ws < 0, ws + P61, ws).astype(np.uint64)
+    assert np.array_equal(orc.lift(orc.linear(x, w, P61), P61), xs @ ws)
+
+
+@pytest.mark.parametrize("stride,pad,k", [(1, 1, 3), (2, 1, 3), (1, 0, 1), (2, 3, 7), (2, 0, 1)])
+def test_conv_matches_torch_int64(stride, pad, k):
+    import torch
+    rng = np.random.default_rng(31 + k + stride)
+    B, Ci, H, W, Co = 2, 3, 9, 8, 4
+    xs = rng.integers(-2 ** 12, 2 ** 12, (B, Ci, H, W), dtype=np.int64)
+    ws = rng.integers(-2 ** 12, 2 ** 12, (Co, Ci, k, k), dtype=np.int64)
+    want = torch.nn.functional.conv2d(torch.from_numpy(xs), torch.from_numpy(ws), stride=stride, padding=pad).numpy()
+    x = np.where(xs < 0, xs + P61, xs).astype(np.uint64)[None]
+    w = np.where(ws < 0, ws + P61, ws).astype(np.uint64)[None]
+    got = orc.conv(x, w, stride, pad, P61)
+    assert got.shape[1:] == want.shape
+    assert np.array_equal(orc.lift(got, P61)[0], want)
+    flat = np.array([0, 5, got.size - 1, got.size // 2], np.uint64)
+    assert np.array_equal(orc.conv_points(x, w, stride, pad, P61, flat), got.reshape(-1)[flat.astype(np.int64)])
+
+
+def test_conv_full_range_against_bigints_and_per_party_independence():
+    rng = np.random.default_rng(33)
+    n, B, Ci, H, W, Co, k = 2, 1, 2, 4, 5, 2, 3
+    x = rng.integers(0, P61, (n, B, Ci, H, W), dtype=np.uint64)
+    w = rng.integers(0, P61, (n, Co, Ci, k, k), dtype=np.uint64)
+    y = orc.conv(x, w, 1, 1, P61)
+    for i in range(n):
+        for co in range(Co):
+            for ho in range(H):
+                for wo in range(W):
+                    acc = 0
+                    for c in range(Ci):
+                        for r in range(k):
+                            for s in range(k):
+                                hi, wi = ho - 1 + r, wo - 1 + s
+                                if 0 <= hi < H and 0 <= wi < W:
+                                    acc += int(x[i, 0, c, hi, wi]) * int(w[i, co, c, r, s])
+                    assert int(y[i, 0, co, ho, wo]) == acc % P61
+    # party 1's output only depends on party 1's operands
+    x2, w2 = x.copy(), w.copy()
+    x2[0] = 1
+    w2[0] = 2
+    assert np.array_equal(orc.conv(x2, w2, 1, 1, P61)[1], y[1])
+
+
+# ----------------------------------------------------------------- end to end
+def test_tiny_secure_gemm_matches_float64_on_dequantised_operands():
+    # share X and W, local product, degree reduction, truncation, reconstruct:
+    # the decoded result is floor-truncated, so it lies in (exact - 2^-f, exact]
+    from ssnet_inputs import gaussian
+    n, t, f, p = 3, 1, 13, P61
+    M, K, N = 8, 32, 6
+    X, Wt = gaussian((M, K), 1), gaussian((K, N), 2)
+    xe, we = orc.encode(X, f, p), orc.encode(Wt, f, p)
+    xs = orc.share(xe, n, t, p, seed=7, stream_id=1)
+    ws = orc.share(we, n, t, p, seed=7, stream_id=2)
+    y2 = orc.linear(xs, ws, p)                                       # degree 2t
+    # the untruncated product reconstructs exactly from all 2t+1 parties
+    exact = orc.decode(xe, f, p) @ orc.decode(we, f, p)
+    assert np.array_equal(orc.decode(orc.reconstruct(y2, [1, 2, 3], p), 2 * f, p), exact)
+    yr = orc.degree_reduce(y2.reshape(n, -1), n, t, p, seed=7, stream_id=3)
+    yt = orc.truncate(yr, n, t, f, p, seed=7, stream_id=4)
+    for ids in ([1, 2], [2, 3], [1, 3]):
+        got = orc.decode(orc.reconstruct(yt, ids, p), f, p).reshape(M, N)
+        err = exact - got
+        assert err.min() >= 0 and err.max() < 2.0 ** -f
+    assert np.max(np.abs(got - X @ Wt)) < 2.0 ** -8
