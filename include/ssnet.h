@@ -1,0 +1,164 @@
+/*
+ * ssnet.h - C ABI of the MI355X (gfx950) library for the per-party arithmetic
+ * of Shamir-secret-sharing neural-network inference.
+ *
+ * All n parties of a (k = t+1, n) threshold scheme are simulated as the
+ * leading (batch) dimension of every share tensor on one GPU; no data leaves
+ * the device inside a call.  The field is F_p with p = 2^61 - 1; a field
+ * element is a uint64_t in [0, p-1] (canonical: the value p never appears).
+ *
+ * Conventions for every entry point below
+ *   - `d_` pointers are DEVICE pointers owned by the caller (8-byte aligned;
+ *     16-byte aligned buffers take the faster vector path).  The library never
+ *     allocates, frees or keeps them, except the workspace handed over with
+ *     ssnet_set_workspace, which it uses until replaced or the context dies.
+ *   - Share tensors are party-major: shares[i*count + e] is the share of
+ *     element e held by the party with ID i+1 (IDs are 1..n, Sec. IV-A).
+ *   - Work is enqueued on the HIP stream given at creation; calls do not
+ *     synchronise.  Inputs and outputs must not alias unless stated.
+ *   - Inputs must be canonical (< p); outputs always are.
+ *   - Return value: SSNET_OK (0) or a negative SSNET_E* code; nothing throws.
+ *   - Randomness: every random polynomial coefficient is a pure function of
+ *     (seed, domain, stream_id, party, coefficient index, element index) by the
+ *     counter-based generator documented with ssnet_rng_key / ssnet_rng_draw,
+ *     so equal arguments give equal bits.  Use a fresh stream_id per call.
+ */
+#ifndef SSNET_H
+#define SSNET_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SSNET_OK 0
+#define SSNET_EINVAL (-1)     /* null pointer, bad n/t/f/degree/shape                 */
+#define SSNET_EPRIME (-2)     /* p is not 2^61 - 1                                     */
+#define SSNET_ESHARES (-3)    /* fewer than degree+1 parties given to reconstruct      */
+#define SSNET_EID (-4)        /* party id outside [1, n] or repeated                   */
+#define SSNET_EWORKSPACE (-5) /* workspace missing or too small for this call          */
+#define SSNET_EHIP (-6)       /* a HIP call failed; see ssnet_last_hip_error           */
+
+#define SSNET_MAX_PARTIES 8   /* n <= 8                                                */
+#define SSNET_MAX_T 3         /* t <= 3 (n >= 2t+1)                                    */
+#define SSNET_MAX_K 16383     /* contraction length of linear/conv (int32 exactness)   */
+
+#define SSNET_P61 0x1FFFFFFFFFFFFFFFULL
+
+typedef struct ssnet_ctx ssnet_ctx;
+
+/* Context: parameters of the scheme plus host-computed constant tables
+ * (Lagrange multipliers of Eq. 2 for IDs 1..k, the factors of the reduction
+ * matrix R = B^-1 P B of Eq. 3).  Requires n >= 2t+1 (Sec. III-B), 1 <= t <=
+ * SSNET_MAX_T, n <= SSNET_MAX_PARTIES, p == 2^61-1, 1 <= f <= 31.
+ * `hip_stream` is a hipStream_t (NULL = the default stream).  Host-only work:
+ * creating a context does not touch the GPU. */
+int ssnet_create(ssnet_ctx **out, int n, int t, uint64_t p, int f, uint64_t seed, void *hip_stream);
+int ssnet_destroy(ssnet_ctx *ctx);
+
+/* Scratch memory for the inter-party messages of ssnet_degree_reduce /
+ * ssnet_truncate on `count` elements, and for the int8 limb tiles of
+ * ssnet_linear_mod / ssnet_conv_mod.  Sizes are in bytes; a workspace of the
+ * maximum over the calls that will be made serves all of them. */
+size_t ssnet_workspace_bytes_stream(const ssnet_ctx *ctx, size_t count);
+size_t ssnet_workspace_bytes_linear(const ssnet_ctx *ctx, int M, int K, int N);
+size_t ssnet_workspace_bytes_conv(const ssnet_ctx *ctx, int B, int C, int H, int W, int Co, int kh, int kw,
+                                  int stride, int pad);
+int ssnet_set_workspace(ssnet_ctx *ctx, void *d_workspace, size_t bytes);
+
+/* GEN (Eq. 1): for each element e draw a_1..a_degree uniformly from F_p
+ * (domain SHARE) and write share_i[e] = a0 + a1 i + ... + a_d i^d mod p for
+ * i = 1..n.  d_secret [count] -> d_shares [n][count].  0 <= degree <= 2t. */
+int ssnet_share(ssnet_ctx *ctx, const uint64_t *d_secret, size_t count, int degree, uint64_t stream_id,
+                uint64_t *d_shares);
+
+/* REC (Eq. 2): secret[e] = sum_{i in ids} lambda_i * shares[i-1][e] mod p with
+ * lambda_i = prod_{j != i} j / (j - i).  `party_ids` is a HOST array of m
+ * distinct IDs in [1, n]; m >= degree+1 else SSNET_ESHARES (degree = t or 2t).
+ * d_shares [n][count] (only the m named planes are read) -> d_secret [count]. */
+int ssnet_reconstruct(ssnet_ctx *ctx, const uint64_t *d_shares, size_t count, const int *party_ids, int m,
+                      int degree, uint64_t *d_secret);
+
+/* SSS-Linear step 1, dense (Sec. VI-A): every party multiplies its own share
+ * matrices, y_i = x_i * w_i mod p.  d_x [n][M][K], d_w [n][K][N] -> d_y
+ * [n][M][N], all row-major.  The result is a degree-2t sharing.
+ * K <= SSNET_MAX_K.  Needs a workspace (ssnet_workspace_bytes_linear). */
+int ssnet_linear_mod(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_w, int M, int K, int N,
+                     uint64_t *d_y);
+
+/* SSS-Linear step 1, convolution (Sec. VI-A): per party, cross-correlation
+ * (no kernel flip) with zero padding, mod p.  d_x [n][B][C][H][W], d_w
+ * [n][Co][C][kh][kw] -> d_y [n][B][Co][Ho][Wo], Ho = (H+2*pad-kh)/stride+1.
+ * C*kh*kw <= SSNET_MAX_K.  Needs a workspace (ssnet_workspace_bytes_conv). */
+int ssnet_conv_mod(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_w, int B, int C, int H, int W,
+                   int Co, int kh, int kw, int stride, int pad, uint64_t *d_y);
+
+/* Weights are fixed across inferences (Sec. II-B: preprocessing is done once
+ * for a sequence of inferences), so their int8 limb tiles can be prepared
+ * once: ssnet_pack_weights_* writes them to caller memory of
+ * ssnet_packed_weight_bytes(rows, K) * n bytes, and the *_packed variants of
+ * the two layer calls take that buffer in place of d_w.  rows = N (dense) or
+ * Co (conv), K = contraction length.  Results are bit-identical. */
+size_t ssnet_packed_weight_bytes(int rows, int K);
+int ssnet_pack_weights_linear(ssnet_ctx *ctx, const uint64_t *d_w /*[n][K][N]*/, int K, int N, void *d_packed);
+int ssnet_pack_weights_conv(ssnet_ctx *ctx, const uint64_t *d_w /*[n][Co][C][kh][kw]*/, int Co, int CKK,
+                            void *d_packed);
+int ssnet_linear_mod_packed(ssnet_ctx *ctx, const uint64_t *d_x, const void *d_w_packed, int M, int K, int N,
+                            uint64_t *d_y);
+int ssnet_conv_mod_packed(ssnet_ctx *ctx, const uint64_t *d_x, const void *d_w_packed, int B, int C, int H,
+                          int W, int Co, int kh, int kw, int stride, int pad, uint64_t *d_y);
+
+/* RED by resharing (Sec. IV-B, the three protocol steps with the matrix of
+ * Eq. 3) followed by RERAND (Sec. IV-C), all n parties:
+ *   1. parties 1..2t+1: GEN(c_i, k, k) towards parties 1..k   (domain RESHARE, party i)
+ *   2. parties 1..k: received row vector times R               -> one value per party 1..n
+ *   3. parties 1..n: REC of the k values received, then add the party's share
+ *      of a fresh degree-t sharing of zero                     (domain ZERO)
+ * d_c [n][count] (degree 2t) -> d_out [n][count] (degree t).  The messages of
+ * steps 1 and 2 are materialised in the workspace ([2t+1][k][count] and
+ * [k][n][count]).  d_out may alias d_c. */
+int ssnet_degree_reduce(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id, uint64_t *d_out);
+
+/* SSS-Truncation (Sec. VI-B) by r = 2^f: shares of floor(x / 2^f), x read as a
+ * signed value in [-(p-1)/2, (p-1)/2].
+ *   1. parties 1..k add their share of alpha = e*2^f, e uniform in [1, 2^(32-f)]
+ *      (Sec. VII-B; domains MASK_E, MASK_ALPHA)
+ *   2. the elite party reconstructs x+alpha, shifts right by f (arithmetic) and
+ *      re-shares the result                                    (domain TRUNC_GEN)
+ *   3. all n parties add their share of alpha~ = -e             (domain MASK_ALPHAT)
+ * d_x [n][count] (degree t; planes 1..k are read) -> d_out [n][count].
+ * Requires |x| + 2^32 <= (p-1)/2.  Messages go through the workspace.
+ * d_out may alias d_x. */
+int ssnet_truncate(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, uint64_t stream_id, uint64_t *d_out);
+
+/* Host-side generator, exposed so that its bits can be checked without a GPU.
+ * key = absorb(seed, domain, stream_id, party, j) with h <- mix64((h ^ word) +
+ * 0x9E3779B97F4A7C15) from h = 0, mix64 being the SplitMix64 output function;
+ * draw(key, e) = mix64(key + (e+1) * 0x9E3779B97F4A7C15); the field element is
+ * draw >> 3, with the single value p mapped to 0. */
+#define SSNET_DOM_SHARE 1
+#define SSNET_DOM_RESHARE 2
+#define SSNET_DOM_ZERO 3
+#define SSNET_DOM_MASK_E 4
+#define SSNET_DOM_MASK_ALPHA 5
+#define SSNET_DOM_MASK_ALPHAT 6
+#define SSNET_DOM_TRUNC_GEN 7
+uint64_t ssnet_rng_key(uint64_t seed, uint64_t domain, uint64_t stream_id, uint64_t party, uint64_t j);
+uint64_t ssnet_rng_draw(uint64_t key, uint64_t e);
+uint64_t ssnet_rng_field(uint64_t key, uint64_t e);
+
+/* Host-side constant tables of a context, for inspection: Lagrange multipliers
+ * of an ID set (Eq. 2) into out[m]; the reduction matrix R (Eq. 3, row-vector
+ * convention c' = c R) as [2t+1][n] row-major into out. */
+int ssnet_host_lagrange(const ssnet_ctx *ctx, const int *party_ids, int m, uint64_t *out);
+int ssnet_host_reduction_matrix(const ssnet_ctx *ctx, uint64_t *out);
+
+const char *ssnet_strerror(int code);
+int ssnet_last_hip_error(const ssnet_ctx *ctx); /* hipError_t of the last failed HIP call, 0 if none */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSNET_H */

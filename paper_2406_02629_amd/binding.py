@@ -1,0 +1,275 @@
+"""ctypes binding of libssnet.so (the C ABI of include/ssnet.h).
+
+Argument marshalling only: every operation on share data runs in the HIP
+kernels of the library.  torch supplies device memory (int64 tensors hold the
+61-bit field elements) and the stream.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+from . import build as _build
+
+P61 = (1 << 61) - 1
+
+OK, EINVAL, EPRIME, ESHARES, EID, EWORKSPACE, EHIP = 0, -1, -2, -3, -4, -5, -6
+DOM_SHARE, DOM_RESHARE, DOM_ZERO, DOM_MASK_E, DOM_MASK_ALPHA, DOM_MASK_ALPHAT, DOM_TRUNC_GEN = range(1, 8)
+
+_u64, _sz, _int, _ptr = C.c_uint64, C.c_size_t, C.c_int, C.c_void_p
+
+# name -> (restype, argtypes): every symbol include/ssnet.h declares
+SIGNATURES = {
+    "ssnet_create": (_int, [C.POINTER(_ptr), _int, _int, _u64, _int, _u64, _ptr]),
+    "ssnet_destroy": (_int, [_ptr]),
+    "ssnet_workspace_bytes_stream": (_sz, [_ptr, _sz]),
+    "ssnet_workspace_bytes_linear": (_sz, [_ptr, _int, _int, _int]),
+    "ssnet_workspace_bytes_conv": (_sz, [_ptr] + [_int] * 9),
+    "ssnet_set_workspace": (_int, [_ptr, _ptr, _sz]),
+    "ssnet_share": (_int, [_ptr, _ptr, _sz, _int, _u64, _ptr]),
+    "ssnet_reconstruct": (_int, [_ptr, _ptr, _sz, C.POINTER(_int), _int, _int, _ptr]),
+    "ssnet_linear_mod": (_int, [_ptr, _ptr, _ptr, _int, _int, _int, _ptr]),
+    "ssnet_conv_mod": (_int, [_ptr, _ptr, _ptr] + [_int] * 9 + [_ptr]),
+    "ssnet_packed_weight_bytes": (_sz, [_int, _int]),
+    "ssnet_pack_weights_linear": (_int, [_ptr, _ptr, _int, _int, _ptr]),
+    "ssnet_pack_weights_conv": (_int, [_ptr, _ptr, _int, _int, _ptr]),
+    "ssnet_linear_mod_packed": (_int, [_ptr, _ptr, _ptr, _int, _int, _int, _ptr]),
+    "ssnet_conv_mod_packed": (_int, [_ptr, _ptr, _ptr] + [_int] * 9 + [_ptr]),
+    "ssnet_degree_reduce": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
+    "ssnet_truncate": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
+    "ssnet_rng_key": (_u64, [_u64] * 5),
+    "ssnet_rng_draw": (_u64, [_u64, _u64]),
+    "ssnet_rng_field": (_u64, [_u64, _u64]),
+    "ssnet_host_lagrange": (_int, [_ptr, C.POINTER(_int), _int, C.POINTER(_u64)]),
+    "ssnet_host_reduction_matrix": (_int, [_ptr, C.POINTER(_u64)]),
+    "ssnet_strerror": (C.c_char_p, [_int]),
+    "ssnet_last_hip_error": (_int, [_ptr]),
+}
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Load the built library; build it first only if no library is there.
+    There is no fallback: without the HIP library nothing here works."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            _build.build(force=True)
+        lib = C.CDLL(_build.LIB)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+class SSNetError(RuntimeError):
+    def __init__(self, code: int, where: str, hip: int = 0):
+        msg = load_library().ssnet_strerror(code).decode()
+        super().__init__(f"{where}: {msg} (code {code}" + (f", hipError {hip})" if hip else ")"))
+        self.code = code
+
+
+def _dptr(t: torch.Tensor) -> int:
+    return t.data_ptr()
+
+
+def _check_i64(t: torch.Tensor, name: str) -> torch.Tensor:
+    if t.dtype != torch.int64 or not t.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous int64 tensor")
+    return t
+
+
+class SSNet:
+    """One (k = t+1, n) scheme over F_p, p = 2^61-1, fixed-point fraction bits f."""
+
+    def __init__(self, n: int, t: int, f: int = 13, seed: int = 0, p: int = P61,
+                 device: Optional[str] = "cuda:0", stream: Optional[int] = None):
+        self.lib = load_library()
+        self.n, self.t, self.k, self.f, self.p, self.seed = n, t, t + 1, f, p, seed
+        self.device = None if device is None else torch.device(device)
+        if stream is None and self.device is not None:
+            stream = torch.cuda.current_stream(self.device).cuda_stream
+        self._ctx = _ptr()
+        rc = self.lib.ssnet_create(C.byref(self._ctx), n, t, p, f, seed, _ptr(stream or 0))
+        if rc:
+            self._ctx = None
+            raise SSNetError(rc, "ssnet_create")
+        self._ws: Optional[torch.Tensor] = None
+
+    def close(self):
+        if getattr(self, "_ctx", None):
+            self.lib.ssnet_destroy(self._ctx)
+            self._ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _ok(self, rc: int, where: str):
+        if rc:
+            raise SSNetError(rc, where, self.lib.ssnet_last_hip_error(self._ctx))
+
+    # ---- workspace ----
+    def reserve(self, nbytes: int):
+        """Make the workspace at least nbytes large (allocates through torch)."""
+        if self._ws is None or self._ws.numel() < nbytes:
+            self._ws = torch.empty(int(nbytes), dtype=torch.uint8, device=self.device)
+            self._ok(self.lib.ssnet_set_workspace(self._ctx, _dptr(self._ws), self._ws.numel()), "ssnet_set_workspace")
+
+    def workspace_bytes_stream(self, count: int) -> int:
+        return self.lib.ssnet_workspace_bytes_stream(self._ctx, count)
+
+    def workspace_bytes_linear(self, M: int, K: int, N: int) -> int:
+        return self.lib.ssnet_workspace_bytes_linear(self._ctx, M, K, N)
+
+    def workspace_bytes_conv(self, B, Ci, H, W, Co, kh, kw, stride, pad) -> int:
+        return self.lib.ssnet_workspace_bytes_conv(self._ctx, B, Ci, H, W, Co, kh, kw, stride, pad)
+
+    # ---- GEN / REC ----
+    def share(self, secret: torch.Tensor, stream_id: int, degree: Optional[int] = None,
+              out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        _check_i64(secret, "secret")
+        degree = self.t if degree is None else degree
+        if out is None:
+            out = torch.empty((self.n,) + tuple(secret.shape), dtype=torch.int64, device=secret.device)
+        self._ok(self.lib.ssnet_share(self._ctx, _dptr(secret), secret.numel(), degree, stream_id, _dptr(out)),
+                 "ssnet_share")
+        return out
+
+    def reconstruct(self, shares: torch.Tensor, ids: Sequence[int], degree: Optional[int] = None,
+                    out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        _check_i64(shares, "shares")
+        degree = self.t if degree is None else degree
+        count = shares[0].numel()
+        if out is None:
+            out = torch.empty(tuple(shares.shape[1:]), dtype=torch.int64, device=shares.device)
+        arr = (_int * len(ids))(*ids)
+        self._ok(self.lib.ssnet_reconstruct(self._ctx, _dptr(shares), count, arr, len(ids), degree, _dptr(out)),
+                 "ssnet_reconstruct")
+        return out
+
+    # ---- linear layers ----
+    def linear_mod(self, x: torch.Tensor, w: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        _check_i64(x, "x"), _check_i64(w, "w")
+        n, M, K = x.shape
+        n2, K2, N = w.shape
+        if n != self.n or n2 != self.n or K != K2:
+            raise ValueError("shape mismatch")
+        self.reserve(self.workspace_bytes_linear(M, K, N))
+        if out is None:
+            out = torch.empty((n, M, N), dtype=torch.int64, device=x.device)
+        self._ok(self.lib.ssnet_linear_mod(self._ctx, _dptr(x), _dptr(w), M, K, N, _dptr(out)), "ssnet_linear_mod")
+        return out
+
+    def conv_mod(self, x: torch.Tensor, w: torch.Tensor, stride: int, pad: int,
+                 out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        _check_i64(x, "x"), _check_i64(w, "w")
+        n, B, Ci, H, W = x.shape
+        n2, Co, Ci2, kh, kw = w.shape
+        if n != self.n or n2 != self.n or Ci != Ci2:
+            raise ValueError("shape mismatch")
+        need = self.workspace_bytes_conv(B, Ci, H, W, Co, kh, kw, stride, pad)
+        if need == 0:
+            raise SSNetError(EINVAL, "ssnet_workspace_bytes_conv")
+        self.reserve(need)
+        Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+        if out is None:
+            out = torch.empty((n, B, Co, Ho, Wo), dtype=torch.int64, device=x.device)
+        self._ok(self.lib.ssnet_conv_mod(self._ctx, _dptr(x), _dptr(w), B, Ci, H, W, Co, kh, kw, stride, pad,
+                                         _dptr(out)), "ssnet_conv_mod")
+        return out
+
+    def pack_weights_linear(self, w: torch.Tensor) -> torch.Tensor:
+        _check_i64(w, "w")
+        n, K, N = w.shape
+        packed = torch.empty(self.n * self.lib.ssnet_packed_weight_bytes(N, K), dtype=torch.uint8, device=w.device)
+        self._ok(self.lib.ssnet_pack_weights_linear(self._ctx, _dptr(w), K, N, _dptr(packed)),
+                 "ssnet_pack_weights_linear")
+        return packed
+
+    def pack_weights_conv(self, w: torch.Tensor) -> torch.Tensor:
+        _check_i64(w, "w")
+        n, Co, Ci, kh, kw = w.shape
+        K = Ci * kh * kw
+        packed = torch.empty(self.n * self.lib.ssnet_packed_weight_bytes(Co, K), dtype=torch.uint8, device=w.device)
+        self._ok(self.lib.ssnet_pack_weights_conv(self._ctx, _dptr(w), Co, K, _dptr(packed)),
+                 "ssnet_pack_weights_conv")
+        return packed
+
+    def linear_mod_packed(self, x: torch.Tensor, w_packed: torch.Tensor, N: int,
+                          out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        _check_i64(x, "x")
+        n, M, K = x.shape
+        self.reserve(self.workspace_bytes_linear(M, K, N))
+        if out is None:
+            out = torch.empty((n, M, N), dtype=torch.int64, device=x.device)
+        self._ok(self.lib.ssnet_linear_mod_packed(self._ctx, _dptr(x), _dptr(w_packed), M, K, N, _dptr(out)),
+                 "ssnet_linear_mod_packed")
+        return out
+
+    def conv_mod_packed(self, x: torch.Tensor, w_packed: torch.Tensor, Co: int, kh: int, kw: int, stride: int,
+                        pad: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        _check_i64(x, "x")
+        n, B, Ci, H, W = x.shape
+        need = self.workspace_bytes_conv(B, Ci, H, W, Co, kh, kw, stride, pad)
+        if need == 0:
+            raise SSNetError(EINVAL, "ssnet_workspace_bytes_conv")
+        self.reserve(need)
+        Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+        if out is None:
+            out = torch.empty((n, B, Co, Ho, Wo), dtype=torch.int64, device=x.device)
+        self._ok(self.lib.ssnet_conv_mod_packed(self._ctx, _dptr(x), _dptr(w_packed), B, Ci, H, W, Co, kh, kw, stride,
+                                                pad, _dptr(out)), "ssnet_conv_mod_packed")
+        return out
+
+    # ---- RED + RERAND, truncation ----
+    def degree_reduce(self, c: torch.Tensor, stream_id: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        _check_i64(c, "c")
+        count = c[0].numel()
+        self.reserve(self.workspace_bytes_stream(count))
+        if out is None:
+            out = torch.empty_like(c)
+        self._ok(self.lib.ssnet_degree_reduce(self._ctx, _dptr(c), count, stream_id, _dptr(out)),
+                 "ssnet_degree_reduce")
+        return out
+
+    def truncate(self, x: torch.Tensor, stream_id: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        _check_i64(x, "x")
+        count = x[0].numel()
+        self.reserve(self.workspace_bytes_stream(count))
+        if out is None:
+            out = torch.empty_like(x)
+        self._ok(self.lib.ssnet_truncate(self._ctx, _dptr(x), count, stream_id, _dptr(out)), "ssnet_truncate")
+        return out
+
+    # ---- host-side tables (no GPU needed) ----
+    def host_lagrange(self, ids: Sequence[int]):
+        arr = (_int * len(ids))(*ids)
+        out = (_u64 * len(ids))()
+        self._ok(self.lib.ssnet_host_lagrange(self._ctx, arr, len(ids), out), "ssnet_host_lagrange")
+        return list(out)
+
+    def host_reduction_matrix(self):
+        nr = 2 * self.t + 1
+        out = (_u64 * (nr * self.n))()
+        self._ok(self.lib.ssnet_host_reduction_matrix(self._ctx, out), "ssnet_host_reduction_matrix")
+        return [[out[i * self.n + m] for m in range(self.n)] for i in range(nr)]
+
+
+def rng_key(seed, domain, stream_id, party, j) -> int:
+    return load_library().ssnet_rng_key(seed, domain, stream_id, party, j)
+
+
+def rng_draw(key, e) -> int:
+    return load_library().ssnet_rng_draw(key, e)
+
+
+def rng_field(key, e) -> int:
+    return load_library().ssnet_rng_field(key, e)

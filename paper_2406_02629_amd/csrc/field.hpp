@@ -1,0 +1,113 @@
+// Field arithmetic over p = 2^61 - 1 and the counter-based generator, for
+// device and host code of the GPU library.  2^61 = 1 (mod p), so a value is
+// reduced by adding its bits above 61 to its low 61 bits ("fold").
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef uint64_t u64;
+typedef uint32_t u32;
+
+#define SS_P 0x1FFFFFFFFFFFFFFFULL
+#define SS_GAMMA 0x9E3779B97F4A7C15ULL
+#define SS_MAXN 8
+#define SS_MAXT 3
+#define SS_MAXK (SS_MAXT + 1)
+
+#define SS_HD __host__ __device__ __forceinline__
+
+// x < 2^64  ->  result < 2^61 + 8, same residue
+SS_HD u64 ss_fold(u64 x) { return (x & SS_P) + (x >> 61); }
+
+// x < 2p  ->  canonical
+SS_HD u64 ss_canon(u64 x) { return x >= SS_P ? x - SS_P : x; }
+
+// any x < 2^64  ->  canonical
+SS_HD u64 ss_reduce(u64 x) { return ss_canon(ss_fold(x)); }
+
+SS_HD u64 ss_add(u64 a, u64 b) { return ss_canon(a + b); }          // a, b canonical
+SS_HD u64 ss_sub(u64 a, u64 b) { return ss_canon(a + SS_P - b); }   // a, b canonical
+SS_HD u64 ss_neg(u64 a) { return a ? SS_P - a : 0; }
+
+SS_HD u64 ss_mulhi(u64 a, u64 b)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __umul64hi(a, b);
+#else
+    return (u64)(((unsigned __int128)a * b) >> 64);
+#endif
+}
+
+// any 128-bit value hi:lo -> canonical.  2^64 = 2^3 (mod p), so
+// hi * 2^64 = ((hi mod 2^58) << 3) + (hi >> 58) * 2^61 = ((hi mod 2^58) << 3) + (hi >> 58)
+SS_HD u64 ss_reduce128(u64 hi, u64 lo)
+{
+    u64 r = (lo & SS_P) + (lo >> 61) + ((hi << 3) & SS_P) + (hi >> 58);   // < 2^62 + 2^7
+    return ss_reduce(r);
+}
+
+// a, b < 2^61: product < 2^122, hi < 2^58
+SS_HD u64 ss_mul(u64 a, u64 b) { return ss_reduce128(ss_mulhi(a, b), a * b); }
+
+// 128-bit accumulator for sums of a few products of canonical values
+struct ss_acc {
+    u64 hi, lo;
+    SS_HD void clear() { hi = 0; lo = 0; }
+    SS_HD void mac(u64 a, u64 b)
+    {
+        u64 l = a * b, h = ss_mulhi(a, b);
+        lo += l;
+        hi += h + (lo < l);
+    }
+    // exact while the sum stays below 2^128: up to 2^6 products of values below 2^61
+    SS_HD u64 value() const { return ss_reduce128(hi, lo); }
+};
+
+// x canonical, c a small constant (c <= 8): x*c < 2^64
+SS_HD u64 ss_mul_small(u64 x, u32 c) { return ss_reduce(x * (u64)c); }
+
+// ---- generator ----
+SS_HD u64 ss_mix64(u64 z)
+{
+    z ^= z >> 30;
+    z *= 0xBF58476D1CE4E5B9ULL;
+    z ^= z >> 27;
+    z *= 0x94D049BB133111EBULL;
+    z ^= z >> 31;
+    return z;
+}
+
+SS_HD u64 ss_key(u64 seed, u64 domain, u64 stream_id, u64 party, u64 j)
+{
+    u64 h = 0;
+    h = ss_mix64((h ^ seed) + SS_GAMMA);
+    h = ss_mix64((h ^ domain) + SS_GAMMA);
+    h = ss_mix64((h ^ stream_id) + SS_GAMMA);
+    h = ss_mix64((h ^ party) + SS_GAMMA);
+    h = ss_mix64((h ^ j) + SS_GAMMA);
+    return h;
+}
+
+SS_HD u64 ss_draw(u64 key, u64 e) { return ss_mix64(key + (e + 1) * SS_GAMMA); }
+
+SS_HD u64 ss_draw_field(u64 key, u64 e)
+{
+    u64 r = ss_draw(key, e) >> 3;
+    return r == SS_P ? 0 : r;
+}
+
+// polynomial a0 + c[0] x + ... + c[d-1] x^d at the small point x (1..8), by
+// Horner.  MAXD bounds d at compile time so that c[] stays in registers.
+template <int MAXD>
+SS_HD u64 ss_poly_eval(u64 a0, const u64 *c, int d, u32 x)
+{
+    u64 acc = 0;
+#pragma unroll
+    for (int j = MAXD; j >= 1; j--) {
+        if (j <= d) {
+            acc = ss_add(acc, c[j - 1]);
+            acc = ss_mul_small(acc, x);
+        }
+    }
+    return ss_add(acc, a0);
+}

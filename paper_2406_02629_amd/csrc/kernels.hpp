@@ -1,0 +1,57 @@
+// Internal launch interface between the C ABI (ssnet_api.hip) and the kernel
+// files.  Every launcher enqueues on `stream` and returns hipGetLastError().
+#pragma once
+#include "field.hpp"
+
+#define SS_MAXDEG (2 * SS_MAXT)   // highest polynomial degree ssnet_share accepts
+
+struct ss_keys {                  // generator keys, one per coefficient index j = 1..
+    u64 k[SS_MAXDEG];
+};
+
+struct ss_rec_params {            // REC: which planes, which multipliers
+    int m;
+    int plane[SS_MAXN];
+    u64 lambda[SS_MAXN];
+};
+
+struct ss_dr_params {             // RED + RERAND constants
+    int n, t;
+    u64 reshare_key[2 * SS_MAXT + 1][SS_MAXT];   // [party i][j]
+    u64 zero_key[SS_MAXT];
+    u64 binv[2 * SS_MAXT + 1][SS_MAXK];          // first k columns of B^-1 (Eq. 3)
+    u64 lambda[SS_MAXK];                         // Lagrange multipliers of IDs 1..k
+};
+
+struct ss_tr_params {             // truncation constants
+    int n, t, f;
+    u64 e_key;
+    u64 alpha_key[SS_MAXT], alphat_key[SS_MAXT], gen_key[SS_MAXT];
+    u64 lambda[SS_MAXK];
+};
+
+// ---- streaming family (stream_kernels.hip) ----
+hipError_t ss_launch_share(const u64 *secret, u64 *shares, size_t count, int n, int degree,
+                           const ss_keys &keys, hipStream_t stream);
+hipError_t ss_launch_reconstruct(const u64 *shares, u64 *secret, size_t count, const ss_rec_params &rp,
+                                 hipStream_t stream);
+hipError_t ss_launch_degree_reduce(const u64 *c, u64 *msg1, u64 *msg2, u64 *out, size_t count,
+                                   const ss_dr_params &dp, hipStream_t stream);
+hipError_t ss_launch_truncate(const u64 *x, u64 *u, u64 *wsh, u64 *out, size_t count, const ss_tr_params &tp,
+                              hipStream_t stream);
+
+// ---- int8-limb MFMA family (gemm_kernels.hip) ----
+// Packed operand: int8 tiles [row block of 16][k block of 64][limb 0..7][lane 0..63][16 bytes];
+// byte b of lane l is limb `limb` of element (row = 16*rb + l%16, k = 64*kb + 16*(l/16) + b).
+size_t ss_packed_bytes(int rows, int K);
+
+// element (r, k) of party i is src[i*party_stride + r*stride_r + k*stride_k]
+hipError_t ss_launch_pack_matrix(const u64 *src, void *dst, int n, int rows, int K, size_t party_stride,
+                                 size_t stride_r, size_t stride_k, hipStream_t stream);
+// rows = (b, ho, wo), k = (c, r, s) of x [n][B][C][H][W]
+hipError_t ss_launch_pack_im2col(const u64 *x, void *dst, int n, int B, int C, int H, int W, int kh, int kw,
+                                 int stride, int pad, int Ho, int Wo, hipStream_t stream);
+// out[i][row*stride_row + (col / cdiv)*stride_cb + col % cdiv] = sum_k A_i[row][k] * B_i[col][k] mod p
+hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, int n, int rows, int cols, int K,
+                          size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb,
+                          hipStream_t stream);

@@ -1,0 +1,371 @@
+// C ABI of the library (include/ssnet.h): argument checks, host-side constant
+// tables, workspace partitioning, kernel launches.  No arithmetic on share data
+// happens on the host.
+#include "../../include/ssnet.h"
+
+#include <limits.h>
+#include <new>
+
+#include "kernels.hpp"
+
+struct ssnet_ctx {
+    int n, t, f;
+    u64 seed;
+    hipStream_t stream;
+    void *ws;
+    size_t ws_bytes;
+    int last_hip;
+    u64 binv[2 * SS_MAXT + 1][SS_MAXK];   // first k columns of the inverse Vandermonde matrix (Eq. 3)
+    u64 lambda_k[SS_MAXK];                // Lagrange multipliers of IDs 1..k (Eq. 2)
+};
+
+namespace {
+
+u64 h_pow(u64 a, u64 e)
+{
+    u64 r = 1;
+    while (e) {
+        if (e & 1) r = ss_mul(r, a);
+        a = ss_mul(a, a);
+        e >>= 1;
+    }
+    return r;
+}
+
+u64 h_inv(u64 a) { return h_pow(a, SS_P - 2); }
+
+// Eq. 2 multipliers for an ID set
+void h_lagrange(const int *ids, int m, u64 *lambda)
+{
+    for (int i = 0; i < m; i++) {
+        u64 num = 1, den = 1;
+        for (int j = 0; j < m; j++) {
+            if (j == i) continue;
+            num = ss_mul(num, (u64)ids[j]);
+            den = ss_mul(den, ss_sub((u64)ids[j], (u64)ids[i]));
+        }
+        lambda[i] = ss_mul(num, h_inv(den));
+    }
+}
+
+// Row i of B^-1 holds the coefficients of the Lagrange basis polynomial
+// l_i(x) = prod_{l != i} (x - ID_l) / (ID_i - ID_l) over IDs 1..nr, because the
+// coefficient vector of the polynomial through the shares c is sum_i c_i l_i.
+// Only the k lowest coefficients survive the projection P.
+void h_inverse_vandermonde(int nr, int k, u64 (*binv)[SS_MAXK])
+{
+    for (int i = 0; i < nr; i++) {
+        u64 poly[2 * SS_MAXT + 2] = {1};   // running product, ascending powers
+        int deg = 0;
+        u64 den = 1;
+        for (int l = 0; l < nr; l++) {
+            if (l == i) continue;
+            const u64 root = (u64)(l + 1);
+            // poly *= (x - root)
+            for (int d = deg + 1; d >= 0; d--) {
+                const u64 up = d > 0 ? poly[d - 1] : 0;
+                const u64 keep = d <= deg ? ss_mul(poly[d], ss_neg(root)) : 0;
+                poly[d] = ss_add(up, keep);
+            }
+            deg++;
+            den = ss_mul(den, ss_sub((u64)(i + 1), root));
+        }
+        const u64 s = h_inv(den);
+        for (int j = 0; j < k; j++) binv[i][j] = ss_mul(poly[j], s);
+    }
+}
+
+int fail_hip(ssnet_ctx *ctx, hipError_t e)
+{
+    ctx->last_hip = (int)e;
+    return SSNET_EHIP;
+}
+
+int conv_out(int H, int k, int stride, int pad) { return (H + 2 * pad - k) / stride + 1; }
+
+size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+// largest element count whose 1-D grid fits
+constexpr size_t MAX_COUNT = (size_t)1 << 38;
+
+bool gemm_shape_ok(long rows, long cols, long K)
+{
+    return rows >= 1 && cols >= 1 && K >= 1 && K <= SSNET_MAX_K && rows <= 16L * 65535 * 2 && cols <= (1L << 30);
+}
+
+int run_gemm(ssnet_ctx *ctx, const void *pa, const void *pb, u64 *out, int rows, int cols, int K,
+             size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb)
+{
+    hipError_t e = ss_launch_gemm(pa, pb, out, ctx->n, rows, cols, K, out_party_stride, stride_row, cdiv, stride_cb,
+                                  ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+}  // namespace
+
+extern "C" {
+
+int ssnet_create(ssnet_ctx **out, int n, int t, uint64_t p, int f, uint64_t seed, void *hip_stream)
+{
+    if (!out) return SSNET_EINVAL;
+    *out = nullptr;
+    if (p != SSNET_P61) return SSNET_EPRIME;
+    if (t < 1 || t > SSNET_MAX_T || n < 2 * t + 1 || n > SSNET_MAX_PARTIES || f < 1 || f > 31) return SSNET_EINVAL;
+    ssnet_ctx *c = new (std::nothrow) ssnet_ctx();
+    if (!c) return SSNET_EINVAL;
+    c->n = n;
+    c->t = t;
+    c->f = f;
+    c->seed = seed;
+    c->stream = (hipStream_t)hip_stream;
+    c->ws = nullptr;
+    c->ws_bytes = 0;
+    c->last_hip = 0;
+    int ids[SS_MAXK];
+    for (int q = 0; q <= t; q++) ids[q] = q + 1;
+    h_lagrange(ids, t + 1, c->lambda_k);
+    h_inverse_vandermonde(2 * t + 1, t + 1, c->binv);
+    *out = c;
+    return SSNET_OK;
+}
+
+int ssnet_destroy(ssnet_ctx *ctx)
+{
+    delete ctx;
+    return SSNET_OK;
+}
+
+size_t ssnet_workspace_bytes_stream(const ssnet_ctx *ctx, size_t count)
+{
+    if (!ctx) return 0;
+    const size_t k = ctx->t + 1, nr = 2 * ctx->t + 1, n = ctx->n;
+    const size_t dr = (nr * k + k * n) * count * 8, tr = (k + n) * count * 8;
+    return align256(dr > tr ? dr : tr);
+}
+
+size_t ssnet_workspace_bytes_linear(const ssnet_ctx *ctx, int M, int K, int N)
+{
+    if (!ctx || M < 1 || K < 1 || N < 1) return 0;
+    return (size_t)ctx->n * (ss_packed_bytes(M, K) + ss_packed_bytes(N, K));
+}
+
+size_t ssnet_workspace_bytes_conv(const ssnet_ctx *ctx, int B, int C, int H, int W, int Co, int kh, int kw, int stride,
+                                  int pad)
+{
+    if (!ctx || B < 1 || C < 1 || Co < 1 || kh < 1 || kw < 1 || stride < 1 || pad < 0) return 0;
+    const int Ho = conv_out(H, kh, stride, pad), Wo = conv_out(W, kw, stride, pad);
+    if (Ho < 1 || Wo < 1) return 0;
+    const long M = (long)B * Ho * Wo, K = (long)C * kh * kw;
+    if (M > INT_MAX || K > INT_MAX) return 0;
+    return (size_t)ctx->n * (ss_packed_bytes((int)M, (int)K) + ss_packed_bytes(Co, (int)K));
+}
+
+int ssnet_set_workspace(ssnet_ctx *ctx, void *d_workspace, size_t bytes)
+{
+    if (!ctx || (!d_workspace && bytes) || ((uintptr_t)d_workspace & 15)) return SSNET_EINVAL;
+    ctx->ws = d_workspace;
+    ctx->ws_bytes = bytes;
+    return SSNET_OK;
+}
+
+int ssnet_share(ssnet_ctx *ctx, const uint64_t *d_secret, size_t count, int degree, uint64_t stream_id,
+                uint64_t *d_shares)
+{
+    if (!ctx || !d_secret || !d_shares || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
+    if (degree < 0 || degree > 2 * ctx->t || degree > ctx->n - 1) return SSNET_EINVAL;
+    ss_keys keys = {};
+    for (int j = 1; j <= degree; j++) keys.k[j - 1] = ss_key(ctx->seed, SSNET_DOM_SHARE, stream_id, 0, (u64)j);
+    hipError_t e = ss_launch_share(d_secret, d_shares, count, ctx->n, degree, keys, ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+int ssnet_reconstruct(ssnet_ctx *ctx, const uint64_t *d_shares, size_t count, const int *party_ids, int m, int degree,
+                      uint64_t *d_secret)
+{
+    if (!ctx || !d_shares || !d_secret || !party_ids || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
+    if (degree < 0 || degree > 2 * ctx->t || m < 1 || m > ctx->n) return SSNET_EINVAL;
+    for (int i = 0; i < m; i++) {
+        if (party_ids[i] < 1 || party_ids[i] > ctx->n) return SSNET_EID;
+        for (int j = 0; j < i; j++)
+            if (party_ids[j] == party_ids[i]) return SSNET_EID;
+    }
+    if (m < degree + 1) return SSNET_ESHARES;
+    ss_rec_params rp = {};
+    rp.m = m;
+    for (int i = 0; i < m; i++) rp.plane[i] = party_ids[i] - 1;
+    h_lagrange(party_ids, m, rp.lambda);
+    hipError_t e = ss_launch_reconstruct(d_shares, d_secret, count, rp, ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+size_t ssnet_packed_weight_bytes(int rows, int K)
+{
+    if (rows < 1 || K < 1) return 0;
+    return ss_packed_bytes(rows, K);
+}
+
+int ssnet_pack_weights_linear(ssnet_ctx *ctx, const uint64_t *d_w, int K, int N, void *d_packed)
+{
+    if (!ctx || !d_w || !d_packed || !gemm_shape_ok(N, 1, K) || ((uintptr_t)d_packed & 15)) return SSNET_EINVAL;
+    // row = output column c of w [K][N], contraction index strides by N
+    hipError_t e = ss_launch_pack_matrix(d_w, d_packed, ctx->n, N, K, (size_t)K * N, 1, (size_t)N, ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+int ssnet_pack_weights_conv(ssnet_ctx *ctx, const uint64_t *d_w, int Co, int CKK, void *d_packed)
+{
+    if (!ctx || !d_w || !d_packed || !gemm_shape_ok(Co, 1, CKK) || ((uintptr_t)d_packed & 15)) return SSNET_EINVAL;
+    hipError_t e = ss_launch_pack_matrix(d_w, d_packed, ctx->n, Co, CKK, (size_t)Co * CKK, (size_t)CKK, 1, ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+int ssnet_linear_mod_packed(ssnet_ctx *ctx, const uint64_t *d_x, const void *d_w_packed, int M, int K, int N,
+                            uint64_t *d_y)
+{
+    if (!ctx || !d_x || !d_w_packed || !d_y || !gemm_shape_ok(M, N, K)) return SSNET_EINVAL;
+    const size_t need = (size_t)ctx->n * ss_packed_bytes(M, K);
+    if (!ctx->ws || ctx->ws_bytes < need) return SSNET_EWORKSPACE;
+    hipError_t e = ss_launch_pack_matrix(d_x, ctx->ws, ctx->n, M, K, (size_t)M * K, (size_t)K, 1, ctx->stream);
+    if (e != hipSuccess) return fail_hip(ctx, e);
+    return run_gemm(ctx, ctx->ws, d_w_packed, d_y, M, N, K, (size_t)M * N, (size_t)N, INT_MAX, 0);
+}
+
+int ssnet_linear_mod(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_w, int M, int K, int N, uint64_t *d_y)
+{
+    if (!ctx || !d_x || !d_w || !d_y || !gemm_shape_ok(M, N, K)) return SSNET_EINVAL;
+    const size_t xa = (size_t)ctx->n * ss_packed_bytes(M, K), wa = (size_t)ctx->n * ss_packed_bytes(N, K);
+    if (!ctx->ws || ctx->ws_bytes < xa + wa) return SSNET_EWORKSPACE;
+    void *pw = (char *)ctx->ws + xa;
+    int rc = ssnet_pack_weights_linear(ctx, d_w, K, N, pw);
+    if (rc) return rc;
+    return ssnet_linear_mod_packed(ctx, d_x, pw, M, K, N, d_y);
+}
+
+int ssnet_conv_mod_packed(ssnet_ctx *ctx, const uint64_t *d_x, const void *d_w_packed, int B, int C, int H, int W,
+                          int Co, int kh, int kw, int stride, int pad, uint64_t *d_y)
+{
+    if (!ctx || !d_x || !d_w_packed || !d_y || B < 1 || C < 1 || H < 1 || W < 1 || Co < 1 || kh < 1 || kw < 1 ||
+        stride < 1 || pad < 0)
+        return SSNET_EINVAL;
+    const int Ho = conv_out(H, kh, stride, pad), Wo = conv_out(W, kw, stride, pad);
+    if (H + 2 * pad < kh || W + 2 * pad < kw || Ho < 1 || Wo < 1) return SSNET_EINVAL;
+    const long M = (long)B * Ho * Wo, K = (long)C * kh * kw;
+    if (M > (1L << 30) || !gemm_shape_ok(Co, M, K)) return SSNET_EINVAL;
+    const size_t need = (size_t)ctx->n * ss_packed_bytes((int)M, (int)K);
+    if (!ctx->ws || ctx->ws_bytes < need) return SSNET_EWORKSPACE;
+    hipError_t e = ss_launch_pack_im2col(d_x, ctx->ws, ctx->n, B, C, H, W, kh, kw, stride, pad, Ho, Wo, ctx->stream);
+    if (e != hipSuccess) return fail_hip(ctx, e);
+    const size_t HW = (size_t)Ho * Wo;
+    // rows = output channel, cols = (b, ho, wo): y[b][co][hw]
+    return run_gemm(ctx, d_w_packed, ctx->ws, d_y, Co, (int)M, (int)K, (size_t)B * Co * HW, HW, (int)HW, (size_t)Co * HW);
+}
+
+int ssnet_conv_mod(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_w, int B, int C, int H, int W, int Co, int kh,
+                   int kw, int stride, int pad, uint64_t *d_y)
+{
+    if (!ctx || !d_w) return SSNET_EINVAL;
+    const size_t total = ssnet_workspace_bytes_conv(ctx, B, C, H, W, Co, kh, kw, stride, pad);
+    if (total == 0) return SSNET_EINVAL;
+    if (!ctx->ws || ctx->ws_bytes < total) return SSNET_EWORKSPACE;
+    const long K = (long)C * kh * kw;
+    if (K > SSNET_MAX_K) return SSNET_EINVAL;
+    void *pw = (char *)ctx->ws + (total - (size_t)ctx->n * ss_packed_bytes(Co, (int)K));
+    int rc = ssnet_pack_weights_conv(ctx, d_w, Co, (int)K, pw);
+    if (rc) return rc;
+    return ssnet_conv_mod_packed(ctx, d_x, pw, B, C, H, W, Co, kh, kw, stride, pad, d_y);
+}
+
+int ssnet_degree_reduce(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id, uint64_t *d_out)
+{
+    if (!ctx || !d_c || !d_out || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
+    const int t = ctx->t, k = t + 1, nr = 2 * t + 1, n = ctx->n;
+    const size_t need = ((size_t)nr * k + (size_t)k * n) * count * 8;
+    if (!ctx->ws || ctx->ws_bytes < need) return SSNET_EWORKSPACE;
+    ss_dr_params dp = {};
+    dp.n = n;
+    dp.t = t;
+    for (int i = 0; i < nr; i++)
+        for (int j = 1; j <= t; j++)
+            dp.reshare_key[i][j - 1] = ss_key(ctx->seed, SSNET_DOM_RESHARE, stream_id, (u64)(i + 1), (u64)j);
+    for (int j = 1; j <= t; j++) dp.zero_key[j - 1] = ss_key(ctx->seed, SSNET_DOM_ZERO, stream_id, 0, (u64)j);
+    for (int i = 0; i < nr; i++)
+        for (int j = 0; j < k; j++) dp.binv[i][j] = ctx->binv[i][j];
+    for (int q = 0; q < k; q++) dp.lambda[q] = ctx->lambda_k[q];
+    u64 *msg1 = (u64 *)ctx->ws, *msg2 = msg1 + (size_t)nr * k * count;
+    hipError_t e = ss_launch_degree_reduce(d_c, msg1, msg2, d_out, count, dp, ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+int ssnet_truncate(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, uint64_t stream_id, uint64_t *d_out)
+{
+    if (!ctx || !d_x || !d_out || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
+    const int t = ctx->t, k = t + 1, n = ctx->n;
+    const size_t need = ((size_t)k + n) * count * 8;
+    if (!ctx->ws || ctx->ws_bytes < need) return SSNET_EWORKSPACE;
+    ss_tr_params tp = {};
+    tp.n = n;
+    tp.t = t;
+    tp.f = ctx->f;
+    tp.e_key = ss_key(ctx->seed, SSNET_DOM_MASK_E, stream_id, 0, 0);
+    for (int j = 1; j <= t; j++) {
+        tp.alpha_key[j - 1] = ss_key(ctx->seed, SSNET_DOM_MASK_ALPHA, stream_id, 0, (u64)j);
+        tp.alphat_key[j - 1] = ss_key(ctx->seed, SSNET_DOM_MASK_ALPHAT, stream_id, 0, (u64)j);
+        tp.gen_key[j - 1] = ss_key(ctx->seed, SSNET_DOM_TRUNC_GEN, stream_id, 0, (u64)j);
+    }
+    for (int q = 0; q < k; q++) tp.lambda[q] = ctx->lambda_k[q];
+    u64 *u = (u64 *)ctx->ws, *wsh = u + (size_t)k * count;
+    hipError_t e = ss_launch_truncate(d_x, u, wsh, d_out, count, tp, ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+uint64_t ssnet_rng_key(uint64_t seed, uint64_t domain, uint64_t stream_id, uint64_t party, uint64_t j)
+{
+    return ss_key(seed, domain, stream_id, party, j);
+}
+
+uint64_t ssnet_rng_draw(uint64_t key, uint64_t e) { return ss_draw(key, e); }
+
+uint64_t ssnet_rng_field(uint64_t key, uint64_t e) { return ss_draw_field(key, e); }
+
+int ssnet_host_lagrange(const ssnet_ctx *ctx, const int *party_ids, int m, uint64_t *out)
+{
+    if (!ctx || !party_ids || !out || m < 1 || m > ctx->n) return SSNET_EINVAL;
+    for (int i = 0; i < m; i++) {
+        if (party_ids[i] < 1 || party_ids[i] > ctx->n) return SSNET_EID;
+        for (int j = 0; j < i; j++)
+            if (party_ids[j] == party_ids[i]) return SSNET_EID;
+    }
+    h_lagrange(party_ids, m, out);
+    return SSNET_OK;
+}
+
+int ssnet_host_reduction_matrix(const ssnet_ctx *ctx, uint64_t *out)
+{
+    if (!ctx || !out) return SSNET_EINVAL;
+    const int k = ctx->t + 1, nr = 2 * ctx->t + 1;
+    for (int i = 0; i < nr; i++)
+        for (int m = 0; m < ctx->n; m++) {
+            u64 acc = 0;
+            for (int j = k - 1; j >= 0; j--) acc = ss_add(ss_mul(acc, (u64)(m + 1)), ctx->binv[i][j]);
+            out[i * ctx->n + m] = acc;
+        }
+    return SSNET_OK;
+}
+
+const char *ssnet_strerror(int code)
+{
+    switch (code) {
+        case SSNET_OK: return "ok";
+        case SSNET_EINVAL: return "invalid argument";
+        case SSNET_EPRIME: return "unsupported prime (only 2^61-1)";
+        case SSNET_ESHARES: return "too few shares for this degree";
+        case SSNET_EID: return "party id out of range or repeated";
+        case SSNET_EWORKSPACE: return "workspace missing or too small";
+        case SSNET_EHIP: return "HIP error";
+        default: return "unknown error";
+    }
+}
+
+int ssnet_last_hip_error(const ssnet_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
+
+}  // extern "C"

@@ -1,0 +1,222 @@
+"""GPU-vs-oracle parity, element by element and bit-exact, through the C ABI.
+Sizes span several workgroup tiles plus ragged tails; the oracle finishes each
+case in well under a second."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+from paper_2406_02629_amd import SSNet, SSNetError, binding
+from util import P61, field_uniform, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+SCHEMES = [(3, 1), (5, 2), (7, 3), (5, 1), (8, 2)]
+COUNTS = [1, 2, 7, 255, 256, 513, 1000, 4099, 65538]
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+@pytest.mark.parametrize("n,t", SCHEMES)
+def test_share_parity(n, t):
+    s = SSNet(n, t, seed=1234)
+    for count in COUNTS:
+        for degree in (t, 2 * t, 0):
+            if degree > n - 1:
+                continue
+            say("share", n, t, count, degree)
+            secret = field_uniform(count, seed=count + degree)
+            got = to_np(s.share(to_dev(secret), stream_id=count, degree=degree))
+            want = orc.share(secret, n, degree, P61, 1234, count)
+            assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("n,t", SCHEMES)
+def test_reconstruct_parity(n, t):
+    s = SSNet(n, t, seed=5)
+    for count in (1, 513, 4099, 65538):
+        shares = field_uniform((n, count), seed=count)
+        d = to_dev(shares)
+        subsets = list(itertools.combinations(range(1, n + 1), t + 1))[:6] + [tuple(range(1, 2 * t + 2)),
+                                                                            tuple(range(n, n - t - 1, -1))]
+        for ids in subsets:
+            say("reconstruct", n, t, count, ids)
+            deg = t if len(ids) == t + 1 else 2 * t
+            got = to_np(s.reconstruct(d, list(ids), degree=deg))
+            assert np.array_equal(got, orc.reconstruct(shares, list(ids), P61))
+
+
+@pytest.mark.parametrize("n,t", SCHEMES)
+def test_share_then_reconstruct_roundtrip(n, t):
+    s = SSNet(n, t, seed=77)
+    secret = field_uniform(10001, seed=3)
+    sh = s.share(to_dev(secret), stream_id=9)
+    for ids in ([1 + i for i in range(t + 1)], [n - i for i in range(t + 1)]):
+        assert np.array_equal(to_np(s.reconstruct(sh, ids)), secret)
+
+
+@pytest.mark.parametrize("n,t", SCHEMES)
+def test_degree_reduce_parity_with_messages(n, t):
+    s = SSNet(n, t, seed=42)
+    k, nr = t + 1, 2 * t + 1
+    for count in (1, 2, 513, 1000, 4099, 65538):
+        say("degree_reduce", n, t, count)
+        c = field_uniform((n, count), seed=count + 1)
+        got = to_np(s.degree_reduce(to_dev(c), stream_id=count))
+        want, msg1, msg2, red = orc.degree_reduce(c, n, t, P61, 42, count, full=True)
+        ws = to_np(s._ws[: (nr * k + k * n) * count * 8].view(torch.int64))
+        assert np.array_equal(ws[: nr * k * count].reshape(nr, k, count), msg1)
+        assert np.array_equal(ws[nr * k * count:].reshape(k, n, count), msg2)
+        assert np.array_equal(got, want)
+
+
+def test_degree_reduce_in_place_and_on_real_products():
+    n, t = 5, 2
+    s = SSNet(n, t, seed=8)
+    a, b = field_uniform(3000, 1), field_uniform(3000, 2)
+    sa, sb = orc.share(a, n, t, P61, 8, 0), orc.share(b, n, t, P61, 8, 1)
+    prod = np.array([[int(x) * int(y) % P61 for x, y in zip(ra, rb)] for ra, rb in zip(sa, sb)], np.uint64)
+    d = to_dev(prod)
+    out = s.degree_reduce(d, stream_id=5, out=d)                     # aliasing allowed
+    want = orc.degree_reduce(prod, n, t, P61, 8, 5)
+    assert np.array_equal(to_np(out), want)
+    ab = np.array([int(x) * int(y) % P61 for x, y in zip(a, b)], np.uint64)
+    assert np.array_equal(to_np(s.reconstruct(out, [2, 4, 5])), ab)
+
+
+@pytest.mark.parametrize("n,t,f", [(3, 1, 13), (5, 2, 13), (7, 3, 8), (5, 1, 16), (3, 1, 1), (3, 1, 31)])
+def test_truncate_parity(n, t, f):
+    s = SSNet(n, t, f=f, seed=99)
+    for count in (1, 2, 513, 4099, 65538):
+        say("truncate", n, t, f, count)
+        rng = np.random.default_rng(count)
+        xs = rng.integers(-(1 << 58), 1 << 58, count, dtype=np.int64)
+        xs[: min(count, 6)] = [0, -1, 1, (1 << f) - 1, -(1 << f), -(1 << f) - 1][: min(count, 6)]
+        secret = np.where(xs < 0, xs + P61, xs).astype(np.uint64)
+        xsh = orc.share(secret, n, t, P61, 99, 1)
+        got = to_np(s.truncate(to_dev(xsh), stream_id=count))
+        want, u, wsh = orc.truncate(xsh, n, t, f, P61, 99, count, full=True)
+        ws = to_np(s._ws[: (t + 1 + n) * count * 8].view(torch.int64))
+        assert np.array_equal(ws[: (t + 1) * count].reshape(t + 1, count), u)
+        assert np.array_equal(ws[(t + 1) * count:].reshape(n, count), wsh)
+        assert np.array_equal(got, want)
+        rec = to_np(s.reconstruct(to_dev(got), list(range(1, t + 2))))
+        assert np.array_equal(orc.lift(rec, P61), xs >> f)
+
+
+LINEAR_SHAPES = [(1, 1, 1), (3, 5, 7), (16, 64, 16), (17, 65, 33), (32, 128, 32), (33, 129, 31), (64, 256, 128),
+                 (100, 300, 70), (1, 2048, 100), (49, 700, 80)]
+
+
+@pytest.mark.parametrize("n,t", [(3, 1), (5, 2)])
+def test_linear_parity(n, t):
+    s = SSNet(n, t, seed=1)
+    for M, K, N in LINEAR_SHAPES:
+        say("linear", n, M, K, N)
+        x = field_uniform((n, M, K), seed=M * 7 + K)
+        w = field_uniform((n, K, N), seed=N * 3 + K)
+        got = to_np(s.linear_mod(to_dev(x), to_dev(w)))
+        assert np.array_equal(got, orc.linear(x, w, P61))
+
+
+def test_linear_extreme_operands():
+    # all digits at their extremes: p-1 everywhere, and the values whose balanced
+    # digits are all -128 / all +127, at the longest contraction the int32
+    # accumulators are sized for
+    n, t = 3, 1
+    s = SSNet(n, t, seed=1)
+    all_neg = 0x007F7F7F7F7F7F80        # digits: seven times -128, then +1
+    all_pos = 0x1F7F7F7F7F7F7F7F        # digits: seven times +127, then +31
+    for K in (64, 4608, 16383):
+        for xv, wv in ((P61 - 1, P61 - 1), (all_neg, all_neg), (all_pos, all_pos), (all_neg, all_pos)):
+            say("linear extreme", K, hex(xv), hex(wv))
+            x = np.full((n, 2, K), xv, np.uint64)
+            w = np.full((n, K, 3), wv, np.uint64)
+            got = to_np(s.linear_mod(to_dev(x), to_dev(w)))
+            assert np.all(got == np.uint64(K * xv * wv % P61))
+
+
+def test_linear_packed_weights_identical():
+    n, t = 5, 2
+    s = SSNet(n, t, seed=1)
+    M, K, N = 37, 190, 45
+    x, w = field_uniform((n, M, K), 5), field_uniform((n, K, N), 6)
+    wd = to_dev(w)
+    packed = s.pack_weights_linear(wd)
+    a = to_np(s.linear_mod_packed(to_dev(x), packed, N))
+    assert np.array_equal(a, orc.linear(x, w, P61))
+    assert np.array_equal(a, to_np(s.linear_mod(to_dev(x), wd)))
+
+
+CONV_CASES = [  # B, C, H, W, Co, k, stride, pad
+    (1, 3, 8, 8, 4, 3, 1, 1), (2, 5, 9, 7, 6, 3, 2, 1), (1, 16, 14, 14, 32, 1, 1, 0), (1, 8, 15, 15, 8, 1, 2, 0),
+    (1, 3, 20, 20, 16, 7, 2, 3), (3, 4, 6, 6, 40, 3, 1, 1), (1, 70, 5, 5, 33, 3, 1, 1), (2, 2, 4, 4, 2, 4, 1, 0),
+    (1, 64, 14, 14, 64, 3, 1, 1)]
+
+
+@pytest.mark.parametrize("n,t", [(3, 1), (5, 2)])
+def test_conv_parity(n, t):
+    s = SSNet(n, t, seed=1)
+    for (B, Ci, H, W, Co, k, stride, pad) in CONV_CASES:
+        say("conv", n, B, Ci, H, W, Co, k, stride, pad)
+        x = field_uniform((n, B, Ci, H, W), seed=H + Ci)
+        w = field_uniform((n, Co, Ci, k, k), seed=Co + k)
+        got = to_np(s.conv_mod(to_dev(x), to_dev(w), stride, pad))
+        want = orc.conv(x, w, stride, pad, P61)
+        assert got.shape == want.shape
+        assert np.array_equal(got, want)
+        packed = s.pack_weights_conv(to_dev(w))
+        got2 = to_np(s.conv_mod_packed(to_dev(x), packed, Co, k, k, stride, pad))
+        assert np.array_equal(got2, want)
+
+
+def test_config1_tiny_secure_gemm_end_to_end():
+    """n=3, t=1, f=13, X 64x256 ~ N(0,1), W 256x128 ~ N(0,1): share, multiply,
+    reduce, truncate, reconstruct, decode."""
+    from paper_2406_02629_amd import fixedpoint as fx
+    from ssnet_inputs import gaussian
+    n, t, f, seed = 3, 1, 13, 2024
+    X, Wt = gaussian((64, 256), 1), gaussian((256, 128), 2)
+    s = SSNet(n, t, f=f, seed=seed)
+    xe = fx.encode(torch.from_numpy(X).cuda(), f)
+    we = fx.encode(torch.from_numpy(Wt).cuda(), f)
+    assert np.array_equal(to_np(xe), orc.encode(X, f, P61)) and np.array_equal(to_np(we), orc.encode(Wt, f, P61))
+    xs, ws = s.share(xe, stream_id=1), s.share(we, stream_id=2)
+    y2 = s.linear_mod(xs, ws)
+    yr = s.degree_reduce(y2.view(n, -1), stream_id=3)
+    yt = s.truncate(yr, stream_id=4)
+    rec = s.reconstruct(yt, [1, 2]).view(64, 128)
+    # oracle pipeline on the same seeds
+    oxs, ows = orc.share(orc.encode(X, f, P61), n, t, P61, seed, 1), orc.share(orc.encode(Wt, f, P61), n, t, P61, seed, 2)
+    assert np.array_equal(to_np(xs), oxs) and np.array_equal(to_np(ws), ows)
+    oy2 = orc.linear(oxs, ows, P61)
+    assert np.array_equal(to_np(y2), oy2)
+    oyr = orc.degree_reduce(oy2.reshape(n, -1), n, t, P61, seed, 3)
+    assert np.array_equal(to_np(yr), oyr)
+    oyt = orc.truncate(oyr, n, t, f, P61, seed, 4)
+    assert np.array_equal(to_np(yt), oyt)
+    orec = orc.reconstruct(oyt, [1, 2], P61)
+    assert np.array_equal(to_np(rec).reshape(-1), orec)
+    # every pair of parties agrees
+    for ids in ([2, 3], [1, 3]):
+        assert torch.equal(s.reconstruct(yt, ids).view(64, 128), rec)
+    dec = fx.decode(rec, f).cpu().numpy()
+    exact = orc.decode(orc.encode(X, f, P61), f, P61) @ orc.decode(orc.encode(Wt, f, P61), f, P61)
+    err = exact - dec
+    assert err.min() >= 0 and err.max() < 2.0 ** -f                  # floor truncation of exact product
+    assert np.max(np.abs(dec - X @ Wt)) < 2.0 ** -8                  # vs float64 plaintext
+
+
+def test_errors_surface_as_codes_not_crashes():
+    s = SSNet(3, 1, seed=1)
+    x = to_dev(field_uniform((3, 16), 1))
+    with pytest.raises(SSNetError) as ei:
+        s.reconstruct(x, [1], degree=1)
+    assert ei.value.code == binding.ESHARES
+    with pytest.raises(SSNetError) as ei:
+        s.reconstruct(x, [1, 4], degree=1)
+    assert ei.value.code == binding.EID

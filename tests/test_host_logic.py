@@ -1,0 +1,105 @@
+"""CPU-only checks of the GPU library: it loads, exports the whole C ABI, and
+its host-side logic (tables, generator, argument checks) is right.  No kernel
+is launched here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle as orc
+from paper_2406_02629_amd import SSNet, SSNetError, binding
+
+P61 = (1 << 61) - 1
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "ssnet.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(ssnet_[a-z0-9_]+)\s*\(", header))
+    assert len(declared) >= 20
+    lib = binding.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(binding.SIGNATURES), declared ^ set(binding.SIGNATURES)
+
+
+def test_create_rejects_bad_parameters():
+    for args, code in [((3, 1, 11, 13, 0), binding.EPRIME), ((2, 1, P61, 13, 0), binding.EINVAL),
+                       ((4, 2, P61, 13, 0), binding.EINVAL), ((9, 1, P61, 13, 0), binding.EINVAL),
+                       ((3, 0, P61, 13, 0), binding.EINVAL), ((3, 1, P61, 0, 0), binding.EINVAL),
+                       ((3, 1, P61, 32, 0), binding.EINVAL), ((9, 4, P61, 13, 0), binding.EINVAL)]:
+        n, t, p, f, seed = args
+        with pytest.raises(SSNetError) as ei:
+            SSNet(n, t, f=f, seed=seed, p=p, device=None)
+        assert ei.value.code == code, args
+    assert binding.load_library().ssnet_create(None, 3, 1, P61, 13, 0, None) == binding.EINVAL
+
+
+def test_null_and_range_checks_before_any_launch():
+    s = SSNet(5, 2, device=None)
+    lib, ctx = s.lib, s._ctx
+    ids = (C.c_int * 3)(1, 2, 3)
+    assert lib.ssnet_share(ctx, None, 8, 2, 0, None) == binding.EINVAL
+    assert lib.ssnet_share(ctx, 16, 0, 2, 0, 16) == binding.EINVAL
+    assert lib.ssnet_share(ctx, 16, 8, 5, 0, 16) == binding.EINVAL            # degree > 2t
+    assert lib.ssnet_reconstruct(ctx, 16, 8, ids, 3, 4, 16) == binding.ESHARES   # 3 shares, degree 4
+    assert lib.ssnet_reconstruct(ctx, 16, 8, (C.c_int * 3)(1, 2, 6), 3, 2, 16) == binding.EID
+    assert lib.ssnet_reconstruct(ctx, 16, 8, (C.c_int * 3)(1, 2, 2), 3, 2, 16) == binding.EID
+    assert lib.ssnet_reconstruct(ctx, 16, 8, (C.c_int * 3)(0, 1, 2), 3, 2, 16) == binding.EID
+    assert lib.ssnet_degree_reduce(ctx, 16, 8, 0, 16) == binding.EWORKSPACE
+    assert lib.ssnet_truncate(ctx, 16, 8, 0, 16) == binding.EWORKSPACE
+    assert lib.ssnet_linear_mod(ctx, 16, 16, 4, 4, 4, 16) == binding.EWORKSPACE
+    assert lib.ssnet_linear_mod(ctx, 16, 16, 4, 16384, 4, 16) == binding.EINVAL   # K too long for int32
+    assert lib.ssnet_linear_mod(ctx, 16, 16, 0, 4, 4, 16) == binding.EINVAL
+    assert lib.ssnet_conv_mod(ctx, 16, 16, 1, 3, 4, 4, 2, 5, 5, 1, 0, 16) == binding.EINVAL  # kernel > input
+    assert lib.ssnet_conv_mod(ctx, 16, 16, 1, 3, 8, 8, 2, 3, 3, 1, 1, 16) == binding.EWORKSPACE
+    assert lib.ssnet_set_workspace(ctx, 8, 64) == binding.EINVAL                   # misaligned
+    assert lib.ssnet_strerror(binding.ESHARES) == b"too few shares for this degree"
+
+
+def test_workspace_sizes():
+    s = SSNet(5, 2, device=None)
+    # RED messages: [2t+1][k][count] + [k][n][count] field elements
+    assert s.workspace_bytes_stream(1000) >= (5 * 3 + 3 * 5) * 1000 * 8
+    s3 = SSNet(3, 1, device=None)
+    assert s3.workspace_bytes_stream(1 << 20) == (3 * 2 + 2 * 3) * 8 << 20
+    # limb tiles: 8 bytes per element, rows padded to 16 and K to 64
+    assert s3.lib.ssnet_packed_weight_bytes(16, 64) == 8192
+    assert s3.lib.ssnet_packed_weight_bytes(17, 65) == 4 * 8192
+    assert s3.workspace_bytes_linear(64, 256, 128) == 3 * (64 * 256 * 8 + 128 * 256 * 8)
+
+
+@pytest.mark.parametrize("n,t", [(3, 1), (5, 2), (7, 3), (5, 1), (8, 3)])
+def test_host_tables_match_oracle(n, t):
+    s = SSNet(n, t, device=None)
+    assert s.host_reduction_matrix() == [[int(v) for v in r] for r in orc.red_matrix(n, t, P61)]
+    import itertools
+    for m in (t + 1, 2 * t + 1):
+        for ids in list(itertools.combinations(range(1, n + 1), m))[:12]:
+            assert s.host_lagrange(ids) == [int(v) for v in orc.lagrange(list(ids), P61)]
+    perm = list(range(n, 0, -1))[: t + 1]
+    assert s.host_lagrange(perm) == [int(v) for v in orc.lagrange(perm, P61)]
+
+
+def test_generator_matches_golden_vectors():
+    path = os.path.join(ROOT, "tests", "golden", "rng_vectors.txt")
+    nkeys = ndraws = 0
+    for line in open(path):
+        parts = line.split()
+        if not parts or parts[0].startswith("#"):
+            continue
+        if parts[0] == "key":
+            vals = [int(v) for v in parts[1:]]
+            assert binding.rng_key(*vals[:5]) == vals[5]
+            nkeys += 1
+        elif parts[0] == "draw":
+            key, e, out, fld = (int(v) for v in parts[1:])
+            assert binding.rng_draw(key, e) == out
+            assert binding.rng_field(key, e) == fld
+            ndraws += 1
+    assert nkeys == 8 and ndraws == 32
+    want = [int(l, 16) for l in open(os.path.join(ROOT, "tests", "golden", "splitmix64.txt")) if l.startswith("0x")]
+    assert [binding.rng_draw(0, e) for e in range(3)] == want
