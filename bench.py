@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Benchmark of the Shamir-share hot path on one MI355X.
+
+A step is one pass of the share arithmetic of the ResNet-152-shaped linear
+stack (n=5, t=2, p=2^61-1, f=13, batch 1): for each of the 152 layers
+    GEN of the layer input -> conv/dense on shares (int8-limb MFMA) ->
+    degree reduction + re-randomisation -> truncation -> REC,
+on inputs already resident in HBM (each layer's plaintext input was produced
+by an untimed pass that applied ReLU/pooling between layers).  Weight shares
+and their limb tiles are prepared once, before timing.
+
+Prints ONE JSON line: throughput in field multiply-accumulates per second over
+all parties, the roofline of the dominant kernel (the MFMA GEMM), the bulk
+share/reconstruct roofline (2^28 elements, HBM-bound) and the CPU oracle timed
+on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "mod-p GEMM field-MAC/s over all parties + ResNet-152 linear-stack latency, n=5"
+INT8_PEAK_TOPS = 5000.0      # MI355X dense int8, published
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+OPS_PER_FIELD_MAC = 128      # 8 x 8 int8 limb products, multiply + add
+
+
+def event_ms(fn, stream, reps=1):
+    import torch
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(stream)
+    for _ in range(reps):
+        fn()
+    b.record(stream)
+    b.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def bulk_share_reconstruct(log2_count, reps):
+    """configs[1]: n=5, t=2, 2^28 uniform field elements: GEN, then REC from
+    parties {1,2,3} and from {3,4,5}.  Returns per-kernel ms and GB/s on the
+    algorithmic bytes (share: 1 read + n writes; reconstruct: m reads + 1 write)."""
+    import torch
+    from paper_2406_02629_amd import SSNet
+    from ssnet_inputs import P61, uniform_below
+    n, t, count = 5, 2, 1 << log2_count
+    ss = SSNet(n, t, f=13, seed=2)
+    stream = torch.cuda.current_stream()
+    secret = torch.from_numpy(uniform_below(count, P61, 2).view("int64")).cuda()
+    shares = torch.empty((n, count), dtype=torch.int64, device="cuda")
+    rec = torch.empty(count, dtype=torch.int64, device="cuda")
+    ss.share(secret, stream_id=0, out=shares)
+    ss.reconstruct(shares, [1, 2, 3], out=rec)
+    torch.cuda.synchronize()
+    ok = bool(torch.equal(rec, secret))
+    ss.reconstruct(shares, [3, 4, 5], out=rec)
+    ok = ok and bool(torch.equal(rec, secret))
+    t_share = event_ms(lambda: ss.share(secret, stream_id=0, out=shares), stream, reps)
+    t_r1 = event_ms(lambda: ss.reconstruct(shares, [1, 2, 3], out=rec), stream, reps)
+    t_r2 = event_ms(lambda: ss.reconstruct(shares, [3, 4, 5], out=rec), stream, reps)
+    b_share, b_rec = (1 + n) * 8 * count, (3 + 1) * 8 * count
+    total_ms = t_share + t_r1 + t_r2
+    out = {
+        "workload": f"bulk share/reconstruct n=5 t=2 2^{log2_count} elements (configs[1])",
+        "roundtrip_ok": ok,
+        "share": {"ms": t_share, "GB/s": b_share / t_share / 1e6},
+        "reconstruct_123": {"ms": t_r1, "GB/s": b_rec / t_r1 / 1e6},
+        "reconstruct_345": {"ms": t_r2, "GB/s": b_rec / t_r2 / 1e6},
+        "bound": "hbm", "achieved": (b_share + 2 * b_rec) / total_ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+    }
+    out["frac"] = out["achieved"] / HBM_PEAK_GBS
+    del secret, shares, rec
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline(nlayers):
+    """The CPU oracle, as it stands, on the first `nlayers` layers of the same
+    stack with uniform random shares as operands: GEN, conv, RED+RERAND,
+    truncation, REC per layer.  Returns field-MAC/s over that sample."""
+    import numpy as np
+    import oracle as orc
+    from ssnet_inputs import P61, resnet_chain, uniform_below
+    n, t, f = 5, 2, 13
+    layers = resnet_chain(152)[:nlayers]
+    macs, secs = 0, 0.0
+    for l, L in enumerate(layers):
+        x = uniform_below(L.cin * L.hin * L.hin, 1 << 20, 10 + l).reshape(1, L.cin, L.hin, L.hin)
+        w = uniform_below(n * L.cout * L.K, P61, 50 + l).reshape(n, L.cout, L.cin, L.ksize, L.ksize)
+        t0 = time.perf_counter()
+        xs = orc.share(x, n, t, P61, 1, l)
+        y = orc.conv(xs, w, L.stride, L.pad, P61)
+        yr = orc.degree_reduce(y.reshape(n, -1), n, t, P61, 1, l)
+        yt = orc.truncate(yr, n, t, f, P61, 1, l)
+        orc.reconstruct(yt, [1, 2, 3], P61)
+        secs += time.perf_counter() - t0
+        macs += n * L.macs
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": macs / secs, "unit": "field-MAC/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {nlayers} of 152 layers, all five steps per layer, {macs / 1e9:.2f} G field-MAC "
+                      f"in {secs:.1f} s (conv loop uses all cores via OpenMP, the element-wise steps one core)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--depth", type=int, default=152, help="ResNet depth of the stack (152 is the benchmark)")
+    ap.add_argument("--bulk-log2", type=int, default=28)
+    ap.add_argument("--no-bulk", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=11)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (all parties are a batch dimension on it); "
+                 "use --gpus 1")
+
+    import torch
+    from paper_2406_02629_amd import SSNet
+    from paper_2406_02629_amd.chain import Chain
+    from ssnet_inputs import resnet_chain
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+
+    n, t, f = 5, 2, 13
+    ss = SSNet(n, t, f=f, seed=20240602)
+    chain = Chain(ss, resnet_chain(args.depth))
+    chain.forward_prepare()
+    torch.cuda.synchronize()
+    for _ in range(args.warmup):
+        chain.forward_timed()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        chain.forward_timed()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    macs = chain.total_field_macs()
+
+    # live per-class kernel time over one more pass (HIP events on the library's stream)
+    ss.profile_begin()
+    chain.forward_timed()
+    prof = ss.profile_end()
+    gemm_ms, gemm_launches = prof["gemm"]
+    achieved = macs * OPS_PER_FIELD_MAC / (gemm_ms * 1e-3) / 1e12
+    breakdown = {k: {"ms": round(v[0], 4), "spans": int(v[1])} for k, v in prof.items() if v[1]}
+
+    out_elems = sum(L.cout * L.M for L in chain.layers)
+    dr_bytes = n * ((1 + ss.k) + 2 * ss.k + (ss.k + 1)) * 8 * out_elems      # three passes, messages once each way
+    tr_bytes = (3 * ss.k + 3 * n) * 8 * out_elems
+    result = {
+        "metric": METRIC, "value": macs / (ms_per_step * 1e-3), "unit": "field-MAC/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u64 mod 2^61-1 (int8 limbs, int32 MFMA accumulate)",
+        "data": "synthetic",
+        "config": {"workload": f"resnet{args.depth}-shaped linear stack, n=5 t=2 f=13 batch 1 (configs[4])",
+                   "layers": len(chain.layers), "field_macs_per_step": macs,
+                   "steps_in_timed_region": "share, conv/dense, degree_reduce+rerand, truncate, reconstruct"},
+        "roofline": {"bound": "mfma", "kernel": "gemm_limb_kernel", "achieved": achieved, "peak": INT8_PEAK_TOPS,
+                     "unit": "TOP/s", "frac": achieved / INT8_PEAK_TOPS, "traffic": None,
+                     "launches": int(gemm_launches), "avg_launch_us": gemm_ms * 1e3 / max(gemm_launches, 1),
+                     "int8_ops_per_step": macs * OPS_PER_FIELD_MAC},
+        "kernel_ms_per_step": breakdown,
+        "stream_GBps_in_chain": {
+            "degree_reduce": dr_bytes / (prof["degree_reduce"][0] * 1e-3) / 1e9,
+            "truncate": tr_bytes / (prof["truncate"][0] * 1e-3) / 1e9},
+    }
+    if not args.no_bulk:
+        result["roofline_hbm"] = bulk_share_reconstruct(args.bulk_log2, reps=5)
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(args.cpu_layers)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

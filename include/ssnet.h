@@ -155,6 +155,24 @@ uint64_t ssnet_rng_field(uint64_t key, uint64_t e);
 int ssnet_host_lagrange(const ssnet_ctx *ctx, const int *party_ids, int m, uint64_t *out);
 int ssnet_host_reduction_matrix(const ssnet_ctx *ctx, uint64_t *out);
 
+/* Live kernel timing.  Between ssnet_profile_begin and ssnet_profile_end every
+ * entry point brackets the kernels of each class below with a pair of HIP
+ * events recorded on the context's stream.  ssnet_profile_end waits for those
+ * events and writes, per class, the summed elapsed milliseconds and the number
+ * of bracketed spans into two HOST arrays of SSNET_PROF_CLASSES entries.  A
+ * span is one kernel, except DEGREE_REDUCE and TRUNCATE (three kernels each).
+ * Not for use under stream capture. */
+#define SSNET_PROF_SHARE 0
+#define SSNET_PROF_RECONSTRUCT 1
+#define SSNET_PROF_PACK_W 2
+#define SSNET_PROF_PACK_X 3
+#define SSNET_PROF_GEMM 4
+#define SSNET_PROF_DEGREE_REDUCE 5
+#define SSNET_PROF_TRUNCATE 6
+#define SSNET_PROF_CLASSES 7
+int ssnet_profile_begin(ssnet_ctx *ctx);
+int ssnet_profile_end(ssnet_ctx *ctx, double *ms_by_class, uint64_t *spans_by_class);
+
 const char *ssnet_strerror(int code);
 int ssnet_last_hip_error(const ssnet_ctx *ctx); /* hipError_t of the last failed HIP call, 0 if none */
 

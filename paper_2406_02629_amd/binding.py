@@ -45,6 +45,8 @@ SIGNATURES = {
     "ssnet_rng_field": (_u64, [_u64, _u64]),
     "ssnet_host_lagrange": (_int, [_ptr, C.POINTER(_int), _int, C.POINTER(_u64)]),
     "ssnet_host_reduction_matrix": (_int, [_ptr, C.POINTER(_u64)]),
+    "ssnet_profile_begin": (_int, [_ptr]),
+    "ssnet_profile_end": (_int, [_ptr, C.POINTER(C.c_double), C.POINTER(_u64)]),
     "ssnet_strerror": (C.c_char_p, [_int]),
     "ssnet_last_hip_error": (_int, [_ptr]),
 }
@@ -248,6 +250,19 @@ class SSNet:
             out = torch.empty_like(x)
         self._ok(self.lib.ssnet_truncate(self._ctx, _dptr(x), count, stream_id, _dptr(out)), "ssnet_truncate")
         return out
+
+    # ---- live kernel timing ----
+    PROF_CLASSES = ("share", "reconstruct", "pack_w", "pack_x", "gemm", "degree_reduce", "truncate")
+
+    def profile_begin(self):
+        self._ok(self.lib.ssnet_profile_begin(self._ctx), "ssnet_profile_begin")
+
+    def profile_end(self):
+        """-> {class: (total_ms, spans)} for the calls since profile_begin"""
+        ms = (C.c_double * len(self.PROF_CLASSES))()
+        cnt = (_u64 * len(self.PROF_CLASSES))()
+        self._ok(self.lib.ssnet_profile_end(self._ctx, ms, cnt), "ssnet_profile_end")
+        return {name: (ms[i], cnt[i]) for i, name in enumerate(self.PROF_CLASSES)}
 
     # ---- host-side tables (no GPU needed) ----
     def host_lagrange(self, ids: Sequence[int]):

@@ -1,0 +1,124 @@
+"""Harness for a sequential stack of linear layers evaluated on Shamir shares.
+
+Per layer, on the GPU library (Sec. VI, order Linear -> Truncation):
+    share the layer input (GEN) -> conv / dense on shares -> degree reduction
+    with re-randomisation -> truncation by 2^f -> reconstruct (REC).
+Between layers the harness applies the plaintext steps (ReLU, pooling) to the
+reconstructed integers and hands the result to the next layer; that part is
+outside the share arithmetic and outside any timed region.  Weight shares and
+their int8 limb tiles are prepared once (offline preprocessing of the model).
+"""
+from __future__ import annotations
+
+from typing import List, Optional
+
+import torch
+
+from ssnet_inputs import Layer, gaussian, he_normal
+
+from . import fixedpoint as fx
+from .binding import SSNet
+
+WEIGHT_STREAM_BASE = 1 << 20      # stream ids of the weight sharings, apart from the per-layer ones
+
+
+def post_plain(y: torch.Tensor, post: Optional[str]) -> torch.Tensor:
+    """Plaintext step after a layer, on signed integers [B, C, H, W] (int64)."""
+    if post is None:
+        return y
+    y = torch.clamp(y, min=0)
+    if post == "relu":
+        return y
+    if post == "relu+maxpool3s2":
+        # values are below 2^53, so the float64 detour is exact
+        z = torch.nn.functional.max_pool2d(y.to(torch.float64), kernel_size=3, stride=2, padding=1)
+        return z.to(torch.int64)
+    if post == "relu+gap":
+        hw = y.shape[-1] * y.shape[-2]
+        return torch.div(y.sum(dim=(-1, -2), keepdim=True), hw, rounding_mode="floor")
+    raise ValueError(post)
+
+
+class Chain:
+    def __init__(self, ss: SSNet, layers: List[Layer], batch: int = 1, image_seed: int = 5,
+                 weight_seed_base: int = 100, keep_weight_shares: bool = False):
+        self.ss, self.layers, self.batch = ss, layers, batch
+        dev = ss.device
+        self.packed: List[torch.Tensor] = []
+        self.wshares: List[Optional[torch.Tensor]] = []
+        for l, L in enumerate(layers):
+            shape = (L.cout, L.cin, L.ksize, L.ksize) if L.kind == "conv" else (L.cin, L.cout)
+            w = he_normal(shape, L.K, weight_seed_base + l)
+            we = fx.encode(torch.from_numpy(w).to(dev), ss.f)
+            wsh = ss.share(we, stream_id=WEIGHT_STREAM_BASE + l)
+            self.packed.append(ss.pack_weights_conv(wsh) if L.kind == "conv" else ss.pack_weights_linear(wsh))
+            self.wshares.append(wsh if keep_weight_shares else None)
+        L0 = layers[0]
+        img = gaussian((batch, L0.cin, L0.hin, L0.hin), image_seed)
+        self.image = fx.encode(torch.from_numpy(img).to(dev), ss.f)
+        self.ids = list(range(1, ss.k + 1))
+        # per-layer buffers so that the timed loop allocates nothing
+        self.x_plain: List[Optional[torch.Tensor]] = [None] * len(layers)
+        self.x_shares = [torch.empty((ss.n,) + self._in_shape(L), dtype=torch.int64, device=dev) for L in layers]
+        self.y = [torch.empty((ss.n,) + self._out_shape(L), dtype=torch.int64, device=dev) for L in layers]
+        self.rec = [torch.empty(self._out_shape(L), dtype=torch.int64, device=dev) for L in layers]
+        need = 0
+        for L in layers:
+            count = batch * L.cout * L.M
+            need = max(need, ss.workspace_bytes_stream(count))
+            if L.kind == "conv":
+                need = max(need, ss.workspace_bytes_conv(batch, L.cin, L.hin, L.hin, L.cout, L.ksize, L.ksize,
+                                                         L.stride, L.pad))
+            else:
+                need = max(need, ss.workspace_bytes_linear(batch, L.cin, L.cout))
+        ss.reserve(need)
+
+    def _in_shape(self, L: Layer):
+        return (self.batch, L.cin, L.hin, L.hin) if L.kind == "conv" else (self.batch, L.cin)
+
+    def _out_shape(self, L: Layer):
+        return (self.batch, L.cout, L.hout, L.hout) if L.kind == "conv" else (self.batch, L.cout)
+
+    def run_layer(self, l: int, x_plain: torch.Tensor, stages: str = "sgdtr") -> torch.Tensor:
+        """All share arithmetic of layer l.  `stages` selects steps for timing
+        breakdowns: s=share, g=gemm/conv, d=degree_reduce, t=truncate, r=reconstruct."""
+        ss, L = self.ss, self.layers[l]
+        xs, y = self.x_shares[l], self.y[l]
+        if "s" in stages:
+            ss.share(x_plain, stream_id=l, out=xs)
+        if "g" in stages:
+            if L.kind == "conv":
+                ss.conv_mod_packed(xs, self.packed[l], L.cout, L.ksize, L.ksize, L.stride, L.pad, out=y)
+            else:
+                ss.linear_mod_packed(xs, self.packed[l], L.cout, out=y)
+        yv = y.view(ss.n, -1)
+        if "d" in stages:
+            ss.degree_reduce(yv, stream_id=l, out=yv)
+        if "t" in stages:
+            ss.truncate(yv, stream_id=l, out=yv)
+        if "r" in stages:
+            ss.reconstruct(y, self.ids, out=self.rec[l])
+        return self.rec[l]
+
+    def forward_prepare(self):
+        """One full pass with the plaintext steps in between; records every
+        layer's plaintext input so that timed passes can replay the share
+        arithmetic back to back.  Returns the last layer's output (field elements)."""
+        x = self.image
+        out = None
+        for l, L in enumerate(self.layers):
+            if L.kind == "fc":
+                x = x.reshape(self.batch, -1)
+            self.x_plain[l] = x.contiguous()
+            out = self.run_layer(l, self.x_plain[l])
+            if L.post is not None:
+                x = fx.from_signed(post_plain(fx.lift(out), L.post))
+        return out
+
+    def forward_timed(self, stages: str = "sgdtr"):
+        """Share arithmetic of every layer on the recorded inputs, nothing else."""
+        for l in range(len(self.layers)):
+            self.run_layer(l, self.x_plain[l], stages)
+
+    def total_field_macs(self) -> int:
+        return self.ss.n * self.batch * sum(L.macs for L in self.layers)

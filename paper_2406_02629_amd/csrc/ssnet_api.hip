@@ -5,6 +5,7 @@
 
 #include <limits.h>
 #include <new>
+#include <vector>
 
 #include "kernels.hpp"
 
@@ -17,6 +18,11 @@ struct ssnet_ctx {
     int last_hip;
     u64 binv[2 * SS_MAXT + 1][SS_MAXK];   // first k columns of the inverse Vandermonde matrix (Eq. 3)
     u64 lambda_k[SS_MAXK];                // Lagrange multipliers of IDs 1..k (Eq. 2)
+    // optional per-kernel-class timing with HIP events on the context's stream
+    bool prof;
+    struct span { hipEvent_t a, b; int cls; };
+    std::vector<span> spans;              // recorded since ssnet_profile_begin
+    std::vector<span> pool;               // events kept for reuse
 };
 
 namespace {
@@ -81,6 +87,33 @@ int fail_hip(ssnet_ctx *ctx, hipError_t e)
     return SSNET_EHIP;
 }
 
+// Brackets the launches of one kernel class with a pair of events while
+// profiling is on; costs nothing otherwise.
+struct timed {
+    ssnet_ctx *ctx;
+    ssnet_ctx::span sp;
+    bool on;
+    timed(ssnet_ctx *c, int cls) : ctx(c), on(c->prof)
+    {
+        if (!on) return;
+        if (!c->pool.empty()) {
+            sp = c->pool.back();
+            c->pool.pop_back();
+        } else if (hipEventCreate(&sp.a) != hipSuccess || hipEventCreate(&sp.b) != hipSuccess) {
+            on = false;
+            return;
+        }
+        sp.cls = cls;
+        (void)hipEventRecord(sp.a, c->stream);
+    }
+    ~timed()
+    {
+        if (!on) return;
+        (void)hipEventRecord(sp.b, ctx->stream);
+        ctx->spans.push_back(sp);
+    }
+};
+
 int conv_out(int H, int k, int stride, int pad) { return (H + 2 * pad - k) / stride + 1; }
 
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
@@ -96,6 +129,7 @@ bool gemm_shape_ok(long rows, long cols, long K)
 int run_gemm(ssnet_ctx *ctx, const void *pa, const void *pb, u64 *out, int rows, int cols, int K,
              size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb)
 {
+    timed tm(ctx, SSNET_PROF_GEMM);
     hipError_t e = ss_launch_gemm(pa, pb, out, ctx->n, rows, cols, K, out_party_stride, stride_row, cdiv, stride_cb,
                                   ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
@@ -121,6 +155,7 @@ int ssnet_create(ssnet_ctx **out, int n, int t, uint64_t p, int f, uint64_t seed
     c->ws = nullptr;
     c->ws_bytes = 0;
     c->last_hip = 0;
+    c->prof = false;
     int ids[SS_MAXK];
     for (int q = 0; q <= t; q++) ids[q] = q + 1;
     h_lagrange(ids, t + 1, c->lambda_k);
@@ -131,8 +166,48 @@ int ssnet_create(ssnet_ctx **out, int n, int t, uint64_t p, int f, uint64_t seed
 
 int ssnet_destroy(ssnet_ctx *ctx)
 {
+    if (!ctx) return SSNET_OK;
+    for (auto &v : {&ctx->spans, &ctx->pool})
+        for (auto &sp : *v) {
+            (void)hipEventDestroy(sp.a);
+            (void)hipEventDestroy(sp.b);
+        }
     delete ctx;
     return SSNET_OK;
+}
+
+int ssnet_profile_begin(ssnet_ctx *ctx)
+{
+    if (!ctx) return SSNET_EINVAL;
+    for (auto &sp : ctx->spans) ctx->pool.push_back(sp);
+    ctx->spans.clear();
+    ctx->prof = true;
+    return SSNET_OK;
+}
+
+int ssnet_profile_end(ssnet_ctx *ctx, double *ms_by_class, uint64_t *spans_by_class)
+{
+    if (!ctx || !ms_by_class || !spans_by_class) return SSNET_EINVAL;
+    ctx->prof = false;
+    for (int c = 0; c < SSNET_PROF_CLASSES; c++) {
+        ms_by_class[c] = 0.0;
+        spans_by_class[c] = 0;
+    }
+    int rc = SSNET_OK;
+    for (auto &sp : ctx->spans) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(sp.b);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, sp.a, sp.b);
+        if (e != hipSuccess) {
+            rc = fail_hip(ctx, e);
+        } else {
+            ms_by_class[sp.cls] += ms;
+            spans_by_class[sp.cls] += 1;
+        }
+        ctx->pool.push_back(sp);
+    }
+    ctx->spans.clear();
+    return rc;
 }
 
 size_t ssnet_workspace_bytes_stream(const ssnet_ctx *ctx, size_t count)
@@ -175,6 +250,7 @@ int ssnet_share(ssnet_ctx *ctx, const uint64_t *d_secret, size_t count, int degr
     if (degree < 0 || degree > 2 * ctx->t || degree > ctx->n - 1) return SSNET_EINVAL;
     ss_keys keys = {};
     for (int j = 1; j <= degree; j++) keys.k[j - 1] = ss_key(ctx->seed, SSNET_DOM_SHARE, stream_id, 0, (u64)j);
+    timed tm(ctx, SSNET_PROF_SHARE);
     hipError_t e = ss_launch_share(d_secret, d_shares, count, ctx->n, degree, keys, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
@@ -194,6 +270,7 @@ int ssnet_reconstruct(ssnet_ctx *ctx, const uint64_t *d_shares, size_t count, co
     rp.m = m;
     for (int i = 0; i < m; i++) rp.plane[i] = party_ids[i] - 1;
     h_lagrange(party_ids, m, rp.lambda);
+    timed tm(ctx, SSNET_PROF_RECONSTRUCT);
     hipError_t e = ss_launch_reconstruct(d_shares, d_secret, count, rp, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
@@ -208,6 +285,7 @@ int ssnet_pack_weights_linear(ssnet_ctx *ctx, const uint64_t *d_w, int K, int N,
 {
     if (!ctx || !d_w || !d_packed || !gemm_shape_ok(N, 1, K) || ((uintptr_t)d_packed & 15)) return SSNET_EINVAL;
     // row = output column c of w [K][N], contraction index strides by N
+    timed tm(ctx, SSNET_PROF_PACK_W);
     hipError_t e = ss_launch_pack_matrix(d_w, d_packed, ctx->n, N, K, (size_t)K * N, 1, (size_t)N, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
@@ -215,6 +293,7 @@ int ssnet_pack_weights_linear(ssnet_ctx *ctx, const uint64_t *d_w, int K, int N,
 int ssnet_pack_weights_conv(ssnet_ctx *ctx, const uint64_t *d_w, int Co, int CKK, void *d_packed)
 {
     if (!ctx || !d_w || !d_packed || !gemm_shape_ok(Co, 1, CKK) || ((uintptr_t)d_packed & 15)) return SSNET_EINVAL;
+    timed tm(ctx, SSNET_PROF_PACK_W);
     hipError_t e = ss_launch_pack_matrix(d_w, d_packed, ctx->n, Co, CKK, (size_t)Co * CKK, (size_t)CKK, 1, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
@@ -225,8 +304,11 @@ int ssnet_linear_mod_packed(ssnet_ctx *ctx, const uint64_t *d_x, const void *d_w
     if (!ctx || !d_x || !d_w_packed || !d_y || !gemm_shape_ok(M, N, K)) return SSNET_EINVAL;
     const size_t need = (size_t)ctx->n * ss_packed_bytes(M, K);
     if (!ctx->ws || ctx->ws_bytes < need) return SSNET_EWORKSPACE;
-    hipError_t e = ss_launch_pack_matrix(d_x, ctx->ws, ctx->n, M, K, (size_t)M * K, (size_t)K, 1, ctx->stream);
-    if (e != hipSuccess) return fail_hip(ctx, e);
+    {
+        timed tm(ctx, SSNET_PROF_PACK_X);
+        hipError_t e = ss_launch_pack_matrix(d_x, ctx->ws, ctx->n, M, K, (size_t)M * K, (size_t)K, 1, ctx->stream);
+        if (e != hipSuccess) return fail_hip(ctx, e);
+    }
     return run_gemm(ctx, ctx->ws, d_w_packed, d_y, M, N, K, (size_t)M * N, (size_t)N, INT_MAX, 0);
 }
 
@@ -253,8 +335,12 @@ int ssnet_conv_mod_packed(ssnet_ctx *ctx, const uint64_t *d_x, const void *d_w_p
     if (M > (1L << 30) || !gemm_shape_ok(Co, M, K)) return SSNET_EINVAL;
     const size_t need = (size_t)ctx->n * ss_packed_bytes((int)M, (int)K);
     if (!ctx->ws || ctx->ws_bytes < need) return SSNET_EWORKSPACE;
-    hipError_t e = ss_launch_pack_im2col(d_x, ctx->ws, ctx->n, B, C, H, W, kh, kw, stride, pad, Ho, Wo, ctx->stream);
-    if (e != hipSuccess) return fail_hip(ctx, e);
+    {
+        timed tm(ctx, SSNET_PROF_PACK_X);
+        hipError_t e =
+            ss_launch_pack_im2col(d_x, ctx->ws, ctx->n, B, C, H, W, kh, kw, stride, pad, Ho, Wo, ctx->stream);
+        if (e != hipSuccess) return fail_hip(ctx, e);
+    }
     const size_t HW = (size_t)Ho * Wo;
     // rows = output channel, cols = (b, ho, wo): y[b][co][hw]
     return run_gemm(ctx, d_w_packed, ctx->ws, d_y, Co, (int)M, (int)K, (size_t)B * Co * HW, HW, (int)HW, (size_t)Co * HW);
@@ -292,6 +378,7 @@ int ssnet_degree_reduce(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint6
         for (int j = 0; j < k; j++) dp.binv[i][j] = ctx->binv[i][j];
     for (int q = 0; q < k; q++) dp.lambda[q] = ctx->lambda_k[q];
     u64 *msg1 = (u64 *)ctx->ws, *msg2 = msg1 + (size_t)nr * k * count;
+    timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
     hipError_t e = ss_launch_degree_reduce(d_c, msg1, msg2, d_out, count, dp, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
@@ -314,6 +401,7 @@ int ssnet_truncate(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, uint64_t s
     }
     for (int q = 0; q < k; q++) tp.lambda[q] = ctx->lambda_k[q];
     u64 *u = (u64 *)ctx->ws, *wsh = u + (size_t)k * count;
+    timed tm(ctx, SSNET_PROF_TRUNCATE);
     hipError_t e = ss_launch_truncate(d_x, u, wsh, d_out, count, tp, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
