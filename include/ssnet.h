@@ -59,9 +59,15 @@ int ssnet_create(ssnet_ctx **out, int n, int t, uint64_t p, int f, uint64_t seed
 int ssnet_destroy(ssnet_ctx *ctx);
 
 /* Scratch memory for the inter-party messages of ssnet_degree_reduce /
- * ssnet_truncate on `count` elements, and for the int8 limb tiles of
- * ssnet_linear_mod / ssnet_conv_mod.  Sizes are in bytes; a workspace of the
- * maximum over the calls that will be made serves all of them. */
+ * ssnet_truncate on `count` elements, and for the int8 limb tiles and split
+ * partial sums of ssnet_linear_mod / ssnet_conv_mod.  Sizes are in bytes; a
+ * workspace of the maximum over the calls that will be made serves all of them.
+ * The first SSNET_WS_HEADER_BYTES of a workspace hold arrival counters that the
+ * library zeroes in ssnet_set_workspace (one small kernel on the stream) and
+ * keeps zero between calls; the messages of ssnet_degree_reduce ([2t+1][k][count]
+ * then [k][n][count]) and of ssnet_truncate ([k][count] then [n][count]) start
+ * right behind that header.  16-byte aligned. */
+#define SSNET_WS_HEADER_BYTES 65536
 size_t ssnet_workspace_bytes_stream(const ssnet_ctx *ctx, size_t count);
 size_t ssnet_workspace_bytes_linear(const ssnet_ctx *ctx, int M, int K, int N);
 size_t ssnet_workspace_bytes_conv(const ssnet_ctx *ctx, int B, int C, int H, int W, int Co, int kh, int kw,

@@ -152,6 +152,7 @@ void orc_draw_coeffs(u64 seed, u64 domain, u64 stream_id, u64 party, int degree,
 {
     for (int j = 1; j <= degree; j++) {
         u64 key = orc_key(seed, domain, stream_id, party, (u64)j);
+#pragma omp parallel for schedule(static)
         for (size_t e = 0; e < count; e++)
             coef[(size_t)(j - 1) * count + e] = orc_draw_field(key, eidx ? eidx[e] : (u64)e, p);
     }
@@ -177,9 +178,11 @@ static u64 poly_eval(u64 a0, const u64 *coef, size_t count, size_t e, int degree
 void orc_share_explicit(const u64 *secret, const u64 *coef, size_t count, int n, int degree, u64 p,
                         u64 *shares)
 {
-    for (int i = 1; i <= n; i++)
+    for (int i = 1; i <= n; i++) {
+#pragma omp parallel for schedule(static)
         for (size_t e = 0; e < count; e++)
             shares[(size_t)(i - 1) * count + e] = poly_eval(secret[e], coef, count, e, degree, (u64)i, p);
+    }
 }
 
 void orc_share(const u64 *secret, size_t count, const u64 *eidx, int n, int degree, u64 p, u64 seed,
@@ -214,6 +217,7 @@ void orc_reconstruct(const u64 *shares, size_t count, const int *ids, int m, u64
 {
     u64 lambda[ORC_MAXN];
     orc_lagrange(ids, m, p, lambda);
+#pragma omp parallel for schedule(static)
     for (size_t e = 0; e < count; e++) {
         u64 acc = 0;
         for (int i = 0; i < m; i++)
@@ -411,28 +415,34 @@ int orc_degree_reduce_explicit(const u64 *c, const u64 *rcoef, const u64 *zcoef,
 
     /* step 2, on party q = 1..k: row vector of received sub-shares times R */
     for (int q = 0; q < k; q++)
-        for (int m = 0; m < n; m++)
+        for (int m = 0; m < n; m++) {
+#pragma omp parallel for schedule(static)
             for (size_t e = 0; e < count; e++) {
                 u64 acc = 0;
                 for (int i = 0; i < nr; i++)
                     acc = orc_add(acc, orc_mul(m1[((size_t)i * k + q) * count + e], R[i * n + m], p), p);
                 m2[((size_t)q * n + m) * count + e] = acc;
             }
+        }
 
     /* step 3, on each party m: REC of the k sub-shares it received */
-    for (int m = 0; m < n; m++)
+    for (int m = 0; m < n; m++) {
+#pragma omp parallel for schedule(static)
         for (size_t e = 0; e < count; e++) {
             u64 acc = 0;
             for (int q = 0; q < k; q++)
                 acc = orc_add(acc, orc_mul(lambda[q], m2[((size_t)q * n + m) * count + e], p), p);
             rd[(size_t)m * count + e] = acc;
         }
+    }
 
     /* RERAND on all n parties: add the party's share of zero */
-    for (int m = 0; m < n; m++)
+    for (int m = 0; m < n; m++) {
+#pragma omp parallel for schedule(static)
         for (size_t e = 0; e < count; e++)
             out[(size_t)m * count + e] =
                 orc_add(rd[(size_t)m * count + e], poly_eval(0, zcoef, count, e, t, (u64)(m + 1), p), p);
+    }
 
     if (!msg1) free(m1);
     if (!msg2) free(m2);

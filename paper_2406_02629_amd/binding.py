@@ -16,6 +16,7 @@ from . import build as _build
 
 P61 = (1 << 61) - 1
 
+WS_HEADER_BYTES = 65536      # SSNET_WS_HEADER_BYTES
 OK, EINVAL, EPRIME, ESHARES, EID, EWORKSPACE, EHIP = 0, -1, -2, -3, -4, -5, -6
 DOM_SHARE, DOM_RESHARE, DOM_ZERO, DOM_MASK_E, DOM_MASK_ALPHA, DOM_MASK_ALPHAT, DOM_TRUNC_GEN = range(1, 8)
 
@@ -124,6 +125,11 @@ class SSNet:
         if self._ws is None or self._ws.numel() < nbytes:
             self._ws = torch.empty(int(nbytes), dtype=torch.uint8, device=self.device)
             self._ok(self.lib.ssnet_set_workspace(self._ctx, _dptr(self._ws), self._ws.numel()), "ssnet_set_workspace")
+
+    def messages(self) -> torch.Tensor:
+        """int64 view of the workspace behind its header: where the inter-party
+        messages of the last degree_reduce / truncate call were written."""
+        return self._ws[WS_HEADER_BYTES:(self._ws.numel() // 8) * 8].view(torch.int64)
 
     def workspace_bytes_stream(self, count: int) -> int:
         return self.lib.ssnet_workspace_bytes_stream(self._ctx, count)

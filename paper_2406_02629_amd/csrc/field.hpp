@@ -63,6 +63,27 @@ struct ss_acc {
     SS_HD u64 value() const { return ss_reduce128(hi, lo); }
 };
 
+// Accumulator for sums of v * c with v canonical and c a small signed integer
+// (|c| < 2^26), at most 8 terms: the two 32-bit halves of v are multiplied
+// separately, so a term costs two 32 x 32 -> 64 multiply-adds instead of a
+// 64 x 64 -> 128 product.  A negative c multiplies p - v instead.
+struct ss_sacc {
+    u64 lo, hi;
+    SS_HD void clear() { lo = 0; hi = 0; }
+    SS_HD void mac(u64 v, int c)
+    {
+        const u64 w = c < 0 ? SS_P - v : v;
+        const u32 m = (u32)(c < 0 ? -c : c);
+        lo += (w & 0xFFFFFFFFull) * (u64)m;   // each < 2^58
+        hi += (w >> 32) * (u64)m;             // each < 2^55
+    }
+    // lo + hi 2^32 with 2^61 = 1
+    SS_HD u64 value() const
+    {
+        return ss_reduce(ss_fold(lo) + ((hi & ((1ULL << 29) - 1)) << 32) + (hi >> 29));
+    }
+};
+
 // x canonical, c a small constant (c <= 8): x*c < 2^64
 SS_HD u64 ss_mul_small(u64 x, u32 c) { return ss_reduce(x * (u64)c); }
 

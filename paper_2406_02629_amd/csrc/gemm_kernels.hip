@@ -4,12 +4,13 @@
 //   x = sum_{i<8} d_i 2^(8i),  d_i in [-128, 127],
 // which is one add and one xor: the bytes of x + 0x80..80 are d_i + 128.  The
 // integer dot product sum_k x_k w_k is then sum_{i,j} 2^(8(i+j)) sum_k d_i(x_k)
-// d_j(w_k): 64 int8 dot products, each exact in int32 for K <= 16383.  They are
-// one int8 GEMM of shape (8 rows) x K x (8 cols): the limb index multiplies the
-// row and column counts, so one wave holds a 16 x 16 tile of field outputs as
-// 8 x 8 MFMA 16x16x64 accumulators.  The epilogue adds the 64 accumulators of
-// each output along anti-diagonals, propagates them into a 61-bit residue with
-// 2^61 = 1 (mod p) and stores the canonical field element.
+// d_j(w_k): 64 int8 dot products.  Only the 15 anti-diagonal sums
+//   D_s = sum_{i+j=s} sum_k d_i(x_k) d_j(w_k),   |D_s| <= 8 K 2^14 < 2^31 for K <= 16383,
+// are needed, so the 64 MFMA 16x16x64 products of a 16 x 16 tile of field
+// outputs accumulate straight into 15 int32 accumulator tiles (the MFMA's own
+// C operand does the diagonal sum).  The epilogue turns the 15 sums of each
+// output into a 61-bit residue with 2^61 = 1 (mod p) and stores the canonical
+// field element.
 #include "kernels.hpp"
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -88,109 +89,162 @@ __global__ __launch_bounds__(256) void pack_im2col_kernel(const u64 *__restrict_
     store_tiles(y, dst + (size_t)blockIdx.z * dst_party_stride, rb, kb, Kb, lane);
 }
 
-// One workgroup = 4 waves (2 x 2) = 32 x 32 field outputs.  Per k block the
-// workgroup stages two row blocks of A and two of B (16 KB each, already in
-// MFMA lane order) through LDS, double buffered, with the next block's global
-// loads in flight during the 64 MFMAs of the current one.
-__global__ __launch_bounds__(256, 1) void gemm_limb_kernel(const v4i *__restrict__ A, const v4i *__restrict__ Bm,
-                                                           u64 *__restrict__ out, int rows, int cols, int Rb,
-                                                           int Cb, int Kb, size_t a_party_stride,
-                                                           size_t b_party_stride, size_t out_party_stride,
-                                                           size_t stride_row, int cdiv, size_t stride_cb, u64 negbias)
+struct gemm_args {
+    const v4i *A, *B;          // packed operands, all parties
+    u64 *out;
+    u64 *partials;             // [tile][S][64*64] field elements, used when S > 1
+    unsigned *counters;        // [tile], zero between launches
+    int rows, cols, Rb, Cb, Kb, RT, CT, S;
+    size_t a_party_stride, b_party_stride, out_party_stride, stride_row, stride_cb;
+    int cdiv;
+    u64 negbias;
+};
+
+// 15 diagonal sums of one output -> canonical field element
+__device__ __forceinline__ u64 fold_diagonals(const v4i (&acc)[15], int r, u64 negbias)
 {
-    __shared__ v4i lds[2][2048];
+    u32 U[15];
+#pragma unroll
+    for (int s = 0; s < 15; s++) U[s] = (u32)acc[s][r] ^ 0x80000000u;   // D_s + 2^31, non-negative
+    const u64 g0 = (u64)U[0] + ((u64)U[1] << 8) + ((u64)U[2] << 16) + ((u64)U[3] << 24);
+    const u64 g1 = (u64)U[4] + ((u64)U[5] << 8) + ((u64)U[6] << 16) + ((u64)U[7] << 24);
+    const u64 g2 = (u64)U[8] + ((u64)U[9] << 8) + ((u64)U[10] << 16) + ((u64)U[11] << 24);
+    const u64 g3 = (u64)U[12] + ((u64)U[13] << 8) + ((u64)U[14] << 16);
+    // g0 + g1 2^32 + g2 2^64 + g3 2^96 with 2^61 = 1: 2^64 = 2^3, 2^96 = 2^35
+    const u64 tot = g0 + ((g1 & ((1ULL << 29) - 1)) << 32) + (g1 >> 29) + (g2 << 3) +
+                    ((g3 & ((1ULL << 26) - 1)) << 35) + (g3 >> 26);
+    return ss_reduce(ss_fold(tot) + negbias);   // minus the 2^31 offsets
+}
+
+// One workgroup = 8 waves (4 x 2) = 64 x 64 field outputs over the k blocks
+// [kb0, kb1) of its split; wave (wr, wc) owns row block wr and column blocks
+// 2wc, 2wc+1 (2 x 15 accumulator tiles).  Per k block the workgroup needs four
+// row blocks of A and four column blocks of B, 8 KB each and already in MFMA
+// lane order, so wave w copies block w (A for w < 4, B otherwise) straight
+// into LDS with eight 1 KB global->LDS loads; two stages, the next block's
+// loads in flight during the 128 MFMAs per wave of the current one.
+//
+// With S > 1 splits of the contraction, every split stores its residues to the
+// partials buffer and bumps the tile's counter; the split that arrives last
+// adds the others' residues to its own and writes the output.  Integer sums
+// are exact, so the result does not depend on S or on arrival order.
+__global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
+{
+    extern __shared__ v4i lds[];   // 2 stages x (4 A blocks + 4 B blocks) x 512
+    __shared__ unsigned arrival;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wr = wave >> 1, wc = wave & 1;
-    const int rb0 = blockIdx.y * 2, cb0 = blockIdx.x * 2;
-    const v4i *Ap = A + (size_t)blockIdx.z * a_party_stride;
-    const v4i *Bp = Bm + (size_t)blockIdx.z * b_party_stride;
+    int item = blockIdx.x;
+    const int ks = item % g.S;
+    item /= g.S;
+    const int ct = item % g.CT;
+    item /= g.CT;
+    const int rt = item % g.RT, party = item / g.RT;
+    const int kb0 = (int)((long)ks * g.Kb / g.S), kb1 = (int)((long)(ks + 1) * g.Kb / g.S);
 
-    // slot q of this thread: element tid + 256 q of a 1024-entry chunk; q = 0, 1
-    // lie in the first block of the pair, q = 2, 3 in the second.  Blocks past
-    // the end are clamped: their products are computed and never stored.
-    const v4i *asrc[4], *bsrc[4];
-#pragma unroll
-    for (int q = 0; q < 4; q++) {
-        const int half = q >> 1, within = (tid + 256 * q) & 511;
-        const int rb = min(rb0 + half, Rb - 1), cb = min(cb0 + half, Cb - 1);
-        asrc[q] = Ap + (size_t)rb * Kb * 512 + within;
-        bsrc[q] = Bp + (size_t)cb * Kb * 512 + within;
-    }
+    // this wave's source block; blocks past the end are clamped (their
+    // products are computed and never stored)
+    const v4i *src;
+    if (wave < 4)
+        src = g.A + (size_t)party * g.a_party_stride + (size_t)min(rt * 4 + wave, g.Rb - 1) * g.Kb * 512 + lane;
+    else
+        src = g.B + (size_t)party * g.b_party_stride + (size_t)min(ct * 4 + wave - 4, g.Cb - 1) * g.Kb * 512 + lane;
+    v4i *mine = lds + wave * 512;   // wave-uniform LDS destination of this wave's block
 
-    v4i acc[8][8];
+    v4i acc[2][15];
 #pragma unroll
-    for (int i = 0; i < 8; i++)
+    for (int h = 0; h < 2; h++)
 #pragma unroll
-        for (int j = 0; j < 8; j++) acc[i][j] = (v4i){0, 0, 0, 0};
+        for (int s = 0; s < 15; s++) acc[h][s] = (v4i){0, 0, 0, 0};
 
-    v4i pa[4], pb[4];
 #pragma unroll
-    for (int q = 0; q < 4; q++) {
-        pa[q] = asrc[q][0];
-        pb[q] = bsrc[q][0];
-    }
-#pragma unroll
-    for (int q = 0; q < 4; q++) {
-        lds[0][tid + 256 * q] = pa[q];
-        lds[0][1024 + tid + 256 * q] = pb[q];
-    }
-    __syncthreads();
+    for (int u = 0; u < 8; u++)
+        __builtin_amdgcn_global_load_lds(src + (size_t)kb0 * 512 + u * 64, mine + u * 64, 16, 0, 0);
 
-    for (int kb = 0; kb < Kb; kb++) {
-        const int cur = kb & 1;
-        const bool more = kb + 1 < Kb;
-        if (more) {
+    for (int kb = kb0; kb < kb1; kb++) {
+        const int st = (kb - kb0) & 1;
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of block kb is in LDS
+        __syncthreads();                      // everyone's part is; stage st^1 is no longer read
+        if (kb + 1 < kb1) {
 #pragma unroll
-            for (int q = 0; q < 4; q++) {
-                pa[q] = asrc[q][(size_t)(kb + 1) * 512];
-                pb[q] = bsrc[q][(size_t)(kb + 1) * 512];
-            }
+            for (int u = 0; u < 8; u++)
+                __builtin_amdgcn_global_load_lds(src + (size_t)(kb + 1) * 512 + u * 64,
+                                                 mine + (st ^ 1) * 4096 + u * 64, 16, 0, 0);
         }
-        v4i a[8], b[8];
+        const v4i *sa = lds + st * 4096 + wr * 512 + lane;
+        const v4i *sb = lds + st * 4096 + 2048 + wc * 1024 + lane;
+        v4i a[8];
 #pragma unroll
-        for (int i = 0; i < 8; i++) {
-            a[i] = lds[cur][wr * 512 + i * 64 + lane];
-            b[i] = lds[cur][1024 + wc * 512 + i * 64 + lane];
-        }
+        for (int i = 0; i < 8; i++) a[i] = sa[i * 64];
 #pragma unroll
-        for (int i = 0; i < 8; i++)
+        for (int h = 0; h < 2; h++) {
+            v4i b[8];
 #pragma unroll
-            for (int j = 0; j < 8; j++)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[i][j], 0, 0, 0);
-        if (more) {
-#pragma unroll
-            for (int q = 0; q < 4; q++) {
-                lds[cur ^ 1][tid + 256 * q] = pa[q];
-                lds[cur ^ 1][1024 + tid + 256 * q] = pb[q];
-            }
-        }
-        __syncthreads();
-    }
-
-    // lane holds column lane%16 and rows 4*(lane/16)+r of the wave's 16 x 16 tile
-    const int col = (cb0 + wc) * 16 + (lane & 15);
-    u64 *op = out + (size_t)blockIdx.z * out_party_stride + (size_t)(col / cdiv) * stride_cb + (col % cdiv);
-#pragma unroll
-    for (int r = 0; r < 4; r++) {
-        u32 U[15];
-#pragma unroll
-        for (int s = 0; s < 15; s++) {
-            int d = 0;
+            for (int j = 0; j < 8; j++) b[j] = sb[h * 512 + j * 64];
 #pragma unroll
             for (int i = 0; i < 8; i++)
-                if (s - i >= 0 && s - i < 8) d += acc[i][s - i][r];
-            U[s] = (u32)d ^ 0x80000000u;   // d + 2^31, non-negative
+#pragma unroll
+                for (int j = 0; j < 8; j++)
+                    acc[h][i + j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[h][i + j], 0, 0, 0);
         }
-        const u64 g0 = (u64)U[0] + ((u64)U[1] << 8) + ((u64)U[2] << 16) + ((u64)U[3] << 24);
-        const u64 g1 = (u64)U[4] + ((u64)U[5] << 8) + ((u64)U[6] << 16) + ((u64)U[7] << 24);
-        const u64 g2 = (u64)U[8] + ((u64)U[9] << 8) + ((u64)U[10] << 16) + ((u64)U[11] << 24);
-        const u64 g3 = (u64)U[12] + ((u64)U[13] << 8) + ((u64)U[14] << 16);
-        // g0 + g1 2^32 + g2 2^64 + g3 2^96 with 2^61 = 1: 2^64 = 2^3, 2^96 = 2^35
-        const u64 tot = g0 + ((g1 & ((1ULL << 29) - 1)) << 32) + (g1 >> 29) + (g2 << 3) +
-                        ((g3 & ((1ULL << 26) - 1)) << 35) + (g3 >> 26);
-        const u64 v = ss_reduce(ss_fold(tot) + negbias);   // minus the 2^31 offsets
-        const int row = (rb0 + wr) * 16 + 4 * (lane >> 4) + r;
-        if (row < rows && col < cols) op[(size_t)row * stride_row] = v;
     }
+
+    // lane holds, per column block h, column lane%16 and rows 4*(lane/16)+r
+    u64 v[2][4];
+#pragma unroll
+    for (int h = 0; h < 2; h++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) v[h][r] = fold_diagonals(acc[h], r, g.negbias);
+
+    const int lrow = wr * 16 + 4 * (lane >> 4), lcol = wc * 32 + (lane & 15);   // within the 64 x 64 tile
+    if (g.S > 1) {
+        // Hand-over between workgroups that may sit on different XCDs (separate
+        // L2s): the residues and the counter are moved with agent-scope atomic
+        // accesses, which are performed at the device's coherence point, and the
+        // counter is bumped only after this workgroup's stores have completed.
+        // No cache-wide fence is used: it would evict the operand tiles that all
+        // other workgroups are reusing.
+        const size_t tile = ((size_t)party * g.RT + rt) * g.CT + ct;
+        u64 *part = g.partials + (tile * g.S) * 4096;
+#pragma unroll
+        for (int h = 0; h < 2; h++)
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+                __hip_atomic_store(&part[(size_t)ks * 4096 + (lrow + r) * 64 + lcol + 16 * h], v[h][r],
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the stores above are done
+        __syncthreads();
+        if (tid == 0)
+            arrival = __hip_atomic_fetch_add(&g.counters[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (arrival != (unsigned)(g.S - 1)) return;
+        if (tid == 0) __hip_atomic_store(&g.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int s = 0; s < g.S; s++) {
+            if (s == ks) continue;
+#pragma unroll
+            for (int h = 0; h < 2; h++)
+#pragma unroll
+                for (int r = 0; r < 4; r++)
+                    v[h][r] = ss_add(v[h][r],
+                                     __hip_atomic_load(&part[(size_t)s * 4096 + (lrow + r) * 64 + lcol + 16 * h],
+                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < 2; h++) {
+        const int col = ct * 64 + lcol + 16 * h;
+        u64 *op = g.out + (size_t)party * g.out_party_stride + (size_t)(col / g.cdiv) * g.stride_cb + (col % g.cdiv);
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            const int row = rt * 64 + lrow + r;
+            if (row < g.rows && col < g.cols) op[(size_t)row * g.stride_row] = v[h][r];
+        }
+    }
+}
+
+__global__ void zero_words_kernel(unsigned *p, size_t nwords)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < nwords) p[i] = 0;
 }
 
 // residue of sum_{s<15} 2^31 2^(8s), negated
@@ -202,6 +256,43 @@ u64 neg_bias()
 }
 
 }  // namespace
+
+// Number of splits of the contraction: enough workgroups to occupy every CU a
+// few times over, but each split keeps at least two k blocks.  Modelled cost per
+// workgroup: a fixed part worth about 1.5 k blocks plus its k blocks; the CUs
+// take the workgroups in rounds.
+int ss_gemm_splits(int n, int rows, int cols, int K)
+{
+    const long tiles = (long)n * ((rows + 63) / 64) * ((cols + 63) / 64);
+    const int Kb = (K + 63) / 64;
+    if (tiles > SS_GEMM_MAX_SPLIT_TILES) return 1;
+    int best = 1;
+    double best_cost = 1e300;
+    for (int S = 1; S <= 32 && S <= Kb; S++) {
+        if (S > 1 && Kb / S < 2) break;
+        const long rounds = (tiles * S + SS_GEMM_CUS - 1) / SS_GEMM_CUS;
+        const double cost = (double)rounds * ((Kb + S - 1) / S + 1.5 + (S > 1 ? 0.5 : 0.0));
+        if (cost < best_cost - 1e-9) {
+            best_cost = cost;
+            best = S;
+        }
+    }
+    return best;
+}
+
+size_t ss_gemm_scratch_bytes(int n, int rows, int cols, int K)
+{
+    const size_t tiles = (size_t)n * ((rows + 63) / 64) * ((cols + 63) / 64);
+    const int S = ss_gemm_splits(n, rows, cols, K);
+    return S > 1 ? tiles * S * 4096 * sizeof(u64) : 0;
+}
+
+hipError_t ss_launch_zero_counters(unsigned *counters, hipStream_t stream)
+{
+    hipLaunchKernelGGL(zero_words_kernel, dim3((SS_GEMM_MAX_SPLIT_TILES + 255) / 256), dim3(256), 0, stream, counters,
+                       (size_t)SS_GEMM_MAX_SPLIT_TILES);
+    return hipGetLastError();
+}
 
 size_t ss_packed_bytes(int rows, int K)
 {
@@ -228,12 +319,39 @@ hipError_t ss_launch_pack_im2col(const u64 *x, void *dst, int n, int B, int C, i
 }
 
 hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, int n, int rows, int cols, int K,
-                          size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb, hipStream_t stream)
+                          size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb, unsigned *counters,
+                          u64 *partials, hipStream_t stream)
 {
-    const int Rb = (rows + 15) / 16, Cb = (cols + 15) / 16, Kb = (K + 63) / 64;
-    hipLaunchKernelGGL(gemm_limb_kernel, dim3((Cb + 1) / 2, (Rb + 1) / 2, n), dim3(256), 0, stream,
-                       (const v4i *)packedA, (const v4i *)packedB, out, rows, cols, Rb, Cb, Kb,
-                       ss_packed_bytes(rows, K) / 16, ss_packed_bytes(cols, K) / 16, out_party_stride, stride_row, cdiv,
-                       stride_cb, neg_bias());
+    static bool lds_opt_in = false;
+    constexpr int LDS_BYTES = 2 * 4096 * 16;
+    if (!lds_opt_in) {
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_limb_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           LDS_BYTES);
+        if (e != hipSuccess) return e;
+        lds_opt_in = true;
+    }
+    gemm_args g;
+    g.A = (const v4i *)packedA;
+    g.B = (const v4i *)packedB;
+    g.out = out;
+    g.partials = partials;
+    g.counters = counters;
+    g.rows = rows;
+    g.cols = cols;
+    g.Rb = (rows + 15) / 16;
+    g.Cb = (cols + 15) / 16;
+    g.Kb = (K + 63) / 64;
+    g.RT = (rows + 63) / 64;
+    g.CT = (cols + 63) / 64;
+    g.S = ss_gemm_splits(n, rows, cols, K);
+    g.a_party_stride = ss_packed_bytes(rows, K) / 16;
+    g.b_party_stride = ss_packed_bytes(cols, K) / 16;
+    g.out_party_stride = out_party_stride;
+    g.stride_row = stride_row;
+    g.stride_cb = stride_cb;
+    g.cdiv = cdiv;
+    g.negbias = neg_bias();
+    const long items = (long)n * g.RT * g.CT * g.S;
+    hipLaunchKernelGGL(gemm_limb_kernel, dim3((unsigned)items), dim3(512), LDS_BYTES, stream, g);
     return hipGetLastError();
 }

@@ -9,25 +9,32 @@ struct ss_keys {                  // generator keys, one per coefficient index j
     u64 k[SS_MAXDEG];
 };
 
+// Constant tables reach the kernels as small integers over a common
+// denominator: value = dinv * sum(c_i * v_i), dinv = (denominator)^-1 in F_p.
+// The multipliers of Eq. 2 and the entries of the matrix of Eq. 3 are ratios of
+// small integers, so this replaces wide multiplications by narrow ones.
 struct ss_rec_params {            // REC: which planes, which multipliers
     int m;
     int plane[SS_MAXN];
-    u64 lambda[SS_MAXN];
+    int ilambda[SS_MAXN];         // lambda_i = ilambda[i] * dinv (for IDs up to 8, |ilambda| <= 448)
+    u64 dinv;
 };
 
 struct ss_dr_params {             // RED + RERAND constants
     int n, t;
     u64 reshare_key[2 * SS_MAXT + 1][SS_MAXT];   // [party i][j]
     u64 zero_key[SS_MAXT];
-    u64 binv[2 * SS_MAXT + 1][SS_MAXK];          // first k columns of B^-1 (Eq. 3)
-    u64 lambda[SS_MAXK];                         // Lagrange multipliers of IDs 1..k
+    int ibinv[2 * SS_MAXT + 1][SS_MAXK];         // D * (first k columns of B^-1), Eq. 3
+    int irmat[2 * SS_MAXT + 1][SS_MAXN];         // D * R, R = B^-1 P B, [reducing party][receiving party]
+    u64 dinv;                                    // D^-1
+    int ilambda[SS_MAXK];                        // Lagrange multipliers of IDs 1..k: (-1)^(q-1) C(k, q)
 };
 
 struct ss_tr_params {             // truncation constants
     int n, t, f;
     u64 e_key;
     u64 alpha_key[SS_MAXT], alphat_key[SS_MAXT], gen_key[SS_MAXT];
-    u64 lambda[SS_MAXK];
+    int ilambda[SS_MAXK];
 };
 
 // ---- streaming family (stream_kernels.hip) ----
@@ -51,7 +58,15 @@ hipError_t ss_launch_pack_matrix(const u64 *src, void *dst, int n, int rows, int
 // rows = (b, ho, wo), k = (c, r, s) of x [n][B][C][H][W]
 hipError_t ss_launch_pack_im2col(const u64 *x, void *dst, int n, int B, int C, int H, int W, int kh, int kw,
                                  int stride, int pad, int Ho, int Wo, hipStream_t stream);
-// out[i][row*stride_row + (col / cdiv)*stride_cb + col % cdiv] = sum_k A_i[row][k] * B_i[col][k] mod p
+// out[i][row*stride_row + (col / cdiv)*stride_cb + col % cdiv] = sum_k A_i[row][k] * B_i[col][k] mod p.
+// The contraction may be split over several workgroups per output tile
+// (ss_gemm_splits); then `partials` must hold ss_gemm_scratch_bytes and
+// `counters` SS_GEMM_MAX_SPLIT_TILES zeroed words (they are left zeroed).
+#define SS_GEMM_MAX_SPLIT_TILES 16384
+#define SS_GEMM_CUS 256
+int ss_gemm_splits(int n, int rows, int cols, int K);
+size_t ss_gemm_scratch_bytes(int n, int rows, int cols, int K);
+hipError_t ss_launch_zero_counters(unsigned *counters, hipStream_t stream);
 hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, int n, int rows, int cols, int K,
-                          size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb,
-                          hipStream_t stream);
+                          size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb, unsigned *counters,
+                          u64 *partials, hipStream_t stream);

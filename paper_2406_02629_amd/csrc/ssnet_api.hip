@@ -13,11 +13,16 @@ struct ssnet_ctx {
     int n, t, f;
     u64 seed;
     hipStream_t stream;
-    void *ws;
+    void *ws;                             // caller's workspace: [split counters][scratch]
     size_t ws_bytes;
     int last_hip;
     u64 binv[2 * SS_MAXT + 1][SS_MAXK];   // first k columns of the inverse Vandermonde matrix (Eq. 3)
     u64 lambda_k[SS_MAXK];                // Lagrange multipliers of IDs 1..k (Eq. 2)
+    // the same tables as exact small integers over the common denominator D
+    int ibinv[2 * SS_MAXT + 1][SS_MAXK];
+    int irmat[2 * SS_MAXT + 1][SS_MAXN];
+    int ilambda_k[SS_MAXK];
+    u64 dinv;
     // optional per-kernel-class timing with HIP events on the context's stream
     bool prof;
     struct span { hipEvent_t a, b; int cls; };
@@ -81,6 +86,94 @@ void h_inverse_vandermonde(int nr, int k, u64 (*binv)[SS_MAXK])
     }
 }
 
+long h_gcd(long a, long b)
+{
+    a = a < 0 ? -a : a;
+    b = b < 0 ? -b : b;
+    while (b) {
+        const long r = a % b;
+        a = b;
+        b = r;
+    }
+    return a;
+}
+
+u64 h_from_signed(long v) { return v >= 0 ? (u64)v % SS_P : ss_neg((u64)(-v) % SS_P); }
+
+constexpr long SMALL_LIMIT = 1L << 26;   // magnitude bound of the integer tables (ss_sacc)
+
+// Eq. 2 multipliers as exact integers over a common denominator:
+// lambda_i = c[i] / D.  False if a c[i] is too large for the narrow multiply.
+bool h_lagrange_int(const int *ids, int m, int *c, u64 *dinv)
+{
+    long num[SS_MAXN], den[SS_MAXN], D = 1;
+    for (int i = 0; i < m; i++) {
+        long nu = 1, de = 1;
+        for (int j = 0; j < m; j++) {
+            if (j == i) continue;
+            nu *= ids[j];
+            de *= ids[j] - ids[i];
+        }
+        const long g = h_gcd(nu, de);
+        nu /= g;
+        de /= g;
+        if (de < 0) {
+            nu = -nu;
+            de = -de;
+        }
+        num[i] = nu;
+        den[i] = de;
+        D = D / h_gcd(D, de) * de;
+    }
+    for (int i = 0; i < m; i++) {
+        const long v = num[i] * (D / den[i]);
+        if (v >= SMALL_LIMIT || v <= -SMALL_LIMIT) return false;
+        c[i] = (int)v;
+    }
+    *dinv = h_inv((u64)D % SS_P);
+    return true;
+}
+
+// Integer form of the tables of Eq. 3 for IDs 1..nr: the Lagrange basis
+// polynomial of party i is prod_{l != i} (x - l) / prod_{l != i} (i - l), an
+// integer polynomial over an integer; D is the least common multiple of the
+// denominators.  irmat[i][m] = D * R[i][m] = sum_j ibinv[i][j] (m+1)^j.
+bool h_reduction_tables_int(int nr, int k, int n, int (*ibinv)[SS_MAXK], int (*irmat)[SS_MAXN], u64 *dinv)
+{
+    long poly[2 * SS_MAXT + 1][2 * SS_MAXT + 2], den[2 * SS_MAXT + 1], D = 1;
+    for (int i = 0; i < nr; i++) {
+        long *pl = poly[i];
+        for (int d = 0; d < 2 * SS_MAXT + 2; d++) pl[d] = 0;
+        pl[0] = 1;
+        int deg = 0;
+        den[i] = 1;
+        for (int l = 0; l < nr; l++) {
+            if (l == i) continue;
+            for (int d = deg + 1; d >= 0; d--) pl[d] = (d > 0 ? pl[d - 1] : 0) - (long)(l + 1) * (d <= deg ? pl[d] : 0);
+            deg++;
+            den[i] *= (i - l);
+        }
+        const long a = den[i] < 0 ? -den[i] : den[i];
+        D = D / h_gcd(D, a) * a;
+    }
+    for (int i = 0; i < nr; i++) {
+        const long scale = D / den[i];   // exact, carries the sign of den[i]
+        for (int j = 0; j < k; j++) {
+            const long v = poly[i][j] * scale;
+            if (v >= SMALL_LIMIT || v <= -SMALL_LIMIT) return false;
+            ibinv[i][j] = (int)v;
+        }
+        for (int m = 0; m < n; m++) {
+            long acc = 0;
+            for (int j = k - 1; j >= 0; j--) acc = acc * (m + 1) + ibinv[i][j];
+            if (acc >= SMALL_LIMIT || acc <= -SMALL_LIMIT) return false;
+            irmat[i][m] = (int)acc;
+        }
+    }
+    *dinv = h_inv((u64)D % SS_P);
+    return true;
+}
+
 int fail_hip(ssnet_ctx *ctx, hipError_t e)
 {
     ctx->last_hip = (int)e;
@@ -118,6 +211,14 @@ int conv_out(int H, int k, int stride, int pad) { return (H + 2 * pad - k) / str
 
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
+// The first bytes of the workspace hold the arrival counters of split
+// contractions (zeroed when the workspace is set, left zeroed by every launch);
+// everything else lives behind them.
+constexpr size_t WS_COUNTER_BYTES = (size_t)SS_GEMM_MAX_SPLIT_TILES * sizeof(unsigned);
+
+char *ws_scratch(const ssnet_ctx *c) { return (char *)c->ws + WS_COUNTER_BYTES; }
+bool ws_fits(const ssnet_ctx *c, size_t scratch) { return c->ws && c->ws_bytes >= WS_COUNTER_BYTES + scratch; }
+
 // largest element count whose 1-D grid fits
 constexpr size_t MAX_COUNT = (size_t)1 << 38;
 
@@ -126,12 +227,13 @@ bool gemm_shape_ok(long rows, long cols, long K)
     return rows >= 1 && cols >= 1 && K >= 1 && K <= SSNET_MAX_K && rows <= 16L * 65535 * 2 && cols <= (1L << 30);
 }
 
+// partial residues of a split contraction go to the start of the scratch area
 int run_gemm(ssnet_ctx *ctx, const void *pa, const void *pb, u64 *out, int rows, int cols, int K,
              size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb)
 {
     timed tm(ctx, SSNET_PROF_GEMM);
     hipError_t e = ss_launch_gemm(pa, pb, out, ctx->n, rows, cols, K, out_party_stride, stride_row, cdiv, stride_cb,
-                                  ctx->stream);
+                                  (unsigned *)ctx->ws, (u64 *)ws_scratch(ctx), ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
 
@@ -160,6 +262,17 @@ int ssnet_create(ssnet_ctx **out, int n, int t, uint64_t p, int f, uint64_t seed
     for (int q = 0; q <= t; q++) ids[q] = q + 1;
     h_lagrange(ids, t + 1, c->lambda_k);
     h_inverse_vandermonde(2 * t + 1, t + 1, c->binv);
+    // integer forms, cross-checked against the field-valued tables computed above by other means
+    u64 one = 0;
+    bool ok = h_lagrange_int(ids, t + 1, c->ilambda_k, &one) && one == 1 &&
+              h_reduction_tables_int(2 * t + 1, t + 1, n, c->ibinv, c->irmat, &c->dinv);
+    for (int q = 0; ok && q <= t; q++) ok = h_from_signed(c->ilambda_k[q]) == c->lambda_k[q];
+    for (int i = 0; ok && i < 2 * t + 1; i++)
+        for (int j = 0; ok && j <= t; j++) ok = ss_mul(h_from_signed(c->ibinv[i][j]), c->dinv) == c->binv[i][j];
+    if (!ok) {
+        delete c;
+        return SSNET_EINVAL;
+    }
     *out = c;
     return SSNET_OK;
 }
@@ -215,13 +328,14 @@ size_t ssnet_workspace_bytes_stream(const ssnet_ctx *ctx, size_t count)
     if (!ctx) return 0;
     const size_t k = ctx->t + 1, nr = 2 * ctx->t + 1, n = ctx->n;
     const size_t dr = (nr * k + k * n) * count * 8, tr = (k + n) * count * 8;
-    return align256(dr > tr ? dr : tr);
+    return WS_COUNTER_BYTES + align256(dr > tr ? dr : tr);
 }
 
 size_t ssnet_workspace_bytes_linear(const ssnet_ctx *ctx, int M, int K, int N)
 {
     if (!ctx || M < 1 || K < 1 || N < 1) return 0;
-    return (size_t)ctx->n * (ss_packed_bytes(M, K) + ss_packed_bytes(N, K));
+    return WS_COUNTER_BYTES + align256(ss_gemm_scratch_bytes(ctx->n, M, N, K)) +
+           (size_t)ctx->n * (ss_packed_bytes(M, K) + ss_packed_bytes(N, K));
 }
 
 size_t ssnet_workspace_bytes_conv(const ssnet_ctx *ctx, int B, int C, int H, int W, int Co, int kh, int kw, int stride,
@@ -232,7 +346,8 @@ size_t ssnet_workspace_bytes_conv(const ssnet_ctx *ctx, int B, int C, int H, int
     if (Ho < 1 || Wo < 1) return 0;
     const long M = (long)B * Ho * Wo, K = (long)C * kh * kw;
     if (M > INT_MAX || K > INT_MAX) return 0;
-    return (size_t)ctx->n * (ss_packed_bytes((int)M, (int)K) + ss_packed_bytes(Co, (int)K));
+    return WS_COUNTER_BYTES + align256(ss_gemm_scratch_bytes(ctx->n, Co, (int)M, (int)K)) +
+           (size_t)ctx->n * (ss_packed_bytes((int)M, (int)K) + ss_packed_bytes(Co, (int)K));
 }
 
 int ssnet_set_workspace(ssnet_ctx *ctx, void *d_workspace, size_t bytes)
@@ -240,6 +355,10 @@ int ssnet_set_workspace(ssnet_ctx *ctx, void *d_workspace, size_t bytes)
     if (!ctx || (!d_workspace && bytes) || ((uintptr_t)d_workspace & 15)) return SSNET_EINVAL;
     ctx->ws = d_workspace;
     ctx->ws_bytes = bytes;
+    if (d_workspace && bytes >= WS_COUNTER_BYTES) {
+        hipError_t e = ss_launch_zero_counters((unsigned *)d_workspace, ctx->stream);
+        if (e != hipSuccess) return fail_hip(ctx, e);
+    }
     return SSNET_OK;
 }
 
@@ -269,7 +388,7 @@ int ssnet_reconstruct(ssnet_ctx *ctx, const uint64_t *d_shares, size_t count, co
     ss_rec_params rp = {};
     rp.m = m;
     for (int i = 0; i < m; i++) rp.plane[i] = party_ids[i] - 1;
-    h_lagrange(party_ids, m, rp.lambda);
+    if (!h_lagrange_int(party_ids, m, rp.ilambda, &rp.dinv)) return SSNET_EINVAL;
     timed tm(ctx, SSNET_PROF_RECONSTRUCT);
     hipError_t e = ss_launch_reconstruct(d_shares, d_secret, count, rp, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
@@ -302,22 +421,24 @@ int ssnet_linear_mod_packed(ssnet_ctx *ctx, const uint64_t *d_x, const void *d_w
                             uint64_t *d_y)
 {
     if (!ctx || !d_x || !d_w_packed || !d_y || !gemm_shape_ok(M, N, K)) return SSNET_EINVAL;
-    const size_t need = (size_t)ctx->n * ss_packed_bytes(M, K);
-    if (!ctx->ws || ctx->ws_bytes < need) return SSNET_EWORKSPACE;
+    const size_t part = align256(ss_gemm_scratch_bytes(ctx->n, M, N, K));
+    if (!ws_fits(ctx, part + (size_t)ctx->n * ss_packed_bytes(M, K))) return SSNET_EWORKSPACE;
+    void *px = ws_scratch(ctx) + part;
     {
         timed tm(ctx, SSNET_PROF_PACK_X);
-        hipError_t e = ss_launch_pack_matrix(d_x, ctx->ws, ctx->n, M, K, (size_t)M * K, (size_t)K, 1, ctx->stream);
+        hipError_t e = ss_launch_pack_matrix(d_x, px, ctx->n, M, K, (size_t)M * K, (size_t)K, 1, ctx->stream);
         if (e != hipSuccess) return fail_hip(ctx, e);
     }
-    return run_gemm(ctx, ctx->ws, d_w_packed, d_y, M, N, K, (size_t)M * N, (size_t)N, INT_MAX, 0);
+    return run_gemm(ctx, px, d_w_packed, d_y, M, N, K, (size_t)M * N, (size_t)N, INT_MAX, 0);
 }
 
 int ssnet_linear_mod(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_w, int M, int K, int N, uint64_t *d_y)
 {
     if (!ctx || !d_x || !d_w || !d_y || !gemm_shape_ok(M, N, K)) return SSNET_EINVAL;
+    const size_t part = align256(ss_gemm_scratch_bytes(ctx->n, M, N, K));
     const size_t xa = (size_t)ctx->n * ss_packed_bytes(M, K), wa = (size_t)ctx->n * ss_packed_bytes(N, K);
-    if (!ctx->ws || ctx->ws_bytes < xa + wa) return SSNET_EWORKSPACE;
-    void *pw = (char *)ctx->ws + xa;
+    if (!ws_fits(ctx, part + xa + wa)) return SSNET_EWORKSPACE;
+    void *pw = ws_scratch(ctx) + part + xa;
     int rc = ssnet_pack_weights_linear(ctx, d_w, K, N, pw);
     if (rc) return rc;
     return ssnet_linear_mod_packed(ctx, d_x, pw, M, K, N, d_y);
@@ -333,17 +454,17 @@ int ssnet_conv_mod_packed(ssnet_ctx *ctx, const uint64_t *d_x, const void *d_w_p
     if (H + 2 * pad < kh || W + 2 * pad < kw || Ho < 1 || Wo < 1) return SSNET_EINVAL;
     const long M = (long)B * Ho * Wo, K = (long)C * kh * kw;
     if (M > (1L << 30) || !gemm_shape_ok(Co, M, K)) return SSNET_EINVAL;
-    const size_t need = (size_t)ctx->n * ss_packed_bytes((int)M, (int)K);
-    if (!ctx->ws || ctx->ws_bytes < need) return SSNET_EWORKSPACE;
+    const size_t part = align256(ss_gemm_scratch_bytes(ctx->n, Co, (int)M, (int)K));
+    if (!ws_fits(ctx, part + (size_t)ctx->n * ss_packed_bytes((int)M, (int)K))) return SSNET_EWORKSPACE;
+    void *px = ws_scratch(ctx) + part;
     {
         timed tm(ctx, SSNET_PROF_PACK_X);
-        hipError_t e =
-            ss_launch_pack_im2col(d_x, ctx->ws, ctx->n, B, C, H, W, kh, kw, stride, pad, Ho, Wo, ctx->stream);
+        hipError_t e = ss_launch_pack_im2col(d_x, px, ctx->n, B, C, H, W, kh, kw, stride, pad, Ho, Wo, ctx->stream);
         if (e != hipSuccess) return fail_hip(ctx, e);
     }
     const size_t HW = (size_t)Ho * Wo;
     // rows = output channel, cols = (b, ho, wo): y[b][co][hw]
-    return run_gemm(ctx, d_w_packed, ctx->ws, d_y, Co, (int)M, (int)K, (size_t)B * Co * HW, HW, (int)HW, (size_t)Co * HW);
+    return run_gemm(ctx, d_w_packed, px, d_y, Co, (int)M, (int)K, (size_t)B * Co * HW, HW, (int)HW, (size_t)Co * HW);
 }
 
 int ssnet_conv_mod(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_w, int B, int C, int H, int W, int Co, int kh,
@@ -355,7 +476,7 @@ int ssnet_conv_mod(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_w, int
     if (!ctx->ws || ctx->ws_bytes < total) return SSNET_EWORKSPACE;
     const long K = (long)C * kh * kw;
     if (K > SSNET_MAX_K) return SSNET_EINVAL;
-    void *pw = (char *)ctx->ws + (total - (size_t)ctx->n * ss_packed_bytes(Co, (int)K));
+    void *pw = (char *)ctx->ws + (total - (size_t)ctx->n * ss_packed_bytes(Co, (int)K));   // last part of the layout
     int rc = ssnet_pack_weights_conv(ctx, d_w, Co, (int)K, pw);
     if (rc) return rc;
     return ssnet_conv_mod_packed(ctx, d_x, pw, B, C, H, W, Co, kh, kw, stride, pad, d_y);
@@ -366,7 +487,7 @@ int ssnet_degree_reduce(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint6
     if (!ctx || !d_c || !d_out || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
     const int t = ctx->t, k = t + 1, nr = 2 * t + 1, n = ctx->n;
     const size_t need = ((size_t)nr * k + (size_t)k * n) * count * 8;
-    if (!ctx->ws || ctx->ws_bytes < need) return SSNET_EWORKSPACE;
+    if (!ws_fits(ctx, need)) return SSNET_EWORKSPACE;
     ss_dr_params dp = {};
     dp.n = n;
     dp.t = t;
@@ -374,10 +495,13 @@ int ssnet_degree_reduce(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint6
         for (int j = 1; j <= t; j++)
             dp.reshare_key[i][j - 1] = ss_key(ctx->seed, SSNET_DOM_RESHARE, stream_id, (u64)(i + 1), (u64)j);
     for (int j = 1; j <= t; j++) dp.zero_key[j - 1] = ss_key(ctx->seed, SSNET_DOM_ZERO, stream_id, 0, (u64)j);
-    for (int i = 0; i < nr; i++)
-        for (int j = 0; j < k; j++) dp.binv[i][j] = ctx->binv[i][j];
-    for (int q = 0; q < k; q++) dp.lambda[q] = ctx->lambda_k[q];
-    u64 *msg1 = (u64 *)ctx->ws, *msg2 = msg1 + (size_t)nr * k * count;
+    for (int i = 0; i < nr; i++) {
+        for (int j = 0; j < k; j++) dp.ibinv[i][j] = ctx->ibinv[i][j];
+        for (int m = 0; m < n; m++) dp.irmat[i][m] = ctx->irmat[i][m];
+    }
+    dp.dinv = ctx->dinv;
+    for (int q = 0; q < k; q++) dp.ilambda[q] = ctx->ilambda_k[q];
+    u64 *msg1 = (u64 *)ws_scratch(ctx), *msg2 = msg1 + (size_t)nr * k * count;
     timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
     hipError_t e = ss_launch_degree_reduce(d_c, msg1, msg2, d_out, count, dp, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
@@ -388,7 +512,7 @@ int ssnet_truncate(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, uint64_t s
     if (!ctx || !d_x || !d_out || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
     const int t = ctx->t, k = t + 1, n = ctx->n;
     const size_t need = ((size_t)k + n) * count * 8;
-    if (!ctx->ws || ctx->ws_bytes < need) return SSNET_EWORKSPACE;
+    if (!ws_fits(ctx, need)) return SSNET_EWORKSPACE;
     ss_tr_params tp = {};
     tp.n = n;
     tp.t = t;
@@ -399,8 +523,8 @@ int ssnet_truncate(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, uint64_t s
         tp.alphat_key[j - 1] = ss_key(ctx->seed, SSNET_DOM_MASK_ALPHAT, stream_id, 0, (u64)j);
         tp.gen_key[j - 1] = ss_key(ctx->seed, SSNET_DOM_TRUNC_GEN, stream_id, 0, (u64)j);
     }
-    for (int q = 0; q < k; q++) tp.lambda[q] = ctx->lambda_k[q];
-    u64 *u = (u64 *)ctx->ws, *wsh = u + (size_t)k * count;
+    for (int q = 0; q < k; q++) tp.ilambda[q] = ctx->ilambda_k[q];
+    u64 *u = (u64 *)ws_scratch(ctx), *wsh = u + (size_t)k * count;
     timed tm(ctx, SSNET_PROF_TRUNCATE);
     hipError_t e = ss_launch_truncate(d_x, u, wsh, d_out, count, tp, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);

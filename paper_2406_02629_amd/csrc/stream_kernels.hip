@@ -1,10 +1,9 @@
-// Bandwidth-bound element-wise kernels: GEN (Eq. 1), REC (Eq. 2), the three
-// steps of reshare degree reduction with RERAND (Sec. IV-B, IV-C) and the
-// three steps of masked truncation (Sec. VI-B).
+// Element-wise kernels: GEN (Eq. 1), REC (Eq. 2), reshare degree reduction with
+// RERAND (Sec. IV-B, IV-C) and masked truncation (Sec. VI-B).
 //
-// One thread owns VEC consecutive elements and walks over all parties of its
-// step, so every plane is read and written with unit stride across a wave and
-// the random coefficients of an element are drawn once, not once per party.
+// One thread owns VEC consecutive elements and walks over all parties, so every
+// plane is read and written with unit stride across a wave and the random
+// coefficients of an element are drawn once, not once per party.
 #include "kernels.hpp"
 
 namespace {
@@ -75,7 +74,8 @@ __global__ __launch_bounds__(BLOCK) void reconstruct_kernel(const u64 *__restric
 {
     const size_t e0 = ((size_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
     if (e0 >= count) return;
-    ss_acc acc[VEC];
+    pack_t<VEC> out;
+    ss_sacc acc[VEC];
 #pragma unroll
     for (int u = 0; u < VEC; u++) acc[u].clear();
 #pragma unroll
@@ -84,121 +84,172 @@ __global__ __launch_bounds__(BLOCK) void reconstruct_kernel(const u64 *__restric
             pack_t<VEC> s;
             s.load(shares + (size_t)rp.plane[i] * count + e0);
 #pragma unroll
-            for (int u = 0; u < VEC; u++) acc[u].mac(s.v[u], rp.lambda[i]);
+            for (int u = 0; u < VEC; u++) acc[u].mac(s.v[u], rp.ilambda[i]);
         }
     }
-    pack_t<VEC> out;
 #pragma unroll
-    for (int u = 0; u < VEC; u++) out.v[u] = acc[u].value();
+    for (int u = 0; u < VEC; u++) out.v[u] = rp.dinv == 1 ? acc[u].value() : ss_mul(acc[u].value(), rp.dinv);
     out.store(secret + e0);
 }
 
-// ------------------------------------------------------------------ RED step 1
-// party i = blockIdx.y + 1 re-shares its value towards parties 1..k
+// ------------------------------------------------------------------ RED + RERAND
+// The three protocol steps for the elements a thread owns.  All parties are
+// simulated by that one thread, so a message is written to the workspace (the
+// "send") and consumed from registers (the "receive"); arithmetic and message
+// contents are exactly those of the per-party steps:
+//   1. party i = 1..2t+1: sub-shares of c_i for parties q = 1..k     -> msg1[i][q]
+//   2. party q: received row vector times R, applied in factored form
+//      R = B^-1[:, :k] * V (V[j][m] = m^j): first the k low coefficients of the
+//      polynomial through the received values, then its value at every party
+//      ID -- same residues as the (2t+1) x n product                 -> msg2[q][m]
+//   3. party m: REC of the k received values, plus its share of zero  -> out[m]
 template <int VEC>
-__global__ __launch_bounds__(BLOCK) void dr1_kernel(const u64 *__restrict__ c, u64 *__restrict__ msg1,
-                                                    size_t count, ss_dr_params dp)
+__global__ __launch_bounds__(BLOCK) void degree_reduce_kernel(const u64 *c, u64 *__restrict__ msg1,
+                                                              u64 *__restrict__ msg2, u64 *out, size_t count,
+                                                              ss_dr_params dp)
 {
     const size_t e0 = ((size_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
     if (e0 >= count) return;
-    const int i = blockIdx.y, k = dp.t + 1;
-    pack_t<VEC> ci;
-    ci.load(c + (size_t)i * count + e0);
-    u64 r[VEC][SS_MAXT];
-#pragma unroll
-    for (int u = 0; u < VEC; u++) draw_coeffs<SS_MAXT>(r[u], dp.reshare_key[i], dp.t, e0 + u);
-#pragma unroll
-    for (int q = 0; q < SS_MAXK; q++) {
-        if (q < k) {
-            pack_t<VEC> s;
-#pragma unroll
-            for (int u = 0; u < VEC; u++) s.v[u] = ss_poly_eval<SS_MAXT>(ci.v[u], r[u], dp.t, q + 1);
-            s.store(msg1 + ((size_t)i * k + q) * count + e0);
-        }
-    }
-}
+    const int k = dp.t + 1, nr = 2 * dp.t + 1;
 
-// ------------------------------------------------------------------ RED step 2
-// party q = blockIdx.y + 1 multiplies the row vector it received by R.  R is
-// applied in factored form R = B^-1[:, :k] * V (V[j][m] = (m+1)^j): first the k
-// low coefficients of the polynomial through the received values, then its
-// value at every party ID.  Same residues as the n x n product, k*(2t+1) wide
-// multiplications instead of n*(2t+1).
-template <int VEC>
-__global__ __launch_bounds__(BLOCK) void dr2_kernel(const u64 *__restrict__ msg1, u64 *__restrict__ msg2,
-                                                    size_t count, ss_dr_params dp)
-{
-    const size_t e0 = ((size_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
-    if (e0 >= count) return;
-    const int q = blockIdx.y, k = dp.t + 1, nr = 2 * dp.t + 1;
-    ss_acc acc[VEC][SS_MAXK];
+    // step 1 fused with the accumulation of step 2: coef[q][j] = sum_i msg1[i][q] * binv[i][j]
+    ss_sacc coef[VEC][SS_MAXK][SS_MAXK];
 #pragma unroll
     for (int u = 0; u < VEC; u++)
 #pragma unroll
-        for (int j = 0; j < SS_MAXK; j++) acc[u][j].clear();
+        for (int q = 0; q < SS_MAXK; q++)
+#pragma unroll
+            for (int j = 0; j < SS_MAXK; j++) coef[u][q][j].clear();
 #pragma unroll
     for (int i = 0; i < 2 * SS_MAXT + 1; i++) {
         if (i < nr) {
-            pack_t<VEC> v;
-            v.load(msg1 + ((size_t)i * k + q) * count + e0);
+            pack_t<VEC> ci;
+            ci.load(c + (size_t)i * count + e0);
+            u64 r[VEC][SS_MAXT];
 #pragma unroll
-            for (int j = 0; j < SS_MAXK; j++)
-                if (j < k)
+            for (int u = 0; u < VEC; u++) draw_coeffs<SS_MAXT>(r[u], dp.reshare_key[i], dp.t, e0 + u);
 #pragma unroll
-                    for (int u = 0; u < VEC; u++) acc[u][j].mac(v.v[u], dp.binv[i][j]);
+            for (int q = 0; q < SS_MAXK; q++) {
+                if (q < k) {
+                    pack_t<VEC> s;
+#pragma unroll
+                    for (int u = 0; u < VEC; u++) {
+                        s.v[u] = ss_poly_eval<SS_MAXT>(ci.v[u], r[u], dp.t, q + 1);
+#pragma unroll
+                        for (int j = 0; j < SS_MAXK; j++)
+                            if (j < k) coef[u][q][j].mac(s.v[u], dp.ibinv[i][j]);
+                    }
+                    s.store(msg1 + ((size_t)i * k + q) * count + e0);
+                }
+            }
         }
     }
-    u64 a0[VEC], cf[VEC][SS_MAXT];
-#pragma unroll
-    for (int u = 0; u < VEC; u++) {
-        a0[u] = acc[u][0].value();
-#pragma unroll
-        for (int j = 1; j < SS_MAXK; j++) cf[u][j - 1] = (j < k) ? acc[u][j].value() : 0;
-    }
-#pragma unroll
-    for (int m = 0; m < SS_MAXN; m++) {
-        if (m < dp.n) {
-            pack_t<VEC> s;
-#pragma unroll
-            for (int u = 0; u < VEC; u++) s.v[u] = ss_poly_eval<SS_MAXT>(a0[u], cf[u], dp.t, m + 1);
-            s.store(msg2 + ((size_t)q * dp.n + m) * count + e0);
-        }
-    }
-}
 
-// ------------------------------------------------------------------ RED step 3 + RERAND
-template <int VEC>
-__global__ __launch_bounds__(BLOCK) void dr3_kernel(const u64 *__restrict__ msg2, u64 *__restrict__ out,
-                                                    size_t count, ss_dr_params dp)
-{
-    const size_t e0 = ((size_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
-    if (e0 >= count) return;
-    const int k = dp.t + 1;
+    // rest of step 2, fused with the accumulation of step 3: red[m] = sum_q lambda_q msg2[q][m]
+    ss_sacc red[VEC][SS_MAXN];
+#pragma unroll
+    for (int u = 0; u < VEC; u++)
+#pragma unroll
+        for (int m = 0; m < SS_MAXN; m++) red[u][m].clear();
+#pragma unroll
+    for (int q = 0; q < SS_MAXK; q++) {
+        if (q < k) {
+            u64 a0[VEC], cf[VEC][SS_MAXT];
+#pragma unroll
+            for (int u = 0; u < VEC; u++) {
+                a0[u] = ss_mul(coef[u][q][0].value(), dp.dinv);
+#pragma unroll
+                for (int j = 1; j < SS_MAXK; j++) cf[u][j - 1] = (j < k) ? ss_mul(coef[u][q][j].value(), dp.dinv) : 0;
+            }
+#pragma unroll
+            for (int m = 0; m < SS_MAXN; m++) {
+                if (m < dp.n) {
+                    pack_t<VEC> s;
+#pragma unroll
+                    for (int u = 0; u < VEC; u++) {
+                        s.v[u] = ss_poly_eval<SS_MAXT>(a0[u], cf[u], dp.t, m + 1);
+                        red[u][m].mac(s.v[u], dp.ilambda[q]);
+                    }
+                    s.store(msg2 + ((size_t)q * dp.n + m) * count + e0);
+                }
+            }
+        }
+    }
+
+    // rest of step 3 and RERAND
     u64 z[VEC][SS_MAXT];
 #pragma unroll
     for (int u = 0; u < VEC; u++) draw_coeffs<SS_MAXT>(z[u], dp.zero_key, dp.t, e0 + u);
 #pragma unroll
     for (int m = 0; m < SS_MAXN; m++) {
         if (m < dp.n) {
-            ss_acc acc[VEC];
-#pragma unroll
-            for (int u = 0; u < VEC; u++) acc[u].clear();
-#pragma unroll
-            for (int q = 0; q < SS_MAXK; q++) {
-                if (q < k) {
-                    pack_t<VEC> v;
-                    v.load(msg2 + ((size_t)q * dp.n + m) * count + e0);
-#pragma unroll
-                    for (int u = 0; u < VEC; u++) acc[u].mac(v.v[u], dp.lambda[q]);
-                }
-            }
             pack_t<VEC> s;
 #pragma unroll
             for (int u = 0; u < VEC; u++)
-                s.v[u] = ss_add(acc[u].value(), ss_poly_eval<SS_MAXT>(0, z[u], dp.t, m + 1));
+                s.v[u] = ss_add(red[u][m].value(), ss_poly_eval<SS_MAXT>(0, z[u], dp.t, m + 1));
             s.store(out + (size_t)m * count + e0);
         }
     }
+}
+
+// Same computation for small tensors, where the serial work of one thread per
+// element leaves most of the chip idle: a workgroup takes 32 elements and eight
+// party lanes per element.  Lane p first plays reducing party p+1 (step 1),
+// while lane 7 draws the coefficients of the zero sharing; then, after these
+// went through LDS, lane p plays receiving party p+1: it forms
+// the k values that parties 1..k would send it (step 2, with the full matrix R
+// instead of its factors, so that the lanes do not wait on each other) and
+// reconstructs from them (step 3, RERAND).  Messages and outputs are the same
+// residues as in degree_reduce_kernel.
+__global__ __launch_bounds__(BLOCK) void degree_reduce_lanes_kernel(const u64 *c, u64 *__restrict__ msg1,
+                                                                    u64 *__restrict__ msg2, u64 *out, size_t count,
+                                                                    ss_dr_params dp)
+{
+    __shared__ u64 sub[2 * SS_MAXT + 1][SS_MAXK][32];
+    __shared__ u64 zero_coef[SS_MAXT][32];
+    const int el = threadIdx.x & 31, p = threadIdx.x >> 5;
+    const size_t e = (size_t)blockIdx.x * 32 + el;
+    const bool live = e < count;
+    const int k = dp.t + 1, nr = 2 * dp.t + 1;
+    if (live && p < nr) {
+        const u64 ci = c[(size_t)p * count + e];
+        u64 r[SS_MAXT];
+        draw_coeffs<SS_MAXT>(r, dp.reshare_key[p], dp.t, e);
+#pragma unroll
+        for (int q = 0; q < SS_MAXK; q++) {
+            if (q < k) {
+                const u64 v = ss_poly_eval<SS_MAXT>(ci, r, dp.t, q + 1);
+                sub[p][q][el] = v;
+                msg1[((size_t)p * k + q) * count + e] = v;
+            }
+        }
+    } else if (live && p == 7) {   // lane 7 never reduces (2t+1 <= 7): it draws the zero sharing for all
+        u64 z[SS_MAXT];
+        draw_coeffs<SS_MAXT>(z, dp.zero_key, dp.t, e);
+#pragma unroll
+        for (int j = 0; j < SS_MAXT; j++) zero_coef[j][el] = z[j];
+    }
+    __syncthreads();
+    if (!live || p >= dp.n) return;
+    ss_sacc red;
+    red.clear();
+#pragma unroll
+    for (int q = 0; q < SS_MAXK; q++) {
+        if (q < k) {
+            ss_sacc acc;
+            acc.clear();
+#pragma unroll
+            for (int i = 0; i < 2 * SS_MAXT + 1; i++)
+                if (i < nr) acc.mac(sub[i][q][el], dp.irmat[i][p]);
+            const u64 v = ss_mul(acc.value(), dp.dinv);
+            msg2[((size_t)q * dp.n + p) * count + e] = v;
+            red.mac(v, dp.ilambda[q]);
+        }
+    }
+    u64 z[SS_MAXT];
+#pragma unroll
+    for (int j = 0; j < SS_MAXT; j++) z[j] = zero_coef[j][el];
+    out[(size_t)p * count + e] = ss_add(red.value(), ss_poly_eval<SS_MAXT>(0, z, dp.t, p + 1));
 }
 
 // ------------------------------------------------------------------ truncation
@@ -207,19 +258,27 @@ __device__ __forceinline__ u64 mask_e(u64 key, u64 e, int f)
     return 1 + ((ss_draw(key, e) >> 3) & ((1ULL << (32 - f)) - 1));
 }
 
-// step 1: parties 1..k add their share of alpha = e * 2^f
+// The three steps of masked truncation for the elements a thread owns, with
+// the same send-to-workspace / receive-from-registers convention as above:
+//   1. parties q = 1..k add their share of alpha = e * 2^f          -> umsg[q]
+//   2. the elite party reconstructs x + alpha, divides by 2^f with floor on
+//      the signed value and shares the quotient                      -> wsh[m]
+//   3. every party m adds its share of alpha~ = -e                   -> out[m]
 template <int VEC>
-__global__ __launch_bounds__(BLOCK) void tr1_kernel(const u64 *__restrict__ x, u64 *__restrict__ umsg,
-                                                    size_t count, ss_tr_params tp)
+__global__ __launch_bounds__(BLOCK) void truncate_kernel(const u64 *x, u64 *__restrict__ umsg,
+                                                         u64 *__restrict__ wsh, u64 *out, size_t count,
+                                                         ss_tr_params tp)
 {
     const size_t e0 = ((size_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
     if (e0 >= count) return;
     const int k = tp.t + 1;
-    u64 alpha[VEC], ca[VEC][SS_MAXT];
+    u64 ev[VEC], ca[VEC][SS_MAXT];
+    ss_sacc acc[VEC];
 #pragma unroll
     for (int u = 0; u < VEC; u++) {
-        alpha[u] = mask_e(tp.e_key, e0 + u, tp.f) << tp.f;
+        ev[u] = mask_e(tp.e_key, e0 + u, tp.f);
         draw_coeffs<SS_MAXT>(ca[u], tp.alpha_key, tp.t, e0 + u);
+        acc[u].clear();
     }
 #pragma unroll
     for (int q = 0; q < SS_MAXK; q++) {
@@ -227,79 +286,43 @@ __global__ __launch_bounds__(BLOCK) void tr1_kernel(const u64 *__restrict__ x, u
             pack_t<VEC> xv, s;
             xv.load(x + (size_t)q * count + e0);
 #pragma unroll
-            for (int u = 0; u < VEC; u++)
-                s.v[u] = ss_add(xv.v[u], ss_poly_eval<SS_MAXT>(alpha[u], ca[u], tp.t, q + 1));
+            for (int u = 0; u < VEC; u++) {
+                s.v[u] = ss_add(xv.v[u], ss_poly_eval<SS_MAXT>(ev[u] << tp.f, ca[u], tp.t, q + 1));
+                acc[u].mac(s.v[u], tp.ilambda[q]);
+            }
             s.store(umsg + (size_t)q * count + e0);
         }
     }
-}
-
-// step 2: the elite party reconstructs x + alpha, divides by 2^f with floor on
-// the signed value, and shares the quotient
-template <int VEC>
-__global__ __launch_bounds__(BLOCK) void tr2_kernel(const u64 *__restrict__ umsg, u64 *__restrict__ wsh,
-                                                    size_t count, ss_tr_params tp)
-{
-    const size_t e0 = ((size_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
-    if (e0 >= count) return;
-    const int k = tp.t + 1;
-    ss_acc acc[VEC];
-#pragma unroll
-    for (int u = 0; u < VEC; u++) acc[u].clear();
-#pragma unroll
-    for (int q = 0; q < SS_MAXK; q++) {
-        if (q < k) {
-            pack_t<VEC> v;
-            v.load(umsg + (size_t)q * count + e0);
-#pragma unroll
-            for (int u = 0; u < VEC; u++) acc[u].mac(v.v[u], tp.lambda[q]);
-        }
-    }
-    u64 w[VEC], cw[VEC][SS_MAXT];
+    u64 w[VEC], at[VEC], cw[VEC][SS_MAXT], cat[VEC][SS_MAXT];
 #pragma unroll
     for (int u = 0; u < VEC; u++) {
         const u64 v = acc[u].value();
-        const int64_t s = (v <= (SS_P - 1) / 2) ? (int64_t)v : (int64_t)v - (int64_t)SS_P;
-        const int64_t qv = s >> tp.f;
+        const int64_t sv = (v <= (SS_P - 1) / 2) ? (int64_t)v : (int64_t)v - (int64_t)SS_P;
+        const int64_t qv = sv >> tp.f;
         w[u] = qv >= 0 ? (u64)qv : SS_P - (u64)(-qv);
+        at[u] = SS_P - ev[u];
         draw_coeffs<SS_MAXT>(cw[u], tp.gen_key, tp.t, e0 + u);
-    }
-#pragma unroll
-    for (int m = 0; m < SS_MAXN; m++) {
-        if (m < tp.n) {
-            pack_t<VEC> s;
-#pragma unroll
-            for (int u = 0; u < VEC; u++) s.v[u] = ss_poly_eval<SS_MAXT>(w[u], cw[u], tp.t, m + 1);
-            s.store(wsh + (size_t)m * count + e0);
-        }
-    }
-}
-
-// step 3: every party adds its share of alpha~ = -e
-template <int VEC>
-__global__ __launch_bounds__(BLOCK) void tr3_kernel(const u64 *__restrict__ wsh, u64 *__restrict__ out,
-                                                    size_t count, ss_tr_params tp)
-{
-    const size_t e0 = ((size_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
-    if (e0 >= count) return;
-    u64 at[VEC], cat[VEC][SS_MAXT];
-#pragma unroll
-    for (int u = 0; u < VEC; u++) {
-        at[u] = SS_P - mask_e(tp.e_key, e0 + u, tp.f);
         draw_coeffs<SS_MAXT>(cat[u], tp.alphat_key, tp.t, e0 + u);
     }
 #pragma unroll
     for (int m = 0; m < SS_MAXN; m++) {
         if (m < tp.n) {
-            pack_t<VEC> wv, s;
-            wv.load(wsh + (size_t)m * count + e0);
+            pack_t<VEC> ws, s;
 #pragma unroll
-            for (int u = 0; u < VEC; u++)
-                s.v[u] = ss_add(wv.v[u], ss_poly_eval<SS_MAXT>(at[u], cat[u], tp.t, m + 1));
+            for (int u = 0; u < VEC; u++) {
+                ws.v[u] = ss_poly_eval<SS_MAXT>(w[u], cw[u], tp.t, m + 1);
+                s.v[u] = ss_add(ws.v[u], ss_poly_eval<SS_MAXT>(at[u], cat[u], tp.t, m + 1));
+            }
+            ws.store(wsh + (size_t)m * count + e0);
             s.store(out + (size_t)m * count + e0);
         }
     }
 }
+
+// below this many elements one element per thread gives more waves to hide latency
+constexpr size_t VEC2_MIN_COUNT = (size_t)1 << 20;
+// below this many elements degree reduction spreads an element over party lanes
+constexpr size_t LANES_MAX_COUNT = (size_t)1 << 20;
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
@@ -342,24 +365,21 @@ hipError_t ss_launch_reconstruct(const u64 *shares, u64 *secret, size_t count, c
 hipError_t ss_launch_degree_reduce(const u64 *c, u64 *msg1, u64 *msg2, u64 *out, size_t count,
                                    const ss_dr_params &dp, hipStream_t stream)
 {
-    const bool v2 = (count % 2 == 0) && aligned16(c) && aligned16(msg1) && aligned16(msg2) && aligned16(out);
-    const int k = dp.t + 1, nr = 2 * dp.t + 1;
-    auto g1 = [&](int vec) { return dim3(blocks_for(count, vec), nr); };
-    auto g2 = [&](int vec) { return dim3(blocks_for(count, vec), k); };
-    auto g3 = [&](int vec) { return dim3(blocks_for(count, vec)); };
-    SS_DISPATCH_VEC(v2, dr1_kernel, g1, c, msg1, count, dp);
-    SS_DISPATCH_VEC(v2, dr2_kernel, g2, (const u64 *)msg1, msg2, count, dp);
-    SS_DISPATCH_VEC(v2, dr3_kernel, g3, (const u64 *)msg2, out, count, dp);
+    if (count < LANES_MAX_COUNT)
+        hipLaunchKernelGGL(degree_reduce_lanes_kernel, dim3((unsigned)((count + 31) / 32)), dim3(BLOCK), 0, stream, c,
+                           msg1, msg2, out, count, dp);
+    else   // one element per thread: the k*k + n wide accumulators of two elements would not fit the register file
+        hipLaunchKernelGGL(degree_reduce_kernel<1>, dim3(blocks_for(count, 1)), dim3(BLOCK), 0, stream, c, msg1, msg2,
+                           out, count, dp);
     return hipGetLastError();
 }
 
 hipError_t ss_launch_truncate(const u64 *x, u64 *u, u64 *wsh, u64 *out, size_t count, const ss_tr_params &tp,
                               hipStream_t stream)
 {
-    const bool v2 = (count % 2 == 0) && aligned16(x) && aligned16(u) && aligned16(wsh) && aligned16(out);
+    const bool v2 = (count % 2 == 0) && aligned16(x) && aligned16(u) && aligned16(wsh) && aligned16(out) &&
+                    count >= VEC2_MIN_COUNT;
     auto grid = [&](int vec) { return dim3(blocks_for(count, vec)); };
-    SS_DISPATCH_VEC(v2, tr1_kernel, grid, x, u, count, tp);
-    SS_DISPATCH_VEC(v2, tr2_kernel, grid, (const u64 *)u, wsh, count, tp);
-    SS_DISPATCH_VEC(v2, tr3_kernel, grid, (const u64 *)wsh, out, count, tp);
+    SS_DISPATCH_VEC(v2, truncate_kernel, grid, x, u, wsh, out, count, tp);
     return hipGetLastError();
 }

@@ -68,10 +68,29 @@ def test_degree_reduce_parity_with_messages(n, t):
         c = field_uniform((n, count), seed=count + 1)
         got = to_np(s.degree_reduce(to_dev(c), stream_id=count))
         want, msg1, msg2, red = orc.degree_reduce(c, n, t, P61, 42, count, full=True)
-        ws = to_np(s._ws[: (nr * k + k * n) * count * 8].view(torch.int64))
+        ws = to_np(s.messages()[: (nr * k + k * n) * count])
         assert np.array_equal(ws[: nr * k * count].reshape(nr, k, count), msg1)
         assert np.array_equal(ws[nr * k * count:].reshape(k, n, count), msg2)
         assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("n,t", [(3, 1), (5, 2)])
+def test_large_tensors_take_the_one_thread_per_element_kernels(n, t):
+    # above 2^20 elements degree reduction and truncation switch kernels
+    s = SSNet(n, t, seed=31)
+    count = (1 << 20) + 6
+    c = field_uniform((n, count), seed=11)
+    d = to_dev(c)
+    got = to_np(s.degree_reduce(d, stream_id=2))
+    want, msg1, msg2, red = orc.degree_reduce(c, n, t, P61, 31, 2, full=True)
+    k, nr = t + 1, 2 * t + 1
+    ws = to_np(s.messages()[: (nr * k + k * n) * count])
+    assert np.array_equal(ws[: nr * k * count].reshape(nr, k, count), msg1)
+    assert np.array_equal(ws[nr * k * count:].reshape(k, n, count), msg2)
+    assert np.array_equal(got, want)
+    xs = np.random.default_rng(4).integers(-(1 << 50), 1 << 50, count, dtype=np.int64)
+    xsh = orc.share(np.where(xs < 0, xs + P61, xs).astype(np.uint64), n, t, P61, 31, 1)
+    assert np.array_equal(to_np(s.truncate(to_dev(xsh), stream_id=3)), orc.truncate(xsh, n, t, 13, P61, 31, 3))
 
 
 def test_degree_reduce_in_place_and_on_real_products():
@@ -100,7 +119,7 @@ def test_truncate_parity(n, t, f):
         xsh = orc.share(secret, n, t, P61, 99, 1)
         got = to_np(s.truncate(to_dev(xsh), stream_id=count))
         want, u, wsh = orc.truncate(xsh, n, t, f, P61, 99, count, full=True)
-        ws = to_np(s._ws[: (t + 1 + n) * count * 8].view(torch.int64))
+        ws = to_np(s.messages()[: (t + 1 + n) * count])
         assert np.array_equal(ws[: (t + 1) * count].reshape(t + 1, count), u)
         assert np.array_equal(ws[(t + 1) * count:].reshape(n, count), wsh)
         assert np.array_equal(got, want)

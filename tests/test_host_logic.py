@@ -63,13 +63,16 @@ def test_null_and_range_checks_before_any_launch():
 def test_workspace_sizes():
     s = SSNet(5, 2, device=None)
     # RED messages: [2t+1][k][count] + [k][n][count] field elements
-    assert s.workspace_bytes_stream(1000) >= (5 * 3 + 3 * 5) * 1000 * 8
+    hdr = binding.WS_HEADER_BYTES
+    assert s.workspace_bytes_stream(1000) >= hdr + (5 * 3 + 3 * 5) * 1000 * 8
     s3 = SSNet(3, 1, device=None)
-    assert s3.workspace_bytes_stream(1 << 20) == (3 * 2 + 2 * 3) * 8 << 20
+    assert s3.workspace_bytes_stream(1 << 20) == hdr + ((3 * 2 + 2 * 3) * 8 << 20)
     # limb tiles: 8 bytes per element, rows padded to 16 and K to 64
     assert s3.lib.ssnet_packed_weight_bytes(16, 64) == 8192
     assert s3.lib.ssnet_packed_weight_bytes(17, 65) == 4 * 8192
-    assert s3.workspace_bytes_linear(64, 256, 128) == 3 * (64 * 256 * 8 + 128 * 256 * 8)
+    # limb tiles of both operands, plus partial sums if the contraction is split
+    assert s3.workspace_bytes_linear(64, 256, 128) >= hdr + 3 * (64 * 256 * 8 + 128 * 256 * 8)
+    assert s3.workspace_bytes_linear(64, 64, 64) == hdr + 3 * (64 * 64 * 8 + 64 * 64 * 8)
 
 
 @pytest.mark.parametrize("n,t", [(3, 1), (5, 2), (7, 3), (5, 1), (8, 3)])
