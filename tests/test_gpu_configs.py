@@ -1,0 +1,213 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py
+times (same classes, same packed weights, same buffers).
+
+The oracle side is a plain numpy/ctypes chain that shares no code with the
+harness in paper_2406_02629_amd/chain.py: it draws the same seeded floats,
+encodes, shares and evaluates every layer with the CPU oracle, and applies the
+plaintext steps (ReLU, max-pool, global average) in numpy.
+"""
+import os
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+from paper_2406_02629_amd import SSNet
+from paper_2406_02629_amd import fixedpoint as fx
+from paper_2406_02629_amd.chain import WEIGHT_STREAM_BASE, Chain, post_plain
+from ssnet_inputs import gaussian, he_normal, resnet_chain, uniform_below
+from util import P61, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    """progress line: to stdout and, because pytest captures stdout, also to a
+    file that a watcher of long runs can see growing"""
+    print(*a, flush=True)
+    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(d):
+        with open(os.path.join(d, "test_progress.log"), "a") as fh:
+            fh.write(" ".join(str(x) for x in a) + "\n")
+
+
+# ------------------------------------------------------------------ oracle-side plaintext steps
+def np_post(y, post):
+    """y: signed int64 [B, C, H, W]"""
+    if post is None:
+        return y
+    y = np.maximum(y, 0)
+    if post == "relu":
+        return y
+    if post == "relu+maxpool3s2":
+        B, C, H, W = y.shape
+        Ho, Wo = (H + 2 - 3) // 2 + 1, (W + 2 - 3) // 2 + 1
+        pad = np.zeros((B, C, H + 2, W + 2), np.int64)      # values are >= 0 after ReLU
+        pad[:, :, 1:-1, 1:-1] = y
+        out = np.zeros((B, C, Ho, Wo), np.int64)
+        for r in range(3):
+            for s in range(3):
+                out = np.maximum(out, pad[:, :, r:r + 2 * Ho:2, s:s + 2 * Wo:2])
+        return out
+    if post == "relu+gap":
+        return y.sum(axis=(-1, -2), keepdims=True) // (y.shape[-1] * y.shape[-2])
+    raise ValueError(post)
+
+
+def np_signed_to_field(v):
+    return np.where(v < 0, v + P61, v).astype(np.uint64)
+
+
+def oracle_layer(L, l, x_plain, n, t, f, seed, wseed_base=100):
+    """-> dict of the oracle's tensors for layer l given its plaintext input (field elements)"""
+    shape = (L.cout, L.cin, L.ksize, L.ksize) if L.kind == "conv" else (L.cin, L.cout)
+    w = orc.encode(he_normal(shape, L.K, wseed_base + l), f, P61)
+    ws = orc.share(w, n, t, P61, seed, WEIGHT_STREAM_BASE + l)
+    xs = orc.share(x_plain, n, t, P61, seed, l)
+    if L.kind == "conv":
+        y2 = orc.conv(xs, ws, L.stride, L.pad, P61)
+    else:
+        y2 = orc.linear(xs, ws, P61)
+    yr = orc.degree_reduce(y2.reshape(n, -1), n, t, P61, seed, l)
+    yt = orc.truncate(yr, n, t, f, P61, seed, l)
+    rec = orc.reconstruct(yt, list(range(1, t + 2)), P61).reshape(y2.shape[1:])
+    return {"xs": xs, "y2": y2, "yr": yr, "yt": yt, "rec": rec}
+
+
+def run_chain_parity(depth, n, t, f, seed, full_every=1):
+    layers = resnet_chain(depth)
+    ss = SSNet(n, t, f=f, seed=seed)
+    chain = Chain(ss, layers)
+    x_gpu = chain.image
+    x_orc = orc.encode(gaussian((1, 3, 224, 224), 5), f, P61)
+    assert np.array_equal(to_np(x_gpu), x_orc)
+    worst_float = 0.0
+    t0 = time.time()
+    for l, L in enumerate(layers):
+        if L.kind == "fc":
+            x_gpu = x_gpu.reshape(1, -1)
+            x_orc = x_orc.reshape(1, -1)
+        x_gpu = x_gpu.contiguous()
+        o = oracle_layer(L, l, x_orc, n, t, f, seed)
+        # the GPU layer, stage by stage, so that every intermediate share tensor can be compared
+        chain.run_layer(l, x_gpu, "sg")
+        assert np.array_equal(to_np(chain.x_shares[l]), o["xs"]), f"layer {l}: input shares"
+        assert np.array_equal(to_np(chain.y[l]), o["y2"]), f"layer {l}: conv/dense output"
+        chain.run_layer(l, x_gpu, "d")
+        if l % full_every == 0:
+            assert np.array_equal(to_np(chain.y[l]).reshape(n, -1), o["yr"]), f"layer {l}: degree_reduce"
+        chain.run_layer(l, x_gpu, "t")
+        assert np.array_equal(to_np(chain.y[l]).reshape(n, -1), o["yt"]), f"layer {l}: truncate"
+        rec = chain.run_layer(l, x_gpu, "r")
+        assert np.array_equal(to_np(rec), o["rec"]), f"layer {l}: reconstruct"
+        # decoded output vs a float64 pass of this layer on the decoded (dequantised) input
+        xin = orc.decode(x_orc, f, P61)
+        shape = (L.cout, L.cin, L.ksize, L.ksize) if L.kind == "conv" else (L.cin, L.cout)
+        wq = orc.decode(orc.encode(he_normal(shape, L.K, 100 + l), f, P61), f, P61)
+        if L.kind == "conv":
+            ref = torch.nn.functional.conv2d(torch.from_numpy(xin), torch.from_numpy(wq), stride=L.stride,
+                                             padding=L.pad).numpy()
+        else:
+            ref = xin @ wq
+        err = ref - orc.decode(o["rec"], f, P61)
+        lo, hi = float(err.min()), float(err.max())
+        assert lo > -2.0 ** -20 and hi < 2.0 ** -f + 2.0 ** -20, f"layer {l}: not a floor truncation {lo} {hi}"
+        worst_float = max(worst_float, float(np.abs(err).max()))
+        assert int(np.abs(orc.lift(o["rec"], P61)).max()) < 1 << 40       # fixed-point range is respected
+        # plaintext step between layers, on each side with its own code
+        if L.post is not None:
+            x_gpu = fx.from_signed(post_plain(fx.lift(rec), L.post))
+            x_orc = np_signed_to_field(np_post(orc.lift(o["rec"], P61), L.post))
+            assert np.array_equal(to_np(x_gpu), x_orc), f"layer {l}: plaintext step"
+        if l % 10 == 0:
+            say(f"resnet{depth} layer {l}/{len(layers)} ok ({time.time() - t0:.0f} s)")
+    assert worst_float < 2.0 ** -8
+    # the timed path (all stages back to back on the recorded inputs) reproduces the same outputs
+    chain.forward_prepare()
+    last = to_np(chain.rec[-1]).copy()
+    chain.forward_timed()
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(chain.rec[-1]), last)
+    assert np.array_equal(last, o["rec"])
+    return worst_float
+
+
+@pytest.mark.timeout(600)
+def test_config2_bulk_share_reconstruct_full_size():
+    """n=5, t=2, 2^28 uniform field elements: shares on sampled elements against the
+    oracle, both reconstructions equal to the secret everywhere."""
+    n, t, count, seed = 5, 2, 1 << 28, 2
+    secret_np = uniform_below(count, P61, 2)
+    secret = torch.from_numpy(secret_np.view(np.int64)).cuda()
+    ss = SSNet(n, t, seed=seed)
+    shares = ss.share(secret, stream_id=0)
+    rng = np.random.default_rng(0)
+    idx = np.unique(np.concatenate([np.arange(2048), np.arange(count - 2048, count),
+                                    rng.integers(0, count, 200000)])).astype(np.uint64)
+    got = to_np(shares[:, torch.from_numpy(idx.astype(np.int64)).cuda()])
+    want = orc.share(secret_np[idx.astype(np.int64)], n, t, P61, seed, 0, eidx=idx)
+    assert np.array_equal(got, want)
+    for ids in ([1, 2, 3], [3, 4, 5]):
+        rec = ss.reconstruct(shares, ids)
+        assert bool(torch.equal(rec, secret))
+        assert np.array_equal(to_np(rec[torch.from_numpy(idx.astype(np.int64)).cuda()]),
+                              orc.reconstruct(want, ids, P61))
+    # a corrupted share plane is detected by disagreement between subsets
+    shares[3, 12345] ^= 1
+    assert int(ss.reconstruct(shares, [3, 4, 5])[12345]) != int(secret[12345])
+    assert int(ss.reconstruct(shares, [1, 2, 3])[12345]) == int(secret[12345])
+
+
+@pytest.mark.timeout(600)
+def test_config3_resnet_conv_layer_full_size():
+    """n=3, t=1, f=13: batch 8 x 64x56x56, 3x3 64->64 stride 1 pad 1, then degree
+    reduction and truncation; every share plane against the oracle."""
+    n, t, f, seed = 3, 1, 13, 3
+    X = gaussian((8, 64, 56, 56), 3)
+    Wt = he_normal((64, 64, 3, 3), 576, 4)
+    ss = SSNet(n, t, f=f, seed=seed)
+    xe, we = orc.encode(X, f, P61), orc.encode(Wt, f, P61)
+    assert np.array_equal(to_np(fx.encode(torch.from_numpy(X).cuda(), f)), xe)
+    xs, ws = ss.share(to_dev(xe), stream_id=1), ss.share(to_dev(we), stream_id=2)
+    oxs, ows = orc.share(xe, n, t, P61, seed, 1), orc.share(we, n, t, P61, seed, 2)
+    assert np.array_equal(to_np(xs), oxs) and np.array_equal(to_np(ws), ows)
+    y2 = ss.conv_mod(xs, ws, 1, 1)
+    oy2 = orc.conv(oxs, ows, 1, 1, P61)
+    say("config3 oracle conv done")
+    assert np.array_equal(to_np(y2), oy2)
+    y2p = ss.conv_mod_packed(xs, ss.pack_weights_conv(ws), 64, 3, 3, 1, 1)
+    assert bool(torch.equal(y2, y2p))
+    yr = ss.degree_reduce(y2.view(n, -1), stream_id=3)
+    oyr = orc.degree_reduce(oy2.reshape(n, -1), n, t, P61, seed, 3)
+    assert np.array_equal(to_np(yr), oyr)
+    yt = ss.truncate(yr, stream_id=4)
+    oyt = orc.truncate(oyr, n, t, f, P61, seed, 4)
+    assert np.array_equal(to_np(yt), oyt)
+    rec = ss.reconstruct(yt, [1, 2])
+    assert np.array_equal(to_np(rec), orc.reconstruct(oyt, [1, 2], P61))
+    dec = fx.decode(rec, f).cpu().numpy().reshape(8, 64, 56, 56)
+    exact = torch.nn.functional.conv2d(torch.from_numpy(orc.decode(xe, f, P61)), torch.from_numpy(orc.decode(we, f, P61)),
+                                       padding=1).numpy()
+    # the gate: against float64 on the dequantised operands the result is the exact product floored
+    # to f fraction bits, far inside 2^-8
+    err = exact - dec
+    lo, hi = float(err.min()), float(err.max())
+    assert lo > -2.0 ** -20 and hi < 2.0 ** -f + 2.0 ** -20, (lo, hi)
+    # reported, not gated: against the un-quantised floats the input rounding alone (2^-14 per operand,
+    # 576 terms) already reaches about 2^-8 in the worst of 1.6 M outputs
+    plain = torch.nn.functional.conv2d(torch.from_numpy(X), torch.from_numpy(Wt), padding=1).numpy()
+    say("config3 max |decoded - unquantised float64| =", float(np.abs(dec - plain).max()))
+
+
+@pytest.mark.timeout(900)
+def test_config4_resnet50_stack():
+    worst = run_chain_parity(50, 5, 2, 13, seed=20240602)
+    say("resnet50 worst per-layer |decoded - float64| =", worst)
+
+
+@pytest.mark.timeout(1500)
+def test_config5_resnet152_stack():
+    worst = run_chain_parity(152, 5, 2, 13, seed=20240602)
+    say("resnet152 worst per-layer |decoded - float64| =", worst)
