@@ -117,6 +117,15 @@ SS_HD u64 ss_draw_field(u64 key, u64 e)
     return r == SS_P ? 0 : r;
 }
 
+// the same draws from the element's counter word (e+1)*GAMMA, which all keys of an element share
+SS_HD u64 ss_counter(u64 e) { return (e + 1) * SS_GAMMA; }
+SS_HD u64 ss_draw_at(u64 key, u64 counter) { return ss_mix64(key + counter); }
+SS_HD u64 ss_draw_field_at(u64 key, u64 counter)
+{
+    u64 r = ss_draw_at(key, counter) >> 3;
+    return r == SS_P ? 0 : r;
+}
+
 // polynomial a0 + c[0] x + ... + c[d-1] x^d at the small point x (1..8), by
 // Horner.  MAXD bounds d at compile time so that c[] stays in registers.
 template <int MAXD>

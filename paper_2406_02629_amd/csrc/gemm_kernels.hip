@@ -22,43 +22,38 @@ constexpr u64 BAL = 0x8080808080808080ULL;
 // balanced digits of x as 8 signed bytes
 __device__ __forceinline__ u64 balanced_digits(u64 x) { return (x + BAL) ^ BAL; }
 
-// bytes `limb` of 16 digit words -> one 16-byte MFMA operand row
-__device__ __forceinline__ v4i gather_limb(const u64 (&y)[16], int limb)
+// Digit words of four consecutive contraction indices -> one dword per limb
+// (byte c of dword `limb` is digit `limb` of y[c]) and store them: the thread
+// owns bytes [4*(kq%4), +4) of lane (row + 16*(kq/4)) in each of the eight limb
+// slices of its tile.
+__device__ __forceinline__ void store_digits(const u64 (&y)[4], v4i *tile, int row, int kq)
 {
-    v4i o;
+    u32 *base = reinterpret_cast<u32 *>(tile) + (row + 16 * (kq >> 2)) * 4 + (kq & 3);
 #pragma unroll
-    for (int w = 0; w < 4; w++) {
-        u32 acc = 0;
-#pragma unroll
-        for (int c = 0; c < 4; c++) acc |= (u32)((y[4 * w + c] >> (8 * limb)) & 0xFF) << (8 * c);
-        o[w] = (int)acc;
+    for (int limb = 0; limb < 8; limb++) {
+        const int i = limb & 3;
+        const u32 a = limb < 4 ? (u32)y[0] : (u32)(y[0] >> 32), b = limb < 4 ? (u32)y[1] : (u32)(y[1] >> 32);
+        const u32 c = limb < 4 ? (u32)y[2] : (u32)(y[2] >> 32), d = limb < 4 ? (u32)y[3] : (u32)(y[3] >> 32);
+        // v_perm_b32: selector byte k picks byte k of {second operand (0..3), first operand (4..7)}; 0x0c = zero
+        const u32 sel = (u32)i | ((u32)(4 + i) << 8) | 0x0c0c0000u;
+        const u32 ab = __builtin_amdgcn_perm(b, a, sel), cd = __builtin_amdgcn_perm(d, c, sel);
+        base[limb * 256] = __builtin_amdgcn_perm(cd, ab, 0x05040100u);
     }
-    return o;
 }
 
-__device__ __forceinline__ void store_tiles(const u64 (&y)[16], v4i *dst, int rb, int kb, int Kb, int lane)
-{
-    v4i *tile = dst + ((size_t)rb * Kb + kb) * 512 + lane;
-#pragma unroll
-    for (int limb = 0; limb < 8; limb++) tile[limb * 64] = gather_limb(y, limb);
-}
-
-// grid (Rb, ceil(Kb/4), n), block (64, 4): one wave per (row block, k block)
+// One workgroup per (row block, k block) tile, one thread per (row, 4 contraction indices).
+// grid (Rb, Kb, n), block 256: thread t -> row t%16, k group t/16.
 __global__ __launch_bounds__(256) void pack_matrix_kernel(const u64 *__restrict__ src, v4i *__restrict__ dst,
                                                           int rows, int K, int Kb, size_t party_stride,
                                                           size_t stride_r, size_t stride_k, size_t dst_party_stride)
 {
-    const int lane = threadIdx.x, kb = blockIdx.y * 4 + threadIdx.y, rb = blockIdx.x;
-    if (kb >= Kb) return;
-    const int row = rb * 16 + (lane & 15), k0 = kb * 64 + 16 * (lane >> 4);
+    const int rb = blockIdx.x, kb = blockIdx.y, r16 = threadIdx.x & 15, kq = threadIdx.x >> 4;
+    const int row = rb * 16 + r16, k0 = kb * 64 + 4 * kq;
     const u64 *s = src + (size_t)blockIdx.z * party_stride + (size_t)row * stride_r;
-    u64 y[16];
+    u64 y[4];
 #pragma unroll
-    for (int b = 0; b < 16; b++) {
-        const int k = k0 + b;
-        y[b] = (row < rows && k < K) ? balanced_digits(s[(size_t)k * stride_k]) : 0;
-    }
-    store_tiles(y, dst + (size_t)blockIdx.z * dst_party_stride, rb, kb, Kb, lane);
+    for (int c = 0; c < 4; c++) y[c] = (row < rows && k0 + c < K) ? balanced_digits(s[(size_t)(k0 + c) * stride_k]) : 0;
+    store_digits(y, dst + (size_t)blockIdx.z * dst_party_stride + ((size_t)rb * Kb + kb) * 512, r16, kq);
 }
 
 // rows = (b, ho, wo), k = (c, r, s) gathered from x [n][B][C][H][W]; zero padding
@@ -66,35 +61,51 @@ __global__ __launch_bounds__(256) void pack_im2col_kernel(const u64 *__restrict_
                                                           int C, int H, int W, int kh, int kw, int stride, int pad,
                                                           int Ho, int Wo, int Kb, size_t dst_party_stride)
 {
-    const int lane = threadIdx.x, kb = blockIdx.y * 4 + threadIdx.y, rb = blockIdx.x;
-    if (kb >= Kb) return;
+    const int rb = blockIdx.x, kb = blockIdx.y, r16 = threadIdx.x & 15, kq = threadIdx.x >> 4;
     const int M = B * Ho * Wo, K = C * kh * kw;
-    const int row = rb * 16 + (lane & 15), k0 = kb * 64 + 16 * (lane >> 4);
+    const int row = rb * 16 + r16, k0 = kb * 64 + 4 * kq;
     const u64 *xi = x + (size_t)blockIdx.z * B * C * H * W;
-    u64 y[16];
+    u64 y[4] = {0, 0, 0, 0};
     if (row < M) {
         const int wo = row % Wo, ho = (row / Wo) % Ho, b = row / (Wo * Ho);
         int c = k0 / (kh * kw), rs = k0 % (kh * kw), r = rs / kw, s = rs % kw;
 #pragma unroll
-        for (int q = 0; q < 16; q++) {
+        for (int q = 0; q < 4; q++) {
             const int hi = ho * stride - pad + r, wi = wo * stride - pad + s;
-            const bool ok = (k0 + q < K) && hi >= 0 && hi < H && wi >= 0 && wi < W;
-            y[q] = ok ? balanced_digits(xi[(((size_t)b * C + c) * H + hi) * W + wi]) : 0;
+            if (k0 + q < K && hi >= 0 && hi < H && wi >= 0 && wi < W)
+                y[q] = balanced_digits(xi[(((size_t)b * C + c) * H + hi) * W + wi]);
             if (++s == kw) { s = 0; if (++r == kh) { r = 0; ++c; } }
         }
-    } else {
-#pragma unroll
-        for (int q = 0; q < 16; q++) y[q] = 0;
     }
-    store_tiles(y, dst + (size_t)blockIdx.z * dst_party_stride, rb, kb, Kb, lane);
+    store_digits(y, dst + (size_t)blockIdx.z * dst_party_stride + ((size_t)rb * Kb + kb) * 512, r16, kq);
 }
 
+#ifdef SS_GEMM_TRACE
+// development aid: workgroup 0 records the shader clock at phase boundaries
+#define SS_TRACE(tag)                                                                 \
+    do {                                                                              \
+        if (g.trace && blockIdx.x == g.trace_block && tid == 0 && tn < 4000) {         \
+            g.trace[2 * tn] = tag;                                                    \
+            g.trace[2 * tn + 1] = __builtin_amdgcn_s_memtime();                       \
+            tn++;                                                                     \
+        }                                                                             \
+    } while (0)
+#else
+#define SS_TRACE(tag)
+#endif
+
 struct gemm_args {
+#ifdef SS_GEMM_TRACE
+    u64 *trace;
+    int trace_block;
+#endif
     const v4i *A, *B;          // packed operands, all parties
     u64 *out;
-    u64 *partials;             // [tile][S][64*64] field elements, used when S > 1
+    u64 *partials;             // [tile][slot][64*64] residues of tiles shared between workgroups
     unsigned *counters;        // [tile], zero between launches
-    int rows, cols, Rb, Cb, Kb, RT, CT, S;
+    int rows, cols, Rb, Cb, Kb, RT, CT;
+    unsigned units;            // tiles * Kb (< 2^31), or 0: one whole tile per workgroup
+    int slots;                 // partial slots per tile
     size_t a_party_stride, b_party_stride, out_party_stride, stride_row, stride_cb;
     int cdiv;
     u64 negbias;
@@ -116,129 +127,196 @@ __device__ __forceinline__ u64 fold_diagonals(const v4i (&acc)[15], int r, u64 n
     return ss_reduce(ss_fold(tot) + negbias);   // minus the 2^31 offsets
 }
 
-// One workgroup = 8 waves (4 x 2) = 64 x 64 field outputs over the k blocks
-// [kb0, kb1) of its split; wave (wr, wc) owns row block wr and column blocks
-// 2wc, 2wc+1 (2 x 15 accumulator tiles).  Per k block the workgroup needs four
-// row blocks of A and four column blocks of B, 8 KB each and already in MFMA
-// lane order, so wave w copies block w (A for w < 4, B otherwise) straight
-// into LDS with eight 1 KB global->LDS loads; two stages, the next block's
-// loads in flight during the 128 MFMAs per wave of the current one.
+// workgroup that owns unit x when `units` units are dealt to `G` workgroups in
+// contiguous ranges [g*units/G, (g+1)*units/G)
+__device__ __forceinline__ int owner_of(unsigned x, unsigned units, unsigned G)
+{
+    return (int)((((unsigned long long)x + 1) * G - 1) / units);
+}
+
+// this wave's source block of tile `tile`: block `wave` of A for waves 0..3, of
+// B for waves 4..7; blocks past the end are clamped (their products are
+// computed and never stored)
+__device__ __forceinline__ const v4i *tile_source(const gemm_args &g, unsigned tile, int wave, int lane)
+{
+    const int ct = (int)(tile % (unsigned)g.CT);
+    const unsigned rem = tile / (unsigned)g.CT;
+    const int rt = (int)(rem % (unsigned)g.RT), party = (int)(rem / (unsigned)g.RT);
+    if (wave < 4)
+        return g.A + (size_t)party * g.a_party_stride + (size_t)min(rt * 4 + wave, g.Rb - 1) * g.Kb * 512 + lane;
+    return g.B + (size_t)party * g.b_party_stride + (size_t)min(ct * 4 + wave - 4, g.Cb - 1) * g.Kb * 512 + lane;
+}
+
+// Persistent kernel, one workgroup of 8 waves (4 x 2) per CU.  The work is the
+// flat list of units (output tile of 64 x 64, k block of 64), tile-major; each
+// workgroup takes one contiguous range of it, so every CU gets the same number
+// of MFMAs whatever the layer shape, and a tile whose k range is cut by a range
+// boundary is finished by the hand-over below.  Wave (wr, wc) owns row block wr
+// and column blocks 2wc, 2wc+1 of the tile (2 x 15 accumulator tiles).
 //
-// With S > 1 splits of the contraction, every split stores its residues to the
-// partials buffer and bumps the tile's counter; the split that arrives last
-// adds the others' residues to its own and writes the output.  Integer sums
-// are exact, so the result does not depend on S or on arrival order.
+// Per unit the workgroup needs four row blocks of A and four column blocks of
+// B, 8 KB each and already in MFMA lane order, so wave w copies block w (A for
+// w < 4, B otherwise) straight into LDS with eight 1 KB global->LDS loads; two
+// stages, the next unit's loads (also across a tile boundary) in flight during
+// the 128 MFMAs per wave of the current one.
+//
+// Hand-over of a tile shared by several workgroups (which may sit on different
+// XCDs with separate L2s): each contributor folds its partial sums to residues,
+// stores them with agent-scope atomic stores, waits for these stores and bumps
+// the tile's counter; the contributor that arrives last adds the others'
+// residues (agent-scope atomic loads) to its own and writes the output.  No
+// cache-wide fence is used: it would evict the operand tiles that all other
+// workgroups are reusing.  Integer sums are exact, so the result does not
+// depend on how the units were dealt or on arrival order.
 __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
 {
     extern __shared__ v4i lds[];   // 2 stages x (4 A blocks + 4 B blocks) x 512
     __shared__ unsigned arrival;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wr = wave >> 1, wc = wave & 1;
-    int item = blockIdx.x;
-    const int ks = item % g.S;
-    item /= g.S;
-    const int ct = item % g.CT;
-    item /= g.CT;
-    const int rt = item % g.RT, party = item / g.RT;
-    const int kb0 = (int)((long)ks * g.Kb / g.S), kb1 = (int)((long)(ks + 1) * g.Kb / g.S);
-
-    // this wave's source block; blocks past the end are clamped (their
-    // products are computed and never stored)
-    const v4i *src;
-    if (wave < 4)
-        src = g.A + (size_t)party * g.a_party_stride + (size_t)min(rt * 4 + wave, g.Rb - 1) * g.Kb * 512 + lane;
-    else
-        src = g.B + (size_t)party * g.b_party_stride + (size_t)min(ct * 4 + wave - 4, g.Cb - 1) * g.Kb * 512 + lane;
+    const unsigned G = gridDim.x;
+#ifdef SS_GEMM_TRACE
+    int tn = 0;
+#endif
+    SS_TRACE(1);
+    // consecutive ranges go to workgroups of the same XCD (workgroups are dealt
+    // round-robin to the 8 XCDs), so that neighbours in the list share an L2
+    const unsigned slot = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
+    unsigned u0, u1;
+    if (g.units) {
+        u0 = (unsigned)((unsigned long long)slot * g.units / G);
+        u1 = (unsigned)((unsigned long long)(slot + 1) * g.units / G);
+    } else {   // one whole tile per workgroup; unit numbers are relative to it
+        u0 = 0;
+        u1 = (unsigned)g.Kb;
+    }
+    if (u0 >= u1) return;
     v4i *mine = lds + wave * 512;   // wave-uniform LDS destination of this wave's block
 
-    v4i acc[2][15];
+    unsigned tile = g.units ? u0 / (unsigned)g.Kb : slot;
+    int kb = (int)(u0 - (g.units ? tile * (unsigned)g.Kb : 0));
+    const v4i *src = tile_source(g, tile, wave, lane);
 #pragma unroll
-    for (int h = 0; h < 2; h++)
-#pragma unroll
-        for (int s = 0; s < 15; s++) acc[h][s] = (v4i){0, 0, 0, 0};
+    for (int q = 0; q < 8; q++) __builtin_amdgcn_global_load_lds(src + (size_t)kb * 512 + q * 64, mine + q * 64, 16, 0, 0);
+    int st = 0;
 
-#pragma unroll
-    for (int u = 0; u < 8; u++)
-        __builtin_amdgcn_global_load_lds(src + (size_t)kb0 * 512 + u * 64, mine + u * 64, 16, 0, 0);
-
-    for (int kb = kb0; kb < kb1; kb++) {
-        const int st = (kb - kb0) & 1;
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of block kb is in LDS
-        __syncthreads();                      // everyone's part is; stage st^1 is no longer read
-        if (kb + 1 < kb1) {
-#pragma unroll
-            for (int u = 0; u < 8; u++)
-                __builtin_amdgcn_global_load_lds(src + (size_t)(kb + 1) * 512 + u * 64,
-                                                 mine + (st ^ 1) * 4096 + u * 64, 16, 0, 0);
-        }
-        const v4i *sa = lds + st * 4096 + wr * 512 + lane;
-        const v4i *sb = lds + st * 4096 + 2048 + wc * 1024 + lane;
-        v4i a[8];
-#pragma unroll
-        for (int i = 0; i < 8; i++) a[i] = sa[i * 64];
-#pragma unroll
-        for (int h = 0; h < 2; h++) {
-            v4i b[8];
-#pragma unroll
-            for (int j = 0; j < 8; j++) b[j] = sb[h * 512 + j * 64];
-#pragma unroll
-            for (int i = 0; i < 8; i++)
-#pragma unroll
-                for (int j = 0; j < 8; j++)
-                    acc[h][i + j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[h][i + j], 0, 0, 0);
-        }
-    }
-
-    // lane holds, per column block h, column lane%16 and rows 4*(lane/16)+r
-    u64 v[2][4];
-#pragma unroll
-    for (int h = 0; h < 2; h++)
-#pragma unroll
-        for (int r = 0; r < 4; r++) v[h][r] = fold_diagonals(acc[h], r, g.negbias);
-
-    const int lrow = wr * 16 + 4 * (lane >> 4), lcol = wc * 32 + (lane & 15);   // within the 64 x 64 tile
-    if (g.S > 1) {
-        // Hand-over between workgroups that may sit on different XCDs (separate
-        // L2s): the residues and the counter are moved with agent-scope atomic
-        // accesses, which are performed at the device's coherence point, and the
-        // counter is bumped only after this workgroup's stores have completed.
-        // No cache-wide fence is used: it would evict the operand tiles that all
-        // other workgroups are reusing.
-        const size_t tile = ((size_t)party * g.RT + rt) * g.CT + ct;
-        u64 *part = g.partials + (tile * g.S) * 4096;
+    unsigned u = u0;
+    while (u < u1) {
+        const int kb_first = kb;
+        v4i acc[2][15];
 #pragma unroll
         for (int h = 0; h < 2; h++)
 #pragma unroll
-            for (int r = 0; r < 4; r++)
-                __hip_atomic_store(&part[(size_t)ks * 4096 + (lrow + r) * 64 + lcol + 16 * h], v[h][r],
-                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the stores above are done
-        __syncthreads();
-        if (tid == 0)
-            arrival = __hip_atomic_fetch_add(&g.counters[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __syncthreads();
-        if (arrival != (unsigned)(g.S - 1)) return;
-        if (tid == 0) __hip_atomic_store(&g.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        for (int s = 0; s < g.S; s++) {
-            if (s == ks) continue;
+            for (int s = 0; s < 15; s++) acc[h][s] = (v4i){0, 0, 0, 0};
+
+        // units of this tile that belong to this workgroup
+        const int kb_end = min(g.Kb, kb + (int)(u1 - u));
+        const v4i *next_src = src;
+        for (; kb < kb_end; kb++, u++) {
+            SS_TRACE(2);
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of the unit is in LDS
+            SS_TRACE(3);
+            __syncthreads();                      // everyone's part is; stage st^1 is no longer read
+            SS_TRACE(4);
+            if (u + 1 < u1) {
+                int nkb = kb + 1;
+                if (nkb == g.Kb) {
+                    nkb = 0;
+                    next_src = tile_source(g, tile + 1, wave, lane);
+                }
+#pragma unroll
+                for (int q = 0; q < 8; q++)
+                    __builtin_amdgcn_global_load_lds(next_src + (size_t)nkb * 512 + q * 64,
+                                                     mine + (st ^ 1) * 4096 + q * 64, 16, 0, 0);
+            }
+            const v4i *sa = lds + st * 4096 + wr * 512 + lane;
+            const v4i *sb = lds + st * 4096 + 2048 + wc * 1024 + lane;
+            v4i a[8];
+#pragma unroll
+            for (int i = 0; i < 8; i++) a[i] = sa[i * 64];
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                v4i b[8];
+#pragma unroll
+                for (int j = 0; j < 8; j++) b[j] = sb[h * 512 + j * 64];
+#pragma unroll
+                for (int i = 0; i < 8; i++)
+#pragma unroll
+                    for (int j = 0; j < 8; j++)
+                        acc[h][i + j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[h][i + j], 0, 0, 0);
+            }
+            st ^= 1;
+        }
+
+        SS_TRACE(5);
+        // lane holds, per column block h, column lane%16 and rows 4*(lane/16)+r
+        u64 v[2][4];
+#pragma unroll
+        for (int h = 0; h < 2; h++)
+#pragma unroll
+            for (int r = 0; r < 4; r++) v[h][r] = fold_diagonals(acc[h], r, g.negbias);
+
+        const int ct = (int)(tile % (unsigned)g.CT);
+        const unsigned rem = tile / (unsigned)g.CT;
+        const int rt = (int)(rem % (unsigned)g.RT), party = (int)(rem / (unsigned)g.RT);
+        const int lrow = wr * 16 + 4 * (lane >> 4), lcol = wc * 32 + (lane & 15);   // within the 64 x 64 tile
+        bool finish = true;
+        SS_TRACE(6);
+        if (kb_first != 0 || kb_end != g.Kb) {   // the tile is shared: uniform over the workgroup
+            const int first = owner_of(tile * (unsigned)g.Kb, g.units, G),
+                      last = owner_of((tile + 1) * (unsigned)g.Kb - 1, g.units, G);
+            u64 *part = g.partials + (size_t)tile * g.slots * 4096;
+            const int my = (int)slot - first;
 #pragma unroll
             for (int h = 0; h < 2; h++)
 #pragma unroll
                 for (int r = 0; r < 4; r++)
-                    v[h][r] = ss_add(v[h][r],
-                                     __hip_atomic_load(&part[(size_t)s * 4096 + (lrow + r) * 64 + lcol + 16 * h],
-                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                    __hip_atomic_store(&part[(size_t)my * 4096 + (lrow + r) * 64 + lcol + 16 * h], v[h][r],
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the stores above are done
+            SS_TRACE(7);
+            __syncthreads();
+            if (tid == 0)
+                arrival = __hip_atomic_fetch_add(&g.counters[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            finish = arrival == (unsigned)(last - first);
+            SS_TRACE(8);
+            if (finish) {
+                if (tid == 0) __hip_atomic_store(&g.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int s = 0; s <= last - first; s++) {
+                    if (s == my) continue;
+#pragma unroll
+                    for (int h = 0; h < 2; h++)
+#pragma unroll
+                        for (int r = 0; r < 4; r++)
+                            v[h][r] = ss_add(v[h][r],
+                                             __hip_atomic_load(&part[(size_t)s * 4096 + (lrow + r) * 64 + lcol + 16 * h],
+                                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                }
+            }
+            __syncthreads();   // `arrival` may be rewritten by the next tile
+        }
+        if (finish) {
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                const int col = ct * 64 + lcol + 16 * h;
+                u64 *op = g.out + (size_t)party * g.out_party_stride + (size_t)(col / g.cdiv) * g.stride_cb + (col % g.cdiv);
+#pragma unroll
+                for (int r = 0; r < 4; r++) {
+                    const int row = rt * 64 + lrow + r;
+                    if (row < g.rows && col < g.cols) op[(size_t)row * g.stride_row] = v[h][r];
+                }
+            }
+        }
+        SS_TRACE(9);
+        if (kb == g.Kb) {
+            kb = 0;
+            tile++;
+            src = next_src;
         }
     }
-#pragma unroll
-    for (int h = 0; h < 2; h++) {
-        const int col = ct * 64 + lcol + 16 * h;
-        u64 *op = g.out + (size_t)party * g.out_party_stride + (size_t)(col / g.cdiv) * g.stride_cb + (col % g.cdiv);
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-            const int row = rt * 64 + lrow + r;
-            if (row < g.rows && col < g.cols) op[(size_t)row * g.stride_row] = v[h][r];
-        }
-    }
+#ifdef SS_GEMM_TRACE
+    if (g.trace && blockIdx.x == g.trace_block && tid == 0) g.trace[8190] = tn;
+#endif
 }
 
 __global__ void zero_words_kernel(unsigned *p, size_t nwords)
@@ -255,36 +333,48 @@ u64 neg_bias()
     return ss_neg(b);
 }
 
+struct gemm_plan {
+    long tiles, units;
+    int Kb, G, slots;
+};
+
+// How the units are dealt: one workgroup per CU unless there are fewer units
+// than CUs; slots = the most workgroups that can share one tile.  When there are
+// more tiles than arrival counters every workgroup gets whole tiles.
+gemm_plan plan_gemm(int n, int rows, int cols, int K)
+{
+    gemm_plan p;
+    p.Kb = (K + 63) / 64;
+    p.tiles = (long)n * ((rows + 63) / 64) * ((cols + 63) / 64);
+    p.units = p.tiles * p.Kb;
+    if (p.tiles > SS_GEMM_MAX_SPLIT_TILES || p.units >= (1L << 31)) {
+        p.G = (int)(p.tiles < (1L << 30) ? p.tiles : 0);   // 0: not launchable, rejected by the caller
+        p.slots = 0;
+        p.units = 0;
+        return p;
+    }
+    p.G = (int)(p.units < SS_GEMM_CUS ? p.units : SS_GEMM_CUS);
+    const long per = p.units / p.G;
+    p.slots = (int)((p.Kb + per - 1) / per) + 1;
+    return p;
+}
+
 }  // namespace
 
-// Number of splits of the contraction: enough workgroups to occupy every CU a
-// few times over, but each split keeps at least two k blocks.  Modelled cost per
-// workgroup: a fixed part worth about 1.5 k blocks plus its k blocks; the CUs
-// take the workgroups in rounds.
-int ss_gemm_splits(int n, int rows, int cols, int K)
+#ifdef SS_GEMM_TRACE
+#include <stdlib.h>
+static u64 *ss_debug_trace = nullptr;
+extern "C" int ssnet_debug_trace_read(u64 *host, size_t n)
 {
-    const long tiles = (long)n * ((rows + 63) / 64) * ((cols + 63) / 64);
-    const int Kb = (K + 63) / 64;
-    if (tiles > SS_GEMM_MAX_SPLIT_TILES) return 1;
-    int best = 1;
-    double best_cost = 1e300;
-    for (int S = 1; S <= 32 && S <= Kb; S++) {
-        if (S > 1 && Kb / S < 2) break;
-        const long rounds = (tiles * S + SS_GEMM_CUS - 1) / SS_GEMM_CUS;
-        const double cost = (double)rounds * ((Kb + S - 1) / S + 1.5 + (S > 1 ? 0.5 : 0.0));
-        if (cost < best_cost - 1e-9) {
-            best_cost = cost;
-            best = S;
-        }
-    }
-    return best;
+    if (!ss_debug_trace) return -1;
+    return (int)hipMemcpy(host, ss_debug_trace, n * sizeof(u64), hipMemcpyDeviceToHost);
 }
+#endif
 
 size_t ss_gemm_scratch_bytes(int n, int rows, int cols, int K)
 {
-    const size_t tiles = (size_t)n * ((rows + 63) / 64) * ((cols + 63) / 64);
-    const int S = ss_gemm_splits(n, rows, cols, K);
-    return S > 1 ? tiles * S * 4096 * sizeof(u64) : 0;
+    const gemm_plan p = plan_gemm(n, rows, cols, K);
+    return (size_t)p.tiles * p.slots * 4096 * sizeof(u64);
 }
 
 hipError_t ss_launch_zero_counters(unsigned *counters, hipStream_t stream)
@@ -303,8 +393,8 @@ hipError_t ss_launch_pack_matrix(const u64 *src, void *dst, int n, int rows, int
                                  size_t stride_r, size_t stride_k, hipStream_t stream)
 {
     const int Rb = (rows + 15) / 16, Kb = (K + 63) / 64;
-    hipLaunchKernelGGL(pack_matrix_kernel, dim3(Rb, (Kb + 3) / 4, n), dim3(64, 4), 0, stream, src, (v4i *)dst, rows, K,
-                       Kb, party_stride, stride_r, stride_k, ss_packed_bytes(rows, K) / 16);
+    hipLaunchKernelGGL(pack_matrix_kernel, dim3(Rb, Kb, n), dim3(256), 0, stream, src, (v4i *)dst, rows, K, Kb,
+                       party_stride, stride_r, stride_k, ss_packed_bytes(rows, K) / 16);
     return hipGetLastError();
 }
 
@@ -313,8 +403,8 @@ hipError_t ss_launch_pack_im2col(const u64 *x, void *dst, int n, int B, int C, i
 {
     const int M = B * Ho * Wo, K = C * kh * kw;
     const int Rb = (M + 15) / 16, Kb = (K + 63) / 64;
-    hipLaunchKernelGGL(pack_im2col_kernel, dim3(Rb, (Kb + 3) / 4, n), dim3(64, 4), 0, stream, x, (v4i *)dst, B, C, H, W,
-                       kh, kw, stride, pad, Ho, Wo, Kb, ss_packed_bytes(M, K) / 16);
+    hipLaunchKernelGGL(pack_im2col_kernel, dim3(Rb, Kb, n), dim3(256), 0, stream, x, (v4i *)dst, B, C, H, W, kh, kw,
+                       stride, pad, Ho, Wo, Kb, ss_packed_bytes(M, K) / 16);
     return hipGetLastError();
 }
 
@@ -330,6 +420,8 @@ hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, in
         if (e != hipSuccess) return e;
         lds_opt_in = true;
     }
+    const gemm_plan p = plan_gemm(n, rows, cols, K);
+    if (p.G <= 0) return hipErrorInvalidValue;
     gemm_args g;
     g.A = (const v4i *)packedA;
     g.B = (const v4i *)packedB;
@@ -340,10 +432,11 @@ hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, in
     g.cols = cols;
     g.Rb = (rows + 15) / 16;
     g.Cb = (cols + 15) / 16;
-    g.Kb = (K + 63) / 64;
+    g.Kb = p.Kb;
     g.RT = (rows + 63) / 64;
     g.CT = (cols + 63) / 64;
-    g.S = ss_gemm_splits(n, rows, cols, K);
+    g.units = (unsigned)p.units;
+    g.slots = p.slots;
     g.a_party_stride = ss_packed_bytes(rows, K) / 16;
     g.b_party_stride = ss_packed_bytes(cols, K) / 16;
     g.out_party_stride = out_party_stride;
@@ -351,7 +444,13 @@ hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, in
     g.stride_cb = stride_cb;
     g.cdiv = cdiv;
     g.negbias = neg_bias();
-    const long items = (long)n * g.RT * g.CT * g.S;
-    hipLaunchKernelGGL(gemm_limb_kernel, dim3((unsigned)items), dim3(512), LDS_BYTES, stream, g);
+#ifdef SS_GEMM_TRACE
+    static u64 *trace_buf = nullptr;
+    if (!trace_buf && hipMalloc(&trace_buf, 8192 * sizeof(u64)) != hipSuccess) return hipErrorOutOfMemory;
+    g.trace = trace_buf;
+    g.trace_block = getenv("SS_TRACE_BLOCK") ? atoi(getenv("SS_TRACE_BLOCK")) : 0;
+    ss_debug_trace = trace_buf;
+#endif
+    hipLaunchKernelGGL(gemm_limb_kernel, dim3((unsigned)p.G), dim3(512), LDS_BYTES, stream, g);
     return hipGetLastError();
 }

@@ -59,12 +59,11 @@ hipError_t ss_launch_pack_matrix(const u64 *src, void *dst, int n, int rows, int
 hipError_t ss_launch_pack_im2col(const u64 *x, void *dst, int n, int B, int C, int H, int W, int kh, int kw,
                                  int stride, int pad, int Ho, int Wo, hipStream_t stream);
 // out[i][row*stride_row + (col / cdiv)*stride_cb + col % cdiv] = sum_k A_i[row][k] * B_i[col][k] mod p.
-// The contraction may be split over several workgroups per output tile
-// (ss_gemm_splits); then `partials` must hold ss_gemm_scratch_bytes and
-// `counters` SS_GEMM_MAX_SPLIT_TILES zeroed words (they are left zeroed).
+// An output tile may be shared by several workgroups; `partials` must hold
+// ss_gemm_scratch_bytes and `counters` SS_GEMM_MAX_SPLIT_TILES zeroed words
+// (they are left zeroed).
 #define SS_GEMM_MAX_SPLIT_TILES 16384
 #define SS_GEMM_CUS 256
-int ss_gemm_splits(int n, int rows, int cols, int K);
 size_t ss_gemm_scratch_bytes(int n, int rows, int cols, int K);
 hipError_t ss_launch_zero_counters(unsigned *counters, hipStream_t stream);
 hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, int n, int rows, int cols, int K,

@@ -39,28 +39,35 @@ struct pack_t<2> {
 template <int MAXD>
 __device__ __forceinline__ void draw_coeffs(u64 (&c)[MAXD], const u64 *keys, int d, u64 e)
 {
+    const u64 counter = ss_counter(e);
 #pragma unroll
-    for (int j = 0; j < MAXD; j++) c[j] = (j < d) ? ss_draw_field(keys[j], e) : 0;
+    for (int j = 0; j < MAXD; j++) c[j] = (j < d) ? ss_draw_field_at(keys[j], counter) : 0;
 }
 
 // ------------------------------------------------------------------ GEN
-template <int VEC>
+// NC, DC > 0 fix the party count and the degree at compile time (the schemes
+// the paper evaluates: (k,n) = (2,3) and (3,5)), so that the evaluation points
+// become immediates; 0 means "take the run-time value".
+template <int VEC, int NC, int DC>
 __global__ __launch_bounds__(BLOCK) void share_kernel(const u64 *__restrict__ secret, u64 *__restrict__ shares,
-                                                      size_t count, int n, int degree, ss_keys keys)
+                                                      size_t count, int n_rt, int degree_rt, ss_keys keys)
 {
+    constexpr int MAXD = DC ? DC : SS_MAXDEG;
+    constexpr int MAXP = NC ? NC : SS_MAXN;
+    const int n = NC ? NC : n_rt, degree = DC ? DC : degree_rt;
     const size_t e0 = ((size_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
     if (e0 >= count) return;
     pack_t<VEC> a0;
     a0.load(secret + e0);
-    u64 c[VEC][SS_MAXDEG];
+    u64 c[VEC][MAXD];
 #pragma unroll
-    for (int u = 0; u < VEC; u++) draw_coeffs<SS_MAXDEG>(c[u], keys.k, degree, e0 + u);
+    for (int u = 0; u < VEC; u++) draw_coeffs<MAXD>(c[u], keys.k, degree, e0 + u);
 #pragma unroll
-    for (int i = 1; i <= SS_MAXN; i++) {
+    for (int i = 1; i <= MAXP; i++) {
         if (i <= n) {
             pack_t<VEC> s;
 #pragma unroll
-            for (int u = 0; u < VEC; u++) s.v[u] = ss_poly_eval<SS_MAXDEG>(a0.v[u], c[u], degree, i);
+            for (int u = 0; u < VEC; u++) s.v[u] = ss_poly_eval<MAXD>(a0.v[u], c[u], degree, i);
             s.store(shares + (size_t)(i - 1) * count + e0);
         }
     }
@@ -348,8 +355,18 @@ hipError_t ss_launch_share(const u64 *secret, u64 *shares, size_t count, int n, 
                            hipStream_t stream)
 {
     const bool v2 = (count % 2 == 0) && aligned16(secret) && aligned16(shares);
-    auto grid = [&](int vec) { return dim3(blocks_for(count, vec)); };
-    SS_DISPATCH_VEC(v2, share_kernel, grid, secret, shares, count, n, degree, keys);
+    const dim3 grid(blocks_for(count, v2 ? 2 : 1)), block(BLOCK);
+#define SS_SHARE(VEC, NC, DC) \
+    hipLaunchKernelGGL((share_kernel<VEC, NC, DC>), grid, block, 0, stream, secret, shares, count, n, degree, keys)
+    if (v2 && n == 5 && degree == 2)
+        SS_SHARE(2, 5, 2);
+    else if (v2 && n == 3 && degree == 1)
+        SS_SHARE(2, 3, 1);
+    else if (v2)
+        SS_SHARE(2, 0, 0);
+    else
+        SS_SHARE(1, 0, 0);
+#undef SS_SHARE
     return hipGetLastError();
 }
 

@@ -70,9 +70,10 @@ def test_workspace_sizes():
     # limb tiles: 8 bytes per element, rows padded to 16 and K to 64
     assert s3.lib.ssnet_packed_weight_bytes(16, 64) == 8192
     assert s3.lib.ssnet_packed_weight_bytes(17, 65) == 4 * 8192
-    # limb tiles of both operands, plus partial sums if the contraction is split
+    # limb tiles of both operands, plus room for the residues of tiles shared between workgroups
     assert s3.workspace_bytes_linear(64, 256, 128) >= hdr + 3 * (64 * 256 * 8 + 128 * 256 * 8)
-    assert s3.workspace_bytes_linear(64, 64, 64) == hdr + 3 * (64 * 64 * 8 + 64 * 64 * 8)
+    assert s3.workspace_bytes_linear(64, 64, 64) >= hdr + 3 * (64 * 64 * 8 + 64 * 64 * 8)
+    assert s3.workspace_bytes_linear(64, 64, 64) < hdr + (1 << 20)
 
 
 @pytest.mark.parametrize("n,t", [(3, 1), (5, 2), (7, 3), (5, 1), (8, 3)])
