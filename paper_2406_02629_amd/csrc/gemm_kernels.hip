@@ -152,7 +152,8 @@ __device__ __forceinline__ const v4i *tile_source(const gemm_args &g, unsigned t
 // workgroup takes one contiguous range of it, so every CU gets the same number
 // of MFMAs whatever the layer shape, and a tile whose k range is cut by a range
 // boundary is finished by the hand-over below.  Wave (wr, wc) owns row block wr
-// and column blocks 2wc, 2wc+1 of the tile (2 x 15 accumulator tiles).
+// and column blocks 2wc, 2wc+1 of the tile (2 x 15 accumulator tiles); the two
+// waves of a SIMD differ in wc.
 //
 // Per unit the workgroup needs four row blocks of A and four column blocks of
 // B, 8 KB each and already in MFMA lane order, so wave w copies block w (A for
@@ -172,7 +173,7 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
 {
     extern __shared__ v4i lds[];   // 2 stages x (4 A blocks + 4 B blocks) x 512
     __shared__ unsigned arrival;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wr = wave >> 1, wc = wave & 1;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wr = wave & 3, wc = wave >> 2;
     const unsigned G = gridDim.x;
 #ifdef SS_GEMM_TRACE
     int tn = 0;
@@ -199,8 +200,17 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
     for (int q = 0; q < 8; q++) __builtin_amdgcn_global_load_lds(src + (size_t)kb * 512 + q * 64, mine + q * 64, 16, 0, 0);
     int st = 0;
 
+    // column blocks of this wave that lie inside the matrix (0 if its row block lies outside): MFMAs of
+    // blocks past the edge are skipped, so a ragged last tile costs only its valid part
+    auto valid_blocks = [&](unsigned t) {
+        const int ct = (int)(t % (unsigned)g.CT), rt = (int)(t / (unsigned)g.CT % (unsigned)g.RT);
+        if (rt * 4 + wr >= g.Rb) return 0;
+        return max(0, min(2, g.Cb - (ct * 4 + 2 * wc)));
+    };
+
     unsigned u = u0;
     while (u < u1) {
+        const int nblk = valid_blocks(tile);
         const int kb_first = kb;
         v4i acc[2][15];
 #pragma unroll
@@ -230,19 +240,33 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
             }
             const v4i *sa = lds + st * 4096 + wr * 512 + lane;
             const v4i *sb = lds + st * 4096 + 2048 + wc * 1024 + lane;
-            v4i a[8];
+            if (nblk == 2) {   // the usual case, kept free of branches so that loads and MFMAs interleave
+                v4i a[8];
 #pragma unroll
-            for (int i = 0; i < 8; i++) a[i] = sa[i * 64];
+                for (int i = 0; i < 8; i++) a[i] = sa[i * 64];
 #pragma unroll
-            for (int h = 0; h < 2; h++) {
-                v4i b[8];
+                for (int h = 0; h < 2; h++) {
+                    v4i b[8];
 #pragma unroll
-                for (int j = 0; j < 8; j++) b[j] = sb[h * 512 + j * 64];
+                    for (int j = 0; j < 8; j++) b[j] = sb[h * 512 + j * 64];
+#pragma unroll
+                    for (int i = 0; i < 8; i++)
+#pragma unroll
+                        for (int j = 0; j < 8; j++)
+                            acc[h][i + j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[h][i + j], 0, 0, 0);
+                }
+            } else if (nblk == 1) {   // ragged edge: only the first column block is inside the matrix
+                v4i a[8], b[8];
+#pragma unroll
+                for (int i = 0; i < 8; i++) {
+                    a[i] = sa[i * 64];
+                    b[i] = sb[i * 64];
+                }
 #pragma unroll
                 for (int i = 0; i < 8; i++)
 #pragma unroll
                     for (int j = 0; j < 8; j++)
-                        acc[h][i + j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[h][i + j], 0, 0, 0);
+                        acc[0][i + j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[0][i + j], 0, 0, 0);
             }
             st ^= 1;
         }

@@ -76,7 +76,7 @@ def test_degree_reduce_parity_with_messages(n, t):
 
 @pytest.mark.parametrize("n,t", [(3, 1), (5, 2)])
 def test_large_tensors_take_the_one_thread_per_element_kernels(n, t):
-    # above 2^20 elements degree reduction and truncation switch kernels
+    # degree reduction switches kernels at 160 K elements, truncation vector width at 2^20
     s = SSNet(n, t, seed=31)
     count = (1 << 20) + 6
     c = field_uniform((n, count), seed=11)
@@ -140,6 +140,18 @@ def test_linear_parity(n, t):
         w = field_uniform((n, K, N), seed=N * 3 + K)
         got = to_np(s.linear_mod(to_dev(x), to_dev(w)))
         assert np.array_equal(got, orc.linear(x, w, P61))
+
+
+def test_linear_more_tiles_than_arrival_counters():
+    # 3 * 130 * 130 output tiles: every workgroup takes one whole tile, nothing is handed over
+    n, t = 3, 1
+    s = SSNet(n, t, seed=1)
+    M, K, N = 8320, 64, 8320
+    x, w = field_uniform((n, M, K), 41), field_uniform((n, K, N), 42)
+    y = s.linear_mod(to_dev(x), to_dev(w))
+    rows = np.r_[0:24, 4000:4024, M - 24:M]
+    got = to_np(y[:, torch.from_numpy(rows).cuda()])
+    assert np.array_equal(got, orc.linear(np.ascontiguousarray(x[:, rows]), w, P61))
 
 
 def test_linear_extreme_operands():
