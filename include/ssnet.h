@@ -139,6 +139,15 @@ int ssnet_degree_reduce(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint6
  * d_out may alias d_x. */
 int ssnet_truncate(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, uint64_t stream_id, uint64_t *d_out);
 
+/* SSS-Linear's reduction followed at once by SSS-Truncation (the default layer
+ * order Linear - Truncation of Sec. VII-A): the result, every message and every
+ * random draw are those of ssnet_degree_reduce(stream_id) followed by
+ * ssnet_truncate(stream_id), in one launch.  Workspace behind the header:
+ * [2t+1][k][count], [k][n][count] (reduction), then [k][count], [n][count]
+ * (truncation).  d_out may alias d_c. */
+int ssnet_degree_reduce_truncate(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id,
+                                 uint64_t *d_out);
+
 /* Host-side generator, exposed so that its bits can be checked without a GPU.
  * key = absorb(seed, domain, stream_id, party, j) with h <- mix64((h ^ word) +
  * 0x9E3779B97F4A7C15) from h = 0, mix64 being the SplitMix64 output function;

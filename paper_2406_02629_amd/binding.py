@@ -41,6 +41,7 @@ SIGNATURES = {
     "ssnet_conv_mod_packed": (_int, [_ptr, _ptr, _ptr] + [_int] * 9 + [_ptr]),
     "ssnet_degree_reduce": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
     "ssnet_truncate": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
+    "ssnet_degree_reduce_truncate": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
     "ssnet_rng_key": (_u64, [_u64] * 5),
     "ssnet_rng_draw": (_u64, [_u64, _u64]),
     "ssnet_rng_field": (_u64, [_u64, _u64]),
@@ -255,6 +256,17 @@ class SSNet:
         if out is None:
             out = torch.empty_like(x)
         self._ok(self.lib.ssnet_truncate(self._ctx, _dptr(x), count, stream_id, _dptr(out)), "ssnet_truncate")
+        return out
+
+    def degree_reduce_truncate(self, c: torch.Tensor, stream_id: int,
+                               out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        _check_i64(c, "c")
+        count = c[0].numel()
+        self.reserve(self.workspace_bytes_stream(count))
+        if out is None:
+            out = torch.empty_like(c)
+        self._ok(self.lib.ssnet_degree_reduce_truncate(self._ctx, _dptr(c), count, stream_id, _dptr(out)),
+                 "ssnet_degree_reduce_truncate")
         return out
 
     # ---- live kernel timing ----

@@ -92,9 +92,11 @@ class Chain:
             else:
                 ss.linear_mod_packed(xs, self.packed[l], L.cout, out=y)
         yv = y.view(ss.n, -1)
-        if "d" in stages:
+        if "d" in stages and "t" in stages:
+            ss.degree_reduce_truncate(yv, stream_id=l, out=yv)
+        elif "d" in stages:
             ss.degree_reduce(yv, stream_id=l, out=yv)
-        if "t" in stages:
+        elif "t" in stages:
             ss.truncate(yv, stream_id=l, out=yv)
         if "r" in stages:
             ss.reconstruct(y, self.ids, out=self.rec[l])

@@ -46,6 +46,9 @@ hipError_t ss_launch_degree_reduce(const u64 *c, u64 *msg1, u64 *msg2, u64 *out,
                                    const ss_dr_params &dp, hipStream_t stream);
 hipError_t ss_launch_truncate(const u64 *x, u64 *u, u64 *wsh, u64 *out, size_t count, const ss_tr_params &tp,
                               hipStream_t stream);
+hipError_t ss_launch_degree_reduce_truncate(const u64 *c, u64 *msg1, u64 *msg2, u64 *u, u64 *wsh, u64 *out,
+                                            size_t count, const ss_dr_params &dp, const ss_tr_params &tp,
+                                            hipStream_t stream);
 
 // ---- int8-limb MFMA family (gemm_kernels.hip) ----
 // Packed operand: int8 tiles [row block of 16][k block of 64][limb 0..7][lane 0..63][16 bytes];

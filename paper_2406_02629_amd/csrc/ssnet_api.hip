@@ -327,8 +327,8 @@ size_t ssnet_workspace_bytes_stream(const ssnet_ctx *ctx, size_t count)
 {
     if (!ctx) return 0;
     const size_t k = ctx->t + 1, nr = 2 * ctx->t + 1, n = ctx->n;
-    const size_t dr = (nr * k + k * n) * count * 8, tr = (k + n) * count * 8;
-    return WS_COUNTER_BYTES + align256(dr > tr ? dr : tr);
+    // the fused call keeps the messages of both protocols at once
+    return WS_COUNTER_BYTES + align256((nr * k + k * n + k + n) * count * 8);
 }
 
 size_t ssnet_workspace_bytes_linear(const ssnet_ctx *ctx, int M, int K, int N)
@@ -482,12 +482,11 @@ int ssnet_conv_mod(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_w, int
     return ssnet_conv_mod_packed(ctx, d_x, pw, B, C, H, W, Co, kh, kw, stride, pad, d_y);
 }
 
-int ssnet_degree_reduce(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id, uint64_t *d_out)
+namespace {
+
+ss_dr_params make_dr_params(const ssnet_ctx *ctx, uint64_t stream_id)
 {
-    if (!ctx || !d_c || !d_out || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
     const int t = ctx->t, k = t + 1, nr = 2 * t + 1, n = ctx->n;
-    const size_t need = ((size_t)nr * k + (size_t)k * n) * count * 8;
-    if (!ws_fits(ctx, need)) return SSNET_EWORKSPACE;
     ss_dr_params dp = {};
     dp.n = n;
     dp.t = t;
@@ -501,20 +500,14 @@ int ssnet_degree_reduce(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint6
     }
     dp.dinv = ctx->dinv;
     for (int q = 0; q < k; q++) dp.ilambda[q] = ctx->ilambda_k[q];
-    u64 *msg1 = (u64 *)ws_scratch(ctx), *msg2 = msg1 + (size_t)nr * k * count;
-    timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
-    hipError_t e = ss_launch_degree_reduce(d_c, msg1, msg2, d_out, count, dp, ctx->stream);
-    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+    return dp;
 }
 
-int ssnet_truncate(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, uint64_t stream_id, uint64_t *d_out)
+ss_tr_params make_tr_params(const ssnet_ctx *ctx, uint64_t stream_id)
 {
-    if (!ctx || !d_x || !d_out || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
-    const int t = ctx->t, k = t + 1, n = ctx->n;
-    const size_t need = ((size_t)k + n) * count * 8;
-    if (!ws_fits(ctx, need)) return SSNET_EWORKSPACE;
+    const int t = ctx->t;
     ss_tr_params tp = {};
-    tp.n = n;
+    tp.n = ctx->n;
     tp.t = t;
     tp.f = ctx->f;
     tp.e_key = ss_key(ctx->seed, SSNET_DOM_MASK_E, stream_id, 0, 0);
@@ -523,10 +516,48 @@ int ssnet_truncate(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, uint64_t s
         tp.alphat_key[j - 1] = ss_key(ctx->seed, SSNET_DOM_MASK_ALPHAT, stream_id, 0, (u64)j);
         tp.gen_key[j - 1] = ss_key(ctx->seed, SSNET_DOM_TRUNC_GEN, stream_id, 0, (u64)j);
     }
-    for (int q = 0; q < k; q++) tp.ilambda[q] = ctx->ilambda_k[q];
+    for (int q = 0; q <= t; q++) tp.ilambda[q] = ctx->ilambda_k[q];
+    return tp;
+}
+
+}  // namespace
+
+int ssnet_degree_reduce(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id, uint64_t *d_out)
+{
+    if (!ctx || !d_c || !d_out || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
+    const int k = ctx->t + 1, nr = 2 * ctx->t + 1, n = ctx->n;
+    const size_t need = ((size_t)nr * k + (size_t)k * n) * count * 8;
+    if (!ws_fits(ctx, need)) return SSNET_EWORKSPACE;
+    u64 *msg1 = (u64 *)ws_scratch(ctx), *msg2 = msg1 + (size_t)nr * k * count;
+    timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
+    hipError_t e = ss_launch_degree_reduce(d_c, msg1, msg2, d_out, count, make_dr_params(ctx, stream_id), ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+int ssnet_truncate(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, uint64_t stream_id, uint64_t *d_out)
+{
+    if (!ctx || !d_x || !d_out || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
+    const int k = ctx->t + 1, n = ctx->n;
+    const size_t need = ((size_t)k + n) * count * 8;
+    if (!ws_fits(ctx, need)) return SSNET_EWORKSPACE;
     u64 *u = (u64 *)ws_scratch(ctx), *wsh = u + (size_t)k * count;
     timed tm(ctx, SSNET_PROF_TRUNCATE);
-    hipError_t e = ss_launch_truncate(d_x, u, wsh, d_out, count, tp, ctx->stream);
+    hipError_t e = ss_launch_truncate(d_x, u, wsh, d_out, count, make_tr_params(ctx, stream_id), ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+int ssnet_degree_reduce_truncate(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id,
+                                 uint64_t *d_out)
+{
+    if (!ctx || !d_c || !d_out || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
+    const int k = ctx->t + 1, nr = 2 * ctx->t + 1, n = ctx->n;
+    const size_t need = ((size_t)nr * k + (size_t)k * n + k + n) * count * 8;
+    if (!ws_fits(ctx, need)) return SSNET_EWORKSPACE;
+    u64 *msg1 = (u64 *)ws_scratch(ctx), *msg2 = msg1 + (size_t)nr * k * count;
+    u64 *u = msg2 + (size_t)k * n * count, *wsh = u + (size_t)k * count;
+    timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
+    hipError_t e = ss_launch_degree_reduce_truncate(d_c, msg1, msg2, u, wsh, d_out, count, make_dr_params(ctx, stream_id),
+                                                    make_tr_params(ctx, stream_id), ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
 

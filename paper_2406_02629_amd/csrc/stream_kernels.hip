@@ -99,6 +99,89 @@ __global__ __launch_bounds__(BLOCK) void reconstruct_kernel(const u64 *__restric
     out.store(secret + e0);
 }
 
+// e of the truncation mask alpha = e * 2^f: uniform in [1, 2^(32-f)]
+__device__ __forceinline__ u64 mask_e(u64 key, u64 e, int f)
+{
+    return 1 + ((ss_draw(key, e) >> 3) & ((1ULL << (32 - f)) - 1));
+}
+
+// what the elite party does with the reconstructed x + alpha: floor division of the signed value by 2^f
+__device__ __forceinline__ u64 shift_signed(u64 v, int f)
+{
+    const int64_t sv = (v <= (SS_P - 1) / 2) ? (int64_t)v : (int64_t)v - (int64_t)SS_P;
+    const int64_t qv = sv >> f;
+    return qv >= 0 ? (u64)qv : SS_P - (u64)(-qv);
+}
+
+// The three steps of masked truncation for the elements a thread owns, with
+// the same send-to-workspace / receive-from-registers convention as above:
+//   1. parties q = 1..k add their share of alpha = e * 2^f          -> umsg[q]
+//   2. the elite party reconstructs x + alpha, divides by 2^f with floor on
+//      the signed value and shares the quotient                      -> wsh[m]
+//   3. every party m adds its share of alpha~ = -e                   -> out[m]
+// x[q] holds the shares of parties q+1 = 1..k.
+template <int VEC>
+__device__ __forceinline__ void truncate_steps(const pack_t<VEC> *x, u64 *__restrict__ umsg, u64 *__restrict__ wsh,
+                                               u64 *out, size_t count, size_t e0, const ss_tr_params &tp)
+{
+    const int k = tp.t + 1;
+    u64 ev[VEC], ca[VEC][SS_MAXT];
+    ss_sacc acc[VEC];
+#pragma unroll
+    for (int u = 0; u < VEC; u++) {
+        ev[u] = mask_e(tp.e_key, e0 + u, tp.f);
+        draw_coeffs<SS_MAXT>(ca[u], tp.alpha_key, tp.t, e0 + u);
+        acc[u].clear();
+    }
+#pragma unroll
+    for (int q = 0; q < SS_MAXK; q++) {
+        if (q < k) {
+            pack_t<VEC> s;
+#pragma unroll
+            for (int u = 0; u < VEC; u++) {
+                s.v[u] = ss_add(x[q].v[u], ss_poly_eval<SS_MAXT>(ev[u] << tp.f, ca[u], tp.t, q + 1));
+                acc[u].mac(s.v[u], tp.ilambda[q]);
+            }
+            s.store(umsg + (size_t)q * count + e0);
+        }
+    }
+    u64 w[VEC], at[VEC], cw[VEC][SS_MAXT], cat[VEC][SS_MAXT];
+#pragma unroll
+    for (int u = 0; u < VEC; u++) {
+        w[u] = shift_signed(acc[u].value(), tp.f);
+        at[u] = SS_P - ev[u];
+        draw_coeffs<SS_MAXT>(cw[u], tp.gen_key, tp.t, e0 + u);
+        draw_coeffs<SS_MAXT>(cat[u], tp.alphat_key, tp.t, e0 + u);
+    }
+#pragma unroll
+    for (int m = 0; m < SS_MAXN; m++) {
+        if (m < tp.n) {
+            pack_t<VEC> ws, s;
+#pragma unroll
+            for (int u = 0; u < VEC; u++) {
+                ws.v[u] = ss_poly_eval<SS_MAXT>(w[u], cw[u], tp.t, m + 1);
+                s.v[u] = ss_add(ws.v[u], ss_poly_eval<SS_MAXT>(at[u], cat[u], tp.t, m + 1));
+            }
+            ws.store(wsh + (size_t)m * count + e0);
+            s.store(out + (size_t)m * count + e0);
+        }
+    }
+}
+
+template <int VEC>
+__global__ __launch_bounds__(BLOCK) void truncate_kernel(const u64 *x, u64 *__restrict__ umsg,
+                                                         u64 *__restrict__ wsh, u64 *out, size_t count,
+                                                         ss_tr_params tp)
+{
+    const size_t e0 = ((size_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
+    if (e0 >= count) return;
+    pack_t<VEC> xs[SS_MAXK];
+#pragma unroll
+    for (int q = 0; q < SS_MAXK; q++)
+        if (q <= tp.t) xs[q].load(x + (size_t)q * count + e0);
+    truncate_steps<VEC>(xs, umsg, wsh, out, count, e0, tp);
+}
+
 // ------------------------------------------------------------------ RED + RERAND
 // The three protocol steps for the elements a thread owns.  All parties are
 // simulated by that one thread, so a message is written to the workspace (the
@@ -110,10 +193,15 @@ __global__ __launch_bounds__(BLOCK) void reconstruct_kernel(const u64 *__restric
 //      polynomial through the received values, then its value at every party
 //      ID -- same residues as the (2t+1) x n product                 -> msg2[q][m]
 //   3. party m: REC of the k received values, plus its share of zero  -> out[m]
-template <int VEC>
+//
+// With TRUNC the reduced, re-randomised shares do not go to `out` but straight
+// into the three truncation steps (truncate_kernel below), whose messages go to
+// umsg / wsh: SSS-Linear followed by SSS-Truncation in one launch.
+template <int VEC, bool TRUNC>
 __global__ __launch_bounds__(BLOCK) void degree_reduce_kernel(const u64 *c, u64 *__restrict__ msg1,
-                                                              u64 *__restrict__ msg2, u64 *out, size_t count,
-                                                              ss_dr_params dp)
+                                                              u64 *__restrict__ msg2, u64 *__restrict__ umsg,
+                                                              u64 *__restrict__ wsh, u64 *out, size_t count,
+                                                              ss_dr_params dp, ss_tr_params tp)
 {
     const size_t e0 = ((size_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
     if (e0 >= count) return;
@@ -187,6 +275,7 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_kernel(const u64 *c, u64 
     u64 z[VEC][SS_MAXT];
 #pragma unroll
     for (int u = 0; u < VEC; u++) draw_coeffs<SS_MAXT>(z[u], dp.zero_key, dp.t, e0 + u);
+    pack_t<VEC> y[TRUNC ? SS_MAXK : 1];   // with TRUNC: the new shares of parties 1..k
 #pragma unroll
     for (int m = 0; m < SS_MAXN; m++) {
         if (m < dp.n) {
@@ -194,26 +283,37 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_kernel(const u64 *c, u64 
 #pragma unroll
             for (int u = 0; u < VEC; u++)
                 s.v[u] = ss_add(red[u][m].value(), ss_poly_eval<SS_MAXT>(0, z[u], dp.t, m + 1));
-            s.store(out + (size_t)m * count + e0);
+            if (!TRUNC)
+                s.store(out + (size_t)m * count + e0);
+            else if (m < SS_MAXK)
+                y[m] = s;
         }
     }
+    if (TRUNC) truncate_steps<VEC>(y, umsg, wsh, out, count, e0, tp);
 }
 
 // Same computation for small tensors, where the serial work of one thread per
 // element leaves most of the chip idle: a workgroup takes 32 elements and eight
 // party lanes per element.  Lane p first plays reducing party p+1 (step 1),
-// while lane 7 draws the coefficients of the zero sharing; then, after these
-// went through LDS, lane p plays receiving party p+1: it forms
-// the k values that parties 1..k would send it (step 2, with the full matrix R
-// instead of its factors, so that the lanes do not wait on each other) and
-// reconstructs from them (step 3, RERAND).  Messages and outputs are the same
-// residues as in degree_reduce_kernel.
+// while the lanes that do not reduce (2t+1 <= 7, so lane 7 at least) draw the
+// coefficients every party needs later; then, after these went through LDS, lane
+// p plays receiving party p+1: it forms the k values that parties 1..k would
+// send it (step 2, with the full matrix R instead of its factors, so that the
+// lanes do not wait on each other) and reconstructs from them (step 3, RERAND).
+// With TRUNC the lanes go on with the truncation steps (mask, reconstruct and
+// shift at the elite party, unmask), exchanging the k masked shares through LDS.
+// Messages and outputs are the same residues as in the kernels above.
+template <bool TRUNC>
 __global__ __launch_bounds__(BLOCK) void degree_reduce_lanes_kernel(const u64 *c, u64 *__restrict__ msg1,
-                                                                    u64 *__restrict__ msg2, u64 *out, size_t count,
-                                                                    ss_dr_params dp)
+                                                                    u64 *__restrict__ msg2, u64 *__restrict__ umsg,
+                                                                    u64 *__restrict__ wsh, u64 *out, size_t count,
+                                                                    ss_dr_params dp, ss_tr_params tp)
 {
     __shared__ u64 sub[2 * SS_MAXT + 1][SS_MAXK][32];
-    __shared__ u64 zero_coef[SS_MAXT][32];
+    // drawn once per element by the spare lanes: 0 zero sharing, 1 alpha, 2 elite re-sharing, 3 alpha~
+    __shared__ u64 coef[4][SS_MAXT][32];
+    __shared__ u64 mask[32];             // e of the truncation mask
+    __shared__ u64 masked[SS_MAXK][32];  // x_q + alpha_q
     const int el = threadIdx.x & 31, p = threadIdx.x >> 5;
     const size_t e = (size_t)blockIdx.x * 32 + el;
     const bool live = e < count;
@@ -230,99 +330,72 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_lanes_kernel(const u64 *c
                 msg1[((size_t)p * k + q) * count + e] = v;
             }
         }
-    } else if (live && p == 7) {   // lane 7 never reduces (2t+1 <= 7): it draws the zero sharing for all
-        u64 z[SS_MAXT];
-        draw_coeffs<SS_MAXT>(z, dp.zero_key, dp.t, e);
+    } else if (live) {   // spare lanes nr..7 share the drawing jobs round-robin
+        const int spare = 8 - nr, me = p - nr;
 #pragma unroll
-        for (int j = 0; j < SS_MAXT; j++) zero_coef[j][el] = z[j];
+        for (int job = 0; job < (TRUNC ? 4 : 1); job++) {
+            if (job % spare == me) {
+                const u64 *keys = job == 0 ? dp.zero_key : job == 1 ? tp.alpha_key : job == 2 ? tp.gen_key : tp.alphat_key;
+                u64 z[SS_MAXT];
+                draw_coeffs<SS_MAXT>(z, keys, dp.t, e);
+#pragma unroll
+                for (int j = 0; j < SS_MAXT; j++) coef[job][j][el] = z[j];
+                if (job == 1) mask[el] = mask_e(tp.e_key, e, tp.f);
+            }
+        }
     }
     __syncthreads();
-    if (!live || p >= dp.n) return;
-    ss_sacc red;
-    red.clear();
+    const bool party = live && p < dp.n;
+    u64 y = 0;   // this party's reduced, re-randomised share
+    if (party) {
+        ss_sacc red;
+        red.clear();
 #pragma unroll
-    for (int q = 0; q < SS_MAXK; q++) {
-        if (q < k) {
-            ss_sacc acc;
-            acc.clear();
+        for (int q = 0; q < SS_MAXK; q++) {
+            if (q < k) {
+                ss_sacc acc;
+                acc.clear();
 #pragma unroll
-            for (int i = 0; i < 2 * SS_MAXT + 1; i++)
-                if (i < nr) acc.mac(sub[i][q][el], dp.irmat[i][p]);
-            const u64 v = ss_mul(acc.value(), dp.dinv);
-            msg2[((size_t)q * dp.n + p) * count + e] = v;
-            red.mac(v, dp.ilambda[q]);
-        }
-    }
-    u64 z[SS_MAXT];
-#pragma unroll
-    for (int j = 0; j < SS_MAXT; j++) z[j] = zero_coef[j][el];
-    out[(size_t)p * count + e] = ss_add(red.value(), ss_poly_eval<SS_MAXT>(0, z, dp.t, p + 1));
-}
-
-// ------------------------------------------------------------------ truncation
-__device__ __forceinline__ u64 mask_e(u64 key, u64 e, int f)
-{
-    return 1 + ((ss_draw(key, e) >> 3) & ((1ULL << (32 - f)) - 1));
-}
-
-// The three steps of masked truncation for the elements a thread owns, with
-// the same send-to-workspace / receive-from-registers convention as above:
-//   1. parties q = 1..k add their share of alpha = e * 2^f          -> umsg[q]
-//   2. the elite party reconstructs x + alpha, divides by 2^f with floor on
-//      the signed value and shares the quotient                      -> wsh[m]
-//   3. every party m adds its share of alpha~ = -e                   -> out[m]
-template <int VEC>
-__global__ __launch_bounds__(BLOCK) void truncate_kernel(const u64 *x, u64 *__restrict__ umsg,
-                                                         u64 *__restrict__ wsh, u64 *out, size_t count,
-                                                         ss_tr_params tp)
-{
-    const size_t e0 = ((size_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
-    if (e0 >= count) return;
-    const int k = tp.t + 1;
-    u64 ev[VEC], ca[VEC][SS_MAXT];
-    ss_sacc acc[VEC];
-#pragma unroll
-    for (int u = 0; u < VEC; u++) {
-        ev[u] = mask_e(tp.e_key, e0 + u, tp.f);
-        draw_coeffs<SS_MAXT>(ca[u], tp.alpha_key, tp.t, e0 + u);
-        acc[u].clear();
-    }
-#pragma unroll
-    for (int q = 0; q < SS_MAXK; q++) {
-        if (q < k) {
-            pack_t<VEC> xv, s;
-            xv.load(x + (size_t)q * count + e0);
-#pragma unroll
-            for (int u = 0; u < VEC; u++) {
-                s.v[u] = ss_add(xv.v[u], ss_poly_eval<SS_MAXT>(ev[u] << tp.f, ca[u], tp.t, q + 1));
-                acc[u].mac(s.v[u], tp.ilambda[q]);
+                for (int i = 0; i < 2 * SS_MAXT + 1; i++)
+                    if (i < nr) acc.mac(sub[i][q][el], dp.irmat[i][p]);
+                const u64 v = ss_mul(acc.value(), dp.dinv);
+                msg2[((size_t)q * dp.n + p) * count + e] = v;
+                red.mac(v, dp.ilambda[q]);
             }
-            s.store(umsg + (size_t)q * count + e0);
         }
+        u64 z[SS_MAXT];
+#pragma unroll
+        for (int j = 0; j < SS_MAXT; j++) z[j] = coef[0][j][el];
+        y = ss_add(red.value(), ss_poly_eval<SS_MAXT>(0, z, dp.t, p + 1));
+        if (!TRUNC) out[(size_t)p * count + e] = y;
     }
-    u64 w[VEC], at[VEC], cw[VEC][SS_MAXT], cat[VEC][SS_MAXT];
+    if (!TRUNC) return;
+
+    if (party && p < k) {   // truncation step 1 on parties 1..k
+        u64 ca[SS_MAXT];
 #pragma unroll
-    for (int u = 0; u < VEC; u++) {
-        const u64 v = acc[u].value();
-        const int64_t sv = (v <= (SS_P - 1) / 2) ? (int64_t)v : (int64_t)v - (int64_t)SS_P;
-        const int64_t qv = sv >> tp.f;
-        w[u] = qv >= 0 ? (u64)qv : SS_P - (u64)(-qv);
-        at[u] = SS_P - ev[u];
-        draw_coeffs<SS_MAXT>(cw[u], tp.gen_key, tp.t, e0 + u);
-        draw_coeffs<SS_MAXT>(cat[u], tp.alphat_key, tp.t, e0 + u);
+        for (int j = 0; j < SS_MAXT; j++) ca[j] = coef[1][j][el];
+        const u64 um = ss_add(y, ss_poly_eval<SS_MAXT>(mask[el] << tp.f, ca, tp.t, p + 1));
+        masked[p][el] = um;
+        umsg[(size_t)p * count + e] = um;
     }
+    __syncthreads();
+    if (party) {   // step 2 (the elite party's result, recomputed by every lane) and step 3
+        ss_sacc acc;
+        acc.clear();
 #pragma unroll
-    for (int m = 0; m < SS_MAXN; m++) {
-        if (m < tp.n) {
-            pack_t<VEC> ws, s;
+        for (int q = 0; q < SS_MAXK; q++)
+            if (q < k) acc.mac(masked[q][el], tp.ilambda[q]);
+        const u64 w = shift_signed(acc.value(), tp.f);
+        u64 cw[SS_MAXT], cat[SS_MAXT];
 #pragma unroll
-            for (int u = 0; u < VEC; u++) {
-                ws.v[u] = ss_poly_eval<SS_MAXT>(w[u], cw[u], tp.t, m + 1);
-                s.v[u] = ss_add(ws.v[u], ss_poly_eval<SS_MAXT>(at[u], cat[u], tp.t, m + 1));
-            }
-            ws.store(wsh + (size_t)m * count + e0);
-            s.store(out + (size_t)m * count + e0);
+        for (int j = 0; j < SS_MAXT; j++) {
+            cw[j] = coef[2][j][el];
+            cat[j] = coef[3][j][el];
         }
+        const u64 ws = ss_poly_eval<SS_MAXT>(w, cw, tp.t, p + 1);
+        wsh[(size_t)p * count + e] = ws;
+        out[(size_t)p * count + e] = ss_add(ws, ss_poly_eval<SS_MAXT>(SS_P - mask[el], cat, tp.t, p + 1));
     }
 }
 
@@ -382,12 +455,26 @@ hipError_t ss_launch_reconstruct(const u64 *shares, u64 *secret, size_t count, c
 hipError_t ss_launch_degree_reduce(const u64 *c, u64 *msg1, u64 *msg2, u64 *out, size_t count,
                                    const ss_dr_params &dp, hipStream_t stream)
 {
+    const ss_tr_params none = {};
     if (count < LANES_MAX_COUNT)
-        hipLaunchKernelGGL(degree_reduce_lanes_kernel, dim3((unsigned)((count + 31) / 32)), dim3(BLOCK), 0, stream, c,
-                           msg1, msg2, out, count, dp);
+        hipLaunchKernelGGL(degree_reduce_lanes_kernel<false>, dim3((unsigned)((count + 31) / 32)), dim3(BLOCK), 0, stream,
+                           c, msg1, msg2, (u64 *)nullptr, (u64 *)nullptr, out, count, dp, none);
     else   // one element per thread: the k*k + n wide accumulators of two elements would not fit the register file
-        hipLaunchKernelGGL(degree_reduce_kernel<1>, dim3(blocks_for(count, 1)), dim3(BLOCK), 0, stream, c, msg1, msg2,
-                           out, count, dp);
+        hipLaunchKernelGGL((degree_reduce_kernel<1, false>), dim3(blocks_for(count, 1)), dim3(BLOCK), 0, stream, c, msg1,
+                           msg2, (u64 *)nullptr, (u64 *)nullptr, out, count, dp, none);
+    return hipGetLastError();
+}
+
+hipError_t ss_launch_degree_reduce_truncate(const u64 *c, u64 *msg1, u64 *msg2, u64 *u, u64 *wsh, u64 *out,
+                                            size_t count, const ss_dr_params &dp, const ss_tr_params &tp,
+                                            hipStream_t stream)
+{
+    if (count < LANES_MAX_COUNT)
+        hipLaunchKernelGGL(degree_reduce_lanes_kernel<true>, dim3((unsigned)((count + 31) / 32)), dim3(BLOCK), 0, stream,
+                           c, msg1, msg2, u, wsh, out, count, dp, tp);
+    else
+        hipLaunchKernelGGL((degree_reduce_kernel<1, true>), dim3(blocks_for(count, 1)), dim3(BLOCK), 0, stream, c, msg1,
+                           msg2, u, wsh, out, count, dp, tp);
     return hipGetLastError();
 }
 

@@ -93,6 +93,30 @@ def test_large_tensors_take_the_one_thread_per_element_kernels(n, t):
     assert np.array_equal(to_np(s.truncate(to_dev(xsh), stream_id=3)), orc.truncate(xsh, n, t, 13, P61, 31, 3))
 
 
+@pytest.mark.parametrize("n,t", SCHEMES)
+def test_fused_reduce_truncate_equals_the_two_calls(n, t):
+    s = SSNet(n, t, f=13, seed=77)
+    k, nr = t + 1, 2 * t + 1
+    for count in (1, 33, 4099, 65538, 200001, (1 << 20) + 2 if n == 3 else 300000):
+        say("reduce+truncate", n, t, count)
+        rng = np.random.default_rng(count)
+        # degree-2t shares of moderate secrets, so that the truncation precondition holds
+        xs = rng.integers(-(1 << 55), 1 << 55, count, dtype=np.int64)
+        c = orc.share(np.where(xs < 0, xs + P61, xs).astype(np.uint64), n, 2 * t if 2 * t < n else t, P61, 5, 0)
+        want_r, m1, m2, _ = orc.degree_reduce(c, n, t, P61, 77, 9, full=True)
+        want, u, wsh = orc.truncate(want_r, n, t, 13, P61, 77, 9, full=True)
+        d = to_dev(c)
+        got = to_np(s.degree_reduce_truncate(d, stream_id=9, out=d))      # in place
+        ws = to_np(s.messages()[: (nr * k + k * n + k + n) * count])
+        o1, o2, o3 = nr * k * count, (nr * k + k * n) * count, (nr * k + k * n + k) * count
+        assert np.array_equal(ws[:o1].reshape(nr, k, count), m1)
+        assert np.array_equal(ws[o1:o2].reshape(k, n, count), m2)
+        assert np.array_equal(ws[o2:o3].reshape(k, count), u)
+        assert np.array_equal(ws[o3:].reshape(n, count), wsh)
+        assert np.array_equal(got, want)
+        assert np.array_equal(orc.lift(orc.reconstruct(got, list(range(1, t + 2)), P61), P61), xs >> 13)
+
+
 def test_degree_reduce_in_place_and_on_real_products():
     n, t = 5, 2
     s = SSNet(n, t, seed=8)

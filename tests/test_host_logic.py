@@ -66,7 +66,8 @@ def test_workspace_sizes():
     hdr = binding.WS_HEADER_BYTES
     assert s.workspace_bytes_stream(1000) >= hdr + (5 * 3 + 3 * 5) * 1000 * 8
     s3 = SSNet(3, 1, device=None)
-    assert s3.workspace_bytes_stream(1 << 20) == hdr + ((3 * 2 + 2 * 3) * 8 << 20)
+    # reduction messages [3][2] + [2][3] and truncation messages [2] + [3] planes of 2^20 elements
+    assert s3.workspace_bytes_stream(1 << 20) == hdr + ((3 * 2 + 2 * 3 + 2 + 3) * 8 << 20)
     # limb tiles: 8 bytes per element, rows padded to 16 and K to 64
     assert s3.lib.ssnet_packed_weight_bytes(16, 64) == 8192
     assert s3.lib.ssnet_packed_weight_bytes(17, 65) == 4 * 8192
