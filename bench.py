@@ -105,6 +105,20 @@ def cpu_baseline(nlayers):
                       f"in {secs:.1f} s (OpenMP over output rows / elements)"}
 
 
+def measured_traffic_bytes(kernel):
+    """HBM bytes per launch of `kernel` (fetch + write, scaled) from the committed summary of the
+    rocprofv3 --pmc runs of this same benchmark; None if the summary is not there."""
+    path = os.path.join(ROOT, "profiles", "bench_resnet152_chain_pmc_traffic.txt")
+    try:
+        for line in open(path):
+            parts = line.split()
+            if parts and parts[0] == kernel and len(parts) >= 5:
+                return float(parts[-1]) * 1024 * 1024
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -164,7 +178,8 @@ def main():
                    "layers": len(chain.layers), "field_macs_per_step": macs,
                    "steps_in_timed_region": "share, conv/dense, degree_reduce+rerand+truncate, reconstruct"},
         "roofline": {"bound": "mfma", "kernel": "gemm_limb_kernel", "achieved": achieved, "peak": INT8_PEAK_TOPS,
-                     "unit": "TOP/s", "frac": achieved / INT8_PEAK_TOPS, "traffic": None,
+                     "unit": "TOP/s", "frac": achieved / INT8_PEAK_TOPS,
+                     "traffic": measured_traffic_bytes("gemm_limb_kernel"), "traffic_unit": "bytes per launch (HBM)",
                      "launches": int(gemm_launches), "avg_launch_us": gemm_ms * 1e3 / max(gemm_launches, 1),
                      "int8_ops_per_step": macs * OPS_PER_FIELD_MAC},
         "kernel_ms_per_step": breakdown,
