@@ -78,6 +78,32 @@ def bulk_share_reconstruct(log2_count, reps):
     return out
 
 
+def conv_layer_roofline(reps):
+    """configs[2]: n=3, t=1, batch 8 x 64x56x56, 3x3 64->64: the modular GEMM on a shape with many tiles
+    (M = 25088, K = 576, N = 64 per party), weights packed beforehand; kernel times from HIP events."""
+    import torch
+    from paper_2406_02629_amd import SSNet
+    from ssnet_inputs import P61, uniform_below
+    n, B, C, H, Co, k = 3, 8, 64, 56, 64, 3
+    ss = SSNet(n, 1, f=13, seed=3)
+    x = torch.from_numpy(uniform_below(n * B * C * H * H, P61, 3).view("int64")).cuda().view(n, B, C, H, H)
+    w = torch.from_numpy(uniform_below(n * Co * C * k * k, P61, 4).view("int64")).cuda().view(n, Co, C, k, k)
+    wp = ss.pack_weights_conv(w)
+    y = ss.conv_mod_packed(x, wp, Co, k, k, 1, 1)
+    torch.cuda.synchronize()
+    ss.profile_begin()
+    for _ in range(reps):
+        ss.conv_mod_packed(x, wp, Co, k, k, 1, 1, out=y)
+    prof = ss.profile_end()
+    macs = n * B * H * H * C * k * k * Co
+    gemm_ms = prof["gemm"][0] / reps
+    achieved = macs * OPS_PER_FIELD_MAC / (gemm_ms * 1e-3) / 1e12
+    return {"workload": "conv 3x3 64->64 on 8x64x56x56, n=3 (configs[2]): M=25088 K=576 N=64 per party",
+            "bound": "mfma", "kernel": "gemm_limb_kernel", "achieved": achieved, "peak": INT8_PEAK_TOPS,
+            "unit": "TOP/s", "frac": achieved / INT8_PEAK_TOPS, "gemm_ms": gemm_ms,
+            "pack_im2col_ms": prof["pack_x"][0] / reps, "field_macs": macs}
+
+
 def cpu_baseline(nlayers):
     """The CPU oracle, as it stands, on the first `nlayers` layers of the same
     stack with uniform random shares as operands: GEN, conv, RED+RERAND,
@@ -195,6 +221,7 @@ def main():
         del src, dst
     if not args.no_bulk:
         result["roofline_hbm"] = bulk_share_reconstruct(args.bulk_log2, reps=5)
+        result["roofline_conv_layer"] = conv_layer_roofline(reps=10)
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(args.cpu_layers)
     print(json.dumps(result))

@@ -105,6 +105,8 @@ struct gemm_args {
     unsigned *counters;        // [tile], zero between launches
     int rows, cols, Rb, Cb, Kb, RT, CT;
     unsigned units;            // tiles * Kb (< 2^31), or 0: one whole tile per workgroup
+    unsigned wlast, wrow;      // cost of one unit of the last column tile; of one k block over a whole tile row
+    unsigned long long cost;   // of all units
     int slots;                 // partial slots per tile
     size_t a_party_stride, b_party_stride, out_party_stride, stride_row, stride_cb;
     int cdiv;
@@ -127,11 +129,43 @@ __device__ __forceinline__ u64 fold_diagonals(const v4i (&acc)[15], int r, u64 n
     return ss_reduce(ss_fold(tot) + negbias);   // minus the 2^31 offsets
 }
 
-// workgroup that owns unit x when `units` units are dealt to `G` workgroups in
-// contiguous ranges [g*units/G, (g+1)*units/G)
-__device__ __forceinline__ int owner_of(unsigned x, unsigned units, unsigned G)
+// The units are dealt to the workgroups by cost, not by count: a unit of a full
+// tile costs SS_UNIT_COST, a unit of the last column tile, where only some of
+// the four column blocks exist and the MFMAs of the others are skipped, costs
+// less (see unit_cost).  With cp(u) the summed cost of all units before u,
+// workgroup s of G owns the units with floor(s cost / G) <= cp(u) <
+// floor((s+1) cost / G).  cost / G >= SS_UNIT_COST, so no range is empty.
+constexpr unsigned SS_UNIT_COST = 9;
+
+// cost position of unit j of tile `tile`
+__device__ __forceinline__ unsigned long long cost_before(const gemm_args &g, unsigned tile, unsigned j)
 {
-    return (int)((((unsigned long long)x + 1) * G - 1) / units);
+    const unsigned ct = tile % (unsigned)g.CT, rg = tile / (unsigned)g.CT;
+    return (unsigned long long)rg * ((unsigned)g.Kb * g.wrow) + ct * SS_UNIT_COST * (unsigned)g.Kb +
+           j * (ct == (unsigned)g.CT - 1 ? g.wlast : SS_UNIT_COST);
+}
+
+// first unit whose cost position is >= x
+__device__ __forceinline__ unsigned unit_at(const gemm_args &g, unsigned long long x)
+{
+    const unsigned rowcost = (unsigned)g.Kb * g.wrow, tilecost = SS_UNIT_COST * (unsigned)g.Kb;
+    const unsigned rg = (unsigned)(x / rowcost), rem = (unsigned)(x - (unsigned long long)rg * rowcost);
+    const unsigned full = ((unsigned)g.CT - 1) * tilecost;
+    unsigned ct, j;
+    if (rem < full) {
+        ct = rem / tilecost;
+        j = (rem - ct * tilecost + SS_UNIT_COST - 1) / SS_UNIT_COST;
+    } else {
+        ct = (unsigned)g.CT - 1;
+        j = (rem - full + g.wlast - 1) / g.wlast;
+    }
+    return (rg * (unsigned)g.CT + ct) * (unsigned)g.Kb + j;   // j == Kb: first unit of the next tile
+}
+
+// workgroup that owns the unit at cost position cp
+__device__ __forceinline__ int owner_of(const gemm_args &g, unsigned long long cp, unsigned G)
+{
+    return (int)(((cp + 1) * G - 1) / g.cost);
 }
 
 // this wave's source block of tile `tile`: block `wave` of A for waves 0..3, of
@@ -149,9 +183,9 @@ __device__ __forceinline__ const v4i *tile_source(const gemm_args &g, unsigned t
 
 // Persistent kernel, one workgroup of 8 waves (4 x 2) per CU.  The work is the
 // flat list of units (output tile of 64 x 64, k block of 64), tile-major; each
-// workgroup takes one contiguous range of it, so every CU gets the same number
-// of MFMAs whatever the layer shape, and a tile whose k range is cut by a range
-// boundary is finished by the hand-over below.  Wave (wr, wc) owns row block wr
+// workgroup takes one contiguous range of it, of equal cost, so every CU gets
+// the same amount of work whatever the layer shape, and a tile whose k range is
+// cut by a range boundary is finished by the hand-over below.  Wave (wr, wc) owns row block wr
 // and column blocks 2wc, 2wc+1 of the tile (2 x 15 accumulator tiles); the two
 // waves of a SIMD differ in wc.
 //
@@ -184,8 +218,8 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
     const unsigned slot = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
     unsigned u0, u1;
     if (g.units) {
-        u0 = (unsigned)((unsigned long long)slot * g.units / G);
-        u1 = (unsigned)((unsigned long long)(slot + 1) * g.units / G);
+        u0 = unit_at(g, (unsigned long long)slot * g.cost / G);
+        u1 = unit_at(g, (unsigned long long)(slot + 1) * g.cost / G);
     } else {   // one whole tile per workgroup; unit numbers are relative to it
         u0 = 0;
         u1 = (unsigned)g.Kb;
@@ -286,8 +320,8 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
         bool finish = true;
         SS_TRACE(6);
         if (kb_first != 0 || kb_end != g.Kb) {   // the tile is shared: uniform over the workgroup
-            const int first = owner_of(tile * (unsigned)g.Kb, g.units, G),
-                      last = owner_of((tile + 1) * (unsigned)g.Kb - 1, g.units, G);
+            const int first = owner_of(g, cost_before(g, tile, 0), G),
+                      last = owner_of(g, cost_before(g, tile, (unsigned)g.Kb - 1), G);
             u64 *part = g.partials + (size_t)tile * g.slots * 4096;
             const int my = (int)slot - first;
 #pragma unroll
@@ -360,7 +394,18 @@ u64 neg_bias()
 struct gemm_plan {
     long tiles, units;
     int Kb, G, slots;
+    unsigned wlast, wrow;
+    unsigned long long cost;
 };
+
+// relative duration of a unit in which `vb` of the four column blocks exist:
+// a fixed part (copy, barrier, LDS reads) plus one part per column block, as
+// measured; the full unit is SS_UNIT_COST
+unsigned unit_cost(int vb)
+{
+    static const unsigned w[5] = {0, 4, 6, 7, SS_UNIT_COST};
+    return w[vb];
+}
 
 // How the units are dealt: one workgroup per CU unless there are fewer units
 // than CUs; slots = the most workgroups that can share one tile.  When there are
@@ -375,11 +420,20 @@ gemm_plan plan_gemm(int n, int rows, int cols, int K)
         p.G = (int)(p.tiles < (1L << 30) ? p.tiles : 0);   // 0: not launchable, rejected by the caller
         p.slots = 0;
         p.units = 0;
+        p.wlast = p.wrow = SS_UNIT_COST;
+        p.cost = 0;
         return p;
     }
-    p.G = (int)(p.units < SS_GEMM_CUS ? p.units : SS_GEMM_CUS);
-    const long per = p.units / p.G;
-    p.slots = (int)((p.Kb + per - 1) / per) + 1;
+    const int CT = (cols + 63) / 64, Cb = (cols + 15) / 16;
+    p.wlast = unit_cost(Cb - 4 * (CT - 1));
+    p.wrow = (unsigned)(CT - 1) * SS_UNIT_COST + p.wlast;
+    p.cost = (unsigned long long)n * ((rows + 63) / 64) * p.Kb * p.wrow;
+    // every range must hold at least one unit start: cost / G >= SS_UNIT_COST
+    const unsigned long long most = p.cost / SS_UNIT_COST;
+    p.G = (int)(most < SS_GEMM_CUS ? (most ? most : 1) : SS_GEMM_CUS);
+    // a tile of cost <= SS_UNIT_COST Kb meets at most this many ranges of length >= cost / G
+    const unsigned long long share = p.cost / p.G;
+    p.slots = (int)(((unsigned long long)SS_UNIT_COST * p.Kb + share - 1) / share) + 1;
     return p;
 }
 
@@ -460,6 +514,9 @@ hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, in
     g.RT = (rows + 63) / 64;
     g.CT = (cols + 63) / 64;
     g.units = (unsigned)p.units;
+    g.wlast = p.wlast;
+    g.wrow = p.wrow;
+    g.cost = p.cost;
     g.slots = p.slots;
     g.a_party_stride = ss_packed_bytes(rows, K) / 16;
     g.b_party_stride = ss_packed_bytes(cols, K) / 16;
