@@ -148,6 +148,16 @@ int ssnet_truncate(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, uint64_t s
 int ssnet_degree_reduce_truncate(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id,
                                  uint64_t *d_out);
 
+/* The same launch followed, per element, by REC (Eq. 2) of the truncated shares
+ * of the parties party_ids[0..m) (distinct IDs in 1..n, m >= t+1): d_out
+ * [n][count] is what ssnet_degree_reduce_truncate writes, d_secret [count] what
+ * ssnet_reconstruct(d_out, party_ids, m, degree t) would then return.  The
+ * layer-by-layer harness uses it where a layer's result is opened at once.
+ * Errors as for the two calls; d_out may alias d_c, d_secret may not alias
+ * either. */
+int ssnet_degree_reduce_truncate_reconstruct(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id,
+                                             uint64_t *d_out, const int *party_ids, int m, uint64_t *d_secret);
+
 /* Host-side generator, exposed so that its bits can be checked without a GPU.
  * key = absorb(seed, domain, stream_id, party, j) with h <- mix64((h ^ word) +
  * 0x9E3779B97F4A7C15) from h = 0, mix64 being the SplitMix64 output function;

@@ -42,6 +42,7 @@ SIGNATURES = {
     "ssnet_degree_reduce": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
     "ssnet_truncate": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
     "ssnet_degree_reduce_truncate": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
+    "ssnet_degree_reduce_truncate_reconstruct": (_int, [_ptr, _ptr, _sz, _u64, _ptr, C.POINTER(_int), _int, _ptr]),
     "ssnet_rng_key": (_u64, [_u64] * 5),
     "ssnet_rng_draw": (_u64, [_u64, _u64]),
     "ssnet_rng_field": (_u64, [_u64, _u64]),
@@ -268,6 +269,25 @@ class SSNet:
         self._ok(self.lib.ssnet_degree_reduce_truncate(self._ctx, _dptr(c), count, stream_id, _dptr(out)),
                  "ssnet_degree_reduce_truncate")
         return out
+
+    def degree_reduce_truncate_reconstruct(self, c: torch.Tensor, stream_id: int, ids: Sequence[int],
+                                           out: Optional[torch.Tensor] = None,
+                                           secret: Optional[torch.Tensor] = None):
+        """-> (truncated shares [n][...], their reconstruction from the parties `ids`)"""
+        _check_i64(c, "c")
+        count = c[0].numel()
+        self.reserve(self.workspace_bytes_stream(count))
+        if out is None:
+            out = torch.empty_like(c)
+        if secret is None:
+            secret = torch.empty(c.shape[1:], dtype=torch.int64, device=c.device)
+        else:
+            _check_i64(secret, "secret")
+        arr = (_int * len(ids))(*ids)
+        self._ok(self.lib.ssnet_degree_reduce_truncate_reconstruct(self._ctx, _dptr(c), count, stream_id, _dptr(out),
+                                                                   arr, len(ids), _dptr(secret)),
+                 "ssnet_degree_reduce_truncate_reconstruct")
+        return out, secret
 
     # ---- live kernel timing ----
     PROF_CLASSES = ("share", "reconstruct", "pack_w", "pack_x", "gemm", "degree_reduce", "truncate")

@@ -92,6 +92,9 @@ class Chain:
             else:
                 ss.linear_mod_packed(xs, self.packed[l], L.cout, out=y)
         yv = y.view(ss.n, -1)
+        if "d" in stages and "t" in stages and "r" in stages:   # one launch for the three steps
+            ss.degree_reduce_truncate_reconstruct(yv, stream_id=l, ids=self.ids, out=yv, secret=self.rec[l])
+            return self.rec[l]
         if "d" in stages and "t" in stages:
             ss.degree_reduce_truncate(yv, stream_id=l, out=yv)
         elif "d" in stages:

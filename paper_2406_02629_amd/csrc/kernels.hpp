@@ -37,6 +37,11 @@ struct ss_tr_params {             // truncation constants
     int ilambda[SS_MAXK];
 };
 
+struct ss_recf_params {           // REC fused behind another step: multiplier of every party's share
+    int coef[SS_MAXN];            // ilambda of the party, 0 for a party that does not take part
+    u64 dinv;
+};
+
 // ---- streaming family (stream_kernels.hip) ----
 hipError_t ss_launch_share(const u64 *secret, u64 *shares, size_t count, int n, int degree,
                            const ss_keys &keys, hipStream_t stream);
@@ -46,9 +51,10 @@ hipError_t ss_launch_degree_reduce(const u64 *c, u64 *msg1, u64 *msg2, u64 *out,
                                    const ss_dr_params &dp, hipStream_t stream);
 hipError_t ss_launch_truncate(const u64 *x, u64 *u, u64 *wsh, u64 *out, size_t count, const ss_tr_params &tp,
                               hipStream_t stream);
+// rec != nullptr: also REC of the truncated shares with the multipliers rf (one more output, same launch)
 hipError_t ss_launch_degree_reduce_truncate(const u64 *c, u64 *msg1, u64 *msg2, u64 *u, u64 *wsh, u64 *out,
-                                            size_t count, const ss_dr_params &dp, const ss_tr_params &tp,
-                                            hipStream_t stream);
+                                            u64 *rec, size_t count, const ss_dr_params &dp, const ss_tr_params &tp,
+                                            const ss_recf_params &rf, hipStream_t stream);
 
 // ---- int8-limb MFMA family (gemm_kernels.hip) ----
 // Packed operand: int8 tiles [row block of 16][k block of 64][limb 0..7][lane 0..63][16 bytes];

@@ -546,19 +546,51 @@ int ssnet_truncate(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, uint64_t s
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
 
-int ssnet_degree_reduce_truncate(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id,
-                                 uint64_t *d_out)
+namespace {
+
+// shared by the two fused entry points; d_rec == nullptr: no reconstruction
+int degree_reduce_truncate(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id, uint64_t *d_out,
+                           const int *party_ids, int m, uint64_t *d_rec)
 {
     if (!ctx || !d_c || !d_out || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
+    ss_recf_params rf = {};
+    if (d_rec) {
+        if (!party_ids || m < 1 || m > ctx->n) return SSNET_EINVAL;
+        for (int i = 0; i < m; i++) {
+            if (party_ids[i] < 1 || party_ids[i] > ctx->n) return SSNET_EID;
+            for (int j = 0; j < i; j++)
+                if (party_ids[j] == party_ids[i]) return SSNET_EID;
+        }
+        if (m < ctx->t + 1) return SSNET_ESHARES;
+        int il[SS_MAXN];
+        if (!h_lagrange_int(party_ids, m, il, &rf.dinv)) return SSNET_EINVAL;
+        for (int i = 0; i < m; i++) rf.coef[party_ids[i] - 1] = il[i];
+    }
     const int k = ctx->t + 1, nr = 2 * ctx->t + 1, n = ctx->n;
     const size_t need = ((size_t)nr * k + (size_t)k * n + k + n) * count * 8;
     if (!ws_fits(ctx, need)) return SSNET_EWORKSPACE;
     u64 *msg1 = (u64 *)ws_scratch(ctx), *msg2 = msg1 + (size_t)nr * k * count;
     u64 *u = msg2 + (size_t)k * n * count, *wsh = u + (size_t)k * count;
     timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
-    hipError_t e = ss_launch_degree_reduce_truncate(d_c, msg1, msg2, u, wsh, d_out, count, make_dr_params(ctx, stream_id),
-                                                    make_tr_params(ctx, stream_id), ctx->stream);
+    hipError_t e = ss_launch_degree_reduce_truncate(d_c, msg1, msg2, u, wsh, d_out, d_rec, count,
+                                                    make_dr_params(ctx, stream_id), make_tr_params(ctx, stream_id), rf,
+                                                    ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+}  // namespace
+
+int ssnet_degree_reduce_truncate(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id,
+                                 uint64_t *d_out)
+{
+    return degree_reduce_truncate(ctx, d_c, count, stream_id, d_out, nullptr, 0, nullptr);
+}
+
+int ssnet_degree_reduce_truncate_reconstruct(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id,
+                                             uint64_t *d_out, const int *party_ids, int m, uint64_t *d_secret)
+{
+    if (!d_secret) return SSNET_EINVAL;
+    return degree_reduce_truncate(ctx, d_c, count, stream_id, d_out, party_ids, m, d_secret);
 }
 
 uint64_t ssnet_rng_key(uint64_t seed, uint64_t domain, uint64_t stream_id, uint64_t party, uint64_t j)

@@ -119,10 +119,12 @@ __device__ __forceinline__ u64 shift_signed(u64 v, int f)
 //   2. the elite party reconstructs x + alpha, divides by 2^f with floor on
 //      the signed value and shares the quotient                      -> wsh[m]
 //   3. every party m adds its share of alpha~ = -e                   -> out[m]
-// x[q] holds the shares of parties q+1 = 1..k.
+// x[q] holds the shares of parties q+1 = 1..k.  With rec != nullptr the new
+// shares are also reconstructed (REC, Eq. 2) with the multipliers rf   -> rec
 template <int VEC>
 __device__ __forceinline__ void truncate_steps(const pack_t<VEC> *x, u64 *__restrict__ umsg, u64 *__restrict__ wsh,
-                                               u64 *out, size_t count, size_t e0, const ss_tr_params &tp)
+                                               u64 *out, size_t count, size_t e0, const ss_tr_params &tp,
+                                               u64 *__restrict__ rec, const ss_recf_params &rf)
 {
     const int k = tp.t + 1;
     u64 ev[VEC], ca[VEC][SS_MAXT];
@@ -153,6 +155,9 @@ __device__ __forceinline__ void truncate_steps(const pack_t<VEC> *x, u64 *__rest
         draw_coeffs<SS_MAXT>(cw[u], tp.gen_key, tp.t, e0 + u);
         draw_coeffs<SS_MAXT>(cat[u], tp.alphat_key, tp.t, e0 + u);
     }
+    ss_sacc racc[VEC];
+#pragma unroll
+    for (int u = 0; u < VEC; u++) racc[u].clear();
 #pragma unroll
     for (int m = 0; m < SS_MAXN; m++) {
         if (m < tp.n) {
@@ -161,10 +166,17 @@ __device__ __forceinline__ void truncate_steps(const pack_t<VEC> *x, u64 *__rest
             for (int u = 0; u < VEC; u++) {
                 ws.v[u] = ss_poly_eval<SS_MAXT>(w[u], cw[u], tp.t, m + 1);
                 s.v[u] = ss_add(ws.v[u], ss_poly_eval<SS_MAXT>(at[u], cat[u], tp.t, m + 1));
+                if (rec && rf.coef[m] != 0) racc[u].mac(s.v[u], rf.coef[m]);
             }
             ws.store(wsh + (size_t)m * count + e0);
             s.store(out + (size_t)m * count + e0);
         }
+    }
+    if (rec) {
+        pack_t<VEC> r;
+#pragma unroll
+        for (int u = 0; u < VEC; u++) r.v[u] = rf.dinv == 1 ? racc[u].value() : ss_mul(racc[u].value(), rf.dinv);
+        r.store(rec + e0);
     }
 }
 
@@ -179,7 +191,8 @@ __global__ __launch_bounds__(BLOCK) void truncate_kernel(const u64 *x, u64 *__re
 #pragma unroll
     for (int q = 0; q < SS_MAXK; q++)
         if (q <= tp.t) xs[q].load(x + (size_t)q * count + e0);
-    truncate_steps<VEC>(xs, umsg, wsh, out, count, e0, tp);
+    const ss_recf_params none = {};
+    truncate_steps<VEC>(xs, umsg, wsh, out, count, e0, tp, nullptr, none);
 }
 
 // ------------------------------------------------------------------ RED + RERAND
@@ -200,8 +213,9 @@ __global__ __launch_bounds__(BLOCK) void truncate_kernel(const u64 *x, u64 *__re
 template <int VEC, bool TRUNC>
 __global__ __launch_bounds__(BLOCK) void degree_reduce_kernel(const u64 *c, u64 *__restrict__ msg1,
                                                               u64 *__restrict__ msg2, u64 *__restrict__ umsg,
-                                                              u64 *__restrict__ wsh, u64 *out, size_t count,
-                                                              ss_dr_params dp, ss_tr_params tp)
+                                                              u64 *__restrict__ wsh, u64 *out, u64 *__restrict__ rec,
+                                                              size_t count, ss_dr_params dp, ss_tr_params tp,
+                                                              ss_recf_params rf)
 {
     const size_t e0 = ((size_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
     if (e0 >= count) return;
@@ -289,7 +303,161 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_kernel(const u64 *c, u64 
                 y[m] = s;
         }
     }
-    if (TRUNC) truncate_steps<VEC>(y, umsg, wsh, out, count, e0, tp);
+    if (TRUNC) truncate_steps<VEC>(y, umsg, wsh, out, count, e0, tp, rec, rf);
+}
+
+// ---- the same steps with n and t fixed at compile time ((k,n) = (2,3), (3,5)) ----
+// Same messages, same outputs, fewer instructions:
+//  * a party evaluates its polynomial at the consecutive points 1, 2, ... by
+//    forward differences (one or two additions per point) instead of Horner
+//    with a modular multiplication per coefficient;
+//  * sums of value * small signed constant keep the value in two pieces of 31
+//    and 30 bits and accumulate in signed 64-bit words (one multiply-add per
+//    piece), with no case split on the sign of the constant;
+//  * sums stay unreduced ("lazy", any 64-bit word of the right residue) until
+//    a value is stored or multiplied.
+
+// values a0 + a[0] x + ... at x = 1..M, canonical, handed to emit(x - 1, value); a0, a[] canonical
+template <int T, int M, typename F>
+__device__ __forceinline__ void eval_points(u64 a0, const u64 (&a)[T], F &&emit)
+{
+    static_assert(T == 1 || T == 2, "degrees 1 and 2");
+    u64 s = a0;
+    if constexpr (T == 1) {
+#pragma unroll
+        for (int x = 1; x <= M; x++) {
+            s = ss_add(s, a[0]);
+            emit(x - 1, s);
+        }
+    } else {
+        // first difference d_x = s(x) - s(x-1) = a1 + (2x - 1) a2, second difference 2 a2
+        u64 d = a[0] + a[1];       // < 2^62
+        const u64 dd = 2 * a[1];   // < 2^62
+#pragma unroll
+        for (int x = 1; x <= M; x++) {
+            if (x > 1) {
+                if (x >= 4 && (x - 4) % 3 == 0) d = ss_fold(d);   // keeps d below 7 * 2^61 + 8
+                d += dd;
+            }
+            s = ss_reduce(s + d);   // s < 2^61, so the sum stays below 2^64
+            emit(x - 1, s);
+        }
+    }
+}
+
+// sum of v * c over at most 8 terms, v canonical given as v = w0 + w1 2^31, |c| < 2^26
+struct ss_sacc2 {
+    long long lo, hi;
+    __device__ __forceinline__ void clear() { lo = 0; hi = 0; }
+    __device__ __forceinline__ void mac(u32 w0, u32 w1, int c)
+    {
+        lo += (long long)(int)w0 * c;   // |sum| < 8 * 2^31 * 2^26 = 2^60
+        hi += (long long)(int)w1 * c;
+    }
+    __device__ __forceinline__ u64 value() const
+    {
+        const u64 l = (u64)(lo + (long long)SS_P), h = (u64)(hi + (long long)SS_P);   // in (2^60, 2^62)
+        // h 2^31 with 2^61 = 1: low 30 bits of h shifted, the rest wraps to weight 1
+        return ss_reduce(l + ((h & 0x3FFFFFFFull) << 31) + (h >> 30));
+    }
+};
+#define SS_SPLIT31(v, w0, w1) const u32 w0 = (u32)(v)&0x7FFFFFFFu, w1 = (u32)((v) >> 31)
+
+template <int N, int T, bool TRUNC>
+__global__ __launch_bounds__(BLOCK) void degree_reduce_fixed_kernel(const u64 *c, u64 *__restrict__ msg1,
+                                                                    u64 *__restrict__ msg2, u64 *__restrict__ umsg,
+                                                                    u64 *__restrict__ wsh, u64 *out,
+                                                                    u64 *__restrict__ rec, size_t count,
+                                                                    ss_dr_params dp, ss_tr_params tp, ss_recf_params rf)
+{
+    constexpr int K = T + 1, NR = 2 * T + 1;
+    const size_t e = (size_t)blockIdx.x * BLOCK + threadIdx.x;
+    if (e >= count) return;
+    const u64 counter = ss_counter(e);
+    auto draw = [&](const u64 *keys, u64 (&r)[T]) {
+#pragma unroll
+        for (int j = 0; j < T; j++) r[j] = ss_draw_field_at(keys[j], counter);
+    };
+
+    // step 1, and of step 2 the sums coef[q][j] = sum_i msg1[i][q] * D binv[i][j]
+    ss_sacc2 coef[K][K];
+#pragma unroll
+    for (int q = 0; q < K; q++)
+#pragma unroll
+        for (int j = 0; j < K; j++) coef[q][j].clear();
+#pragma unroll
+    for (int i = 0; i < NR; i++) {
+        const u64 ci = c[(size_t)i * count + e];
+        u64 r[T];
+        draw(dp.reshare_key[i], r);
+        eval_points<T, K>(ci, r, [&](int q, u64 v) {
+            msg1[((size_t)i * K + q) * count + e] = v;
+            SS_SPLIT31(v, w0, w1);
+#pragma unroll
+            for (int j = 0; j < K; j++) coef[q][j].mac(w0, w1, dp.ibinv[i][j]);
+        });
+    }
+
+    // rest of step 2 (party q evaluates its polynomial at every party ID), and of step 3 the sums
+    // red[m] = sum_q lambda_q msg2[q][m]
+    ss_sacc2 red[N];
+#pragma unroll
+    for (int m = 0; m < N; m++) red[m].clear();
+#pragma unroll
+    for (int q = 0; q < K; q++) {
+        const u64 a0 = ss_mul(coef[q][0].value(), dp.dinv);
+        u64 cf[T];
+#pragma unroll
+        for (int j = 1; j < K; j++) cf[j - 1] = ss_mul(coef[q][j].value(), dp.dinv);
+        eval_points<T, N>(a0, cf, [&](int m, u64 v) {
+            msg2[((size_t)q * N + m) * count + e] = v;
+            SS_SPLIT31(v, w0, w1);
+            red[m].mac(w0, w1, dp.ilambda[q]);
+        });
+    }
+
+    // rest of step 3 and RERAND
+    u64 z[T], y[N];
+    draw(dp.zero_key, z);
+    eval_points<T, N>(0, z, [&](int m, u64 v) { y[m] = ss_add(red[m].value(), v); });
+    if (!TRUNC) {
+#pragma unroll
+        for (int m = 0; m < N; m++) out[(size_t)m * count + e] = y[m];
+        return;
+    }
+
+    // truncation step 1 (parties 1..k mask their share) and the elite party's REC of x + alpha
+    const u64 ev = mask_e(tp.e_key, e, tp.f);
+    u64 ca[T], cw[T], cat[T];
+    draw(tp.alpha_key, ca);
+    ss_sacc2 acc;
+    acc.clear();
+    eval_points<T, K>(ev << tp.f, ca, [&](int q, u64 v) {
+        const u64 um = ss_add(y[q], v);
+        umsg[(size_t)q * count + e] = um;
+        SS_SPLIT31(um, w0, w1);
+        acc.mac(w0, w1, tp.ilambda[q]);
+    });
+    // step 2: shift and re-share; step 3: unmask; then, if asked for, REC of the result
+    const u64 w = shift_signed(acc.value(), tp.f);
+    draw(tp.gen_key, cw);
+    draw(tp.alphat_key, cat);
+    u64 ws[N];
+    eval_points<T, N>(w, cw, [&](int m, u64 v) {
+        wsh[(size_t)m * count + e] = v;
+        ws[m] = v;
+    });
+    ss_sacc2 racc;
+    racc.clear();
+    eval_points<T, N>(SS_P - ev, cat, [&](int m, u64 v) {
+        const u64 o = ss_add(ws[m], v);
+        out[(size_t)m * count + e] = o;
+        if (rec) {
+            SS_SPLIT31(o, w0, w1);
+            racc.mac(w0, w1, rf.coef[m]);
+        }
+    });
+    if (rec) rec[e] = rf.dinv == 1 ? racc.value() : ss_mul(racc.value(), rf.dinv);
 }
 
 // Same computation for small tensors, where the serial work of one thread per
@@ -306,14 +474,16 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_kernel(const u64 *c, u64 
 template <bool TRUNC>
 __global__ __launch_bounds__(BLOCK) void degree_reduce_lanes_kernel(const u64 *c, u64 *__restrict__ msg1,
                                                                     u64 *__restrict__ msg2, u64 *__restrict__ umsg,
-                                                                    u64 *__restrict__ wsh, u64 *out, size_t count,
-                                                                    ss_dr_params dp, ss_tr_params tp)
+                                                                    u64 *__restrict__ wsh, u64 *out,
+                                                                    u64 *__restrict__ rec, size_t count,
+                                                                    ss_dr_params dp, ss_tr_params tp, ss_recf_params rf)
 {
     __shared__ u64 sub[2 * SS_MAXT + 1][SS_MAXK][32];
     // drawn once per element by the spare lanes: 0 zero sharing, 1 alpha, 2 elite re-sharing, 3 alpha~
     __shared__ u64 coef[4][SS_MAXT][32];
     __shared__ u64 mask[32];             // e of the truncation mask
     __shared__ u64 masked[SS_MAXK][32];  // x_q + alpha_q
+    __shared__ u64 fin[SS_MAXN][32];     // truncated shares, for the fused REC
     const int el = threadIdx.x & 31, p = threadIdx.x >> 5;
     const size_t e = (size_t)blockIdx.x * 32 + el;
     const bool live = e < count;
@@ -395,7 +565,19 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_lanes_kernel(const u64 *c
         }
         const u64 ws = ss_poly_eval<SS_MAXT>(w, cw, tp.t, p + 1);
         wsh[(size_t)p * count + e] = ws;
-        out[(size_t)p * count + e] = ss_add(ws, ss_poly_eval<SS_MAXT>(SS_P - mask[el], cat, tp.t, p + 1));
+        const u64 o = ss_add(ws, ss_poly_eval<SS_MAXT>(SS_P - mask[el], cat, tp.t, p + 1));
+        out[(size_t)p * count + e] = o;
+        fin[p][el] = o;
+    }
+    if (!rec) return;   // uniform over the grid
+    __syncthreads();
+    if (live && p == 0) {
+        ss_sacc acc;
+        acc.clear();
+#pragma unroll
+        for (int m = 0; m < SS_MAXN; m++)
+            if (m < dp.n && rf.coef[m] != 0) acc.mac(fin[m][el], rf.coef[m]);
+        rec[e] = rf.dinv == 1 ? acc.value() : ss_mul(acc.value(), rf.dinv);
     }
 }
 
@@ -403,6 +585,8 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_lanes_kernel(const u64 *c
 constexpr size_t VEC2_MIN_COUNT = (size_t)1 << 20;
 // below this many elements degree reduction spreads an element over party lanes
 constexpr size_t LANES_MAX_COUNT = 160 * 1024;   // measured cross-over on MI355X (n = 5, t = 2)
+// the same cross-over against the kernels with n and t fixed at compile time
+constexpr size_t LANES_MAX_COUNT_FIXED = 8 * 1024;
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
@@ -456,25 +640,40 @@ hipError_t ss_launch_degree_reduce(const u64 *c, u64 *msg1, u64 *msg2, u64 *out,
                                    const ss_dr_params &dp, hipStream_t stream)
 {
     const ss_tr_params none = {};
-    if (count < LANES_MAX_COUNT)
+    const ss_recf_params norec = {};
+    const bool fixed = (dp.n == 5 && dp.t == 2) || (dp.n == 3 && dp.t == 1);
+    if (count < (fixed ? LANES_MAX_COUNT_FIXED : LANES_MAX_COUNT))
         hipLaunchKernelGGL(degree_reduce_lanes_kernel<false>, dim3((unsigned)((count + 31) / 32)), dim3(BLOCK), 0, stream,
-                           c, msg1, msg2, (u64 *)nullptr, (u64 *)nullptr, out, count, dp, none);
+                           c, msg1, msg2, (u64 *)nullptr, (u64 *)nullptr, out, (u64 *)nullptr, count, dp, none, norec);
+    else if (dp.n == 5 && dp.t == 2)
+        hipLaunchKernelGGL((degree_reduce_fixed_kernel<5, 2, false>), dim3(blocks_for(count, 1)), dim3(BLOCK), 0, stream, c,
+                           msg1, msg2, (u64 *)nullptr, (u64 *)nullptr, out, (u64 *)nullptr, count, dp, none, norec);
+    else if (dp.n == 3 && dp.t == 1)
+        hipLaunchKernelGGL((degree_reduce_fixed_kernel<3, 1, false>), dim3(blocks_for(count, 1)), dim3(BLOCK), 0, stream, c,
+                           msg1, msg2, (u64 *)nullptr, (u64 *)nullptr, out, (u64 *)nullptr, count, dp, none, norec);
     else   // one element per thread: the k*k + n wide accumulators of two elements would not fit the register file
         hipLaunchKernelGGL((degree_reduce_kernel<1, false>), dim3(blocks_for(count, 1)), dim3(BLOCK), 0, stream, c, msg1,
-                           msg2, (u64 *)nullptr, (u64 *)nullptr, out, count, dp, none);
+                           msg2, (u64 *)nullptr, (u64 *)nullptr, out, (u64 *)nullptr, count, dp, none, norec);
     return hipGetLastError();
 }
 
 hipError_t ss_launch_degree_reduce_truncate(const u64 *c, u64 *msg1, u64 *msg2, u64 *u, u64 *wsh, u64 *out,
-                                            size_t count, const ss_dr_params &dp, const ss_tr_params &tp,
-                                            hipStream_t stream)
+                                            u64 *rec, size_t count, const ss_dr_params &dp, const ss_tr_params &tp,
+                                            const ss_recf_params &rf, hipStream_t stream)
 {
-    if (count < LANES_MAX_COUNT)
+    const bool fixed = (dp.n == 5 && dp.t == 2) || (dp.n == 3 && dp.t == 1);
+    if (count < (fixed ? LANES_MAX_COUNT_FIXED : LANES_MAX_COUNT))
         hipLaunchKernelGGL(degree_reduce_lanes_kernel<true>, dim3((unsigned)((count + 31) / 32)), dim3(BLOCK), 0, stream,
-                           c, msg1, msg2, u, wsh, out, count, dp, tp);
+                           c, msg1, msg2, u, wsh, out, rec, count, dp, tp, rf);
+    else if (dp.n == 5 && dp.t == 2)
+        hipLaunchKernelGGL((degree_reduce_fixed_kernel<5, 2, true>), dim3(blocks_for(count, 1)), dim3(BLOCK), 0, stream, c,
+                           msg1, msg2, u, wsh, out, rec, count, dp, tp, rf);
+    else if (dp.n == 3 && dp.t == 1)
+        hipLaunchKernelGGL((degree_reduce_fixed_kernel<3, 1, true>), dim3(blocks_for(count, 1)), dim3(BLOCK), 0, stream, c,
+                           msg1, msg2, u, wsh, out, rec, count, dp, tp, rf);
     else
         hipLaunchKernelGGL((degree_reduce_kernel<1, true>), dim3(blocks_for(count, 1)), dim3(BLOCK), 0, stream, c, msg1,
-                           msg2, u, wsh, out, count, dp, tp);
+                           msg2, u, wsh, out, rec, count, dp, tp, rf);
     return hipGetLastError();
 }
 

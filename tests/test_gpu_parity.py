@@ -117,6 +117,35 @@ def test_fused_reduce_truncate_equals_the_two_calls(n, t):
         assert np.array_equal(orc.lift(orc.reconstruct(got, list(range(1, t + 2)), P61), P61), xs >> 13)
 
 
+@pytest.mark.parametrize("n,t", [(3, 1), (5, 2), (7, 3), (5, 1)])
+def test_fused_reduce_truncate_reconstruct(n, t):
+    """One launch for degree reduction, truncation and REC: shares, messages and the
+    opened value against the oracle's three functions, for both kernel families."""
+    s = SSNet(n, t, f=13, seed=31)
+    k = t + 1
+    subsets = [list(range(1, k + 1)), list(range(n, n - k, -1)), list(range(1, n + 1))]
+    for count, ids in zip((1, 37, 4099, 170001, 262146), subsets + subsets):
+        say("reduce+truncate+reconstruct", n, t, count, ids)
+        rng = np.random.default_rng(count)
+        xs = rng.integers(-(1 << 55), 1 << 55, count, dtype=np.int64)
+        c = orc.share(np.where(xs < 0, xs + P61, xs).astype(np.uint64), n, 2 * t if 2 * t < n else t, P61, 6, 0)
+        want = orc.truncate(orc.degree_reduce(c, n, t, P61, 31, 4), n, t, 13, P61, 31, 4)
+        want_rec = orc.reconstruct(want, ids, P61)
+        d = to_dev(c)
+        out, rec = s.degree_reduce_truncate_reconstruct(d, stream_id=4, ids=ids, out=d)
+        assert np.array_equal(to_np(out), want)
+        assert np.array_equal(to_np(rec), want_rec)
+        assert np.array_equal(orc.lift(want_rec, P61), xs >> 13)
+        # the same residues as the two separate entry points
+        sep = s.degree_reduce_truncate(to_dev(c), stream_id=4)
+        assert bool(torch.equal(sep, out)) and bool(torch.equal(s.reconstruct(sep, ids), rec))
+    d = to_dev(orc.share(field_uniform(8, 1), n, t, P61, 6, 0))
+    for bad, code in (([1, 1] + list(range(2, k)), "EID"), ([0] + list(range(2, k + 1)), "EID"), (list(range(1, k)), "ESHARES")):
+        with pytest.raises(SSNetError) as ei:
+            s.degree_reduce_truncate_reconstruct(d, stream_id=1, ids=bad)
+        assert ei.value.code == {"EID": -4, "ESHARES": -3}[code]
+
+
 def test_degree_reduce_in_place_and_on_real_products():
     n, t = 5, 2
     s = SSNet(n, t, seed=8)
