@@ -116,6 +116,25 @@ int ssnet_linear_mod_packed(ssnet_ctx *ctx, const uint64_t *d_x, const void *d_w
 int ssnet_conv_mod_packed(ssnet_ctx *ctx, const uint64_t *d_x, const void *d_w_packed, int B, int C, int H,
                           int W, int Co, int kh, int kw, int stride, int pad, uint64_t *d_y);
 
+/* The input of a dense layer or of a 1x1, stride 1, unpadded convolution can be
+ * shared and brought into limb tiles in one launch, and the layer then run on
+ * the tiles alone:
+ *   ssnet_share_packed: GEN (Eq. 1, degree t, domain SHARE) of d_secret
+ *     [B][K][HW] -> d_shares [n][B][K][HW], the very values ssnet_share writes
+ *     for the same stream_id, plus their tiles d_packed (n *
+ *     ssnet_packed_weight_bytes(B*HW, K) bytes, 16-byte aligned).  Dense input
+ *     [M][K]: B = M, HW = 1.  Conv input [B][C][H][W]: K = C, HW = H*W.
+ *   ssnet_linear_mod_prepacked / ssnet_conv1x1_mod_prepacked: SSS-Linear step 1
+ *     (Sec. VI-A) as ssnet_linear_mod_packed / ssnet_conv_mod_packed (kh = kw =
+ *     stride = 1, pad = 0) compute it, bit-identical, from those tiles.  They
+ *     need the workspace of the corresponding ssnet_workspace_bytes_* call. */
+int ssnet_share_packed(ssnet_ctx *ctx, const uint64_t *d_secret, int B, int K, int HW, uint64_t stream_id,
+                       uint64_t *d_shares, void *d_packed);
+int ssnet_linear_mod_prepacked(ssnet_ctx *ctx, const void *d_x_packed, const void *d_w_packed, int M, int K, int N,
+                               uint64_t *d_y);
+int ssnet_conv1x1_mod_prepacked(ssnet_ctx *ctx, const void *d_x_packed, const void *d_w_packed, int B, int C, int HW,
+                                int Co, uint64_t *d_y);
+
 /* RED by resharing (Sec. IV-B, the three protocol steps with the matrix of
  * Eq. 3) followed by RERAND (Sec. IV-C), all n parties:
  *   1. parties 1..2t+1: GEN(c_i, k, k) towards parties 1..k   (domain RESHARE, party i)

@@ -39,6 +39,9 @@ SIGNATURES = {
     "ssnet_pack_weights_conv": (_int, [_ptr, _ptr, _int, _int, _ptr]),
     "ssnet_linear_mod_packed": (_int, [_ptr, _ptr, _ptr, _int, _int, _int, _ptr]),
     "ssnet_conv_mod_packed": (_int, [_ptr, _ptr, _ptr] + [_int] * 9 + [_ptr]),
+    "ssnet_share_packed": (_int, [_ptr, _ptr, _int, _int, _int, _u64, _ptr, _ptr]),
+    "ssnet_linear_mod_prepacked": (_int, [_ptr, _ptr, _ptr, _int, _int, _int, _ptr]),
+    "ssnet_conv1x1_mod_prepacked": (_int, [_ptr, _ptr, _ptr, _int, _int, _int, _int, _ptr]),
     "ssnet_degree_reduce": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
     "ssnet_truncate": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
     "ssnet_degree_reduce_truncate": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
@@ -222,6 +225,46 @@ class SSNet:
             out = torch.empty((n, M, N), dtype=torch.int64, device=x.device)
         self._ok(self.lib.ssnet_linear_mod_packed(self._ctx, _dptr(x), _dptr(w_packed), M, K, N, _dptr(out)),
                  "ssnet_linear_mod_packed")
+        return out
+
+    def share_packed(self, secret: torch.Tensor, stream_id: int, out: Optional[torch.Tensor] = None,
+                     packed: Optional[torch.Tensor] = None):
+        """secret [B][K][H][W] (conv input, 1x1 layer) or [M][K] (dense input)
+        -> (shares [n][...], limb tiles of the shares as a GEMM operand)"""
+        _check_i64(secret, "secret")
+        if secret.dim() == 2:
+            B, K, HW = secret.shape[0], secret.shape[1], 1
+        elif secret.dim() == 4:
+            B, K, HW = secret.shape[0], secret.shape[1], secret.shape[2] * secret.shape[3]
+        else:
+            raise SSNetError(EINVAL, "share_packed: secret must be [M][K] or [B][C][H][W]")
+        if out is None:
+            out = torch.empty((self.n,) + tuple(secret.shape), dtype=torch.int64, device=secret.device)
+        nbytes = self.n * self.lib.ssnet_packed_weight_bytes(B * HW, K)
+        if packed is None:
+            packed = torch.empty(nbytes, dtype=torch.uint8, device=secret.device)
+        elif packed.numel() * packed.element_size() < nbytes:
+            raise SSNetError(EINVAL, "share_packed: packed buffer too small")
+        self._ok(self.lib.ssnet_share_packed(self._ctx, _dptr(secret), B, K, HW, stream_id, _dptr(out), _dptr(packed)),
+                 "ssnet_share_packed")
+        return out, packed
+
+    def linear_mod_prepacked(self, x_packed: torch.Tensor, w_packed: torch.Tensor, M: int, K: int, N: int,
+                             out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        self.reserve(self.workspace_bytes_linear(M, K, N))
+        if out is None:
+            out = torch.empty((self.n, M, N), dtype=torch.int64, device=x_packed.device)
+        self._ok(self.lib.ssnet_linear_mod_prepacked(self._ctx, _dptr(x_packed), _dptr(w_packed), M, K, N, _dptr(out)),
+                 "ssnet_linear_mod_prepacked")
+        return out
+
+    def conv1x1_mod_prepacked(self, x_packed: torch.Tensor, w_packed: torch.Tensor, B: int, C: int, H: int, W: int,
+                              Co: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        self.reserve(self.workspace_bytes_conv(B, C, H, W, Co, 1, 1, 1, 0))
+        if out is None:
+            out = torch.empty((self.n, B, Co, H, W), dtype=torch.int64, device=x_packed.device)
+        self._ok(self.lib.ssnet_conv1x1_mod_prepacked(self._ctx, _dptr(x_packed), _dptr(w_packed), B, C, H * W, Co,
+                                                      _dptr(out)), "ssnet_conv1x1_mod_prepacked")
         return out
 
     def conv_mod_packed(self, x: torch.Tensor, w_packed: torch.Tensor, Co: int, kh: int, kw: int, stride: int,

@@ -62,6 +62,11 @@ class Chain:
         self.x_shares = [torch.empty((ss.n,) + self._in_shape(L), dtype=torch.int64, device=dev) for L in layers]
         self.y = [torch.empty((ss.n,) + self._out_shape(L), dtype=torch.int64, device=dev) for L in layers]
         self.rec = [torch.empty(self._out_shape(L), dtype=torch.int64, device=dev) for L in layers]
+        # dense and 1x1 / stride 1 / unpadded layers take their input tiles straight from the share kernel
+        self.pointwise = [L.kind == "fc" or (L.ksize == 1 and L.stride == 1 and L.pad == 0) for L in layers]
+        tiles = max([ss.n * ss.lib.ssnet_packed_weight_bytes(batch * (L.hin * L.hin if L.kind == "conv" else 1), L.cin)
+                     for L, pw in zip(layers, self.pointwise) if pw] + [16])
+        self.x_tiles = torch.empty(tiles, dtype=torch.uint8, device=dev)
         need = 0
         for L in layers:
             count = batch * L.cout * L.M
@@ -84,6 +89,13 @@ class Chain:
         breakdowns: s=share, g=gemm/conv, d=degree_reduce, t=truncate, r=reconstruct."""
         ss, L = self.ss, self.layers[l]
         xs, y = self.x_shares[l], self.y[l]
+        if self.pointwise[l] and "s" in stages and "g" in stages:
+            ss.share_packed(x_plain, stream_id=l, out=xs, packed=self.x_tiles)
+            if L.kind == "conv":
+                ss.conv1x1_mod_prepacked(self.x_tiles, self.packed[l], self.batch, L.cin, L.hin, L.hin, L.cout, out=y)
+            else:
+                ss.linear_mod_prepacked(self.x_tiles, self.packed[l], self.batch, L.cin, L.cout, out=y)
+            stages = stages.replace("s", "").replace("g", "")
         if "s" in stages:
             ss.share(x_plain, stream_id=l, out=xs)
         if "g" in stages:

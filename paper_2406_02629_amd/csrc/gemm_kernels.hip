@@ -12,6 +12,7 @@
 // output into a 61-bit residue with 2^61 = 1 (mod p) and stores the canonical
 // field element.
 #include "kernels.hpp"
+#include "eval.hpp"
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
@@ -78,6 +79,61 @@ __global__ __launch_bounds__(256) void pack_im2col_kernel(const u64 *__restrict_
         }
     }
     store_digits(y, dst + (size_t)blockIdx.z * dst_party_stride + ((size_t)rb * Kb + kb) * 512, r16, kq);
+}
+
+// GEN (Eq. 1) of the input of a dense or 1x1 convolution layer and its limb
+// tiles in one pass.  The secret is [B][K][HW] (dense: HW = 1); operand row
+// (b, hw), contraction index k.  Thread t of tile (rb, kb): row t%16, four
+// consecutive k; it draws the coefficients of its four elements (element index
+// = position in the secret, as in the plain share kernel), evaluates every
+// party's share, stores it and packs its digits.  N, T > 0 fix the scheme at
+// compile time, 0 takes the run-time values.
+template <int N, int T>
+__global__ __launch_bounds__(256) void share_pack_kernel(const u64 *__restrict__ secret, u64 *__restrict__ shares,
+                                                         v4i *__restrict__ dst, int B, int K, int HW, int Kb,
+                                                         size_t dst_party_stride, int n_rt, int t_rt, ss_keys keys)
+{
+    constexpr int MAXP = N ? N : SS_MAXN, MAXD = T ? T : SS_MAXT;
+    const int n = N ? N : n_rt, t = T ? T : t_rt;
+    const int rb = blockIdx.x, kb = blockIdx.y, r16 = threadIdx.x & 15, kq = threadIdx.x >> 4;
+    const int row = rb * 16 + r16, k0 = kb * 64 + 4 * kq, rows = B * HW;
+    const size_t plane = (size_t)B * K * HW;
+    u64 y[MAXP][4];
+#pragma unroll
+    for (int p = 0; p < MAXP; p++)
+#pragma unroll
+        for (int q = 0; q < 4; q++) y[p][q] = 0;   // digits of padding rows and columns
+    if (row < rows) {
+        const int b = row / HW, hw = row - b * HW;
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            if (k0 + q < K) {
+                const size_t e = ((size_t)b * K + (k0 + q)) * HW + hw;
+                const u64 a0 = secret[e], counter = ss_counter(e);
+                u64 c[MAXD];
+#pragma unroll
+                for (int j = 0; j < MAXD; j++) c[j] = (j < t) ? ss_draw_field_at(keys.k[j], counter) : 0;
+                if constexpr (N != 0) {
+                    eval_points<T, N>(a0, c, [&](int p, u64 v) {
+                        shares[(size_t)p * plane + e] = v;
+                        y[p][q] = balanced_digits(v);
+                    });
+                } else {
+#pragma unroll
+                    for (int p = 0; p < MAXP; p++) {
+                        if (p < n) {
+                            const u64 v = ss_poly_eval<MAXD>(a0, c, t, p + 1);
+                            shares[(size_t)p * plane + e] = v;
+                            y[p][q] = balanced_digits(v);
+                        }
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < MAXP; p++)
+        if (p < n) store_digits(y[p], dst + (size_t)p * dst_party_stride + ((size_t)rb * Kb + kb) * 512, r16, kq);
 }
 
 #ifdef SS_GEMM_TRACE
@@ -473,6 +529,24 @@ hipError_t ss_launch_pack_matrix(const u64 *src, void *dst, int n, int rows, int
     const int Rb = (rows + 15) / 16, Kb = (K + 63) / 64;
     hipLaunchKernelGGL(pack_matrix_kernel, dim3(Rb, Kb, n), dim3(256), 0, stream, src, (v4i *)dst, rows, K, Kb,
                        party_stride, stride_r, stride_k, ss_packed_bytes(rows, K) / 16);
+    return hipGetLastError();
+}
+
+hipError_t ss_launch_share_pack(const u64 *secret, u64 *shares, void *dst, int n, int t, int B, int K, int HW,
+                                const ss_keys &keys, hipStream_t stream)
+{
+    const int rows = B * HW, Rb = (rows + 15) / 16, Kb = (K + 63) / 64;
+    const dim3 grid(Rb, Kb), block(256);
+    const size_t stride = ss_packed_bytes(rows, K) / 16;
+#define SS_SHARE_PACK(NC, TC) \
+    hipLaunchKernelGGL((share_pack_kernel<NC, TC>), grid, block, 0, stream, secret, shares, (v4i *)dst, B, K, HW, Kb, stride, n, t, keys)
+    if (n == 5 && t == 2)
+        SS_SHARE_PACK(5, 2);
+    else if (n == 3 && t == 1)
+        SS_SHARE_PACK(3, 1);
+    else
+        SS_SHARE_PACK(0, 0);
+#undef SS_SHARE_PACK
     return hipGetLastError();
 }
 

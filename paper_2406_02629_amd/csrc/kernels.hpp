@@ -64,6 +64,9 @@ size_t ss_packed_bytes(int rows, int K);
 // element (r, k) of party i is src[i*party_stride + r*stride_r + k*stride_k]
 hipError_t ss_launch_pack_matrix(const u64 *src, void *dst, int n, int rows, int K, size_t party_stride,
                                  size_t stride_r, size_t stride_k, hipStream_t stream);
+// degree-t shares of secret [B][K][HW] -> shares [n][B][K][HW] and their packed operand (rows (b, hw), k)
+hipError_t ss_launch_share_pack(const u64 *secret, u64 *shares, void *dst, int n, int t, int B, int K, int HW,
+                                const ss_keys &keys, hipStream_t stream);
 // rows = (b, ho, wo), k = (c, r, s) of x [n][B][C][H][W]
 hipError_t ss_launch_pack_im2col(const u64 *x, void *dst, int n, int B, int C, int H, int W, int kh, int kw,
                                  int stride, int pad, int Ho, int Wo, hipStream_t stream);

@@ -374,6 +374,19 @@ int ssnet_share(ssnet_ctx *ctx, const uint64_t *d_secret, size_t count, int degr
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
 
+int ssnet_share_packed(ssnet_ctx *ctx, const uint64_t *d_secret, int B, int K, int HW, uint64_t stream_id,
+                       uint64_t *d_shares, void *d_packed)
+{
+    if (!ctx || !d_secret || !d_shares || !d_packed || ((uintptr_t)d_packed & 15)) return SSNET_EINVAL;
+    if (B < 1 || HW < 1 || (long)B * HW > (1L << 30) || !gemm_shape_ok((long)B * HW, 1, K)) return SSNET_EINVAL;
+    if ((size_t)B * K * HW > MAX_COUNT) return SSNET_EINVAL;
+    ss_keys keys = {};
+    for (int j = 1; j <= ctx->t; j++) keys.k[j - 1] = ss_key(ctx->seed, SSNET_DOM_SHARE, stream_id, 0, (u64)j);
+    timed tm(ctx, SSNET_PROF_SHARE);
+    hipError_t e = ss_launch_share_pack(d_secret, d_shares, d_packed, ctx->n, ctx->t, B, K, HW, keys, ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
 int ssnet_reconstruct(ssnet_ctx *ctx, const uint64_t *d_shares, size_t count, const int *party_ids, int m, int degree,
                       uint64_t *d_secret)
 {
@@ -430,6 +443,26 @@ int ssnet_linear_mod_packed(ssnet_ctx *ctx, const uint64_t *d_x, const void *d_w
         if (e != hipSuccess) return fail_hip(ctx, e);
     }
     return run_gemm(ctx, px, d_w_packed, d_y, M, N, K, (size_t)M * N, (size_t)N, INT_MAX, 0);
+}
+
+int ssnet_linear_mod_prepacked(ssnet_ctx *ctx, const void *d_x_packed, const void *d_w_packed, int M, int K, int N,
+                               uint64_t *d_y)
+{
+    if (!ctx || !d_x_packed || !d_w_packed || !d_y || !gemm_shape_ok(M, N, K)) return SSNET_EINVAL;
+    if (!ws_fits(ctx, align256(ss_gemm_scratch_bytes(ctx->n, M, N, K)))) return SSNET_EWORKSPACE;
+    return run_gemm(ctx, d_x_packed, d_w_packed, d_y, M, N, K, (size_t)M * N, (size_t)N, INT_MAX, 0);
+}
+
+int ssnet_conv1x1_mod_prepacked(ssnet_ctx *ctx, const void *d_x_packed, const void *d_w_packed, int B, int C, int HW,
+                                int Co, uint64_t *d_y)
+{
+    if (!ctx || !d_x_packed || !d_w_packed || !d_y || B < 1 || HW < 1 || (long)B * HW > (1L << 30) ||
+        !gemm_shape_ok(Co, (long)B * HW, C))
+        return SSNET_EINVAL;
+    const int M = B * HW;
+    if (!ws_fits(ctx, align256(ss_gemm_scratch_bytes(ctx->n, Co, M, C)))) return SSNET_EWORKSPACE;
+    // rows = output channel, cols = (b, hw): y[b][co][hw]
+    return run_gemm(ctx, d_w_packed, d_x_packed, d_y, Co, M, C, (size_t)B * Co * HW, (size_t)HW, HW, (size_t)Co * HW);
 }
 
 int ssnet_linear_mod(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_w, int M, int K, int N, uint64_t *d_y)

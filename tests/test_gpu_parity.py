@@ -258,6 +258,35 @@ def test_conv_parity(n, t):
         assert np.array_equal(got2, want)
 
 
+@pytest.mark.parametrize("n,t", [(3, 1), (5, 2), (7, 3)])
+def test_share_packed_and_prepacked_layers(n, t):
+    """GEN fused with the limb split: shares against the oracle, tiles against the
+    separate pack call (through identical layer outputs), dense and 1x1 conv."""
+    s = SSNet(n, t, seed=21)
+    # conv input [B][C][H][W], ragged in every direction
+    for (B, C, H, W, Co) in [(1, 3, 5, 7, 2), (2, 70, 9, 9, 33), (1, 128, 14, 14, 64), (3, 64, 1, 1, 17)]:
+        say("share_packed conv", n, t, B, C, H, W, Co)
+        x = field_uniform(B * C * H * W, 3).reshape(B, C, H, W)
+        want = orc.share(x, n, t, P61, 21, 6)
+        xs, tiles = s.share_packed(to_dev(x), stream_id=6)
+        assert np.array_equal(to_np(xs), want)
+        assert bool(torch.equal(xs, s.share(to_dev(x), stream_id=6)))
+        w = orc.share(field_uniform(Co * C, 4).reshape(Co, C, 1, 1), n, t, P61, 21, 7)
+        wp = s.pack_weights_conv(to_dev(w))
+        y = s.conv1x1_mod_prepacked(tiles, wp, B, C, H, W, Co)
+        assert np.array_equal(to_np(y), orc.conv(want, w, 1, 0, P61))
+        assert bool(torch.equal(y, s.conv_mod_packed(xs, wp, Co, 1, 1, 1, 0)))
+    for (M, K, N) in [(1, 1, 1), (5, 100, 9), (1, 2048, 1000), (130, 64, 65)]:
+        say("share_packed dense", n, t, M, K, N)
+        x = field_uniform(M * K, 5).reshape(M, K)
+        want = orc.share(x, n, t, P61, 21, 8)
+        xs, tiles = s.share_packed(to_dev(x), stream_id=8)
+        assert np.array_equal(to_np(xs), want)
+        w = orc.share(field_uniform(K * N, 6).reshape(K, N), n, t, P61, 21, 9)
+        y = s.linear_mod_prepacked(tiles, s.pack_weights_linear(to_dev(w)), M, K, N)
+        assert np.array_equal(to_np(y), orc.linear(want, w, P61))
+
+
 def test_config1_tiny_secure_gemm_end_to_end():
     """n=3, t=1, f=13, X 64x256 ~ N(0,1), W 256x128 ~ N(0,1): share, multiply,
     reduce, truncate, reconstruct, decode."""
