@@ -202,16 +202,19 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"resnet{args.depth}-shaped linear stack, n=5 t=2 f=13 batch 1 (configs[4])",
                    "layers": len(chain.layers), "field_macs_per_step": macs,
-                   "steps_in_timed_region": "share, conv/dense, degree_reduce+rerand+truncate, reconstruct"},
+                   "steps_in_timed_region": "share (+limb split for dense/1x1 layers), conv/dense, "
+                                            "degree_reduce+rerand+truncate+reconstruct (one launch)"},
         "roofline": {"bound": "mfma", "kernel": "gemm_limb_kernel", "achieved": achieved, "peak": INT8_PEAK_TOPS,
                      "unit": "TOP/s", "frac": achieved / INT8_PEAK_TOPS,
                      "traffic": measured_traffic_bytes("gemm_limb_kernel"), "traffic_unit": "bytes per launch (HBM)",
                      "launches": int(gemm_launches), "avg_launch_us": gemm_ms * 1e3 / max(gemm_launches, 1),
                      "int8_ops_per_step": macs * OPS_PER_FIELD_MAC},
         "kernel_ms_per_step": breakdown,
-        # the chain calls ssnet_degree_reduce_truncate: both protocols' algorithmic bytes over one launch per layer
+        # the chain calls ssnet_degree_reduce_truncate_reconstruct: the three protocols' algorithmic bytes over
+        # one launch per layer
         "stream_GBps_in_chain": {
-            "degree_reduce+truncate": (dr_bytes + tr_bytes) / (prof["degree_reduce"][0] * 1e-3) / 1e9},
+            "degree_reduce+truncate+reconstruct":
+                (dr_bytes + tr_bytes + (ss.k + 1) * 8 * out_elems) / (prof["degree_reduce"][0] * 1e-3) / 1e9},
     }
     if args.copy_calibration:
         src = torch.zeros(1 << 27, dtype=torch.int64, device="cuda")
