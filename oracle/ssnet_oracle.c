@@ -20,8 +20,10 @@
  * F_11 truncation case of App. B, 5 * 2^-1 = 8 in F_11 (Sec. IV-A), closed
  * forms for Lagrange multipliers, R^2 = R and rank k for the reduction
  * matrix, brute force over every polynomial of F_11 / F_13, integer GEMM and
- * convolution against numpy / torch int64 on small magnitudes, and the
- * published SplitMix64 output sequence for the generator core.
+ * convolution against numpy / torch int64 on small magnitudes, the
+ * published SplitMix64 output sequence for the generator core, and for
+ * SSS-NonLinear (ReLU under a multiplicative mask, Sec. VI-C) brute force over
+ * every input and mask of a range in F_251 plus mask invariants at 2^61 - 1.
  * The choice of generator itself is not fixed by the paper ("randomly
  * generated", Sec. IV-A): parity unpinned for *which* random bits are drawn.
  */
@@ -142,7 +144,10 @@ enum {
     ORC_DOM_MASK_E = 4,
     ORC_DOM_MASK_ALPHA = 5,
     ORC_DOM_MASK_ALPHAT = 6,
-    ORC_DOM_TRUNC_GEN = 7
+    ORC_DOM_TRUNC_GEN = 7,
+    ORC_DOM_MASK_BETA = 8,
+    ORC_DOM_BETA_GEN = 9,
+    ORC_DOM_BETAINV_GEN = 10
 };
 
 /* coef[(j-1)*count + e] = a_j of element e, j = 1..degree.  eidx gives the
@@ -542,4 +547,79 @@ void orc_truncate(const u64 *x, size_t count, const u64 *eidx, int n, int t, int
     orc_draw_coeffs(seed, ORC_DOM_TRUNC_GEN, stream_id, 0, t, count, eidx, p, cw);
     orc_truncate_explicit(x, eval, ca, cat, cw, count, n, t, f, p, u, wsh, out);
     free(eval); free(ca); free(cat); free(cw);
+}
+
+/* ------------------------------------------------------------------ */
+/* SSS-NonLinear with ReLU (Sec. VI-C; masks: Sec. VII-B).              */
+/*                                                                      */
+/* Trusted source, ahead of the inference: a positive mask beta per      */
+/* element, its field inverse, and a degree-t sharing of each.           */
+/*   beta   [count]     1 <= beta (the paper draws it from (0, 2^28])    */
+/*   cb, cbi [t][count] coefficients of [[beta]] and [[beta^-1]]         */
+/*   sh_b, sh_bi [n][count]                                              */
+/* ------------------------------------------------------------------ */
+
+void orc_nonlinear_masks_explicit(const u64 *beta, const u64 *cb, const u64 *cbi, size_t count, int n, int t,
+                                  u64 p, u64 *sh_b, u64 *sh_bi)
+{
+    u64 *b = (u64 *)malloc(sizeof(u64) * count);
+    u64 *bi = (u64 *)malloc(sizeof(u64) * count);
+    for (size_t e = 0; e < count; e++) {
+        b[e] = beta[e] % p;
+        bi[e] = orc_inv(b[e], p); /* beta * beta^-1 = 1 in F_p */
+    }
+    orc_share_explicit(b, cb, count, n, t, p, sh_b);
+    orc_share_explicit(bi, cbi, count, n, t, p, sh_bi);
+    free(b); free(bi);
+}
+
+/* beta uniform in [1, 2^bbits] from the generator (domain MASK_BETA); the paper's choice is bbits = 28 */
+void orc_nonlinear_masks(size_t count, const u64 *eidx, int n, int t, int bbits, u64 p, u64 seed, u64 stream_id,
+                         u64 *sh_b, u64 *sh_bi)
+{
+    u64 *beta = (u64 *)malloc(sizeof(u64) * count);
+    u64 *cb = (u64 *)malloc(sizeof(u64) * (size_t)t * count);
+    u64 *cbi = (u64 *)malloc(sizeof(u64) * (size_t)t * count);
+    u64 key = orc_key(seed, ORC_DOM_MASK_BETA, stream_id, 0, 0);
+    for (size_t e = 0; e < count; e++)
+        beta[e] = 1 + (orc_draw(key, eidx ? eidx[e] : (u64)e) >> 3) % ((u64)1 << bbits);
+    orc_draw_coeffs(seed, ORC_DOM_BETA_GEN, stream_id, 0, t, count, eidx, p, cb);
+    orc_draw_coeffs(seed, ORC_DOM_BETAINV_GEN, stream_id, 0, t, count, eidx, p, cbi);
+    orc_nonlinear_masks_explicit(beta, cb, cbi, count, n, t, p, sh_b, sh_bi);
+    free(beta); free(cb); free(cbi);
+}
+
+/* The three steps of the protocol:                                      */
+/*   1. parties 1..2t+1: Hadamard product m_i = x_i * beta_i (a sharing   */
+/*      of x*beta of degree 2t)                       -> msg [2t+1][count] */
+/*   2. elite party: v = REC(m; IDs 1..2t+1) = x*beta; the non-linear     */
+/*      function in the clear on the signed value, y = max(v, 0)          */
+/*                                                    -> yplain [count]   */
+/*   3. every party: out_i = y * betainv_i (plain value times share: the  */
+/*      degree stays t)                               -> out [n][count]   */
+/* x, sh_b, sh_bi are [n][count]; msg and yplain may be NULL.            */
+/* Requires |x| * beta < p/2, so that the sign of x*beta is that of x.   */
+void orc_relu(const u64 *x, const u64 *sh_b, const u64 *sh_bi, size_t count, int n, int t, u64 p, u64 *msg,
+              u64 *yplain, u64 *out)
+{
+    int nr = 2 * t + 1;
+    int ids[ORC_MAXN];
+    for (int i = 0; i < nr; i++) ids[i] = i + 1;
+    u64 *m = (u64 *)calloc((size_t)n * count, sizeof(u64));
+    u64 *v = (u64 *)malloc(sizeof(u64) * count);
+    for (int i = 0; i < nr; i++)
+        for (size_t e = 0; e < count; e++) {
+            m[(size_t)i * count + e] = orc_mul(x[(size_t)i * count + e], sh_b[(size_t)i * count + e], p);
+            if (msg) msg[(size_t)i * count + e] = m[(size_t)i * count + e];
+        }
+    orc_reconstruct(m, count, ids, nr, p, v);
+    for (size_t e = 0; e < count; e++) {
+        i64 s = orc_lift1(v[e], p);
+        v[e] = s > 0 ? (u64)s : 0;
+        if (yplain) yplain[e] = v[e];
+    }
+    for (int i = 0; i < n; i++)
+        for (size_t e = 0; e < count; e++)
+            out[(size_t)i * count + e] = orc_mul(v[e], sh_bi[(size_t)i * count + e], p);
+    free(m); free(v);
 }

@@ -20,6 +20,7 @@ sz = C.c_size_t
 P = C.c_void_p
 
 DOM_SHARE, DOM_RESHARE, DOM_ZERO, DOM_MASK_E, DOM_MASK_ALPHA, DOM_MASK_ALPHAT, DOM_TRUNC_GEN = range(1, 8)
+DOM_MASK_BETA, DOM_BETA_GEN, DOM_BETAINV_GEN = 8, 9, 10
 
 
 def _sig(name, res, *args):
@@ -238,3 +239,36 @@ def truncate(x, n, t, f, p, seed, stream_id, eidx=None, full=False):
     out = np.empty((n,) + x.shape[1:], np.uint64)
     _tr(_p(x), count, _p(eidx), n, t, f, p, seed, stream_id, _p(u), _p(wsh), _p(out))
     return (out, u, wsh) if full else out
+
+
+# ---- SSS-NonLinear (ReLU) ----
+_nlm_explicit = _sig("orc_nonlinear_masks_explicit", None, P, P, P, sz, C.c_int, C.c_int, u64, P, P)
+_nlm = _sig("orc_nonlinear_masks", None, sz, P, C.c_int, C.c_int, C.c_int, u64, u64, u64, P, P)
+_relu = _sig("orc_relu", None, P, P, P, sz, C.c_int, C.c_int, u64, P, P, P)
+
+
+def nonlinear_masks_explicit(beta, cb, cbi, n, t, p):
+    """-> (shares of beta, shares of beta^-1), each [n, count]"""
+    beta, cb, cbi = _a(beta), _a(cb), _a(cbi)
+    count = beta.size
+    sb, sbi = np.empty((n, count), np.uint64), np.empty((n, count), np.uint64)
+    _nlm_explicit(_p(beta), _p(cb), _p(cbi), count, n, t, p, _p(sb), _p(sbi))
+    return sb, sbi
+
+
+def nonlinear_masks(count, n, t, bbits, p, seed, stream_id, eidx=None):
+    eidx = None if eidx is None else _a(eidx)
+    sb, sbi = np.empty((n, count), np.uint64), np.empty((n, count), np.uint64)
+    _nlm(count, _p(eidx), n, t, bbits, p, seed, stream_id, _p(sb), _p(sbi))
+    return sb, sbi
+
+
+def relu(x, sh_b, sh_bi, n, t, p, full=False):
+    """-> out [n, ...] (and with full: the 2t+1 masked products and the elite party's plain result)"""
+    x, sh_b, sh_bi = _a(x), _a(sh_b), _a(sh_bi)
+    count = x[0].size
+    msg = np.empty((2 * t + 1, count), np.uint64) if full else None
+    y = np.empty(count, np.uint64) if full else None
+    out = np.empty(x.shape, np.uint64)
+    _relu(_p(x), _p(sh_b), _p(sh_bi), count, n, t, p, _p(msg), _p(y), _p(out))
+    return (out, msg, y) if full else out

@@ -505,3 +505,70 @@ def test_tiny_secure_gemm_matches_float64_on_dequantised_operands():
         err = exact - got
         assert err.min() >= 0 and err.max() < 2.0 ** -f
     assert np.max(np.abs(got - X @ Wt)) < 2.0 ** -8
+
+
+# ----------------------------------------------------------------- SSS-NonLinear (ReLU), Sec. VI-C
+def _poly_shares(a0, coefs, n, p):
+    """shares of the polynomial a0 + c1 x + ... at IDs 1..n, with Python integers"""
+    return [(a0 + sum(c * pow(i, j + 1, p) for j, c in enumerate(coefs))) % p for i in range(1, n + 1)]
+
+
+@pytest.mark.parametrize("n,t", [(3, 1), (5, 2)])
+def test_relu_bruteforce_small_field(n, t):
+    """Every x in [-15, 15] and every mask beta in [1, 8] over F_251 (|x| beta < p/2): the output
+    shares open to max(x, 0) from every k-subset, the messages are the products of the shares,
+    and the elite party sees exactly x * beta."""
+    p, k, nr = 251, t + 1, 2 * t + 1
+    rng = random.Random(7)
+    xs = [x for x in range(-15, 16) for _ in range(8)]
+    betas = [b for _ in range(-15, 16) for b in range(1, 9)]
+    count = len(xs)
+    cx = [[rng.randrange(p) for _ in range(count)] for _ in range(t)]
+    cb = [[rng.randrange(p) for _ in range(count)] for _ in range(t)]
+    cbi = [[rng.randrange(p) for _ in range(count)] for _ in range(t)]
+    x_sh = np.array([_poly_shares(x % p, [c[e] for c in cx], n, p) for e, x in enumerate(xs)], np.uint64).T.copy()
+    sb, sbi = orc.nonlinear_masks_explicit(np.array(betas, np.uint64), np.array(cb, np.uint64),
+                                           np.array(cbi, np.uint64), n, t, p)
+    # the dealer's masks: degree-t sharings of beta and of its inverse
+    for e in range(count):
+        assert [int(v) for v in sb[:, e]] == _poly_shares(betas[e], [c[e] for c in cb], n, p)
+        assert [int(v) for v in sbi[:, e]] == _poly_shares(pow(betas[e], -1, p), [c[e] for c in cbi], n, p)
+    out, msg, y = orc.relu(x_sh, sb, sbi, n, t, p, full=True)
+    for e in range(count):
+        for i in range(nr):
+            assert int(msg[i, e]) == int(x_sh[i, e]) * int(sb[i, e]) % p
+        assert int(y[e]) == max(xs[e] * betas[e], 0)
+    for ids in itertools.combinations(range(1, n + 1), k):
+        rec = orc.reconstruct(out, list(ids), p)
+        assert [int(v) for v in rec] == [max(x, 0) for x in xs], ids
+    # the product sharing has degree 2t: 2t+1 points open it, 2t points in general do not
+    full = orc.reconstruct(np.vstack([msg, np.zeros((n - nr, count), np.uint64)]), list(range(1, nr + 1)), p)
+    assert [int(v) for v in full] == [x * b % p for x, b in zip(xs, betas)]
+    short = orc.reconstruct(np.vstack([msg, np.zeros((n - nr, count), np.uint64)]), list(range(1, nr)), p)
+    assert sum(int(a) != int(b) for a, b in zip(short, full)) > count // 2
+
+
+def test_relu_seeded_masks_mersenne61():
+    """p = 2^61 - 1, beta in [1, 2^28] as in Sec. VII-B: mask invariants and the opened result for
+    16-bit-scale and extreme inputs."""
+    n, t, count, seed = 5, 2, 4096, 11
+    sb, sbi = orc.nonlinear_masks(count, n, t, 28, P61, seed, 3)
+    for ids in ([1, 2, 3], [2, 4, 5], [3, 4, 5]):
+        beta = orc.reconstruct(sb, ids, P61)
+        binv = orc.reconstruct(sbi, ids, P61)
+        assert int(beta.min()) >= 1 and int(beta.max()) <= 1 << 28
+        assert all(int(b) * int(bi) % P61 == 1 for b, bi in zip(beta, binv))
+    assert len(set(int(b) for b in orc.reconstruct(sb, [1, 2, 3], P61))) > count - 8     # not a constant
+    # sampled element indices draw the same masks as the full run
+    idx = np.array([0, 5, 77, 4095], np.uint64)
+    sb2, sbi2 = orc.nonlinear_masks(4, n, t, 28, P61, seed, 3, eidx=idx)
+    assert np.array_equal(sb2, sb[:, idx.astype(np.int64)]) and np.array_equal(sbi2, sbi[:, idx.astype(np.int64)])
+    rng = np.random.default_rng(5)
+    xs = rng.integers(-(1 << 31), 1 << 31, count, dtype=np.int64)
+    xs[:6] = [0, 1, -1, (1 << 32) - 1, -((1 << 32) - 1), 12345]
+    x_sh = orc.share(np.where(xs < 0, xs + P61, xs).astype(np.uint64), n, t, P61, seed, 9)
+    out = orc.relu(x_sh, sb, sbi, n, t, P61)
+    for ids in ([1, 2, 3], [1, 3, 5]):
+        assert np.array_equal(orc.reconstruct(out, ids, P61).astype(np.int64), np.maximum(xs, 0))
+    # degree of the result stays t: k = 3 shares determine the other two
+    assert np.array_equal(orc.reconstruct(out, [1, 2, 3], P61), orc.reconstruct(out, [3, 4, 5], P61))
