@@ -177,6 +177,27 @@ int ssnet_degree_reduce_truncate(ssnet_ctx *ctx, const uint64_t *d_c, size_t cou
 int ssnet_degree_reduce_truncate_reconstruct(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id,
                                              uint64_t *d_out, const int *party_ids, int m, uint64_t *d_secret);
 
+/* SSS-NonLinear with ReLU (Sec. VI-C), on shares that were truncated before
+ * (order Linear - Truncation - NonLinear, Sec. VII-A).
+ *   ssnet_nonlinear_masks: what the trusted source prepares ahead of the
+ *     inference (Sec. VII-B): per element a mask beta, uniform in
+ *     [1, 2^SSNET_BETA_BITS] (domain MASK_BETA), its inverse in F_p, and a
+ *     degree-t sharing of each (domains BETA_GEN, BETAINV_GEN) -> d_beta,
+ *     d_betainv [n][count].
+ *   ssnet_relu: 1. parties 1..2t+1 multiply their share of x by their share of
+ *     beta; 2. the elite party reconstructs x*beta from the 2t+1 products and
+ *     applies max(., 0) to the signed value in the clear; 3. every party
+ *     multiplies that plain value by its share of beta^-1.  d_x, d_beta,
+ *     d_betainv, d_out [n][count]; d_out is a degree-t sharing of max(x, 0).
+ *     Requires |x| * 2^SSNET_BETA_BITS < p/2, i.e. |x| < 2^32.  The 2t+1
+ *     products and the plain value go through the workspace ([2t+1][count] then
+ *     [count] behind the header; ssnet_workspace_bytes_stream(count) covers
+ *     it).  d_out may alias d_x. */
+#define SSNET_BETA_BITS 28
+int ssnet_nonlinear_masks(ssnet_ctx *ctx, size_t count, uint64_t stream_id, uint64_t *d_beta, uint64_t *d_betainv);
+int ssnet_relu(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_beta, const uint64_t *d_betainv, size_t count,
+               uint64_t *d_out);
+
 /* Host-side generator, exposed so that its bits can be checked without a GPU.
  * key = absorb(seed, domain, stream_id, party, j) with h <- mix64((h ^ word) +
  * 0x9E3779B97F4A7C15) from h = 0, mix64 being the SplitMix64 output function;
@@ -189,6 +210,9 @@ int ssnet_degree_reduce_truncate_reconstruct(ssnet_ctx *ctx, const uint64_t *d_c
 #define SSNET_DOM_MASK_ALPHA 5
 #define SSNET_DOM_MASK_ALPHAT 6
 #define SSNET_DOM_TRUNC_GEN 7
+#define SSNET_DOM_MASK_BETA 8
+#define SSNET_DOM_BETA_GEN 9
+#define SSNET_DOM_BETAINV_GEN 10
 uint64_t ssnet_rng_key(uint64_t seed, uint64_t domain, uint64_t stream_id, uint64_t party, uint64_t j);
 uint64_t ssnet_rng_draw(uint64_t key, uint64_t e);
 uint64_t ssnet_rng_field(uint64_t key, uint64_t e);
@@ -213,7 +237,8 @@ int ssnet_host_reduction_matrix(const ssnet_ctx *ctx, uint64_t *out);
 #define SSNET_PROF_GEMM 4
 #define SSNET_PROF_DEGREE_REDUCE 5
 #define SSNET_PROF_TRUNCATE 6
-#define SSNET_PROF_CLASSES 7
+#define SSNET_PROF_NONLINEAR 7
+#define SSNET_PROF_CLASSES 8
 int ssnet_profile_begin(ssnet_ctx *ctx);
 int ssnet_profile_end(ssnet_ctx *ctx, double *ms_by_class, uint64_t *spans_by_class);
 

@@ -46,6 +46,8 @@ SIGNATURES = {
     "ssnet_truncate": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
     "ssnet_degree_reduce_truncate": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
     "ssnet_degree_reduce_truncate_reconstruct": (_int, [_ptr, _ptr, _sz, _u64, _ptr, C.POINTER(_int), _int, _ptr]),
+    "ssnet_nonlinear_masks": (_int, [_ptr, _sz, _u64, _ptr, _ptr]),
+    "ssnet_relu": (_int, [_ptr, _ptr, _ptr, _ptr, _sz, _ptr]),
     "ssnet_rng_key": (_u64, [_u64] * 5),
     "ssnet_rng_draw": (_u64, [_u64, _u64]),
     "ssnet_rng_field": (_u64, [_u64, _u64]),
@@ -333,7 +335,31 @@ class SSNet:
         return out, secret
 
     # ---- live kernel timing ----
-    PROF_CLASSES = ("share", "reconstruct", "pack_w", "pack_x", "gemm", "degree_reduce", "truncate")
+    def nonlinear_masks(self, shape, stream_id: int, device=None):
+        """-> (shares of beta, shares of beta^-1), each [n, *shape]; offline preprocessing"""
+        shape = tuple(shape) if not isinstance(shape, int) else (shape,)
+        device = device or self.device or "cuda"
+        b = torch.empty((self.n,) + shape, dtype=torch.int64, device=device)
+        bi = torch.empty_like(b)
+        self._ok(self.lib.ssnet_nonlinear_masks(self._ctx, b[0].numel(), stream_id, _dptr(b), _dptr(bi)),
+                 "ssnet_nonlinear_masks")
+        return b, bi
+
+    def relu(self, x: torch.Tensor, beta: torch.Tensor, betainv: torch.Tensor,
+             out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        _check_i64(x, "x")
+        _check_i64(beta, "beta")
+        _check_i64(betainv, "betainv")
+        count = x[0].numel()
+        if beta.numel() != x.numel() or betainv.numel() != x.numel():
+            raise SSNetError(EINVAL, "relu: mask shares must have the shape of x")
+        self.reserve(self.workspace_bytes_stream(count))
+        if out is None:
+            out = torch.empty_like(x)
+        self._ok(self.lib.ssnet_relu(self._ctx, _dptr(x), _dptr(beta), _dptr(betainv), count, _dptr(out)), "ssnet_relu")
+        return out
+
+    PROF_CLASSES = ("share", "reconstruct", "pack_w", "pack_x", "gemm", "degree_reduce", "truncate", "nonlinear")
 
     def profile_begin(self):
         self._ok(self.lib.ssnet_profile_begin(self._ctx), "ssnet_profile_begin")

@@ -42,6 +42,14 @@ struct ss_recf_params {           // REC fused behind another step: multiplier o
     u64 dinv;
 };
 
+struct ss_nl_params {             // SSS-NonLinear
+    int n, t, bbits;              // beta uniform in [1, 2^bbits]
+    u64 beta_key;
+    u64 bgen_key[SS_MAXT], bigen_key[SS_MAXT];   // coefficients of [[beta]], [[beta^-1]]
+    int ilambda[2 * SS_MAXT + 1]; // REC from the IDs 1..2t+1 (integers: (-1)^(i-1) C(2t+1, i))
+    u64 dinv;
+};
+
 // ---- streaming family (stream_kernels.hip) ----
 hipError_t ss_launch_share(const u64 *secret, u64 *shares, size_t count, int n, int degree,
                            const ss_keys &keys, hipStream_t stream);
@@ -55,6 +63,11 @@ hipError_t ss_launch_truncate(const u64 *x, u64 *u, u64 *wsh, u64 *out, size_t c
 hipError_t ss_launch_degree_reduce_truncate(const u64 *c, u64 *msg1, u64 *msg2, u64 *u, u64 *wsh, u64 *out,
                                             u64 *rec, size_t count, const ss_dr_params &dp, const ss_tr_params &tp,
                                             const ss_recf_params &rf, hipStream_t stream);
+
+// SSS-NonLinear (Sec. VI-C): the trusted source's masks, then ReLU under the mask
+hipError_t ss_launch_nonlinear_masks(u64 *sh_b, u64 *sh_bi, size_t count, const ss_nl_params &np, hipStream_t stream);
+hipError_t ss_launch_relu(const u64 *x, const u64 *sh_b, const u64 *sh_bi, u64 *msg, u64 *yplain, u64 *out,
+                          size_t count, const ss_nl_params &np, hipStream_t stream);
 
 // ---- int8-limb MFMA family (gemm_kernels.hip) ----
 // Packed operand: int8 tiles [row block of 16][k block of 64][limb 0..7][lane 0..63][16 bytes];

@@ -626,6 +626,50 @@ int ssnet_degree_reduce_truncate_reconstruct(ssnet_ctx *ctx, const uint64_t *d_c
     return degree_reduce_truncate(ctx, d_c, count, stream_id, d_out, party_ids, m, d_secret);
 }
 
+namespace {
+
+bool make_nl_params(const ssnet_ctx *ctx, uint64_t stream_id, ss_nl_params *np)
+{
+    *np = {};
+    np->n = ctx->n;
+    np->t = ctx->t;
+    np->bbits = SSNET_BETA_BITS;
+    np->beta_key = ss_key(ctx->seed, SSNET_DOM_MASK_BETA, stream_id, 0, 0);
+    for (int j = 1; j <= ctx->t; j++) {
+        np->bgen_key[j - 1] = ss_key(ctx->seed, SSNET_DOM_BETA_GEN, stream_id, 0, (u64)j);
+        np->bigen_key[j - 1] = ss_key(ctx->seed, SSNET_DOM_BETAINV_GEN, stream_id, 0, (u64)j);
+    }
+    int ids[2 * SS_MAXT + 1];
+    for (int i = 0; i < 2 * ctx->t + 1; i++) ids[i] = i + 1;
+    return h_lagrange_int(ids, 2 * ctx->t + 1, np->ilambda, &np->dinv);
+}
+
+}  // namespace
+
+int ssnet_nonlinear_masks(ssnet_ctx *ctx, size_t count, uint64_t stream_id, uint64_t *d_beta, uint64_t *d_betainv)
+{
+    if (!ctx || !d_beta || !d_betainv || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
+    ss_nl_params np;
+    if (!make_nl_params(ctx, stream_id, &np)) return SSNET_EINVAL;
+    timed tm(ctx, SSNET_PROF_NONLINEAR);
+    hipError_t e = ss_launch_nonlinear_masks(d_beta, d_betainv, count, np, ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+int ssnet_relu(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_beta, const uint64_t *d_betainv, size_t count,
+               uint64_t *d_out)
+{
+    if (!ctx || !d_x || !d_beta || !d_betainv || !d_out || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
+    const int nr = 2 * ctx->t + 1;
+    if (!ws_fits(ctx, (size_t)(nr + 1) * count * 8)) return SSNET_EWORKSPACE;
+    ss_nl_params np;
+    if (!make_nl_params(ctx, 0, &np)) return SSNET_EINVAL;
+    u64 *msg = (u64 *)ws_scratch(ctx), *yplain = msg + (size_t)nr * count;
+    timed tm(ctx, SSNET_PROF_NONLINEAR);
+    hipError_t e = ss_launch_relu(d_x, d_beta, d_betainv, msg, yplain, d_out, count, np, ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
 uint64_t ssnet_rng_key(uint64_t seed, uint64_t domain, uint64_t stream_id, uint64_t party, uint64_t j)
 {
     return ss_key(seed, domain, stream_id, party, j);

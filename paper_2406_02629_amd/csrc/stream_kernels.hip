@@ -554,6 +554,84 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_lanes_kernel(const u64 *c
     }
 }
 
+// ------------------------------------------------------------------ SSS-NonLinear (Sec. VI-C)
+// What the trusted source prepares ahead of the inference (Sec. VII-B): a positive
+// mask beta per element, its inverse in F_p (Fermat: beta^(p-2), p - 2 = 2^61 - 3)
+// and a degree-t sharing of each.  One thread per element.
+__global__ __launch_bounds__(BLOCK) void nonlinear_masks_kernel(u64 *__restrict__ sh_b, u64 *__restrict__ sh_bi,
+                                                                size_t count, ss_nl_params np)
+{
+    const size_t e = (size_t)blockIdx.x * BLOCK + threadIdx.x;
+    if (e >= count) return;
+    const u64 beta = 1 + ((ss_draw(np.beta_key, e) >> 3) & ((1ULL << np.bbits) - 1));
+    // beta^(2^61 - 3): the exponent is 59 one bits, then 0, then 1
+    u64 inv = beta;
+    for (int i = 0; i < 58; i++) inv = ss_mul(ss_mul(inv, inv), beta);   // beta^(2^59 - 1)
+    inv = ss_mul(inv, inv);                                              // bit 1 of the exponent is 0
+    inv = ss_mul(ss_mul(inv, inv), beta);                                // bit 0 is 1
+    u64 cb[SS_MAXT], cbi[SS_MAXT];
+    draw_coeffs<SS_MAXT>(cb, np.bgen_key, np.t, e);
+    draw_coeffs<SS_MAXT>(cbi, np.bigen_key, np.t, e);
+#pragma unroll
+    for (int m = 0; m < SS_MAXN; m++) {
+        if (m < np.n) {
+            sh_b[(size_t)m * count + e] = ss_poly_eval<SS_MAXT>(beta, cb, np.t, m + 1);
+            sh_bi[(size_t)m * count + e] = ss_poly_eval<SS_MAXT>(inv, cbi, np.t, m + 1);
+        }
+    }
+}
+
+// ReLU on shares, the three steps for the elements a thread owns (send = store
+// to the workspace, receive = from registers, as in the kernels above):
+//   1. parties 1..2t+1: m_i = x_i * beta_i                          -> msg[i]
+//   2. elite party: REC of the 2t+1 products = x * beta; ReLU on the
+//      signed value, in the clear                                   -> yplain
+//   3. every party: out_i = y * betainv_i                            -> out[i]
+template <int VEC>
+__global__ __launch_bounds__(BLOCK) void relu_kernel(const u64 *x, const u64 *__restrict__ sh_b,
+                                                     const u64 *__restrict__ sh_bi, u64 *__restrict__ msg,
+                                                     u64 *__restrict__ yplain, u64 *out, size_t count,
+                                                     ss_nl_params np)
+{
+    const size_t e0 = ((size_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
+    if (e0 >= count) return;
+    const int nr = 2 * np.t + 1;
+    ss_sacc acc[VEC];
+#pragma unroll
+    for (int u = 0; u < VEC; u++) acc[u].clear();
+#pragma unroll
+    for (int i = 0; i < 2 * SS_MAXT + 1; i++) {
+        if (i < nr) {
+            pack_t<VEC> xi, bi, m;
+            xi.load(x + (size_t)i * count + e0);
+            bi.load(sh_b + (size_t)i * count + e0);
+#pragma unroll
+            for (int u = 0; u < VEC; u++) {
+                m.v[u] = ss_mul(xi.v[u], bi.v[u]);
+                acc[u].mac(m.v[u], np.ilambda[i]);
+            }
+            m.store(msg + (size_t)i * count + e0);
+        }
+    }
+    pack_t<VEC> y;
+#pragma unroll
+    for (int u = 0; u < VEC; u++) {
+        const u64 v = np.dinv == 1 ? acc[u].value() : ss_mul(acc[u].value(), np.dinv);
+        y.v[u] = v <= (SS_P - 1) / 2 ? v : 0;   // negative values are the upper half of the field
+    }
+    y.store(yplain + e0);
+#pragma unroll
+    for (int m = 0; m < SS_MAXN; m++) {
+        if (m < np.n) {
+            pack_t<VEC> bi, o;
+            bi.load(sh_bi + (size_t)m * count + e0);
+#pragma unroll
+            for (int u = 0; u < VEC; u++) o.v[u] = ss_mul(y.v[u], bi.v[u]);
+            o.store(out + (size_t)m * count + e0);
+        }
+    }
+}
+
 // below this many elements one element per thread gives more waves to hide latency
 constexpr size_t VEC2_MIN_COUNT = (size_t)1 << 20;
 // below this many elements degree reduction spreads an element over party lanes
@@ -657,5 +735,22 @@ hipError_t ss_launch_truncate(const u64 *x, u64 *u, u64 *wsh, u64 *out, size_t c
                     count >= VEC2_MIN_COUNT;
     auto grid = [&](int vec) { return dim3(blocks_for(count, vec)); };
     SS_DISPATCH_VEC(v2, truncate_kernel, grid, x, u, wsh, out, count, tp);
+    return hipGetLastError();
+}
+
+hipError_t ss_launch_nonlinear_masks(u64 *sh_b, u64 *sh_bi, size_t count, const ss_nl_params &np, hipStream_t stream)
+{
+    hipLaunchKernelGGL(nonlinear_masks_kernel, dim3(blocks_for(count, 1)), dim3(BLOCK), 0, stream, sh_b, sh_bi, count,
+                       np);
+    return hipGetLastError();
+}
+
+hipError_t ss_launch_relu(const u64 *x, const u64 *sh_b, const u64 *sh_bi, u64 *msg, u64 *yplain, u64 *out,
+                          size_t count, const ss_nl_params &np, hipStream_t stream)
+{
+    const bool v2 = (count % 2 == 0) && aligned16(x) && aligned16(sh_b) && aligned16(sh_bi) && aligned16(msg) &&
+                    aligned16(yplain) && aligned16(out);
+    auto grid = [&](int vec) { return dim3(blocks_for(count, vec)); };
+    SS_DISPATCH_VEC(v2, relu_kernel, grid, x, sh_b, sh_bi, msg, yplain, out, count, np);
     return hipGetLastError();
 }

@@ -287,6 +287,32 @@ def test_share_packed_and_prepacked_layers(n, t):
         assert np.array_equal(to_np(y), orc.linear(want, w, P61))
 
 
+@pytest.mark.parametrize("n,t", SCHEMES)
+def test_relu_parity_with_masks_and_messages(n, t):
+    """SSS-NonLinear: the trusted source's mask shares, the 2t+1 masked products, the elite
+    party's plain value and the output shares, all against the oracle."""
+    s = SSNet(n, t, seed=55)
+    nr = 2 * t + 1
+    for count in (1, 2, 255, 4099, 65538):
+        say("relu", n, t, count)
+        sb, sbi = s.nonlinear_masks(count, stream_id=12)
+        osb, osbi = orc.nonlinear_masks(count, n, t, 28, P61, 55, 12)
+        assert np.array_equal(to_np(sb), osb) and np.array_equal(to_np(sbi), osbi)
+        rng = np.random.default_rng(count)
+        xs = rng.integers(-(1 << 31), 1 << 31, count, dtype=np.int64)
+        xs[: min(count, 5)] = [0, (1 << 32) - 1, -((1 << 32) - 1), 1, -1][: min(count, 5)]
+        x = orc.share(np.where(xs < 0, xs + P61, xs).astype(np.uint64), n, t, P61, 55, 13)
+        want, msg, y = orc.relu(x, osb, osbi, n, t, P61, full=True)
+        d = to_dev(x)
+        got = s.relu(d, sb, sbi, out=d)                                  # in place
+        ws = to_np(s.messages()[: (nr + 1) * count])
+        assert np.array_equal(ws[: nr * count].reshape(nr, count), msg)
+        assert np.array_equal(ws[nr * count:], y)
+        assert np.array_equal(to_np(got), want)
+        assert np.array_equal(to_np(s.reconstruct(got, list(range(n, n - t - 1, -1)))).astype(np.int64),
+                              np.maximum(xs, 0))
+
+
 def test_config1_tiny_secure_gemm_end_to_end():
     """n=3, t=1, f=13, X 64x256 ~ N(0,1), W 256x128 ~ N(0,1): share, multiply,
     reduce, truncate, reconstruct, decode."""
