@@ -145,6 +145,35 @@ def measured_traffic_bytes(kernel):
     return None
 
 
+def secure_chain(chain, ss, steps, warmup, macs, out_elems):
+    """The same stack with ReLU evaluated on the shares (SSS-NonLinear, Sec. VI-C): a layer's output
+    shares feed the next layer, nothing is opened except at the two pooling points.  Reported beside
+    the headline, not in it."""
+    import torch
+    chain.secure_prepare()
+    torch.cuda.synchronize()
+    for _ in range(warmup):
+        chain.secure_timed()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        chain.secure_timed()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    ss.profile_begin()
+    chain.secure_timed()
+    prof = ss.profile_end()
+    relu_elems = sum(L.cout * L.M for L in chain.layers if L.post == "relu")
+    nr = 2 * ss.t + 1
+    relu_bytes = (3 * nr + (nr + 1) + 3 * ss.n) * 8 * relu_elems     # per party: operands in, message / result out
+    return {"workload": "same stack, Linear - Truncation - NonLinear per layer on shares; opened only at the "
+                        "max-pool, the global average and the logits",
+            "ms_per_step": ms, "field_MAC_per_s": macs / (ms * 1e-3),
+            "kernel_ms_per_step": {k: {"ms": round(v[0], 4), "spans": int(v[1])} for k, v in prof.items() if v[1]},
+            "relu_GBps": relu_bytes / (prof["nonlinear"][0] * 1e-3) / 1e9 if prof["nonlinear"][1] else None,
+            "relu_elements_per_step": relu_elems}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -154,6 +183,7 @@ def main():
     ap.add_argument("--bulk-log2", type=int, default=28)
     ap.add_argument("--no-bulk", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-secure", action="store_true", help="skip the pass with ReLU on shares")
     ap.add_argument("--cpu-layers", type=int, default=152)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale profiler counters)")
@@ -216,6 +246,8 @@ def main():
             "degree_reduce+truncate+reconstruct":
                 (dr_bytes + tr_bytes + (ss.k + 1) * 8 * out_elems) / (prof["degree_reduce"][0] * 1e-3) / 1e9},
     }
+    if not args.no_secure:
+        result["nonlinear_on_shares"] = secure_chain(chain, ss, args.steps, args.warmup, macs, out_elems)
     if args.copy_calibration:
         src = torch.zeros(1 << 27, dtype=torch.int64, device="cuda")
         dst = torch.empty_like(src)

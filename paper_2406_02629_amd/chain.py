@@ -1,5 +1,14 @@
 """Harness for a sequential stack of linear layers evaluated on Shamir shares.
 
+Two ways through the stack:
+  * `forward_prepare` / `forward_timed`: every layer's result is opened and the
+    activation applied to the plain integers (see below);
+  * `secure_prepare` / `secure_timed`: ReLU runs on the shares (SSS-NonLinear,
+    Sec. VI-C, order Linear - Truncation - NonLinear of Sec. VII-A), so a layer's
+    output shares are the next layer's input and nothing is opened; only the two
+    pooling points of the stack (max-pool after the stem, global average before
+    the classifier) still go through the plain route.
+
 Per layer, on the GPU library (Sec. VI, order Linear -> Truncation):
     share the layer input (GEN) -> conv / dense on shares -> degree reduction
     with re-randomisation -> truncation by 2^f -> reconstruct (REC).
@@ -139,3 +148,56 @@ class Chain:
 
     def total_field_macs(self) -> int:
         return self.ss.n * self.batch * sum(L.macs for L in self.layers)
+
+    # ------------------------------------------------------------------ ReLU on shares
+    MASK_STREAM_BASE = 1 << 21     # stream ids of the non-linear masks, apart from the others
+
+    def secure_setup(self):
+        """Offline part of SSS-NonLinear: the trusted source's mask shares for every layer whose
+        activation is a plain ReLU (Sec. VII-B)."""
+        ss = self.ss
+        self.masks = [ss.nonlinear_masks(self._out_shape(L), stream_id=self.MASK_STREAM_BASE + l, device=ss.device or "cuda")
+                      if L.post == "relu" else None for l, L in enumerate(self.layers)]
+
+    def secure_layer(self, l: int, x_plain: Optional[torch.Tensor], x_shares: Optional[torch.Tensor]):
+        """Layer l from its plain input (shared here) or from the previous layer's output shares.
+        -> (output shares after the activation, or None; opened result, or None)"""
+        ss, L = self.ss, self.layers[l]
+        y = self.y[l]
+        if x_shares is None:
+            x_shares = ss.share(x_plain, stream_id=l, out=self.x_shares[l])
+        if L.kind == "conv":
+            ss.conv_mod_packed(x_shares, self.packed[l], L.cout, L.ksize, L.ksize, L.stride, L.pad, out=y)
+        else:
+            ss.linear_mod_packed(x_shares, self.packed[l], L.cout, out=y)
+        yv = y.view(ss.n, -1)
+        if L.post == "relu":
+            ss.degree_reduce_truncate(yv, stream_id=l, out=yv)
+            b, bi = self.masks[l]
+            ss.relu(y, b, bi, out=y)
+            return y, None
+        ss.degree_reduce_truncate_reconstruct(yv, stream_id=l, ids=self.ids, out=yv, secret=self.rec[l])
+        return None, self.rec[l]
+
+    def secure_prepare(self):
+        """One pass; records the plain inputs of the layers that follow a pooling point.
+        Returns the last layer's opened output."""
+        if not hasattr(self, "masks"):
+            self.secure_setup()
+        self.secure_plain: List[Optional[torch.Tensor]] = [None] * len(self.layers)
+        x_plain, x_shares, out = self.image, None, None
+        for l, L in enumerate(self.layers):
+            if x_shares is None:
+                if L.kind == "fc":
+                    x_plain = x_plain.reshape(self.batch, -1)
+                self.secure_plain[l] = x_plain.contiguous()
+            x_shares, out = self.secure_layer(l, self.secure_plain[l], x_shares)
+            if x_shares is None and L.post is not None:
+                x_plain = fx.from_signed(post_plain(fx.lift(out), L.post))
+        return out
+
+    def secure_timed(self):
+        """The share arithmetic of the whole stack, layer feeding layer."""
+        x_shares = None
+        for l in range(len(self.layers)):
+            x_shares, _ = self.secure_layer(l, self.secure_plain[l], x_shares)

@@ -596,18 +596,28 @@ __global__ __launch_bounds__(BLOCK) void relu_kernel(const u64 *x, const u64 *__
     const size_t e0 = ((size_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
     if (e0 >= count) return;
     const int nr = 2 * np.t + 1;
+    // all operands are requested up front, so that the three steps wait for memory once
+    pack_t<VEC> xi[2 * SS_MAXT + 1], bi[2 * SS_MAXT + 1], binv[SS_MAXN];
+#pragma unroll
+    for (int i = 0; i < 2 * SS_MAXT + 1; i++) {
+        if (i < nr) {
+            xi[i].load(x + (size_t)i * count + e0);
+            bi[i].load(sh_b + (size_t)i * count + e0);
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < SS_MAXN; m++)
+        if (m < np.n) binv[m].load(sh_bi + (size_t)m * count + e0);
     ss_sacc acc[VEC];
 #pragma unroll
     for (int u = 0; u < VEC; u++) acc[u].clear();
 #pragma unroll
     for (int i = 0; i < 2 * SS_MAXT + 1; i++) {
         if (i < nr) {
-            pack_t<VEC> xi, bi, m;
-            xi.load(x + (size_t)i * count + e0);
-            bi.load(sh_b + (size_t)i * count + e0);
+            pack_t<VEC> m;
 #pragma unroll
             for (int u = 0; u < VEC; u++) {
-                m.v[u] = ss_mul(xi.v[u], bi.v[u]);
+                m.v[u] = ss_mul(xi[i].v[u], bi[i].v[u]);
                 acc[u].mac(m.v[u], np.ilambda[i]);
             }
             m.store(msg + (size_t)i * count + e0);
@@ -623,10 +633,9 @@ __global__ __launch_bounds__(BLOCK) void relu_kernel(const u64 *x, const u64 *__
 #pragma unroll
     for (int m = 0; m < SS_MAXN; m++) {
         if (m < np.n) {
-            pack_t<VEC> bi, o;
-            bi.load(sh_bi + (size_t)m * count + e0);
+            pack_t<VEC> o;
 #pragma unroll
-            for (int u = 0; u < VEC; u++) o.v[u] = ss_mul(y.v[u], bi.v[u]);
+            for (int u = 0; u < VEC; u++) o.v[u] = ss_mul(y.v[u], binv[m].v[u]);
             o.store(out + (size_t)m * count + e0);
         }
     }
@@ -749,7 +758,7 @@ hipError_t ss_launch_relu(const u64 *x, const u64 *sh_b, const u64 *sh_bi, u64 *
                           size_t count, const ss_nl_params &np, hipStream_t stream)
 {
     const bool v2 = (count % 2 == 0) && aligned16(x) && aligned16(sh_b) && aligned16(sh_bi) && aligned16(msg) &&
-                    aligned16(yplain) && aligned16(out);
+                    aligned16(yplain) && aligned16(out) && count >= VEC2_MIN_COUNT;
     auto grid = [&](int vec) { return dim3(blocks_for(count, vec)); };
     SS_DISPATCH_VEC(v2, relu_kernel, grid, x, sh_b, sh_bi, msg, yplain, out, count, np);
     return hipGetLastError();

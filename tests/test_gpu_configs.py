@@ -134,6 +134,55 @@ def run_chain_parity(depth, n, t, f, seed, full_every=1):
     return worst_float
 
 
+def run_secure_chain_parity(depth, n, t, f, seed):
+    """The stack with ReLU on shares (SSS-NonLinear): every layer's output shares against an
+    oracle chain of its own, and the opened logits against the chain that opens every layer."""
+    layers = resnet_chain(depth)
+    ss = SSNet(n, t, f=f, seed=seed)
+    chain = Chain(ss, layers)
+    chain.secure_setup()
+    x_plain_g, x_sh_g = chain.image, None
+    x_plain_o, x_sh_o = orc.encode(gaussian((1, 3, 224, 224), 5), f, P61), None
+    t0 = time.time()
+    rec_g = rec_o = None
+    for l, L in enumerate(layers):
+        shape = (L.cout, L.cin, L.ksize, L.ksize) if L.kind == "conv" else (L.cin, L.cout)
+        ws = orc.share(orc.encode(he_normal(shape, L.K, 100 + l), f, P61), n, t, P61, seed, WEIGHT_STREAM_BASE + l)
+        if x_sh_o is None:
+            if L.kind == "fc":
+                x_plain_g, x_plain_o = x_plain_g.reshape(1, -1), x_plain_o.reshape(1, -1)
+            assert np.array_equal(to_np(x_plain_g), x_plain_o), f"layer {l}: plain input"
+            x_sh_o = orc.share(x_plain_o, n, t, P61, seed, l)
+        y2 = orc.conv(x_sh_o, ws, L.stride, L.pad, P61) if L.kind == "conv" else orc.linear(x_sh_o, ws, P61)
+        yt = orc.truncate(orc.degree_reduce(y2.reshape(n, -1), n, t, P61, seed, l), n, t, f, P61, seed, l)
+        x_sh_g, rec_g = chain.secure_layer(l, None if x_sh_g is not None else x_plain_g.contiguous(), x_sh_g)
+        if L.post == "relu":
+            sb, sbi = orc.nonlinear_masks(yt[0].size, n, t, 28, P61, seed, Chain.MASK_STREAM_BASE + l)
+            x_sh_o = orc.relu(yt, sb, sbi, n, t, P61).reshape(y2.shape)
+            assert np.array_equal(to_np(x_sh_g), x_sh_o), f"layer {l}: shares after ReLU"
+        else:
+            rec_o = orc.reconstruct(yt, list(range(1, t + 2)), P61).reshape(y2.shape[1:])
+            assert x_sh_g is None and np.array_equal(to_np(rec_g), rec_o), f"layer {l}: opened result"
+            x_sh_o = None
+            if L.post is not None:
+                x_plain_g = fx.from_signed(post_plain(fx.lift(rec_g), L.post))
+                x_plain_o = np_signed_to_field(np_post(orc.lift(rec_o, P61), L.post))
+        if l % 10 == 0:
+            say(f"secure resnet{depth} layer {l}/{len(layers)} ok ({time.time() - t0:.0f} s)")
+    # whole passes: the same logits as the chain that opens every layer (truncation and ReLU are exact)
+    logits = to_np(chain.secure_prepare()).copy()
+    assert np.array_equal(logits, rec_o)
+    chain.secure_timed()
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(chain.rec[-1]), logits)
+    assert np.array_equal(to_np(chain.forward_prepare()), logits)
+
+
+@pytest.mark.timeout(900)
+def test_resnet50_stack_with_relu_on_shares():
+    run_secure_chain_parity(50, 5, 2, 13, seed=20240602)
+
+
 @pytest.mark.timeout(600)
 def test_config2_bulk_share_reconstruct_full_size():
     """n=5, t=2, 2^28 uniform field elements: shares on sampled elements against the
