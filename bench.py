@@ -247,6 +247,19 @@ def main():
                 (dr_bytes + tr_bytes + (ss.k + 1) * 8 * out_elems) / (prof["degree_reduce"][0] * 1e-3) / 1e9},
     }
     if not args.no_secure:
+        # same step with the outputs of reduction + truncation + opening taken without the protocol's messages
+        for _ in range(args.warmup):
+            chain.forward_timed("sgD")
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            chain.forward_timed("sgD")
+        torch.cuda.synchronize()
+        ms_direct = (time.perf_counter() - t0) * 1e3 / args.steps
+        result["cross_party_single_pass"] = {
+            "workload": "headline step with ssnet_reduce_truncate_direct in place of the protocol kernels "
+                        "(bit-identical outputs, no messages: a simulation shortcut, not the protocol's work)",
+            "ms_per_step": ms_direct, "field_MAC_per_s": macs / (ms_direct * 1e-3)}
         result["nonlinear_on_shares"] = secure_chain(chain, ss, args.steps, args.warmup, macs, out_elems)
     if args.copy_calibration:
         src = torch.zeros(1 << 27, dtype=torch.int64, device="cuda")

@@ -177,6 +177,18 @@ int ssnet_degree_reduce_truncate(ssnet_ctx *ctx, const uint64_t *d_c, size_t cou
 int ssnet_degree_reduce_truncate_reconstruct(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id,
                                              uint64_t *d_out, const int *party_ids, int m, uint64_t *d_secret);
 
+/* The outputs of ssnet_degree_reduce_truncate(_reconstruct) without the protocol:
+ * they do not depend on the reshare and zero randomness (the elite party of the
+ * truncation sees x + alpha, x being the secret of the incoming degree-2t
+ * sharing), so with all parties on one device they follow from REC of the 2t+1
+ * incoming shares and truncation steps 2 and 3.  d_out (and d_secret, if not
+ * NULL) hold the very residues the protocol entry points write for the same
+ * stream_id; no message is formed and no workspace is used.  This is a
+ * simulation shortcut, reported beside the protocol path, never in its place.
+ * d_out may alias d_c. */
+int ssnet_reduce_truncate_direct(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id,
+                                 uint64_t *d_out, const int *party_ids, int m, uint64_t *d_secret);
+
 /* SSS-NonLinear with ReLU (Sec. VI-C), on shares that were truncated before
  * (order Linear - Truncation - NonLinear, Sec. VII-A).
  *   ssnet_nonlinear_masks: what the trusted source prepares ahead of the

@@ -46,6 +46,7 @@ SIGNATURES = {
     "ssnet_truncate": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
     "ssnet_degree_reduce_truncate": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
     "ssnet_degree_reduce_truncate_reconstruct": (_int, [_ptr, _ptr, _sz, _u64, _ptr, C.POINTER(_int), _int, _ptr]),
+    "ssnet_reduce_truncate_direct": (_int, [_ptr, _ptr, _sz, _u64, _ptr, C.POINTER(_int), _int, _ptr]),
     "ssnet_nonlinear_masks": (_int, [_ptr, _sz, _u64, _ptr, _ptr]),
     "ssnet_relu": (_int, [_ptr, _ptr, _ptr, _ptr, _sz, _ptr]),
     "ssnet_rng_key": (_u64, [_u64] * 5),
@@ -335,6 +336,22 @@ class SSNet:
         return out, secret
 
     # ---- live kernel timing ----
+    def reduce_truncate_direct(self, c: torch.Tensor, stream_id: int, ids: Optional[Sequence[int]] = None,
+                               out: Optional[torch.Tensor] = None, secret: Optional[torch.Tensor] = None):
+        """-> (truncated shares, their reconstruction or None): the outputs of the protocol calls, no messages"""
+        _check_i64(c, "c")
+        count = c[0].numel()
+        if out is None:
+            out = torch.empty_like(c)
+        if ids is not None and secret is None:
+            secret = torch.empty(c.shape[1:], dtype=torch.int64, device=c.device)
+        arr = (_int * len(ids))(*ids) if ids is not None else None
+        self._ok(self.lib.ssnet_reduce_truncate_direct(self._ctx, _dptr(c), count, stream_id, _dptr(out), arr,
+                                                       len(ids) if ids is not None else 0,
+                                                       _dptr(secret) if secret is not None else None),
+                 "ssnet_reduce_truncate_direct")
+        return out, secret
+
     def nonlinear_masks(self, shape, stream_id: int, device=None):
         """-> (shares of beta, shares of beta^-1), each [n, *shape]; offline preprocessing"""
         shape = tuple(shape) if not isinstance(shape, int) else (shape,)

@@ -95,7 +95,8 @@ class Chain:
 
     def run_layer(self, l: int, x_plain: torch.Tensor, stages: str = "sgdtr") -> torch.Tensor:
         """All share arithmetic of layer l.  `stages` selects steps for timing
-        breakdowns: s=share, g=gemm/conv, d=degree_reduce, t=truncate, r=reconstruct."""
+        breakdowns: s=share, g=gemm/conv, d=degree_reduce, t=truncate, r=reconstruct;
+        D = the outputs of d, t, r by the no-message shortcut (reported separately)."""
         ss, L = self.ss, self.layers[l]
         xs, y = self.x_shares[l], self.y[l]
         if self.pointwise[l] and "s" in stages and "g" in stages:
@@ -113,6 +114,9 @@ class Chain:
             else:
                 ss.linear_mod_packed(xs, self.packed[l], L.cout, out=y)
         yv = y.view(ss.n, -1)
+        if "D" in stages:   # the outputs of reduction, truncation and opening without the protocol's messages
+            ss.reduce_truncate_direct(yv, stream_id=l, ids=self.ids, out=yv, secret=self.rec[l])
+            return self.rec[l]
         if "d" in stages and "t" in stages and "r" in stages:   # one launch for the three steps
             ss.degree_reduce_truncate_reconstruct(yv, stream_id=l, ids=self.ids, out=yv, secret=self.rec[l])
             return self.rec[l]

@@ -64,6 +64,10 @@ hipError_t ss_launch_degree_reduce_truncate(const u64 *c, u64 *msg1, u64 *msg2, 
                                             u64 *rec, size_t count, const ss_dr_params &dp, const ss_tr_params &tp,
                                             const ss_recf_params &rf, hipStream_t stream);
 
+// outputs of reduction + truncation taken directly from the secret (no messages); open_all carries the
+// multipliers of REC from the IDs 1..2t+1
+hipError_t ss_launch_reduce_truncate_direct(const u64 *c, u64 *out, u64 *rec, size_t count, const ss_nl_params &open_all,
+                                            const ss_tr_params &tp, const ss_recf_params &rf, hipStream_t stream);
 // SSS-NonLinear (Sec. VI-C): the trusted source's masks, then ReLU under the mask
 hipError_t ss_launch_nonlinear_masks(u64 *sh_b, u64 *sh_bi, size_t count, const ss_nl_params &np, hipStream_t stream);
 hipError_t ss_launch_relu(const u64 *x, const u64 *sh_b, const u64 *sh_bi, u64 *msg, u64 *yplain, u64 *out,

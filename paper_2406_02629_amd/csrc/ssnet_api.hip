@@ -646,6 +646,31 @@ bool make_nl_params(const ssnet_ctx *ctx, uint64_t stream_id, ss_nl_params *np)
 
 }  // namespace
 
+int ssnet_reduce_truncate_direct(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id,
+                                 uint64_t *d_out, const int *party_ids, int m, uint64_t *d_secret)
+{
+    if (!ctx || !d_c || !d_out || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
+    ss_recf_params rf = {};
+    if (d_secret) {
+        if (!party_ids || m < 1 || m > ctx->n) return SSNET_EINVAL;
+        for (int i = 0; i < m; i++) {
+            if (party_ids[i] < 1 || party_ids[i] > ctx->n) return SSNET_EID;
+            for (int j = 0; j < i; j++)
+                if (party_ids[j] == party_ids[i]) return SSNET_EID;
+        }
+        if (m < ctx->t + 1) return SSNET_ESHARES;
+        int il[SS_MAXN];
+        if (!h_lagrange_int(party_ids, m, il, &rf.dinv)) return SSNET_EINVAL;
+        for (int i = 0; i < m; i++) rf.coef[party_ids[i] - 1] = il[i];
+    }
+    ss_nl_params open_all;
+    if (!make_nl_params(ctx, 0, &open_all)) return SSNET_EINVAL;
+    timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
+    hipError_t e = ss_launch_reduce_truncate_direct(d_c, d_out, d_secret, count, open_all, make_tr_params(ctx, stream_id),
+                                                    rf, ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
 int ssnet_nonlinear_masks(ssnet_ctx *ctx, size_t count, uint64_t stream_id, uint64_t *d_beta, uint64_t *d_betainv)
 {
     if (!ctx || !d_beta || !d_betainv || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;

@@ -554,6 +554,69 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_lanes_kernel(const u64 *c
     }
 }
 
+// ------------------------------------------------------------------ reduction + truncation, all parties at once
+// The outputs of RED + RERAND + truncation do not depend on the reshare or zero
+// randomness: the elite party of the truncation reconstructs x + alpha, where x
+// is the secret of the incoming degree-2t sharing, whatever the reduced shares
+// look like.  With every party's share in one thread that secret can be taken
+// directly (REC from the 2t+1 incoming shares), and the output shares follow from
+// it as in truncation steps 2 and 3.  Same residues in `out` (and `rec`) as the
+// protocol kernels; no message is formed, so this is not what the parties of the
+// protocol compute, only what they end up with.
+template <int VEC>
+__global__ __launch_bounds__(BLOCK) void reduce_truncate_direct_kernel(const u64 *c, u64 *out, u64 *__restrict__ rec,
+                                                                       size_t count, ss_nl_params open_all,
+                                                                       ss_tr_params tp, ss_recf_params rf)
+{
+    const size_t e0 = ((size_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
+    if (e0 >= count) return;
+    const int nr = 2 * tp.t + 1;
+    ss_sacc acc[VEC], racc[VEC];
+#pragma unroll
+    for (int u = 0; u < VEC; u++) {
+        acc[u].clear();
+        racc[u].clear();
+    }
+#pragma unroll
+    for (int i = 0; i < 2 * SS_MAXT + 1; i++) {
+        if (i < nr) {
+            pack_t<VEC> ci;
+            ci.load(c + (size_t)i * count + e0);
+#pragma unroll
+            for (int u = 0; u < VEC; u++) acc[u].mac(ci.v[u], open_all.ilambda[i]);
+        }
+    }
+    u64 w[VEC], at[VEC], cw[VEC][SS_MAXT], cat[VEC][SS_MAXT];
+#pragma unroll
+    for (int u = 0; u < VEC; u++) {
+        const u64 x = open_all.dinv == 1 ? acc[u].value() : ss_mul(acc[u].value(), open_all.dinv);
+        const u64 ev = mask_e(tp.e_key, e0 + u, tp.f);
+        w[u] = shift_signed(ss_add(x, ev << tp.f), tp.f);
+        at[u] = SS_P - ev;
+        draw_coeffs<SS_MAXT>(cw[u], tp.gen_key, tp.t, e0 + u);
+        draw_coeffs<SS_MAXT>(cat[u], tp.alphat_key, tp.t, e0 + u);
+    }
+#pragma unroll
+    for (int m = 0; m < SS_MAXN; m++) {
+        if (m < tp.n) {
+            pack_t<VEC> s;
+#pragma unroll
+            for (int u = 0; u < VEC; u++) {
+                s.v[u] = ss_add(ss_poly_eval<SS_MAXT>(w[u], cw[u], tp.t, m + 1),
+                                ss_poly_eval<SS_MAXT>(at[u], cat[u], tp.t, m + 1));
+                if (rec && rf.coef[m] != 0) racc[u].mac(s.v[u], rf.coef[m]);
+            }
+            s.store(out + (size_t)m * count + e0);
+        }
+    }
+    if (rec) {
+        pack_t<VEC> r;
+#pragma unroll
+        for (int u = 0; u < VEC; u++) r.v[u] = rf.dinv == 1 ? racc[u].value() : ss_mul(racc[u].value(), rf.dinv);
+        r.store(rec + e0);
+    }
+}
+
 // ------------------------------------------------------------------ SSS-NonLinear (Sec. VI-C)
 // What the trusted source prepares ahead of the inference (Sec. VII-B): a positive
 // mask beta per element, its inverse in F_p (Fermat: beta^(p-2), p - 2 = 2^61 - 3)
@@ -761,5 +824,15 @@ hipError_t ss_launch_relu(const u64 *x, const u64 *sh_b, const u64 *sh_bi, u64 *
                     aligned16(yplain) && aligned16(out) && count >= VEC2_MIN_COUNT;
     auto grid = [&](int vec) { return dim3(blocks_for(count, vec)); };
     SS_DISPATCH_VEC(v2, relu_kernel, grid, x, sh_b, sh_bi, msg, yplain, out, count, np);
+    return hipGetLastError();
+}
+
+hipError_t ss_launch_reduce_truncate_direct(const u64 *c, u64 *out, u64 *rec, size_t count, const ss_nl_params &open_all,
+                                            const ss_tr_params &tp, const ss_recf_params &rf, hipStream_t stream)
+{
+    const bool v2 = (count % 2 == 0) && aligned16(c) && aligned16(out) && (!rec || aligned16(rec)) &&
+                    count >= VEC2_MIN_COUNT;
+    auto grid = [&](int vec) { return dim3(blocks_for(count, vec)); };
+    SS_DISPATCH_VEC(v2, reduce_truncate_direct_kernel, grid, c, out, rec, count, open_all, tp, rf);
     return hipGetLastError();
 }

@@ -146,6 +146,27 @@ def test_fused_reduce_truncate_reconstruct(n, t):
         assert ei.value.code == {"EID": -4, "ESHARES": -3}[code]
 
 
+@pytest.mark.parametrize("n,t", SCHEMES)
+def test_reduce_truncate_direct_gives_the_protocol_outputs(n, t):
+    """The no-message shortcut writes the very residues of the protocol path (oracle: the three
+    steps of RED, RERAND, the three steps of truncation), whatever the reshare randomness was."""
+    s = SSNet(n, t, f=13, seed=91)
+    for count in (1, 2, 4099, 65538, (1 << 20) + 2):
+        say("direct", n, t, count)
+        rng = np.random.default_rng(count)
+        xs = rng.integers(-(1 << 55), 1 << 55, count, dtype=np.int64)
+        c = orc.share(np.where(xs < 0, xs + P61, xs).astype(np.uint64), n, 2 * t if 2 * t < n else t, P61, 2, 0)
+        want = orc.truncate(orc.degree_reduce(c, n, t, P61, 91, 7), n, t, 13, P61, 91, 7)
+        ids = list(range(n, n - t - 1, -1))
+        d = to_dev(c)
+        out, rec = s.reduce_truncate_direct(d, stream_id=7, ids=ids, out=d)
+        assert np.array_equal(to_np(out), want)
+        assert np.array_equal(to_np(rec), orc.reconstruct(want, ids, P61))
+        assert np.array_equal(orc.lift(to_np(rec), P61), xs >> 13)
+        out2, none = s.reduce_truncate_direct(to_dev(c), stream_id=7)
+        assert none is None and bool(torch.equal(out2, out))
+
+
 def test_degree_reduce_in_place_and_on_real_products():
     n, t = 5, 2
     s = SSNet(n, t, seed=8)
