@@ -78,6 +78,41 @@ def bulk_share_reconstruct(log2_count, reps):
     return out
 
 
+def bulk_streaming_steps(log2_count, reps):
+    """The other element-wise steps at a size where launch cost does not matter (n=5, t=2): reduction +
+    truncation + opening in one launch, and ReLU on shares.  GB/s on the algorithmic bytes (a message is
+    written once and read once; random coefficients cost nothing)."""
+    import torch
+    from paper_2406_02629_amd import SSNet
+    from ssnet_inputs import uniform_below
+    n, t, count = 5, 2, 1 << log2_count
+    k, nr = t + 1, 2 * t + 1
+    ss = SSNet(n, t, f=13, seed=4)
+    stream = torch.cuda.current_stream()
+    c = torch.from_numpy(uniform_below(n * count, 1 << 45, 3).view("int64")).cuda().view(n, count)
+    out = torch.empty_like(c)
+    rec = torch.empty(count, dtype=torch.int64, device="cuda")
+    ids = list(range(1, k + 1))
+    ss.degree_reduce_truncate_reconstruct(c, 1, ids, out=out, secret=rec)     # reserves the workspace
+    torch.cuda.synchronize()
+    t_red = event_ms(lambda: ss.degree_reduce_truncate_reconstruct(c, 1, ids, out=out, secret=rec), stream, reps)
+    b_red = (n * (1 + k) + 2 * k * n + n * (k + 1) + 3 * k + 3 * n + k + 1) * 8 * count
+    x = torch.from_numpy(uniform_below(n * count, 1 << 30, 5).view("int64")).cuda().view(n, count)
+    b, bi = ss.nonlinear_masks(count, stream_id=2)
+    ss.relu(x, b, bi, out=out)
+    torch.cuda.synchronize()
+    t_relu = event_ms(lambda: ss.relu(x, b, bi, out=out), stream, reps)
+    b_relu = (3 * nr + nr + 1 + 3 * n) * 8 * count
+    res = {"workload": f"n=5 t=2, 2^{log2_count} elements",
+           "degree_reduce+truncate+reconstruct": {"ms": t_red, "GB/s": b_red / t_red / 1e6,
+                                                  "bytes_per_element": b_red // count},
+           "relu": {"ms": t_relu, "GB/s": b_relu / t_relu / 1e6, "bytes_per_element": b_relu // count},
+           "bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    del c, out, rec, x, b, bi
+    torch.cuda.empty_cache()
+    return res
+
+
 def conv_layer_roofline(reps):
     """configs[2]: n=3, t=1, batch 8 x 64x56x56, 3x3 64->64: the modular GEMM on a shape with many tiles
     (M = 25088, K = 576, N = 64 per party), weights packed beforehand; kernel times from HIP events."""
@@ -270,6 +305,7 @@ def main():
     if not args.no_bulk:
         result["roofline_hbm"] = bulk_share_reconstruct(args.bulk_log2, reps=5)
         result["roofline_conv_layer"] = conv_layer_roofline(reps=10)
+        result["roofline_hbm_other_steps"] = bulk_streaming_steps(24, reps=5)
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(args.cpu_layers)
     print(json.dumps(result))
