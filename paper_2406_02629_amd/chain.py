@@ -50,12 +50,14 @@ def post_plain(y: torch.Tensor, post: Optional[str]) -> torch.Tensor:
 
 class Chain:
     def __init__(self, ss: SSNet, layers: List[Layer], batch: int = 1, image_seed: int = 5,
-                 weight_seed_base: int = 100, keep_weight_shares: bool = False):
+                 weight_seed_base: int = 100, keep_weight_shares: bool = False, weights_of: "Optional[Chain]" = None):
+        """weights_of: another harness over the same layers and context whose prepared weight tiles are
+        reused (they do not depend on the batch size)."""
         self.ss, self.layers, self.batch = ss, layers, batch
         dev = ss.device
-        self.packed: List[torch.Tensor] = []
-        self.wshares: List[Optional[torch.Tensor]] = []
-        for l, L in enumerate(layers):
+        self.packed: List[torch.Tensor] = [] if weights_of is None else list(weights_of.packed)
+        self.wshares: List[Optional[torch.Tensor]] = [] if weights_of is None else list(weights_of.wshares)
+        for l, L in enumerate(layers if weights_of is None else []):
             shape = (L.cout, L.cin, L.ksize, L.ksize) if L.kind == "conv" else (L.cin, L.cout)
             w = he_normal(shape, L.K, weight_seed_base + l)
             we = fx.encode(torch.from_numpy(w).to(dev), ss.f)
