@@ -216,6 +216,23 @@ def test_linear_parity(n, t):
         assert np.array_equal(got, orc.linear(x, w, P61))
 
 
+def test_linear_random_shapes_cover_the_unit_dealing():
+    """Seeded sweep of ragged shapes: whole tiles and tiles cut between 2 to 8 workgroups, light last
+    column tiles of 1 to 3 blocks, fewer units than workgroups, one party to eight."""
+    rng = np.random.default_rng(2024)
+    cases = [(3, 1, 1, 1, 1), (3, 1, 1, 16383, 1), (5, 2, 64, 64, 64), (5, 2, 65, 65, 65), (8, 2, 17, 700, 49),
+             (3, 1, 200, 129, 3), (5, 2, 1, 2048, 1000), (7, 3, 130, 1000, 196)]
+    for _ in range(24):
+        n, t = [(3, 1), (5, 2), (7, 3), (5, 1)][int(rng.integers(4))]
+        cases.append((n, t, int(rng.integers(1, 400)), int(rng.integers(1, 2500)), int(rng.integers(1, 400))))
+    for (n, t, M, K, N) in cases:
+        say("linear", n, t, M, K, N)
+        s = SSNet(n, t, seed=3)
+        x, w = field_uniform((n, M, K), M + K), field_uniform((n, K, N), N + K)
+        y = s.linear_mod(to_dev(x), to_dev(w))
+        assert np.array_equal(to_np(y), orc.linear(x, w, P61)), (n, t, M, K, N)
+
+
 def test_linear_more_tiles_than_arrival_counters():
     # 3 * 130 * 130 output tiles: every workgroup takes one whole tile, nothing is handed over
     n, t = 3, 1
