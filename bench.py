@@ -123,20 +123,33 @@ def conv_layer_roofline(reps):
     ss = SSNet(n, 1, f=13, seed=3)
     x = torch.from_numpy(uniform_below(n * B * C * H * H, P61, 3).view("int64")).cuda().view(n, B, C, H, H)
     w = torch.from_numpy(uniform_below(n * Co * C * k * k, P61, 4).view("int64")).cuda().view(n, Co, C, k, k)
-    wp = ss.pack_weights_conv(w)
-    y = ss.conv_mod_packed(x, wp, Co, k, k, 1, 1)
+    macs = n * B * H * H * C * k * k * Co
+    # (i) input gathered from channel-innermost limb planes (the path the stack uses for k x k layers)
+    wt = ss.pack_weights_conv_taps(w)
+    planes = ss.split_planes(x)
+    y = ss.conv_mod_planes(planes, wt, B, C, H, H, Co, k, k, 1, 1)
     torch.cuda.synchronize()
     ss.profile_begin()
     for _ in range(reps):
-        ss.conv_mod_packed(x, wp, Co, k, k, 1, 1, out=y)
+        ss.split_planes(x, planes=planes)
+        ss.conv_mod_planes(planes, wt, B, C, H, H, Co, k, k, 1, 1, out=y)
     prof = ss.profile_end()
-    macs = n * B * H * H * C * k * k * Co
     gemm_ms = prof["gemm"][0] / reps
     achieved = macs * OPS_PER_FIELD_MAC / (gemm_ms * 1e-3) / 1e12
+    # (ii) the same layer through a materialised im2col matrix
+    wp = ss.pack_weights_conv(w)
+    y2 = ss.conv_mod_packed(x, wp, Co, k, k, 1, 1)
+    same = bool(torch.equal(y, y2))
+    ss.profile_begin()
+    for _ in range(reps):
+        ss.conv_mod_packed(x, wp, Co, k, k, 1, 1, out=y2)
+    prof2 = ss.profile_end()
     return {"workload": "conv 3x3 64->64 on 8x64x56x56, n=3 (configs[2]): M=25088 K=576 N=64 per party",
-            "bound": "mfma", "kernel": "gemm_limb_kernel", "achieved": achieved, "peak": INT8_PEAK_TOPS,
-            "unit": "TOP/s", "frac": achieved / INT8_PEAK_TOPS, "gemm_ms": gemm_ms,
-            "pack_im2col_ms": prof["pack_x"][0] / reps, "field_macs": macs}
+            "bound": "mfma", "kernel": "gemm_limb_kernel<true> (input gathered from limb planes)", "achieved": achieved,
+            "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": achieved / INT8_PEAK_TOPS, "gemm_ms": gemm_ms,
+            "split_planes_ms": prof["pack_x"][0] / reps, "field_macs": macs,
+            "via_im2col_matrix": {"gemm_ms": prof2["gemm"][0] / reps, "pack_im2col_ms": prof2["pack_x"][0] / reps,
+                                  "same_result": same}}
 
 
 def cpu_baseline(nlayers):

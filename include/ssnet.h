@@ -135,6 +135,30 @@ int ssnet_linear_mod_prepacked(ssnet_ctx *ctx, const void *d_x_packed, const voi
 int ssnet_conv1x1_mod_prepacked(ssnet_ctx *ctx, const void *d_x_packed, const void *d_w_packed, int B, int C, int HW,
                                 int Co, uint64_t *d_y);
 
+/* Convolution without a materialised im2col matrix (SSS-Linear step 1, Sec.
+ * VI-A, for kh x kw kernels with C a multiple of 64): the input is kept as
+ * channel-innermost int8 limb planes, per party [limb 0..7][b][h][w][c] plus a
+ * 256-byte pad (ssnet_conv_planes_bytes(B, C, H, W) bytes per party, n parties
+ * back to back, 16-byte aligned; 0 for an unsupported shape), from which the
+ * product kernel gathers the 16 channels of one tap of one output pixel as 16
+ * consecutive bytes; the weights are packed with contraction index (tap,
+ * channel).
+ *   ssnet_share_planes: GEN (Eq. 1, degree t, domain SHARE) of d_secret
+ *     [B][C][H][W] -> d_shares [n][B][C][H][W] (the values of ssnet_share for
+ *     the same stream_id) and their planes, in one launch.
+ *   ssnet_split_planes: planes of existing shares d_x [n][B][C][H][W].
+ *   ssnet_pack_weights_conv_taps: d_w [n][Co][C][kh][kw] -> tiles of
+ *     ssnet_packed_weight_bytes(Co, C*kh*kw) bytes per party.
+ *   ssnet_conv_mod_planes: d_y [n][B][Co][Ho][Wo], bit-identical to
+ *     ssnet_conv_mod on the same shares; workspace as ssnet_workspace_bytes_conv. */
+size_t ssnet_conv_planes_bytes(int B, int C, int H, int W);
+int ssnet_share_planes(ssnet_ctx *ctx, const uint64_t *d_secret, int B, int C, int H, int W, uint64_t stream_id,
+                       uint64_t *d_shares, void *d_planes);
+int ssnet_split_planes(ssnet_ctx *ctx, const uint64_t *d_x, int B, int C, int H, int W, void *d_planes);
+int ssnet_pack_weights_conv_taps(ssnet_ctx *ctx, const uint64_t *d_w, int Co, int C, int kh, int kw, void *d_packed);
+int ssnet_conv_mod_planes(ssnet_ctx *ctx, const void *d_planes, const void *d_w_packed, int B, int C, int H, int W,
+                          int Co, int kh, int kw, int stride, int pad, uint64_t *d_y);
+
 /* RED by resharing (Sec. IV-B, the three protocol steps with the matrix of
  * Eq. 3) followed by RERAND (Sec. IV-C), all n parties:
  *   1. parties 1..2t+1: GEN(c_i, k, k) towards parties 1..k   (domain RESHARE, party i)

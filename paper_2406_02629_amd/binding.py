@@ -42,6 +42,11 @@ SIGNATURES = {
     "ssnet_share_packed": (_int, [_ptr, _ptr, _int, _int, _int, _u64, _ptr, _ptr]),
     "ssnet_linear_mod_prepacked": (_int, [_ptr, _ptr, _ptr, _int, _int, _int, _ptr]),
     "ssnet_conv1x1_mod_prepacked": (_int, [_ptr, _ptr, _ptr, _int, _int, _int, _int, _ptr]),
+    "ssnet_conv_planes_bytes": (_sz, [_int] * 4),
+    "ssnet_share_planes": (_int, [_ptr, _ptr, _int, _int, _int, _int, _u64, _ptr, _ptr]),
+    "ssnet_split_planes": (_int, [_ptr, _ptr, _int, _int, _int, _int, _ptr]),
+    "ssnet_pack_weights_conv_taps": (_int, [_ptr, _ptr, _int, _int, _int, _int, _ptr]),
+    "ssnet_conv_mod_planes": (_int, [_ptr, _ptr, _ptr] + [_int] * 9 + [_ptr]),
     "ssnet_degree_reduce": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
     "ssnet_truncate": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
     "ssnet_degree_reduce_truncate": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
@@ -268,6 +273,61 @@ class SSNet:
             out = torch.empty((self.n, B, Co, H, W), dtype=torch.int64, device=x_packed.device)
         self._ok(self.lib.ssnet_conv1x1_mod_prepacked(self._ctx, _dptr(x_packed), _dptr(w_packed), B, C, H * W, Co,
                                                       _dptr(out)), "ssnet_conv1x1_mod_prepacked")
+        return out
+
+    # ---- convolution on channel-innermost limb planes (no im2col matrix) ----
+    def planes_supported(self, B: int, C: int, H: int, W: int) -> bool:
+        return self.lib.ssnet_conv_planes_bytes(B, C, H, W) != 0
+
+    def _planes_buffer(self, B, C, H, W, planes, device):
+        nbytes = self.n * self.lib.ssnet_conv_planes_bytes(B, C, H, W)
+        if nbytes == 0:
+            raise SSNetError(EINVAL, "ssnet_conv_planes_bytes")
+        if planes is None:
+            planes = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        elif planes.numel() * planes.element_size() < nbytes:
+            raise SSNetError(EINVAL, "planes buffer too small")
+        return planes
+
+    def share_planes(self, secret: torch.Tensor, stream_id: int, out: Optional[torch.Tensor] = None,
+                     planes: Optional[torch.Tensor] = None):
+        """secret [B][C][H][W] -> (shares [n][B][C][H][W], their limb planes)"""
+        _check_i64(secret, "secret")
+        B, C, H, W = secret.shape
+        planes = self._planes_buffer(B, C, H, W, planes, secret.device)
+        if out is None:
+            out = torch.empty((self.n,) + tuple(secret.shape), dtype=torch.int64, device=secret.device)
+        self._ok(self.lib.ssnet_share_planes(self._ctx, _dptr(secret), B, C, H, W, stream_id, _dptr(out), _dptr(planes)),
+                 "ssnet_share_planes")
+        return out, planes
+
+    def split_planes(self, x: torch.Tensor, planes: Optional[torch.Tensor] = None) -> torch.Tensor:
+        _check_i64(x, "x")
+        n, B, C, H, W = x.shape
+        planes = self._planes_buffer(B, C, H, W, planes, x.device)
+        self._ok(self.lib.ssnet_split_planes(self._ctx, _dptr(x), B, C, H, W, _dptr(planes)), "ssnet_split_planes")
+        return planes
+
+    def pack_weights_conv_taps(self, w: torch.Tensor) -> torch.Tensor:
+        _check_i64(w, "w")
+        n, Co, C, kh, kw = w.shape
+        packed = torch.empty(self.n * self.lib.ssnet_packed_weight_bytes(Co, C * kh * kw), dtype=torch.uint8,
+                             device=w.device)
+        self._ok(self.lib.ssnet_pack_weights_conv_taps(self._ctx, _dptr(w), Co, C, kh, kw, _dptr(packed)),
+                 "ssnet_pack_weights_conv_taps")
+        return packed
+
+    def conv_mod_planes(self, planes: torch.Tensor, w_packed: torch.Tensor, B: int, C: int, H: int, W: int, Co: int,
+                        kh: int, kw: int, stride: int, pad: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        need = self.workspace_bytes_conv(B, C, H, W, Co, kh, kw, stride, pad)
+        if need == 0:
+            raise SSNetError(EINVAL, "ssnet_workspace_bytes_conv")
+        self.reserve(need)
+        Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+        if out is None:
+            out = torch.empty((self.n, B, Co, Ho, Wo), dtype=torch.int64, device=planes.device)
+        self._ok(self.lib.ssnet_conv_mod_planes(self._ctx, _dptr(planes), _dptr(w_packed), B, C, H, W, Co, kh, kw, stride,
+                                                pad, _dptr(out)), "ssnet_conv_mod_planes")
         return out
 
     def conv_mod_packed(self, x: torch.Tensor, w_packed: torch.Tensor, Co: int, kh: int, kw: int, stride: int,

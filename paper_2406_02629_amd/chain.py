@@ -55,6 +55,10 @@ class Chain:
         reused (they do not depend on the batch size)."""
         self.ss, self.layers, self.batch = ss, layers, batch
         dev = ss.device
+        # k x k layers whose channel count allows it read their input from channel-innermost limb planes
+        # instead of an im2col matrix; their weights are packed in (tap, channel) order
+        self.on_planes = [L.kind == "conv" and L.ksize > 1 and ss.planes_supported(batch, L.cin, L.hin, L.hin)
+                          for L in layers]
         self.packed: List[torch.Tensor] = [] if weights_of is None else list(weights_of.packed)
         self.wshares: List[Optional[torch.Tensor]] = [] if weights_of is None else list(weights_of.wshares)
         for l, L in enumerate(layers if weights_of is None else []):
@@ -62,7 +66,10 @@ class Chain:
             w = he_normal(shape, L.K, weight_seed_base + l)
             we = fx.encode(torch.from_numpy(w).to(dev), ss.f)
             wsh = ss.share(we, stream_id=WEIGHT_STREAM_BASE + l)
-            self.packed.append(ss.pack_weights_conv(wsh) if L.kind == "conv" else ss.pack_weights_linear(wsh))
+            if self.on_planes[l]:
+                self.packed.append(ss.pack_weights_conv_taps(wsh))
+            else:
+                self.packed.append(ss.pack_weights_conv(wsh) if L.kind == "conv" else ss.pack_weights_linear(wsh))
             self.wshares.append(wsh if keep_weight_shares else None)
         L0 = layers[0]
         img = gaussian((batch, L0.cin, L0.hin, L0.hin), image_seed)
@@ -78,6 +85,9 @@ class Chain:
         tiles = max([ss.n * ss.lib.ssnet_packed_weight_bytes(batch * (L.hin * L.hin if L.kind == "conv" else 1), L.cin)
                      for L, pw in zip(layers, self.pointwise) if pw] + [16])
         self.x_tiles = torch.empty(tiles, dtype=torch.uint8, device=dev)
+        planes = max([ss.n * ss.lib.ssnet_conv_planes_bytes(batch, L.cin, L.hin, L.hin)
+                      for L, pl in zip(layers, self.on_planes) if pl] + [16])
+        self.x_planes = torch.empty(planes, dtype=torch.uint8, device=dev)
         need = 0
         for L in layers:
             count = batch * L.cout * L.M
@@ -107,6 +117,14 @@ class Chain:
                 ss.conv1x1_mod_prepacked(self.x_tiles, self.packed[l], self.batch, L.cin, L.hin, L.hin, L.cout, out=y)
             else:
                 ss.linear_mod_prepacked(self.x_tiles, self.packed[l], self.batch, L.cin, L.cout, out=y)
+            stages = stages.replace("s", "").replace("g", "")
+        if self.on_planes[l] and "g" in stages:
+            if "s" in stages:
+                ss.share_planes(x_plain, stream_id=l, out=xs, planes=self.x_planes)
+            else:
+                ss.split_planes(xs, planes=self.x_planes)
+            ss.conv_mod_planes(self.x_planes, self.packed[l], self.batch, L.cin, L.hin, L.hin, L.cout, L.ksize, L.ksize,
+                               L.stride, L.pad, out=y)
             stages = stages.replace("s", "").replace("g", "")
         if "s" in stages:
             ss.share(x_plain, stream_id=l, out=xs)
@@ -172,7 +190,11 @@ class Chain:
         y = self.y[l]
         if x_shares is None:
             x_shares = ss.share(x_plain, stream_id=l, out=self.x_shares[l])
-        if L.kind == "conv":
+        if self.on_planes[l]:
+            ss.split_planes(x_shares, planes=self.x_planes)
+            ss.conv_mod_planes(self.x_planes, self.packed[l], self.batch, L.cin, L.hin, L.hin, L.cout, L.ksize, L.ksize,
+                               L.stride, L.pad, out=y)
+        elif L.kind == "conv":
             ss.conv_mod_packed(x_shares, self.packed[l], L.cout, L.ksize, L.ksize, L.stride, L.pad, out=y)
         else:
             ss.linear_mod_packed(x_shares, self.packed[l], L.cout, out=y)

@@ -44,16 +44,24 @@ __device__ __forceinline__ void store_digits(const u64 (&y)[4], v4i *tile, int r
 
 // One workgroup per (row block, k block) tile, one thread per (row, 4 contraction indices).
 // grid (Rb, Kb, n), block 256: thread t -> row t%16, k group t/16.
+// taps > 0: the contraction index of the packed operand runs (tap, channel) while the source runs (channel,
+// tap) with `taps` taps per channel (convolution weights for the kernel that reads its other operand from
+// channel-innermost planes); stride_k is then the stride of the source's own index.
 __global__ __launch_bounds__(256) void pack_matrix_kernel(const u64 *__restrict__ src, v4i *__restrict__ dst,
                                                           int rows, int K, int Kb, size_t party_stride,
-                                                          size_t stride_r, size_t stride_k, size_t dst_party_stride)
+                                                          size_t stride_r, size_t stride_k, size_t dst_party_stride,
+                                                          int taps)
 {
     const int rb = blockIdx.x, kb = blockIdx.y, r16 = threadIdx.x & 15, kq = threadIdx.x >> 4;
     const int row = rb * 16 + r16, k0 = kb * 64 + 4 * kq;
     const u64 *s = src + (size_t)blockIdx.z * party_stride + (size_t)row * stride_r;
+    const int C = taps ? K / taps : 1;
     u64 y[4];
 #pragma unroll
-    for (int c = 0; c < 4; c++) y[c] = (row < rows && k0 + c < K) ? balanced_digits(s[(size_t)(k0 + c) * stride_k]) : 0;
+    for (int c = 0; c < 4; c++) {
+        const int k = k0 + c, ks = taps ? (k % C) * taps + k / C : k;
+        y[c] = (row < rows && k < K) ? balanced_digits(s[(size_t)ks * stride_k]) : 0;
+    }
     store_digits(y, dst + (size_t)blockIdx.z * dst_party_stride + ((size_t)rb * Kb + kb) * 512, r16, kq);
 }
 
@@ -136,6 +144,77 @@ __global__ __launch_bounds__(256) void share_pack_kernel(const u64 *__restrict__
         if (p < n) store_digits(y[p], dst + (size_t)p * dst_party_stride + ((size_t)rb * Kb + kb) * 512, r16, kq);
 }
 
+// one dword per limb from the digit words of four consecutive channels (byte c of the result is digit
+// `limb` of y[c])
+__device__ __forceinline__ u32 limb_dword(const u64 (&y)[4], int limb)
+{
+    const int i = limb & 3;
+    const u32 a = limb < 4 ? (u32)y[0] : (u32)(y[0] >> 32), b = limb < 4 ? (u32)y[1] : (u32)(y[1] >> 32);
+    const u32 c = limb < 4 ? (u32)y[2] : (u32)(y[2] >> 32), d = limb < 4 ? (u32)y[3] : (u32)(y[3] >> 32);
+    const u32 sel = (u32)i | ((u32)(4 + i) << 8) | 0x0c0c0000u;
+    return __builtin_amdgcn_perm(__builtin_amdgcn_perm(d, c, sel), __builtin_amdgcn_perm(b, a, sel), 0x05040100u);
+}
+
+// Conv input [B][C][H][W] -> channel-innermost limb planes [party][limb][b][h][w][c] (int8), the form the
+// convolution kernel gathers its second operand from (16 consecutive channels of one tap of one output pixel
+// are 16 consecutive bytes).  GEN: the input is the plaintext tensor and the kernel also is GEN (Eq. 1): it
+// draws the coefficients of each element (element index = position in the tensor), writes the n shares and
+// their planes; otherwise the input is the share tensor [n][B][C][H][W].  Thread t of block (pixel block,
+// channel block of 64): pixel t%16, four channels from 4 (t/16).  Every party's planes end in a pad whose
+// first 16 bytes are zero (the source of taps that fall into the padding).
+template <int N, int T, bool GEN>
+__global__ __launch_bounds__(256) void planes_kernel(const u64 *__restrict__ in, u64 *__restrict__ shares,
+                                                     signed char *__restrict__ planes, int B, int C, int HW,
+                                                     size_t party_bytes, int n_rt, int t_rt, ss_keys keys)
+{
+    constexpr int MAXP = N ? N : SS_MAXN, MAXD = T ? T : SS_MAXT;
+    const int n = N ? N : n_rt, t = T ? T : t_rt;
+    const int pix = blockIdx.x * 16 + (threadIdx.x & 15), c0 = blockIdx.y * 64 + 4 * (threadIdx.x >> 4);
+    const size_t plane = (size_t)B * HW * C, count = plane;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < MAXP && (int)threadIdx.x < n)
+        *reinterpret_cast<v4i *>(planes + threadIdx.x * party_bytes + 8 * plane) = (v4i){0, 0, 0, 0};
+    if (pix >= B * HW) return;
+    const int b = pix / HW, hw = pix - b * HW;
+    u64 y[MAXP][4];
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+        const size_t e = ((size_t)b * C + (c0 + q)) * HW + hw;
+        if constexpr (GEN) {
+            const u64 a0 = in[e], counter = ss_counter(e);
+            u64 c[MAXD];
+#pragma unroll
+            for (int j = 0; j < MAXD; j++) c[j] = (j < t) ? ss_draw_field_at(keys.k[j], counter) : 0;
+            if constexpr (N != 0) {
+                eval_points<T, N>(a0, c, [&](int p, u64 v) {
+                    shares[(size_t)p * count + e] = v;
+                    y[p][q] = balanced_digits(v);
+                });
+            } else {
+#pragma unroll
+                for (int p = 0; p < MAXP; p++) {
+                    if (p < n) {
+                        const u64 v = ss_poly_eval<MAXD>(a0, c, t, p + 1);
+                        shares[(size_t)p * count + e] = v;
+                        y[p][q] = balanced_digits(v);
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int p = 0; p < MAXP; p++)
+                if (p < n) y[p][q] = balanced_digits(in[(size_t)p * count + e]);
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < MAXP; p++) {
+        if (p < n) {
+            u32 *dst = reinterpret_cast<u32 *>(planes + p * party_bytes + (size_t)pix * C + c0);
+#pragma unroll
+            for (int limb = 0; limb < 8; limb++) dst[limb * (plane / 4)] = limb_dword(y[p], limb);
+        }
+    }
+}
+
 #ifdef SS_GEMM_TRACE
 // development aid: workgroup 0 records the shader clock at phase boundaries
 #define SS_TRACE(tag)                                                                 \
@@ -167,6 +246,18 @@ struct gemm_args {
     size_t a_party_stride, b_party_stride, out_party_stride, stride_row, stride_cb;
     int cdiv;
     u64 negbias;
+    // second operand read straight from channel-innermost limb planes (convolution without a materialised
+    // im2col): planes [party][limb][b][h][w][c] int8, contraction index (tap, channel), C a multiple of 64
+    const v4i *planes, *zero;          // zero: 16 zero bytes, for taps that fall into the padding
+    unsigned plane16, party16;         // strides of a limb plane and of a party, in 16-byte units
+    int cvH, cvW, cvC16, cvKw, cvStride, cvPad, cvHoWo, cvWo, cvKbTap;   // C16 = C/16, KbTap = C/64
+};
+
+// where one wave's block of a unit comes from: limb slice q is the 64 lanes x 16 bytes at base + q * qs
+struct wave_src {
+    const v4i *p;    // block pointer (packed operand), or the party's planes (implicit operand)
+    int hw, bpix;    // implicit operand: (h0 << 16) | (w0 & 0xffff) of this lane's output pixel, and the
+                     // pixel index of its image, -1 if the lane's column is past the matrix
 };
 
 // 15 diagonal sums of one output -> canonical field element
@@ -227,14 +318,44 @@ __device__ __forceinline__ int owner_of(const gemm_args &g, unsigned long long c
 // this wave's source block of tile `tile`: block `wave` of A for waves 0..3, of
 // B for waves 4..7; blocks past the end are clamped (their products are
 // computed and never stored)
-__device__ __forceinline__ const v4i *tile_source(const gemm_args &g, unsigned tile, int wave, int lane)
+template <bool IMPLICIT>
+__device__ __forceinline__ wave_src tile_source(const gemm_args &g, unsigned tile, int wave, int lane)
 {
     const int ct = (int)(tile % (unsigned)g.CT);
     const unsigned rem = tile / (unsigned)g.CT;
     const int rt = (int)(rem % (unsigned)g.RT), party = (int)(rem / (unsigned)g.RT);
-    if (wave < 4)
-        return g.A + (size_t)party * g.a_party_stride + (size_t)min(rt * 4 + wave, g.Rb - 1) * g.Kb * 512 + lane;
-    return g.B + (size_t)party * g.b_party_stride + (size_t)min(ct * 4 + wave - 4, g.Cb - 1) * g.Kb * 512 + lane;
+    wave_src ws = {nullptr, 0, 0};
+    if (wave < 4) {
+        ws.p = g.A + (size_t)party * g.a_party_stride + (size_t)min(rt * 4 + wave, g.Rb - 1) * g.Kb * 512 + lane;
+    } else if (!IMPLICIT) {
+        ws.p = g.B + (size_t)party * g.b_party_stride + (size_t)min(ct * 4 + wave - 4, g.Cb - 1) * g.Kb * 512 + lane;
+    } else {
+        // lane l of a block holds column 16 cb + l%16 = output pixel (b, ho, wo)
+        const int col = min(ct * 4 + wave - 4, g.Cb - 1) * 16 + (lane & 15);
+        const int cc = min(col, g.cols - 1), b = cc / g.cvHoWo, r = cc - b * g.cvHoWo, ho = r / g.cvWo, wo = r - ho * g.cvWo;
+        ws.p = g.planes + (size_t)party * g.party16;
+        ws.hw = (int)((unsigned)(ho * g.cvStride - g.cvPad) << 16) | ((wo * g.cvStride - g.cvPad) & 0xffff);
+        ws.bpix = col < g.cols ? b * g.cvH * g.cvW : -1;
+    }
+    return ws;
+}
+
+// base address and limb stride (16-byte units) of the wave's block for k block kb
+template <bool IMPLICIT>
+__device__ __forceinline__ const v4i *unit_base(const gemm_args &g, const wave_src &ws, int kb, int wave, int lane,
+                                                unsigned &qs)
+{
+    if (!IMPLICIT || wave < 4) {
+        qs = 64;
+        return ws.p + (size_t)kb * 512;
+    }
+    // k block kb = channels [64 (kb % KbTap), +64) of tap kb / KbTap; this lane: 16 of them
+    const int tap = kb / g.cvKbTap, c16 = (kb - tap * g.cvKbTap) * 4 + (lane >> 4);
+    const int r = tap / g.cvKw, sx = tap - r * g.cvKw;
+    const int hi = (ws.hw >> 16) + r, wi = (int)(short)(ws.hw & 0xffff) + sx;
+    const bool ok = ws.bpix >= 0 && (unsigned)hi < (unsigned)g.cvH && (unsigned)wi < (unsigned)g.cvW;
+    qs = ok ? g.plane16 : 0;
+    return ok ? ws.p + (size_t)(ws.bpix + hi * g.cvW + wi) * g.cvC16 + c16 : g.zero;
 }
 
 // Persistent kernel, one workgroup of 8 waves (4 x 2) per CU.  The work is the
@@ -259,6 +380,7 @@ __device__ __forceinline__ const v4i *tile_source(const gemm_args &g, unsigned t
 // cache-wide fence is used: it would evict the operand tiles that all other
 // workgroups are reusing.  Integer sums are exact, so the result does not
 // depend on how the units were dealt or on arrival order.
+template <bool IMPLICIT>
 __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
 {
     extern __shared__ v4i lds[];   // 2 stages x (4 A blocks + 4 B blocks) x 512
@@ -285,9 +407,13 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
 
     unsigned tile = g.units ? u0 / (unsigned)g.Kb : slot;
     int kb = (int)(u0 - (g.units ? tile * (unsigned)g.Kb : 0));
-    const v4i *src = tile_source(g, tile, wave, lane);
+    wave_src src = tile_source<IMPLICIT>(g, tile, wave, lane);
+    {
+        unsigned qs;
+        const v4i *ub = unit_base<IMPLICIT>(g, src, kb, wave, lane, qs);
 #pragma unroll
-    for (int q = 0; q < 8; q++) __builtin_amdgcn_global_load_lds(src + (size_t)kb * 512 + q * 64, mine + q * 64, 16, 0, 0);
+        for (int q = 0; q < 8; q++) __builtin_amdgcn_global_load_lds(ub + (size_t)q * qs, mine + q * 64, 16, 0, 0);
+    }
     int st = 0;
 
     // column blocks of this wave that lie inside the matrix (0 if its row block lies outside): MFMAs of
@@ -310,7 +436,7 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
 
         // units of this tile that belong to this workgroup
         const int kb_end = min(g.Kb, kb + (int)(u1 - u));
-        const v4i *next_src = src;
+        wave_src next_src = src;
         for (; kb < kb_end; kb++, u++) {
             SS_TRACE(2);
             __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of the unit is in LDS
@@ -321,12 +447,20 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
                 int nkb = kb + 1;
                 if (nkb == g.Kb) {
                     nkb = 0;
-                    next_src = tile_source(g, tile + 1, wave, lane);
+                    next_src = tile_source<IMPLICIT>(g, tile + 1, wave, lane);
                 }
+                if constexpr (!IMPLICIT) {
 #pragma unroll
-                for (int q = 0; q < 8; q++)
-                    __builtin_amdgcn_global_load_lds(next_src + (size_t)nkb * 512 + q * 64,
-                                                     mine + (st ^ 1) * 4096 + q * 64, 16, 0, 0);
+                    for (int q = 0; q < 8; q++)
+                        __builtin_amdgcn_global_load_lds(next_src.p + (size_t)nkb * 512 + q * 64,
+                                                         mine + (st ^ 1) * 4096 + q * 64, 16, 0, 0);
+                } else {
+                    unsigned qs;
+                    const v4i *ub = unit_base<true>(g, next_src, nkb, wave, lane, qs);
+#pragma unroll
+                    for (int q = 0; q < 8; q++)
+                        __builtin_amdgcn_global_load_lds(ub + (size_t)q * qs, mine + (st ^ 1) * 4096 + q * 64, 16, 0, 0);
+                }
             }
             const v4i *sa = lds + st * 4096 + wr * 512 + lane;
             const v4i *sb = lds + st * 4096 + 2048 + wc * 1024 + lane;
@@ -524,11 +658,11 @@ size_t ss_packed_bytes(int rows, int K)
 }
 
 hipError_t ss_launch_pack_matrix(const u64 *src, void *dst, int n, int rows, int K, size_t party_stride,
-                                 size_t stride_r, size_t stride_k, hipStream_t stream)
+                                 size_t stride_r, size_t stride_k, int taps, hipStream_t stream)
 {
     const int Rb = (rows + 15) / 16, Kb = (K + 63) / 64;
     hipLaunchKernelGGL(pack_matrix_kernel, dim3(Rb, Kb, n), dim3(256), 0, stream, src, (v4i *)dst, rows, K, Kb,
-                       party_stride, stride_r, stride_k, ss_packed_bytes(rows, K) / 16);
+                       party_stride, stride_r, stride_k, ss_packed_bytes(rows, K) / 16, taps);
     return hipGetLastError();
 }
 
@@ -550,6 +684,25 @@ hipError_t ss_launch_share_pack(const u64 *secret, u64 *shares, void *dst, int n
     return hipGetLastError();
 }
 
+hipError_t ss_launch_planes(const u64 *in, u64 *shares, void *planes, int n, int t, int B, int C, int HW, bool gen,
+                            const ss_keys &keys, hipStream_t stream)
+{
+    const dim3 grid((B * HW + 15) / 16, C / 64), block(256);
+    const size_t party_bytes = (size_t)8 * B * HW * C + 256;
+#define SS_PLANES(NC, TC, G) \
+    hipLaunchKernelGGL((planes_kernel<NC, TC, G>), grid, block, 0, stream, in, shares, (signed char *)planes, B, C, HW, party_bytes, n, t, keys)
+    if (!gen)
+        SS_PLANES(0, 0, false);
+    else if (n == 5 && t == 2)
+        SS_PLANES(5, 2, true);
+    else if (n == 3 && t == 1)
+        SS_PLANES(3, 1, true);
+    else
+        SS_PLANES(0, 0, true);
+#undef SS_PLANES
+    return hipGetLastError();
+}
+
 hipError_t ss_launch_pack_im2col(const u64 *x, void *dst, int n, int B, int C, int H, int W, int kh, int kw,
                                  int stride, int pad, int Ho, int Wo, hipStream_t stream)
 {
@@ -560,21 +713,31 @@ hipError_t ss_launch_pack_im2col(const u64 *x, void *dst, int n, int B, int C, i
     return hipGetLastError();
 }
 
-hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, int n, int rows, int cols, int K,
-                          size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb, unsigned *counters,
-                          u64 *partials, hipStream_t stream)
+namespace {
+
+struct conv_planes {   // geometry of an operand given as channel-innermost limb planes
+    const void *planes;
+    int B, C, H, W, kh, kw, stride, pad, Ho, Wo;
+};
+
+hipError_t launch_gemm(const void *packedA, const void *packedB, const conv_planes *cv, u64 *out, int n, int rows,
+                       int cols, int K, size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb,
+                       unsigned *counters, u64 *partials, hipStream_t stream)
 {
     static bool lds_opt_in = false;
     constexpr int LDS_BYTES = 2 * 4096 * 16;
     if (!lds_opt_in) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_limb_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           LDS_BYTES);
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_limb_kernel<false>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)gemm_limb_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    LDS_BYTES);
         if (e != hipSuccess) return e;
         lds_opt_in = true;
     }
     const gemm_plan p = plan_gemm(n, rows, cols, K);
     if (p.G <= 0) return hipErrorInvalidValue;
-    gemm_args g;
+    gemm_args g = {};
     g.A = (const v4i *)packedA;
     g.B = (const v4i *)packedB;
     g.out = out;
@@ -599,6 +762,15 @@ hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, in
     g.stride_cb = stride_cb;
     g.cdiv = cdiv;
     g.negbias = neg_bias();
+    if (cv) {
+        const size_t plane = (size_t)cv->B * cv->H * cv->W * cv->C;   // bytes
+        g.planes = (const v4i *)cv->planes;
+        g.plane16 = (unsigned)(plane / 16);
+        g.party16 = (unsigned)(ss_planes_bytes(cv->B, cv->C, cv->H, cv->W) / 16);
+        g.zero = g.planes + (size_t)8 * g.plane16;   // the pad behind the first party's planes
+        g.cvH = cv->H, g.cvW = cv->W, g.cvC16 = cv->C / 16, g.cvKw = cv->kw, g.cvStride = cv->stride, g.cvPad = cv->pad;
+        g.cvHoWo = cv->Ho * cv->Wo, g.cvWo = cv->Wo, g.cvKbTap = cv->C / 64;
+    }
 #ifdef SS_GEMM_TRACE
     static u64 *trace_buf = nullptr;
     if (!trace_buf && hipMalloc(&trace_buf, 8192 * sizeof(u64)) != hipSuccess) return hipErrorOutOfMemory;
@@ -606,6 +778,35 @@ hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, in
     g.trace_block = getenv("SS_TRACE_BLOCK") ? atoi(getenv("SS_TRACE_BLOCK")) : 0;
     ss_debug_trace = trace_buf;
 #endif
-    hipLaunchKernelGGL(gemm_limb_kernel, dim3((unsigned)p.G), dim3(512), LDS_BYTES, stream, g);
+    if (cv)
+        hipLaunchKernelGGL(gemm_limb_kernel<true>, dim3((unsigned)p.G), dim3(512), LDS_BYTES, stream, g);
+    else
+        hipLaunchKernelGGL(gemm_limb_kernel<false>, dim3((unsigned)p.G), dim3(512), LDS_BYTES, stream, g);
     return hipGetLastError();
+}
+
+}  // namespace
+
+size_t ss_planes_bytes(int B, int C, int H, int W)
+{
+    return (size_t)8 * B * H * W * C + 256;   // eight limb planes and a pad that starts with 16 zero bytes
+}
+
+hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, int n, int rows, int cols, int K,
+                          size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb, unsigned *counters,
+                          u64 *partials, hipStream_t stream)
+{
+    return launch_gemm(packedA, packedB, nullptr, out, n, rows, cols, K, out_party_stride, stride_row, cdiv, stride_cb,
+                       counters, partials, stream);
+}
+
+hipError_t ss_launch_gemm_conv(const void *packedW, const void *planes, u64 *out, int n, int B, int C, int H, int W,
+                               int Co, int kh, int kw, int stride, int pad, int Ho, int Wo, unsigned *counters,
+                               u64 *partials, hipStream_t stream)
+{
+    const conv_planes cv = {planes, B, C, H, W, kh, kw, stride, pad, Ho, Wo};
+    const size_t HW = (size_t)Ho * Wo;
+    // rows = output channel, cols = (b, ho, wo): y[b][co][hw]
+    return launch_gemm(packedW, nullptr, &cv, out, n, Co, (int)(B * HW), C * kh * kw, (size_t)B * Co * HW, HW, (int)HW,
+                       (size_t)Co * HW, counters, partials, stream);
 }

@@ -78,12 +78,23 @@ hipError_t ss_launch_relu(const u64 *x, const u64 *sh_b, const u64 *sh_bi, u64 *
 // byte b of lane l is limb `limb` of element (row = 16*rb + l%16, k = 64*kb + 16*(l/16) + b).
 size_t ss_packed_bytes(int rows, int K);
 
-// element (r, k) of party i is src[i*party_stride + r*stride_r + k*stride_k]
+// element (r, k) of party i is src[i*party_stride + r*stride_r + k*stride_k]; taps > 0: packed index k =
+// tap*C + c reads source index c*taps + tap (C = K / taps)
 hipError_t ss_launch_pack_matrix(const u64 *src, void *dst, int n, int rows, int K, size_t party_stride,
-                                 size_t stride_r, size_t stride_k, hipStream_t stream);
+                                 size_t stride_r, size_t stride_k, int taps, hipStream_t stream);
 // degree-t shares of secret [B][K][HW] -> shares [n][B][K][HW] and their packed operand (rows (b, hw), k)
 hipError_t ss_launch_share_pack(const u64 *secret, u64 *shares, void *dst, int n, int t, int B, int K, int HW,
                                 const ss_keys &keys, hipStream_t stream);
+// Channel-innermost limb planes of a conv input: per party [limb 0..7][b][h][w][c] int8 and a 256-byte pad
+// whose first 16 bytes are zero; C a multiple of 64.
+size_t ss_planes_bytes(int B, int C, int H, int W);   // per party
+// gen: `in` is the plaintext [B][C][HW] and the shares [n][B][C][HW] are written too; else `in` is the shares
+hipError_t ss_launch_planes(const u64 *in, u64 *shares, void *planes, int n, int t, int B, int C, int HW, bool gen,
+                            const ss_keys &keys, hipStream_t stream);
+// convolution with the input given as planes and the weights packed with contraction index (tap, channel)
+hipError_t ss_launch_gemm_conv(const void *packedW, const void *planes, u64 *out, int n, int B, int C, int H, int W,
+                               int Co, int kh, int kw, int stride, int pad, int Ho, int Wo, unsigned *counters,
+                               u64 *partials, hipStream_t stream);
 // rows = (b, ho, wo), k = (c, r, s) of x [n][B][C][H][W]
 hipError_t ss_launch_pack_im2col(const u64 *x, void *dst, int n, int B, int C, int H, int W, int kh, int kw,
                                  int stride, int pad, int Ho, int Wo, hipStream_t stream);

@@ -418,7 +418,7 @@ int ssnet_pack_weights_linear(ssnet_ctx *ctx, const uint64_t *d_w, int K, int N,
     if (!ctx || !d_w || !d_packed || !gemm_shape_ok(N, 1, K) || ((uintptr_t)d_packed & 15)) return SSNET_EINVAL;
     // row = output column c of w [K][N], contraction index strides by N
     timed tm(ctx, SSNET_PROF_PACK_W);
-    hipError_t e = ss_launch_pack_matrix(d_w, d_packed, ctx->n, N, K, (size_t)K * N, 1, (size_t)N, ctx->stream);
+    hipError_t e = ss_launch_pack_matrix(d_w, d_packed, ctx->n, N, K, (size_t)K * N, 1, (size_t)N, 0, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
 
@@ -426,7 +426,7 @@ int ssnet_pack_weights_conv(ssnet_ctx *ctx, const uint64_t *d_w, int Co, int CKK
 {
     if (!ctx || !d_w || !d_packed || !gemm_shape_ok(Co, 1, CKK) || ((uintptr_t)d_packed & 15)) return SSNET_EINVAL;
     timed tm(ctx, SSNET_PROF_PACK_W);
-    hipError_t e = ss_launch_pack_matrix(d_w, d_packed, ctx->n, Co, CKK, (size_t)Co * CKK, (size_t)CKK, 1, ctx->stream);
+    hipError_t e = ss_launch_pack_matrix(d_w, d_packed, ctx->n, Co, CKK, (size_t)Co * CKK, (size_t)CKK, 1, 0, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
 
@@ -439,7 +439,7 @@ int ssnet_linear_mod_packed(ssnet_ctx *ctx, const uint64_t *d_x, const void *d_w
     void *px = ws_scratch(ctx) + part;
     {
         timed tm(ctx, SSNET_PROF_PACK_X);
-        hipError_t e = ss_launch_pack_matrix(d_x, px, ctx->n, M, K, (size_t)M * K, (size_t)K, 1, ctx->stream);
+        hipError_t e = ss_launch_pack_matrix(d_x, px, ctx->n, M, K, (size_t)M * K, (size_t)K, 1, 0, ctx->stream);
         if (e != hipSuccess) return fail_hip(ctx, e);
     }
     return run_gemm(ctx, px, d_w_packed, d_y, M, N, K, (size_t)M * N, (size_t)N, INT_MAX, 0);
@@ -463,6 +463,71 @@ int ssnet_conv1x1_mod_prepacked(ssnet_ctx *ctx, const void *d_x_packed, const vo
     if (!ws_fits(ctx, align256(ss_gemm_scratch_bytes(ctx->n, Co, M, C)))) return SSNET_EWORKSPACE;
     // rows = output channel, cols = (b, hw): y[b][co][hw]
     return run_gemm(ctx, d_w_packed, d_x_packed, d_y, Co, M, C, (size_t)B * Co * HW, (size_t)HW, HW, (size_t)Co * HW);
+}
+
+namespace {
+
+bool planes_shape_ok(long B, long C, long H, long W)
+{
+    return B >= 1 && C >= 64 && C % 64 == 0 && H >= 1 && W >= 1 && H < 32768 && W < 32768 && B * H * W < (1L << 30) &&
+           B * H * W * C < (1L << 35);
+}
+
+}  // namespace
+
+size_t ssnet_conv_planes_bytes(int B, int C, int H, int W)
+{
+    return planes_shape_ok(B, C, H, W) ? ss_planes_bytes(B, C, H, W) : 0;
+}
+
+int ssnet_share_planes(ssnet_ctx *ctx, const uint64_t *d_secret, int B, int C, int H, int W, uint64_t stream_id,
+                       uint64_t *d_shares, void *d_planes)
+{
+    if (!ctx || !d_secret || !d_shares || !d_planes || ((uintptr_t)d_planes & 15) || !planes_shape_ok(B, C, H, W))
+        return SSNET_EINVAL;
+    if ((size_t)B * C * H * W > MAX_COUNT) return SSNET_EINVAL;
+    ss_keys keys = {};
+    for (int j = 1; j <= ctx->t; j++) keys.k[j - 1] = ss_key(ctx->seed, SSNET_DOM_SHARE, stream_id, 0, (u64)j);
+    timed tm(ctx, SSNET_PROF_SHARE);
+    hipError_t e = ss_launch_planes(d_secret, d_shares, d_planes, ctx->n, ctx->t, B, C, H * W, true, keys, ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+int ssnet_split_planes(ssnet_ctx *ctx, const uint64_t *d_x, int B, int C, int H, int W, void *d_planes)
+{
+    if (!ctx || !d_x || !d_planes || ((uintptr_t)d_planes & 15) || !planes_shape_ok(B, C, H, W)) return SSNET_EINVAL;
+    const ss_keys none = {};
+    timed tm(ctx, SSNET_PROF_PACK_X);
+    hipError_t e = ss_launch_planes(d_x, nullptr, d_planes, ctx->n, ctx->t, B, C, H * W, false, none, ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+int ssnet_pack_weights_conv_taps(ssnet_ctx *ctx, const uint64_t *d_w, int Co, int C, int kh, int kw, void *d_packed)
+{
+    if (!ctx || !d_w || !d_packed || ((uintptr_t)d_packed & 15) || C < 1 || kh < 1 || kw < 1 ||
+        !gemm_shape_ok(Co, 1, (long)C * kh * kw))
+        return SSNET_EINVAL;
+    const int K = C * kh * kw;
+    timed tm(ctx, SSNET_PROF_PACK_W);
+    hipError_t e = ss_launch_pack_matrix(d_w, d_packed, ctx->n, Co, K, (size_t)Co * K, (size_t)K, 1, kh * kw, ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+int ssnet_conv_mod_planes(ssnet_ctx *ctx, const void *d_planes, const void *d_w_packed, int B, int C, int H, int W, int Co,
+                          int kh, int kw, int stride, int pad, uint64_t *d_y)
+{
+    if (!ctx || !d_planes || !d_w_packed || !d_y || !planes_shape_ok(B, C, H, W) || Co < 1 || kh < 1 || kw < 1 ||
+        stride < 1 || pad < 0 || pad >= 32768)
+        return SSNET_EINVAL;
+    const int Ho = conv_out(H, kh, stride, pad), Wo = conv_out(W, kw, stride, pad);
+    if (Ho < 1 || Wo < 1) return SSNET_EINVAL;
+    const long M = (long)B * Ho * Wo, K = (long)C * kh * kw;
+    if (!gemm_shape_ok(Co, M, K)) return SSNET_EINVAL;
+    if (!ws_fits(ctx, align256(ss_gemm_scratch_bytes(ctx->n, Co, (int)M, (int)K)))) return SSNET_EWORKSPACE;
+    timed tm(ctx, SSNET_PROF_GEMM);
+    hipError_t e = ss_launch_gemm_conv(d_w_packed, d_planes, d_y, ctx->n, B, C, H, W, Co, kh, kw, stride, pad, Ho, Wo,
+                                       (unsigned *)ctx->ws, (u64 *)ws_scratch(ctx), ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
 
 int ssnet_linear_mod(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_w, int M, int K, int N, uint64_t *d_y)

@@ -351,6 +351,40 @@ def test_relu_parity_with_masks_and_messages(n, t):
                               np.maximum(xs, 0))
 
 
+@pytest.mark.parametrize("n,t", [(3, 1), (5, 2), (7, 3)])
+def test_conv_on_limb_planes(n, t):
+    """Convolution that gathers its input from channel-innermost limb planes (no im2col matrix):
+    the same residues as the oracle's convolution, for planes made from shares and for planes
+    made together with the shares; strides, paddings, ragged pixel counts, several images."""
+    s = SSNet(n, t, seed=17)
+    cases = [(1, 64, 5, 5, 7, 3, 1, 1), (2, 128, 9, 7, 65, 3, 2, 1), (1, 64, 14, 14, 64, 1, 1, 0),
+             (1, 192, 6, 6, 10, 5, 1, 2), (3, 64, 4, 4, 130, 3, 1, 1), (1, 256, 14, 14, 256, 3, 1, 1),
+             (1, 64, 8, 8, 16, 2, 2, 0), (1, 64, 3, 3, 5, 3, 1, 0)]
+    for (B, C, H, W, Co, k, stride, pad) in cases:
+        say("planes conv", n, t, B, C, H, W, Co, k, stride, pad)
+        x = field_uniform(B * C * H * W, 3).reshape(B, C, H, W)
+        xs_o = orc.share(x, n, t, P61, 17, 5)
+        w = orc.share(field_uniform(Co * C * k * k, 4).reshape(Co, C, k, k), n, t, P61, 17, 6)
+        want = orc.conv(xs_o, w, stride, pad, P61)
+        wp = s.pack_weights_conv_taps(to_dev(w))
+        xs, planes = s.share_planes(to_dev(x), stream_id=5)
+        assert np.array_equal(to_np(xs), xs_o)
+        y = s.conv_mod_planes(planes, wp, B, C, H, W, Co, k, k, stride, pad)
+        assert np.array_equal(to_np(y), want)
+        planes2 = s.split_planes(to_dev(xs_o))                          # planes of existing shares: same bytes
+        per = planes.numel() // n
+        data = 8 * B * C * H * W + 16                                   # the rest of the pad is unspecified
+        assert bool(torch.equal(planes2.view(n, per)[:, :data], planes.view(n, per)[:, :data]))
+        # extreme digits everywhere: all limbs at -128 / +127, and p - 1
+    for v in (P61 - 1, 0x0080808080808080, 0x007F7F7F7F7F7F7F):
+        B, C, H, W, Co, k = 1, 64 * 8, 6, 6, 33, 3        # K = 4608
+        x = np.full((n, B, C, H, W), v, np.uint64)
+        w = np.full((n, Co, C, k, k), v, np.uint64)
+        y = s.conv_mod_planes(s.split_planes(to_dev(x)), s.pack_weights_conv_taps(to_dev(w)), B, C, H, W, Co, k, k, 1, 1)
+        assert np.array_equal(to_np(y), orc.conv(x, w, 1, 1, P61))
+    assert not s.planes_supported(1, 3, 8, 8) and not s.planes_supported(1, 96, 8, 8)
+
+
 def test_config1_tiny_secure_gemm_end_to_end():
     """n=3, t=1, f=13, X 64x256 ~ N(0,1), W 256x128 ~ N(0,1): share, multiply,
     reduce, truncate, reconstruct, decode."""
