@@ -89,63 +89,8 @@ __global__ __launch_bounds__(256) void pack_im2col_kernel(const u64 *__restrict_
     store_digits(y, dst + (size_t)blockIdx.z * dst_party_stride + ((size_t)rb * Kb + kb) * 512, r16, kq);
 }
 
-// GEN (Eq. 1) of the input of a dense or 1x1 convolution layer and its limb
-// tiles in one pass.  The secret is [B][K][HW] (dense: HW = 1); operand row
-// (b, hw), contraction index k.  Thread t of tile (rb, kb): row t%16, four
-// consecutive k; it draws the coefficients of its four elements (element index
-// = position in the secret, as in the plain share kernel), evaluates every
-// party's share, stores it and packs its digits.  N, T > 0 fix the scheme at
-// compile time, 0 takes the run-time values.
-template <int N, int T>
-__global__ __launch_bounds__(256) void share_pack_kernel(const u64 *__restrict__ secret, u64 *__restrict__ shares,
-                                                         v4i *__restrict__ dst, int B, int K, int HW, int Kb,
-                                                         size_t dst_party_stride, int n_rt, int t_rt, ss_keys keys)
-{
-    constexpr int MAXP = N ? N : SS_MAXN, MAXD = T ? T : SS_MAXT;
-    const int n = N ? N : n_rt, t = T ? T : t_rt;
-    const int rb = blockIdx.x, kb = blockIdx.y, r16 = threadIdx.x & 15, kq = threadIdx.x >> 4;
-    const int row = rb * 16 + r16, k0 = kb * 64 + 4 * kq, rows = B * HW;
-    const size_t plane = (size_t)B * K * HW;
-    u64 y[MAXP][4];
-#pragma unroll
-    for (int p = 0; p < MAXP; p++)
-#pragma unroll
-        for (int q = 0; q < 4; q++) y[p][q] = 0;   // digits of padding rows and columns
-    if (row < rows) {
-        const int b = row / HW, hw = row - b * HW;
-#pragma unroll
-        for (int q = 0; q < 4; q++) {
-            if (k0 + q < K) {
-                const size_t e = ((size_t)b * K + (k0 + q)) * HW + hw;
-                const u64 a0 = secret[e], counter = ss_counter(e);
-                u64 c[MAXD];
-#pragma unroll
-                for (int j = 0; j < MAXD; j++) c[j] = (j < t) ? ss_draw_field_at(keys.k[j], counter) : 0;
-                if constexpr (N != 0) {
-                    eval_points<T, N>(a0, c, [&](int p, u64 v) {
-                        shares[(size_t)p * plane + e] = v;
-                        y[p][q] = balanced_digits(v);
-                    });
-                } else {
-#pragma unroll
-                    for (int p = 0; p < MAXP; p++) {
-                        if (p < n) {
-                            const u64 v = ss_poly_eval<MAXD>(a0, c, t, p + 1);
-                            shares[(size_t)p * plane + e] = v;
-                            y[p][q] = balanced_digits(v);
-                        }
-                    }
-                }
-            }
-        }
-    }
-#pragma unroll
-    for (int p = 0; p < MAXP; p++)
-        if (p < n) store_digits(y[p], dst + (size_t)p * dst_party_stride + ((size_t)rb * Kb + kb) * 512, r16, kq);
-}
-
-// one dword per limb from the digit words of four consecutive channels (byte c of the result is digit
-// `limb` of y[c])
+// one dword per limb from the digit words of four consecutive contraction indices (byte c of the result is
+// digit `limb` of y[c]); limb may differ from lane to lane
 __device__ __forceinline__ u32 limb_dword(const u64 (&y)[4], int limb)
 {
     const int i = limb & 3;
@@ -155,15 +100,127 @@ __device__ __forceinline__ u32 limb_dword(const u64 (&y)[4], int limb)
     return __builtin_amdgcn_perm(__builtin_amdgcn_perm(d, c, sel), __builtin_amdgcn_perm(b, a, sel), 0x05040100u);
 }
 
+// The two kernels below take one element per thread: lane l of a wave holds row (or pixel) l%16 and the
+// contraction index (or channel) 4 g + l/16 of the wave's group g of four.  The four lanes of a row swap
+// their digit words (ds_bpermute), after which each of them owns all four and writes two of the eight limb
+// dwords.  The layers of a batch-1 network are small: one element per thread is what fills the chip.
+
+// shares of element e of the plaintext tensor, as GEN (Eq. 1) draws them (element index = position in the
+// tensor, so the values are those of the plain share kernel): stored, and returned as digit words
+template <int N, int T>
+__device__ __forceinline__ void gen_digits(const u64 *__restrict__ secret, u64 *__restrict__ shares, size_t count,
+                                           size_t e, int n, int t, const ss_keys &keys, u64 (&dig)[N ? N : SS_MAXN])
+{
+    constexpr int MAXP = N ? N : SS_MAXN, MAXD = T ? T : SS_MAXT;
+    const u64 a0 = secret[e], counter = ss_counter(e);
+    u64 c[MAXD];
+#pragma unroll
+    for (int j = 0; j < MAXD; j++) c[j] = (j < t) ? ss_draw_field_at(keys.k[j], counter) : 0;
+    if constexpr (N != 0) {
+        eval_points<T, N>(a0, c, [&](int p, u64 v) {
+            shares[(size_t)p * count + e] = v;
+            dig[p] = balanced_digits(v);
+        });
+    } else {
+#pragma unroll
+        for (int p = 0; p < MAXP; p++) {
+            if (p < n) {
+                const u64 v = ss_poly_eval<MAXD>(a0, c, t, p + 1);
+                shares[(size_t)p * count + e] = v;
+                dig[p] = balanced_digits(v);
+            }
+        }
+    }
+}
+
+// GEN (Eq. 1) of the input of a dense or 1x1 convolution layer and its limb
+// tiles in one pass.  The secret is [B][K][HW] (dense: HW = 1); operand row
+// (b, hw), contraction index k.  grid (row blocks, 4 Kb), block 256: wave w of
+// block (rb, y) takes the group of four contraction indices 4 y + w of row block
+// rb.  N, T > 0 fix the scheme at compile time, 0 takes the run-time values.
+template <int N, int T>
+__global__ __launch_bounds__(256) void share_pack_kernel(const u64 *__restrict__ secret, u64 *__restrict__ shares,
+                                                         v4i *__restrict__ dst, int B, int K, int HW, int Kb,
+                                                         size_t dst_party_stride, int n_rt, int t_rt, ss_keys keys)
+{
+    constexpr int MAXP = N ? N : SS_MAXN;
+    const int n = N ? N : n_rt, t = T ? T : t_rt;
+    const int lane = threadIdx.x & 63, r16 = lane & 15, j = lane >> 4;
+    const int g = blockIdx.y * 4 + (threadIdx.x >> 6), kb = g >> 4, kq = g & 15;
+    const int rb = blockIdx.x, row = rb * 16 + r16, k = kb * 64 + 4 * kq + j, rows = B * HW;
+    u64 dig[MAXP];
+#pragma unroll
+    for (int p = 0; p < MAXP; p++) dig[p] = 0;   // digits of padding rows and columns
+    if (row < rows && k < K) {
+        const int b = row / HW, hw = row - b * HW;
+        gen_digits<N, T>(secret, shares, (size_t)B * K * HW, ((size_t)b * K + k) * HW + hw, n, t, keys, dig);
+    }
+    u32 *base = reinterpret_cast<u32 *>(dst + ((size_t)rb * Kb + kb) * 512) + (r16 + 16 * (kq >> 2)) * 4 + (kq & 3);
+#pragma unroll
+    for (int p = 0; p < MAXP; p++) {
+        if (p < n) {
+            u64 y[4];
+#pragma unroll
+            for (int q = 0; q < 4; q++) y[q] = __shfl(dig[p], r16 + 16 * q);
+            u32 *bp = base + (size_t)p * dst_party_stride * 4;
+            bp[(2 * j) * 256] = limb_dword(y, 2 * j);
+            bp[(2 * j + 1) * 256] = limb_dword(y, 2 * j + 1);
+        }
+    }
+}
+
 // Conv input [B][C][H][W] -> channel-innermost limb planes [party][limb][b][h][w][c] (int8), the form the
 // convolution kernel gathers its second operand from (16 consecutive channels of one tap of one output pixel
-// are 16 consecutive bytes).  GEN: the input is the plaintext tensor and the kernel also is GEN (Eq. 1): it
-// draws the coefficients of each element (element index = position in the tensor), writes the n shares and
-// their planes; otherwise the input is the share tensor [n][B][C][H][W].  Thread t of block (pixel block,
-// channel block of 64): pixel t%16, four channels from 4 (t/16).  Every party's planes end in a pad whose
-// first 16 bytes are zero (the source of taps that fall into the padding).
+// are 16 consecutive bytes).  GEN: the input is the plaintext tensor and the kernel also is GEN (Eq. 1):
+// it writes the n shares and their planes; otherwise the input is the share tensor [n][B][C][H][W].
+// grid (pixel blocks of 16, C / 16), block 256: wave w of block (x, y) takes channels 16 y + 4 w .. +3.
+// Every party's planes end in a pad whose first 16 bytes are zero (the source of taps in the padding).
 template <int N, int T, bool GEN>
 __global__ __launch_bounds__(256) void planes_kernel(const u64 *__restrict__ in, u64 *__restrict__ shares,
+                                                     signed char *__restrict__ planes, int B, int C, int HW,
+                                                     size_t party_bytes, int n_rt, int t_rt, ss_keys keys)
+{
+    constexpr int MAXP = N ? N : SS_MAXN;
+    const int n = N ? N : n_rt, t = T ? T : t_rt;
+    const int lane = threadIdx.x & 63, r16 = lane & 15, j = lane >> 4;
+    const int pix = blockIdx.x * 16 + r16, c0 = blockIdx.y * 16 + 4 * (threadIdx.x >> 6);
+    const size_t plane = (size_t)B * HW * C;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x < n)
+        *reinterpret_cast<v4i *>(planes + threadIdx.x * party_bytes + 8 * plane) = (v4i){0, 0, 0, 0};
+    u64 dig[MAXP];
+#pragma unroll
+    for (int p = 0; p < MAXP; p++) dig[p] = 0;
+    const bool live = pix < B * HW;
+    if (live) {
+        const int b = pix / HW, hw = pix - b * HW;
+        const size_t e = ((size_t)b * C + (c0 + j)) * HW + hw;
+        if constexpr (GEN) {
+            gen_digits<N, T>(in, shares, plane, e, n, t, keys, dig);
+        } else {
+#pragma unroll
+            for (int p = 0; p < MAXP; p++)
+                if (p < n) dig[p] = balanced_digits(in[(size_t)p * plane + e]);
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < MAXP; p++) {
+        if (p < n) {
+            u64 y[4];
+#pragma unroll
+            for (int q = 0; q < 4; q++) y[q] = __shfl(dig[p], r16 + 16 * q);
+            if (live) {
+                u32 *bp = reinterpret_cast<u32 *>(planes + p * party_bytes + (size_t)pix * C + c0);
+                bp[(2 * j) * (plane / 4)] = limb_dword(y, 2 * j);
+                bp[(2 * j + 1) * (plane / 4)] = limb_dword(y, 2 * j + 1);
+            }
+        }
+    }
+}
+
+// The same with four channels per thread (thread t of block (pixel block, channel block of 64): pixel t%16,
+// channels from 4 (t/16)): fewer, longer threads, the better shape for large tensors.
+template <int N, int T, bool GEN>
+__global__ __launch_bounds__(256) void planes4_kernel(const u64 *__restrict__ in, u64 *__restrict__ shares,
                                                      signed char *__restrict__ planes, int B, int C, int HW,
                                                      size_t party_bytes, int n_rt, int t_rt, ss_keys keys)
 {
@@ -670,7 +727,7 @@ hipError_t ss_launch_share_pack(const u64 *secret, u64 *shares, void *dst, int n
                                 const ss_keys &keys, hipStream_t stream)
 {
     const int rows = B * HW, Rb = (rows + 15) / 16, Kb = (K + 63) / 64;
-    const dim3 grid(Rb, Kb), block(256);
+    const dim3 grid(Rb, Kb * 4), block(256);
     const size_t stride = ss_packed_bytes(rows, K) / 16;
 #define SS_SHARE_PACK(NC, TC) \
     hipLaunchKernelGGL((share_pack_kernel<NC, TC>), grid, block, 0, stream, secret, shares, (v4i *)dst, B, K, HW, Kb, stride, n, t, keys)
@@ -687,10 +744,20 @@ hipError_t ss_launch_share_pack(const u64 *secret, u64 *shares, void *dst, int n
 hipError_t ss_launch_planes(const u64 *in, u64 *shares, void *planes, int n, int t, int B, int C, int HW, bool gen,
                             const ss_keys &keys, hipStream_t stream)
 {
-    const dim3 grid((B * HW + 15) / 16, C / 64), block(256);
+    // one element per thread fills the chip for the small tensors of a batch-1 network; from about half a
+    // million elements on, four per thread move the data with fewer instructions
+    const bool big = (size_t)B * HW * C >= ((size_t)1 << 19);
+    const dim3 grid((B * HW + 15) / 16, big ? C / 64 : C / 16), block(256);
     const size_t party_bytes = (size_t)8 * B * HW * C + 256;
-#define SS_PLANES(NC, TC, G) \
-    hipLaunchKernelGGL((planes_kernel<NC, TC, G>), grid, block, 0, stream, in, shares, (signed char *)planes, B, C, HW, party_bytes, n, t, keys)
+#define SS_PLANES(NC, TC, G)                                                                                        \
+    do {                                                                                                            \
+        if (big)                                                                                                    \
+            hipLaunchKernelGGL((planes4_kernel<NC, TC, G>), grid, block, 0, stream, in, shares, (signed char *)planes, B, \
+                               C, HW, party_bytes, n, t, keys);                                                     \
+        else                                                                                                        \
+            hipLaunchKernelGGL((planes_kernel<NC, TC, G>), grid, block, 0, stream, in, shares, (signed char *)planes, B,  \
+                               C, HW, party_bytes, n, t, keys);                                                     \
+    } while (0)
     if (!gen)
         SS_PLANES(0, 0, false);
     else if (n == 5 && t == 2)

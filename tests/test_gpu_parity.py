@@ -359,7 +359,8 @@ def test_conv_on_limb_planes(n, t):
     s = SSNet(n, t, seed=17)
     cases = [(1, 64, 5, 5, 7, 3, 1, 1), (2, 128, 9, 7, 65, 3, 2, 1), (1, 64, 14, 14, 64, 1, 1, 0),
              (1, 192, 6, 6, 10, 5, 1, 2), (3, 64, 4, 4, 130, 3, 1, 1), (1, 256, 14, 14, 256, 3, 1, 1),
-             (1, 64, 8, 8, 16, 2, 2, 0), (1, 64, 3, 3, 5, 3, 1, 0)]
+             (1, 64, 8, 8, 16, 2, 2, 0), (1, 64, 3, 3, 5, 3, 1, 0),
+             (2, 64, 72, 72, 8, 3, 1, 1)]            # > 2^19 elements: the four-channels-per-thread kernels
     for (B, C, H, W, Co, k, stride, pad) in cases:
         say("planes conv", n, t, B, C, H, W, Co, k, stride, pad)
         x = field_uniform(B * C * H * W, 3).reshape(B, C, H, W)
