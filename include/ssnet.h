@@ -234,6 +234,27 @@ int ssnet_nonlinear_masks(ssnet_ctx *ctx, size_t count, uint64_t stream_id, uint
 int ssnet_relu(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_beta, const uint64_t *d_betainv, size_t count,
                uint64_t *d_out);
 
+/* The tail of a convolution layer in the default order Linear - Truncation -
+ * NonLinear (Sec. VII-A) in one launch: ssnet_degree_reduce_truncate(stream_id)
+ * of the product shares d_c [n][B][C][HW], then ssnet_relu with the masks
+ * d_beta, d_betainv [n][B][C][HW]; d_out [n][B][C][HW] holds the residues these
+ * two calls give, and d_planes, if not NULL, the same values as channel-innermost
+ * limb planes for the next ssnet_conv_mod_planes (C a multiple of 64 then).
+ * Messages behind the workspace header: those of the reduction and truncation,
+ * then the 2t+1 masked products and the plain value of the ReLU, as planes of
+ * P = ssnet_layer_tail_message_plane(B, C, HW) positions each
+ * ([2t+1][k][P], [k][n][P], [k][P], [n][P], [2t+1][P], [P]).  For the schemes
+ * (3,1) and (5,2), which run as one kernel, a plane is ordered by that kernel's
+ * threads, blocks of 16 pixels x 16 channels: element (b, c, hw), pix = b*HW+hw,
+ * sits at ((c/16) * ceil(B*HW/16) + pix/16) * 256 + (c%16/4) * 64 + (c%4) * 16 +
+ * pix%16, and P counts the padded blocks; for other schemes P = B*C*HW in
+ * element order.  ssnet_workspace_bytes_layer_tail gives the bytes needed.
+ * d_out may alias d_c. */
+size_t ssnet_layer_tail_message_plane(const ssnet_ctx *ctx, int B, int C, int HW);
+size_t ssnet_workspace_bytes_layer_tail(const ssnet_ctx *ctx, int B, int C, int HW);
+int ssnet_reduce_truncate_relu(ssnet_ctx *ctx, const uint64_t *d_c, int B, int C, int HW, uint64_t stream_id,
+                               const uint64_t *d_beta, const uint64_t *d_betainv, uint64_t *d_out, void *d_planes);
+
 /* Host-side generator, exposed so that its bits can be checked without a GPU.
  * key = absorb(seed, domain, stream_id, party, j) with h <- mix64((h ^ word) +
  * 0x9E3779B97F4A7C15) from h = 0, mix64 being the SplitMix64 output function;

@@ -52,6 +52,9 @@ SIGNATURES = {
     "ssnet_degree_reduce_truncate": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
     "ssnet_degree_reduce_truncate_reconstruct": (_int, [_ptr, _ptr, _sz, _u64, _ptr, C.POINTER(_int), _int, _ptr]),
     "ssnet_reduce_truncate_direct": (_int, [_ptr, _ptr, _sz, _u64, _ptr, C.POINTER(_int), _int, _ptr]),
+    "ssnet_workspace_bytes_layer_tail": (_sz, [_ptr, _int, _int, _int]),
+    "ssnet_layer_tail_message_plane": (_sz, [_ptr, _int, _int, _int]),
+    "ssnet_reduce_truncate_relu": (_int, [_ptr, _ptr, _int, _int, _int, _u64, _ptr, _ptr, _ptr, _ptr]),
     "ssnet_nonlinear_masks": (_int, [_ptr, _sz, _u64, _ptr, _ptr]),
     "ssnet_relu": (_int, [_ptr, _ptr, _ptr, _ptr, _sz, _ptr]),
     "ssnet_rng_key": (_u64, [_u64] * 5),
@@ -411,6 +414,26 @@ class SSNet:
                                                        _dptr(secret) if secret is not None else None),
                  "ssnet_reduce_truncate_direct")
         return out, secret
+
+    def reduce_truncate_relu(self, c: torch.Tensor, stream_id: int, beta: torch.Tensor, betainv: torch.Tensor,
+                             out: Optional[torch.Tensor] = None, planes: Optional[torch.Tensor] = None,
+                             want_planes: bool = False):
+        """c [n][B][C][H][W] (or [n][B][C]) product shares -> (shares of ReLU(trunc(.)), limb planes or None)"""
+        _check_i64(c, "c")
+        n, B, C = c.shape[0], c.shape[1], c.shape[2]
+        HW = c[0, 0, 0].numel()
+        count = c[0].numel()
+        if beta.numel() != c.numel() or betainv.numel() != c.numel():
+            raise SSNetError(EINVAL, "reduce_truncate_relu: mask shares must have the shape of c")
+        self.reserve(self.lib.ssnet_workspace_bytes_layer_tail(self._ctx, B, C, HW))
+        if out is None:
+            out = torch.empty_like(c)
+        if want_planes and planes is None:
+            planes = self._planes_buffer(B, C, HW, 1, None, c.device)
+        self._ok(self.lib.ssnet_reduce_truncate_relu(self._ctx, _dptr(c), B, C, HW, stream_id, _dptr(beta), _dptr(betainv),
+                                                     _dptr(out), _dptr(planes) if planes is not None else None),
+                 "ssnet_reduce_truncate_relu")
+        return out, planes
 
     def nonlinear_masks(self, shape, stream_id: int, device=None):
         """-> (shares of beta, shares of beta^-1), each [n, *shape]; offline preprocessing"""

@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libssnet.so")
 SOURCES = ["stream_kernels.hip", "gemm_kernels.hip", "ssnet_api.hip"]
-HEADERS = ["field.hpp", "kernels.hpp", "eval.hpp", os.path.join("..", "..", "include", "ssnet.h")]
+HEADERS = ["field.hpp", "kernels.hpp", "eval.hpp", "digits.hpp", os.path.join("..", "..", "include", "ssnet.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument"]

@@ -182,27 +182,40 @@ class Chain:
         ss = self.ss
         self.masks = [ss.nonlinear_masks(self._out_shape(L), stream_id=self.MASK_STREAM_BASE + l, device=ss.device or "cuda")
                       if L.post == "relu" else None for l, L in enumerate(self.layers)]
+        # here every convolution whose channel count allows it reads limb planes, 1x1 ones included: the
+        # tail of the layer before writes them.  For a 1x1 kernel the tap-major tiles are the ordinary ones.
+        self.sec_planes = [L.kind == "conv" and ss.planes_supported(self.batch, L.cin, L.hin, L.hin)
+                           for L in self.layers]
+        self.sec_packed = list(self.packed)
+        need = max([ss.n * ss.lib.ssnet_conv_planes_bytes(self.batch, L.cin, L.hin, L.hin)
+                    for L, pl in zip(self.layers, self.sec_planes) if pl] + [16])
+        if self.x_planes.numel() < need:
+            self.x_planes = torch.empty(need, dtype=torch.uint8, device=self.x_planes.device)
 
-    def secure_layer(self, l: int, x_plain: Optional[torch.Tensor], x_shares: Optional[torch.Tensor]):
-        """Layer l from its plain input (shared here) or from the previous layer's output shares.
+    def secure_layer(self, l: int, x_plain: Optional[torch.Tensor], x_shares: Optional[torch.Tensor],
+                     planes_ready: bool = False):
+        """Layer l from its plain input (shared here) or from the previous layer's output shares
+        (planes_ready: their limb planes already are in self.x_planes).
         -> (output shares after the activation, or None; opened result, or None)"""
         ss, L = self.ss, self.layers[l]
         y = self.y[l]
         if x_shares is None:
             x_shares = ss.share(x_plain, stream_id=l, out=self.x_shares[l])
-        if self.on_planes[l]:
-            ss.split_planes(x_shares, planes=self.x_planes)
-            ss.conv_mod_planes(self.x_planes, self.packed[l], self.batch, L.cin, L.hin, L.hin, L.cout, L.ksize, L.ksize,
-                               L.stride, L.pad, out=y)
+        if self.sec_planes[l]:
+            if not planes_ready:
+                ss.split_planes(x_shares, planes=self.x_planes)
+            ss.conv_mod_planes(self.x_planes, self.sec_packed[l], self.batch, L.cin, L.hin, L.hin, L.cout, L.ksize,
+                               L.ksize, L.stride, L.pad, out=y)
         elif L.kind == "conv":
             ss.conv_mod_packed(x_shares, self.packed[l], L.cout, L.ksize, L.ksize, L.stride, L.pad, out=y)
         else:
             ss.linear_mod_packed(x_shares, self.packed[l], L.cout, out=y)
         yv = y.view(ss.n, -1)
         if L.post == "relu":
-            ss.degree_reduce_truncate(yv, stream_id=l, out=yv)
+            # reduce + truncate + ReLU in one launch, which also leaves the next layer's limb planes
             b, bi = self.masks[l]
-            ss.relu(y, b, bi, out=y)
+            nxt = l + 1 < len(self.layers) and self.sec_planes[l + 1]
+            ss.reduce_truncate_relu(y, l, b, bi, out=y, planes=self.x_planes if nxt else None)
             return y, None
         ss.degree_reduce_truncate_reconstruct(yv, stream_id=l, ids=self.ids, out=yv, secret=self.rec[l])
         return None, self.rec[l]
@@ -219,7 +232,8 @@ class Chain:
                 if L.kind == "fc":
                     x_plain = x_plain.reshape(self.batch, -1)
                 self.secure_plain[l] = x_plain.contiguous()
-            x_shares, out = self.secure_layer(l, self.secure_plain[l], x_shares)
+            x_shares, out = self.secure_layer(l, self.secure_plain[l], x_shares,
+                                              planes_ready=x_shares is not None and self.sec_planes[l])
             if x_shares is None and L.post is not None:
                 x_plain = fx.from_signed(post_plain(fx.lift(out), L.post))
         return out
@@ -228,4 +242,5 @@ class Chain:
         """The share arithmetic of the whole stack, layer feeding layer."""
         x_shares = None
         for l in range(len(self.layers)):
-            x_shares, _ = self.secure_layer(l, self.secure_plain[l], x_shares)
+            x_shares, _ = self.secure_layer(l, self.secure_plain[l], x_shares,
+                                            planes_ready=x_shares is not None and self.sec_planes[l])

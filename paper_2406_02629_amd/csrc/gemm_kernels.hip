@@ -13,15 +13,11 @@
 // field element.
 #include "kernels.hpp"
 #include "eval.hpp"
+#include "digits.hpp"
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
 namespace {
-
-constexpr u64 BAL = 0x8080808080808080ULL;
-
-// balanced digits of x as 8 signed bytes
-__device__ __forceinline__ u64 balanced_digits(u64 x) { return (x + BAL) ^ BAL; }
 
 // Digit words of four consecutive contraction indices -> one dword per limb
 // (byte c of dword `limb` is digit `limb` of y[c]) and store them: the thread
@@ -87,17 +83,6 @@ __global__ __launch_bounds__(256) void pack_im2col_kernel(const u64 *__restrict_
         }
     }
     store_digits(y, dst + (size_t)blockIdx.z * dst_party_stride + ((size_t)rb * Kb + kb) * 512, r16, kq);
-}
-
-// one dword per limb from the digit words of four consecutive contraction indices (byte c of the result is
-// digit `limb` of y[c]); limb may differ from lane to lane
-__device__ __forceinline__ u32 limb_dword(const u64 (&y)[4], int limb)
-{
-    const int i = limb & 3;
-    const u32 a = limb < 4 ? (u32)y[0] : (u32)(y[0] >> 32), b = limb < 4 ? (u32)y[1] : (u32)(y[1] >> 32);
-    const u32 c = limb < 4 ? (u32)y[2] : (u32)(y[2] >> 32), d = limb < 4 ? (u32)y[3] : (u32)(y[3] >> 32);
-    const u32 sel = (u32)i | ((u32)(4 + i) << 8) | 0x0c0c0000u;
-    return __builtin_amdgcn_perm(__builtin_amdgcn_perm(d, c, sel), __builtin_amdgcn_perm(b, a, sel), 0x05040100u);
 }
 
 // The two kernels below take one element per thread: lane l of a wave holds row (or pixel) l%16 and the

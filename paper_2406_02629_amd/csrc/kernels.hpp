@@ -73,6 +73,13 @@ hipError_t ss_launch_nonlinear_masks(u64 *sh_b, u64 *sh_bi, size_t count, const 
 hipError_t ss_launch_relu(const u64 *x, const u64 *sh_b, const u64 *sh_bi, u64 *msg, u64 *yplain, u64 *out,
                           size_t count, const ss_nl_params &np, hipStream_t stream);
 
+// reduction + RERAND + truncation + ReLU of c [n][B][C][HW] in one launch, result as shares and (planes !=
+// nullptr) as limb planes; schemes (3,1) and (5,2) only (hipErrorInvalidValue otherwise, nothing launched)
+hipError_t ss_launch_layer_tail(const u64 *c, u64 *msg1, u64 *msg2, u64 *umsg, u64 *wsh, u64 *rmsg, u64 *yplain,
+                                const u64 *sh_b, const u64 *sh_bi, u64 *out, void *planes, int B, int C, int HW,
+                                const ss_dr_params &dp, const ss_tr_params &tp, const ss_nl_params &np,
+                                hipStream_t stream);
+
 // ---- int8-limb MFMA family (gemm_kernels.hip) ----
 // Packed operand: int8 tiles [row block of 16][k block of 64][limb 0..7][lane 0..63][16 bytes];
 // byte b of lane l is limb `limb` of element (row = 16*rb + l%16, k = 64*kb + 16*(l/16) + b).

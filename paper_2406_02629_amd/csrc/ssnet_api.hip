@@ -736,6 +736,73 @@ int ssnet_reduce_truncate_direct(ssnet_ctx *ctx, const uint64_t *d_c, size_t cou
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
 
+namespace {
+
+// positions per message plane of the layer-tail call: the threads of its one-launch kernel (blocks of 16
+// pixels x 16 channels), or the elements themselves where the separate kernels run
+size_t tail_plane(const ssnet_ctx *ctx, int B, int C, int HW)
+{
+    const bool fused = (ctx->n == 5 && ctx->t == 2) || (ctx->n == 3 && ctx->t == 1);
+    return fused ? (size_t)((B * HW + 15) / 16) * ((C + 15) / 16) * 256 : (size_t)B * C * HW;
+}
+
+}  // namespace
+
+size_t ssnet_layer_tail_message_plane(const ssnet_ctx *ctx, int B, int C, int HW)
+{
+    if (!ctx || B < 1 || C < 1 || HW < 1 || (long)B * HW >= (1L << 30) || (size_t)B * C * HW > MAX_COUNT) return 0;
+    return tail_plane(ctx, B, C, HW);
+}
+
+size_t ssnet_workspace_bytes_layer_tail(const ssnet_ctx *ctx, int B, int C, int HW)
+{
+    const size_t plane = ssnet_layer_tail_message_plane(ctx, B, C, HW);
+    if (!plane) return 0;
+    const size_t k = ctx->t + 1, nr = 2 * ctx->t + 1, n = ctx->n;
+    return WS_COUNTER_BYTES + align256((nr * k + k * n + k + n + nr + 1) * plane * 8);
+}
+
+int ssnet_reduce_truncate_relu(ssnet_ctx *ctx, const uint64_t *d_c, int B, int C, int HW, uint64_t stream_id,
+                               const uint64_t *d_beta, const uint64_t *d_betainv, uint64_t *d_out, void *d_planes)
+{
+    if (!ctx || !d_c || !d_beta || !d_betainv || !d_out || B < 1 || C < 1 || HW < 1) return SSNET_EINVAL;
+    if ((long)B * HW >= (1L << 30) || (size_t)B * C * HW > MAX_COUNT) return SSNET_EINVAL;
+    if (d_planes && (((uintptr_t)d_planes & 15) || C % 64 != 0)) return SSNET_EINVAL;
+    const size_t count = (size_t)B * C * HW, plane = tail_plane(ctx, B, C, HW);
+    const int k = ctx->t + 1, nr = 2 * ctx->t + 1, n = ctx->n;
+    if (!ws_fits(ctx, ((size_t)nr * k + (size_t)k * n + k + n + nr + 1) * plane * 8)) return SSNET_EWORKSPACE;
+    u64 *msg1 = (u64 *)ws_scratch(ctx), *msg2 = msg1 + (size_t)nr * k * plane;
+    u64 *u = msg2 + (size_t)k * n * plane, *wsh = u + (size_t)k * plane;
+    u64 *rmsg = wsh + (size_t)n * plane, *yplain = rmsg + (size_t)nr * plane;
+    ss_nl_params np;
+    if (!make_nl_params(ctx, 0, &np)) return SSNET_EINVAL;
+    const ss_dr_params dp = make_dr_params(ctx, stream_id);
+    const ss_tr_params tp = make_tr_params(ctx, stream_id);
+    hipError_t e;
+    if ((n == 5 && ctx->t == 2) || (n == 3 && ctx->t == 1)) {
+        timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
+        e = ss_launch_layer_tail(d_c, msg1, msg2, u, wsh, rmsg, yplain, d_beta, d_betainv, d_out, d_planes, B, C, HW, dp,
+                                 tp, np, ctx->stream);
+    } else {   // other schemes: the same steps, messages and results in three launches
+        const ss_recf_params norec = {};
+        {
+            timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
+            e = ss_launch_degree_reduce_truncate(d_c, msg1, msg2, u, wsh, d_out, nullptr, count, dp, tp, norec,
+                                                 ctx->stream);
+        }
+        if (e == hipSuccess) {
+            timed tm(ctx, SSNET_PROF_NONLINEAR);
+            e = ss_launch_relu(d_out, d_beta, d_betainv, rmsg, yplain, d_out, count, np, ctx->stream);
+        }
+        if (e == hipSuccess && d_planes) {
+            const ss_keys none = {};
+            timed tm(ctx, SSNET_PROF_PACK_X);
+            e = ss_launch_planes(d_out, nullptr, d_planes, n, ctx->t, B, C, HW, false, none, ctx->stream);
+        }
+    }
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
 int ssnet_nonlinear_masks(ssnet_ctx *ctx, size_t count, uint64_t stream_id, uint64_t *d_beta, uint64_t *d_betainv)
 {
     if (!ctx || !d_beta || !d_betainv || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;

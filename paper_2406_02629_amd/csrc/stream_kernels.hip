@@ -6,6 +6,7 @@
 // coefficients of an element are drawn once, not once per party.
 #include "kernels.hpp"
 #include "eval.hpp"
+#include "digits.hpp"
 
 namespace {
 
@@ -336,16 +337,16 @@ struct ss_sacc2 {
 };
 #define SS_SPLIT31(v, w0, w1) const u32 w0 = (u32)(v)&0x7FFFFFFFu, w1 = (u32)((v) >> 31)
 
+// all steps for element e; the messages go to the workspace, the new shares (reduced and re-randomised, with
+// TRUNC also truncated) come back in o[]
+// (em, mcount: position and plane size of this element in the message buffers, which need not be e, count)
 template <int N, int T, bool TRUNC>
-__global__ __launch_bounds__(BLOCK) void degree_reduce_fixed_kernel(const u64 *c, u64 *__restrict__ msg1,
-                                                                    u64 *__restrict__ msg2, u64 *__restrict__ umsg,
-                                                                    u64 *__restrict__ wsh, u64 *out,
-                                                                    u64 *__restrict__ rec, size_t count,
-                                                                    ss_dr_params dp, ss_tr_params tp, ss_recf_params rf)
+__device__ __forceinline__ void reduce_truncate_fixed(size_t e, size_t count, size_t em, size_t mcount, const u64 *c,
+                                                      u64 *__restrict__ msg1, u64 *__restrict__ msg2,
+                                                      u64 *__restrict__ umsg, u64 *__restrict__ wsh,
+                                                      const ss_dr_params &dp, const ss_tr_params &tp, u64 (&o)[N])
 {
     constexpr int K = T + 1, NR = 2 * T + 1;
-    const size_t e = (size_t)blockIdx.x * BLOCK + threadIdx.x;
-    if (e >= count) return;
     const u64 counter = ss_counter(e);
     auto draw = [&](const u64 *keys, u64 (&r)[T]) {
 #pragma unroll
@@ -364,7 +365,7 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_fixed_kernel(const u64 *c
         u64 r[T];
         draw(dp.reshare_key[i], r);
         eval_points<T, K>(ci, r, [&](int q, u64 v) {
-            msg1[((size_t)i * K + q) * count + e] = v;
+            msg1[((size_t)i * K + q) * mcount + em] = v;
             SS_SPLIT31(v, w0, w1);
 #pragma unroll
             for (int j = 0; j < K; j++) coef[q][j].mac(w0, w1, dp.ibinv[i][j]);
@@ -383,7 +384,7 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_fixed_kernel(const u64 *c
 #pragma unroll
         for (int j = 1; j < K; j++) cf[j - 1] = ss_mul(coef[q][j].value(), dp.dinv);
         eval_points<T, N>(a0, cf, [&](int m, u64 v) {
-            msg2[((size_t)q * N + m) * count + e] = v;
+            msg2[((size_t)q * N + m) * mcount + em] = v;
             SS_SPLIT31(v, w0, w1);
             red[m].mac(w0, w1, dp.ilambda[q]);
         });
@@ -395,7 +396,7 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_fixed_kernel(const u64 *c
     eval_points<T, N>(0, z, [&](int m, u64 v) { y[m] = ss_add(red[m].value(), v); });
     if (!TRUNC) {
 #pragma unroll
-        for (int m = 0; m < N; m++) out[(size_t)m * count + e] = y[m];
+        for (int m = 0; m < N; m++) o[m] = y[m];
         return;
     }
 
@@ -407,30 +408,127 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_fixed_kernel(const u64 *c
     acc.clear();
     eval_points<T, K>(ev << tp.f, ca, [&](int q, u64 v) {
         const u64 um = ss_add(y[q], v);
-        umsg[(size_t)q * count + e] = um;
+        umsg[(size_t)q * mcount + em] = um;
         SS_SPLIT31(um, w0, w1);
         acc.mac(w0, w1, tp.ilambda[q]);
     });
-    // step 2: shift and re-share; step 3: unmask; then, if asked for, REC of the result
+    // step 2: shift and re-share; step 3: unmask
     const u64 w = shift_signed(acc.value(), tp.f);
     draw(tp.gen_key, cw);
     draw(tp.alphat_key, cat);
     u64 ws[N];
     eval_points<T, N>(w, cw, [&](int m, u64 v) {
-        wsh[(size_t)m * count + e] = v;
+        wsh[(size_t)m * mcount + em] = v;
         ws[m] = v;
     });
-    ss_sacc2 racc;
+    eval_points<T, N>(SS_P - ev, cat, [&](int m, u64 v) { o[m] = ss_add(ws[m], v); });
+}
+
+template <int N, int T, bool TRUNC>
+__global__ __launch_bounds__(BLOCK) void degree_reduce_fixed_kernel(const u64 *c, u64 *__restrict__ msg1,
+                                                                    u64 *__restrict__ msg2, u64 *__restrict__ umsg,
+                                                                    u64 *__restrict__ wsh, u64 *out,
+                                                                    u64 *__restrict__ rec, size_t count,
+                                                                    ss_dr_params dp, ss_tr_params tp, ss_recf_params rf)
+{
+    const size_t e = (size_t)blockIdx.x * BLOCK + threadIdx.x;
+    if (e >= count) return;
+    u64 o[N];
+    reduce_truncate_fixed<N, T, TRUNC>(e, count, e, count, c, msg1, msg2, umsg, wsh, dp, tp, o);
+    ss_sacc2 racc;   // if asked for, REC of the result
     racc.clear();
-    eval_points<T, N>(SS_P - ev, cat, [&](int m, u64 v) {
-        const u64 o = ss_add(ws[m], v);
-        out[(size_t)m * count + e] = o;
-        if (rec) {
-            SS_SPLIT31(o, w0, w1);
+#pragma unroll
+    for (int m = 0; m < N; m++) {
+        out[(size_t)m * count + e] = o[m];
+        if (TRUNC && rec) {
+            SS_SPLIT31(o[m], w0, w1);
             racc.mac(w0, w1, rf.coef[m]);
         }
-    });
-    if (rec) rec[e] = rf.dinv == 1 ? racc.value() : ss_mul(racc.value(), rf.dinv);
+    }
+    if (TRUNC && rec) rec[e] = rf.dinv == 1 ? racc.value() : ss_mul(racc.value(), rf.dinv);
+}
+
+// ReLU under the multiplicative mask for one element (the three steps of relu_kernel below), n and t
+// fixed: x[] the n shares, r[] the n output shares
+template <int N, int T>
+__device__ __forceinline__ void relu_fixed(const u64 (&x)[N], size_t e, size_t count, size_t em, size_t mcount,
+                                           const u64 *__restrict__ sh_b, const u64 *__restrict__ sh_bi,
+                                           u64 *__restrict__ msg, u64 *__restrict__ yplain, const ss_nl_params &np,
+                                           u64 (&r)[N])
+{
+    constexpr int NR = 2 * T + 1;
+    u64 b[NR], bi[N];
+#pragma unroll
+    for (int i = 0; i < NR; i++) b[i] = sh_b[(size_t)i * count + e];
+#pragma unroll
+    for (int m = 0; m < N; m++) bi[m] = sh_bi[(size_t)m * count + e];
+    ss_sacc acc;
+    acc.clear();
+#pragma unroll
+    for (int i = 0; i < NR; i++) {
+        const u64 m = ss_mul(x[i], b[i]);
+        msg[(size_t)i * mcount + em] = m;
+        acc.mac(m, np.ilambda[i]);
+    }
+    const u64 v = np.dinv == 1 ? acc.value() : ss_mul(acc.value(), np.dinv);
+    const u64 y = v <= (SS_P - 1) / 2 ? v : 0;
+    yplain[em] = y;
+#pragma unroll
+    for (int m = 0; m < N; m++) r[m] = ss_mul(y, bi[m]);
+}
+
+// Linear - Truncation - NonLinear tail of a convolution layer in one launch (the order of Sec. VII-A):
+// reduction + RERAND + truncation of the product shares c [n][B][C][HW], then ReLU under the mask, the
+// result stored as shares and, if planes != nullptr, as channel-innermost limb planes for the next
+// convolution.  One element per thread, lanes arranged as in the share + planes kernel (lane l: pixel l%16,
+// channel 4 g + l/16 of the wave's group g).  The messages hold the values of the separate kernels, in the
+// order of this kernel's threads (so that a wave writes 512 consecutive bytes of every message plane): the
+// element of thread t of block (x, y) is at position (y gridDim.x + x) 256 + t of a plane of gridDim.x
+// gridDim.y 256 positions.
+template <int N, int T>
+__global__ __launch_bounds__(BLOCK) void layer_tail_kernel(const u64 *c, u64 *__restrict__ msg1, u64 *__restrict__ msg2,
+                                                           u64 *__restrict__ umsg, u64 *__restrict__ wsh,
+                                                           u64 *__restrict__ rmsg, u64 *__restrict__ yplain,
+                                                           const u64 *__restrict__ sh_b, const u64 *__restrict__ sh_bi,
+                                                           u64 *out, signed char *__restrict__ planes, int B, int C, int HW,
+                                                           size_t party_bytes, ss_dr_params dp, ss_tr_params tp,
+                                                           ss_nl_params np)
+{
+    const int lane = threadIdx.x & 63, r16 = lane & 15, j = lane >> 4;
+    const int pix = blockIdx.x * 16 + r16, c0 = blockIdx.y * 16 + 4 * (threadIdx.x >> 6);
+    const size_t count = (size_t)B * HW * C;
+    if (planes && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < N)
+        *reinterpret_cast<int4 *>(planes + threadIdx.x * party_bytes + 8 * count) = make_int4(0, 0, 0, 0);
+    const bool live = pix < B * HW && c0 + j < C;
+    u64 dig[N];
+#pragma unroll
+    for (int p = 0; p < N; p++) dig[p] = 0;
+    if (live) {
+        const int b = pix / HW, hw = pix - b * HW;
+        const size_t e = ((size_t)b * C + (c0 + j)) * HW + hw;
+        const size_t mcount = (size_t)gridDim.x * gridDim.y * BLOCK;
+        const size_t em = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * BLOCK + threadIdx.x;
+        u64 o[N], r[N];
+        reduce_truncate_fixed<N, T, true>(e, count, em, mcount, c, msg1, msg2, umsg, wsh, dp, tp, o);
+        relu_fixed<N, T>(o, e, count, em, mcount, sh_b, sh_bi, rmsg, yplain, np, r);
+#pragma unroll
+        for (int p = 0; p < N; p++) {
+            out[(size_t)p * count + e] = r[p];
+            dig[p] = balanced_digits(r[p]);
+        }
+    }
+    if (!planes) return;   // uniform
+#pragma unroll
+    for (int p = 0; p < N; p++) {
+        u64 y[4];
+#pragma unroll
+        for (int q = 0; q < 4; q++) y[q] = __shfl(dig[p], r16 + 16 * q);
+        if (live) {
+            u32 *bp = reinterpret_cast<u32 *>(planes + p * party_bytes + (size_t)pix * C + c0);
+            bp[(2 * j) * (count / 4)] = limb_dword(y, 2 * j);
+            bp[(2 * j + 1) * (count / 4)] = limb_dword(y, 2 * j + 1);
+        }
+    }
 }
 
 // Same computation for small tensors, where the serial work of one thread per
@@ -834,5 +932,23 @@ hipError_t ss_launch_reduce_truncate_direct(const u64 *c, u64 *out, u64 *rec, si
                     count >= VEC2_MIN_COUNT;
     auto grid = [&](int vec) { return dim3(blocks_for(count, vec)); };
     SS_DISPATCH_VEC(v2, reduce_truncate_direct_kernel, grid, c, out, rec, count, open_all, tp, rf);
+    return hipGetLastError();
+}
+
+hipError_t ss_launch_layer_tail(const u64 *c, u64 *msg1, u64 *msg2, u64 *umsg, u64 *wsh, u64 *rmsg, u64 *yplain,
+                                const u64 *sh_b, const u64 *sh_bi, u64 *out, void *planes, int B, int C, int HW,
+                                const ss_dr_params &dp, const ss_tr_params &tp, const ss_nl_params &np,
+                                hipStream_t stream)
+{
+    const dim3 grid((B * HW + 15) / 16, (C + 15) / 16), block(BLOCK);
+    const size_t party_bytes = (size_t)8 * B * HW * C + 256;
+    if (dp.n == 5 && dp.t == 2)
+        hipLaunchKernelGGL((layer_tail_kernel<5, 2>), grid, block, 0, stream, c, msg1, msg2, umsg, wsh, rmsg, yplain, sh_b,
+                           sh_bi, out, (signed char *)planes, B, C, HW, party_bytes, dp, tp, np);
+    else if (dp.n == 3 && dp.t == 1)
+        hipLaunchKernelGGL((layer_tail_kernel<3, 1>), grid, block, 0, stream, c, msg1, msg2, umsg, wsh, rmsg, yplain, sh_b,
+                           sh_bi, out, (signed char *)planes, B, C, HW, party_bytes, dp, tp, np);
+    else
+        return hipErrorInvalidValue;   // the caller runs the separate kernels for other schemes
     return hipGetLastError();
 }

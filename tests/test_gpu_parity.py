@@ -386,6 +386,50 @@ def test_conv_on_limb_planes(n, t):
     assert not s.planes_supported(1, 3, 8, 8) and not s.planes_supported(1, 96, 8, 8)
 
 
+@pytest.mark.parametrize("n,t", [(3, 1), (5, 2), (7, 3)])
+def test_layer_tail_in_one_launch(n, t):
+    """Reduction + RERAND + truncation + ReLU of a layer's product shares in one launch: output shares,
+    every message of the three protocols, and the limb planes (through the next convolution) against the
+    oracle's separate steps.  (7,3) takes the library's three-launch route behind the same entry point."""
+    s = SSNet(n, t, f=13, seed=63)
+    k, nr = t + 1, 2 * t + 1
+    for (B, C, H, W) in [(1, 64, 3, 5), (2, 128, 7, 7), (1, 20, 4, 4), (1, 64, 40, 40)]:
+        say("layer tail", n, t, B, C, H, W)
+        count = B * C * H * W
+        rng = np.random.default_rng(count)
+        xs = rng.integers(-(1 << 43), 1 << 43, count, dtype=np.int64)
+        c = orc.share(np.where(xs < 0, xs + P61, xs).astype(np.uint64), n, 2 * t if 2 * t < n else t, P61, 8, 0)
+        sb, sbi = s.nonlinear_masks((B, C, H, W), stream_id=21)
+        osb, osbi = orc.nonlinear_masks(count, n, t, 28, P61, 63, 21)
+        yr, m1, m2, _ = orc.degree_reduce(c, n, t, P61, 63, 5, full=True)
+        yt, u, wsh = orc.truncate(yr, n, t, 13, P61, 63, 5, full=True)
+        want, rmsg, yplain = orc.relu(yt, osb, osbi, n, t, P61, full=True)
+        d = to_dev(c.reshape(n, B, C, H, W))
+        out, planes = s.reduce_truncate_relu(d, 5, sb, sbi, out=d, want_planes=(C % 64 == 0))
+        assert np.array_equal(to_np(out).reshape(n, -1), want)
+        assert np.array_equal(orc.lift(orc.reconstruct(want, list(range(1, k + 1)), P61), P61), np.maximum(xs >> 13, 0))
+        # message planes of P positions; for the one-kernel schemes in the order of that kernel's threads
+        P = s.lib.ssnet_layer_tail_message_plane(s._ctx, B, C, H * W)
+        cc, pix = np.meshgrid(np.arange(C), np.arange(B * H * W), indexing="ij")
+        bb, hw = pix // (H * W), pix % (H * W)
+        elem = ((bb * C + cc) * (H * W) + hw).reshape(-1)
+        if (n, t) not in ((3, 1), (5, 2)):          # three launches, element order
+            assert P == count
+            pos = elem
+        else:
+            pos = (((cc // 16) * ((B * H * W + 15) // 16) + pix // 16) * 256 + (cc % 16 // 4) * 64 + (cc % 4) * 16
+                   + pix % 16).reshape(-1)
+        ws = to_np(s.messages()[: (nr * k + k * n + k + n + nr + 1) * P])
+        o = np.cumsum([0, nr * k, k * n, k, n, nr, 1]) * P
+        for got, ref in zip([ws[o[i]:o[i + 1]] for i in range(6)], (m1, m2, u, wsh, rmsg, yplain)):
+            got, ref = got.reshape(-1, P), ref.reshape(-1, count)
+            assert np.array_equal(got[:, pos], ref[:, elem])
+        if planes is not None:   # the planes feed a convolution: same result as the convolution on the shares
+            w = orc.share(field_uniform(9 * C * 9, 4).reshape(9, C, 3, 3), n, t, P61, 63, 6)
+            y = s.conv_mod_planes(planes, s.pack_weights_conv_taps(to_dev(w)), B, C, H, W, 9, 3, 3, 1, 1)
+            assert np.array_equal(to_np(y), orc.conv(want.reshape(n, B, C, H, W), w, 1, 1, P61))
+
+
 def test_config1_tiny_secure_gemm_end_to_end():
     """n=3, t=1, f=13, X 64x256 ~ N(0,1), W 256x128 ~ N(0,1): share, multiply,
     reduce, truncate, reconstruct, decode."""
