@@ -108,3 +108,37 @@ def test_generator_matches_golden_vectors():
     assert nkeys == 8 and ndraws == 32
     want = [int(l, 16) for l in open(os.path.join(ROOT, "tests", "golden", "splitmix64.txt")) if l.startswith("0x")]
     assert [binding.rng_draw(0, e) for e in range(3)] == want
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """every box has one GPU: bench.py --gpus N with N > 1 exits with a message, before touching a device"""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "one GPU" in (r.stderr + r.stdout)
+
+
+def test_new_entry_points_check_their_arguments():
+    lib = binding.load_library()
+    s = SSNet(5, 2, device=None)
+    ctx = s._ctx
+    # limb planes need a channel count that is a multiple of 64
+    assert lib.ssnet_conv_planes_bytes(1, 64, 8, 8) == 8 * 64 * 64 + 256
+    assert lib.ssnet_conv_planes_bytes(1, 3, 8, 8) == 0 and lib.ssnet_conv_planes_bytes(1, 96, 8, 8) == 0
+    assert lib.ssnet_share_planes(ctx, 16, 1, 3, 8, 8, 0, 16, 16) == binding.EINVAL
+    assert lib.ssnet_conv_mod_planes(ctx, 16, 16, 1, 64, 8, 8, 4, 3, 3, 1, 1, 16) == binding.EWORKSPACE
+    assert lib.ssnet_conv_mod_planes(ctx, 16, 16, 1, 64, 2, 2, 4, 3, 3, 1, 0, 16) == binding.EINVAL   # kernel > input
+    assert lib.ssnet_share_packed(ctx, 16, 0, 4, 4, 0, 16, 16) == binding.EINVAL
+    assert lib.ssnet_relu(ctx, 16, 16, 16, 0, 16) == binding.EINVAL
+    assert lib.ssnet_relu(ctx, 16, 16, 16, 100, 16) == binding.EWORKSPACE
+    assert lib.ssnet_nonlinear_masks(ctx, 0, 1, 16, 16) == binding.EINVAL
+    assert lib.ssnet_reduce_truncate_relu(ctx, 16, 1, 64, 16, 0, 16, 16, 16, 8) == binding.EINVAL    # misaligned planes
+    assert lib.ssnet_reduce_truncate_relu(ctx, 16, 1, 32, 16, 0, 16, 16, 16, 16) == binding.EINVAL   # planes need C % 64 == 0
+    assert lib.ssnet_reduce_truncate_relu(ctx, 16, 1, 32, 16, 0, 16, 16, 16, None) == binding.EWORKSPACE
+    # message planes of the one-launch layer tail count padded 16 x 16 blocks
+    assert lib.ssnet_layer_tail_message_plane(ctx, 1, 20, 17) == 2 * 2 * 256
+    s7 = SSNet(7, 3, device=None)
+    assert s7.lib.ssnet_layer_tail_message_plane(s7._ctx, 1, 20, 17) == 20 * 17
+    ids = (C.c_int * 3)(1, 1, 2)
+    assert lib.ssnet_reduce_truncate_direct(ctx, 16, 8, 0, 16, ids, 3, 16) == binding.EID
