@@ -23,7 +23,11 @@
  * convolution against numpy / torch int64 on small magnitudes, the
  * published SplitMix64 output sequence for the generator core, and for
  * SSS-NonLinear (ReLU under a multiplicative mask, Sec. VI-C) brute force over
- * every input and mask of a range in F_251 plus mask invariants at 2^61 - 1.
+ * every input and mask of a range in F_251 plus mask invariants at 2^61 - 1;
+ * for the pooled form torch's max_pool2d / avg_pool2d on the plain values and
+ * the constancy of beta inside a pooling kernel; for the truncation with the
+ * rounding division of App. C the printed worst case (error 2 for a 2x2
+ * kernel), its bound by brute force, and independence of the mask.
  * The choice of generator itself is not fixed by the paper ("randomly
  * generated", Sec. IV-A): parity unpinned for *which* random bits are drawn.
  */
@@ -622,4 +626,210 @@ void orc_relu(const u64 *x, const u64 *sh_b, const u64 *sh_bi, size_t count, int
         for (size_t e = 0; e < count; e++)
             out[(size_t)i * count + e] = orc_mul(v[e], sh_bi[(size_t)i * count + e], p);
     free(m); free(v);
+}
+
+/* ------------------------------------------------------------------ */
+/* Truncation followed by a rounding division (Sec. VI-C, the extra     */
+/* step for average pooling; App. C): y = [ floor(x / 2^f) / kdiv ],    */
+/* kdiv = kh*kw of the pooling kernel that follows.  The mask becomes   */
+/* alpha = e * 2^f * kdiv, alpha~ = -e stays.  [.] rounds to the        */
+/* nearest integer, a remainder of ceil(kdiv/2) or more going up (the   */
+/* worst case of App. C), i.e. [v/kdiv] = floor((v + floor(kdiv/2)) /   */
+/* kdiv) on the signed value, so that [(v + e*kdiv)/kdiv] = [v/kdiv]+e. */
+/* Arguments as orc_truncate_explicit.                                  */
+/* ------------------------------------------------------------------ */
+
+static i64 floor_div(i64 a, i64 b) /* b > 0 */
+{
+    i64 q = a / b;
+    return (a % b < 0) ? q - 1 : q;
+}
+
+void orc_truncate_div_explicit(const u64 *x, const u64 *eval, const u64 *ca, const u64 *cat, const u64 *cw,
+                               size_t count, int n, int t, int f, int kdiv, u64 p, u64 *u, u64 *wsh, u64 *out)
+{
+    int k = t + 1;
+    int ids[ORC_MAXN];
+    for (int q = 0; q < k; q++) ids[q] = q + 1;
+    u64 *alpha = (u64 *)malloc(sizeof(u64) * count);
+    u64 *alphat = (u64 *)malloc(sizeof(u64) * count);
+    u64 *sh_a = (u64 *)malloc(sizeof(u64) * (size_t)n * count);
+    u64 *sh_at = (u64 *)malloc(sizeof(u64) * (size_t)n * count);
+    u64 *v = (u64 *)malloc(sizeof(u64) * count);
+    u64 *ww = wsh ? wsh : (u64 *)malloc(sizeof(u64) * (size_t)n * count);
+    u64 *ufull = (u64 *)calloc((size_t)n * count, sizeof(u64));
+
+    /* trusted source: alpha = e * r * kh*kw, alpha~ = -e */
+    u64 rk = orc_mul(orc_pow(2 % p, (u64)f, p), (u64)kdiv % p, p);
+    for (size_t e = 0; e < count; e++) {
+        alpha[e] = orc_mul(eval[e] % p, rk, p);
+        alphat[e] = orc_sub(0, eval[e] % p, p);
+    }
+    orc_share_explicit(alpha, ca, count, n, t, p, sh_a);
+    orc_share_explicit(alphat, cat, count, n, t, p, sh_at);
+
+    for (int q = 0; q < k; q++)
+        for (size_t e = 0; e < count; e++) {
+            ufull[(size_t)q * count + e] = orc_add(x[(size_t)q * count + e], sh_a[(size_t)q * count + e], p);
+            if (u) u[(size_t)q * count + e] = ufull[(size_t)q * count + e];
+        }
+
+    /* elite party: REC, floor by 2^f, then the rounding division */
+    orc_reconstruct(ufull, count, ids, k, p, v);
+    for (size_t e = 0; e < count; e++) {
+        i64 s = orc_lift1(v[e], p) >> f;
+        v[e] = orc_from_signed(floor_div(s + kdiv / 2, kdiv), p);
+    }
+    orc_share_explicit(v, cw, count, n, t, p, ww);
+
+    for (int m = 0; m < n; m++)
+        for (size_t e = 0; e < count; e++)
+            out[(size_t)m * count + e] = orc_add(ww[(size_t)m * count + e], sh_at[(size_t)m * count + e], p);
+
+    free(alpha); free(alphat); free(sh_a); free(sh_at); free(v); free(ufull);
+    if (!wsh) free(ww);
+}
+
+/* same draws as orc_truncate: e uniform in [1, 2^(32-f)], the three coefficient domains */
+void orc_truncate_div(const u64 *x, size_t count, const u64 *eidx, int n, int t, int f, int kdiv, u64 p, u64 seed,
+                      u64 stream_id, u64 *u, u64 *wsh, u64 *out)
+{
+    u64 *eval = (u64 *)malloc(sizeof(u64) * count);
+    u64 *ca = (u64 *)malloc(sizeof(u64) * (size_t)t * count);
+    u64 *cat = (u64 *)malloc(sizeof(u64) * (size_t)t * count);
+    u64 *cw = (u64 *)malloc(sizeof(u64) * (size_t)t * count);
+    u64 key = orc_key(seed, ORC_DOM_MASK_E, stream_id, 0, 0);
+    for (size_t e = 0; e < count; e++)
+        eval[e] = 1 + (orc_draw(key, eidx ? eidx[e] : (u64)e) >> 3) % ((u64)1 << (32 - f));
+    orc_draw_coeffs(seed, ORC_DOM_MASK_ALPHA, stream_id, 0, t, count, eidx, p, ca);
+    orc_draw_coeffs(seed, ORC_DOM_MASK_ALPHAT, stream_id, 0, t, count, eidx, p, cat);
+    orc_draw_coeffs(seed, ORC_DOM_TRUNC_GEN, stream_id, 0, t, count, eidx, p, cw);
+    orc_truncate_div_explicit(x, eval, ca, cat, cw, count, n, t, f, kdiv, p, u, wsh, out);
+    free(eval); free(ca); free(cat); free(cw);
+}
+
+/* ------------------------------------------------------------------ */
+/* SSS-NonLinear with ReLU followed by pooling (Sec. VI-C).             */
+/*                                                                      */
+/* A tensor is `planes` images of H x W (planes = batch * channels).    */
+/* The pooling kernel is kh x kw, moved by (sh, sw) over the image      */
+/* padded with ph / pw zeros on each side:                              */
+/*   Ho = (H + 2 ph - kh) / sh + 1,  Wo likewise.                       */
+/* The mask beta must be equal inside one pooling kernel.  Where the    */
+/* kernels tile the image (stride = kernel, no padding) that is one     */
+/* beta per kernel position (elements right of / below the last full    */
+/* kernel join the last one); where kernels overlap, every element of   */
+/* a plane is linked to every other through shared kernels, so it is    */
+/* one beta per plane.  The group index is the counter of the beta      */
+/* draw.                                                                */
+/* ------------------------------------------------------------------ */
+
+typedef struct { int H, W, kh, kw, sh, sw, ph, pw, Ho, Wo, tiled; } orc_pool_geom;
+
+static orc_pool_geom pool_geom(int H, int W, int kh, int kw, int sh, int sw, int ph, int pw)
+{
+    orc_pool_geom g = {H, W, kh, kw, sh, sw, ph, pw, 0, 0, 0};
+    g.Ho = (H + 2 * ph - kh) / sh + 1;
+    g.Wo = (W + 2 * pw - kw) / sw + 1;
+    g.tiled = (sh == kh && sw == kw && ph == 0 && pw == 0);
+    return g;
+}
+
+static u64 pool_group_in(const orc_pool_geom *g, size_t plane, int h, int w)
+{
+    if (!g->tiled) return plane;
+    int oh = h / g->kh < g->Ho - 1 ? h / g->kh : g->Ho - 1;
+    int ow = w / g->kw < g->Wo - 1 ? w / g->kw : g->Wo - 1;
+    return ((u64)plane * g->Ho + oh) * g->Wo + ow;
+}
+
+static u64 pool_group_out(const orc_pool_geom *g, size_t plane, int oh, int ow)
+{
+    return g->tiled ? ((u64)plane * g->Ho + oh) * g->Wo + ow : (u64)plane;
+}
+
+int orc_pool_out_size(int H, int k, int s, int pad) { return (H + 2 * pad - k) / s + 1; }
+
+/* Trusted source: shares of beta for every input element [n][planes*H*W]
+ * and of beta^-1 for every pooled element [n][planes*Ho*Wo].  beta of a
+ * group is drawn at counter = group index (domain MASK_BETA), uniform in
+ * [1, 2^bbits]; the sharing coefficients are drawn per element (domains
+ * BETA_GEN at the input element's index, BETAINV_GEN at the pooled one's). */
+void orc_pool_masks(size_t planes, int H, int W, int kh, int kw, int sh, int sw, int ph, int pw, int n, int t,
+                    int bbits, u64 p, u64 seed, u64 stream_id, u64 *sh_b, u64 *sh_bi)
+{
+    orc_pool_geom g = pool_geom(H, W, kh, kw, sh, sw, ph, pw);
+    size_t cin = planes * (size_t)H * W, cout = planes * (size_t)g.Ho * g.Wo;
+    u64 *b = (u64 *)malloc(sizeof(u64) * cin);
+    u64 *bi = (u64 *)malloc(sizeof(u64) * cout);
+    u64 *cb = (u64 *)malloc(sizeof(u64) * (size_t)t * cin);
+    u64 *cbi = (u64 *)malloc(sizeof(u64) * (size_t)t * cout);
+    u64 key = orc_key(seed, ORC_DOM_MASK_BETA, stream_id, 0, 0);
+    for (size_t pl = 0; pl < planes; pl++) {
+        for (int h = 0; h < H; h++)
+            for (int w = 0; w < W; w++)
+                b[(pl * H + h) * W + w] = (1 + (orc_draw(key, pool_group_in(&g, pl, h, w)) >> 3) % ((u64)1 << bbits)) % p;
+        for (int oh = 0; oh < g.Ho; oh++)
+            for (int ow = 0; ow < g.Wo; ow++) {
+                u64 beta = (1 + (orc_draw(key, pool_group_out(&g, pl, oh, ow)) >> 3) % ((u64)1 << bbits)) % p;
+                bi[(pl * g.Ho + oh) * g.Wo + ow] = orc_inv(beta, p);
+            }
+    }
+    orc_draw_coeffs(seed, ORC_DOM_BETA_GEN, stream_id, 0, t, cin, NULL, p, cb);
+    orc_draw_coeffs(seed, ORC_DOM_BETAINV_GEN, stream_id, 0, t, cout, NULL, p, cbi);
+    orc_share_explicit(b, cb, cin, n, t, p, sh_b);
+    orc_share_explicit(bi, cbi, cout, n, t, p, sh_bi);
+    free(b); free(bi); free(cb); free(cbi);
+}
+
+/* The three steps, with pooling in the elite party's plain part:
+ *   1. parties 1..2t+1: m_i = x_i * beta_i                 -> msg [2t+1][planes*H*W]
+ *   2. elite party: v = REC(m) = x*beta elementwise; r = max(v, 0) on the
+ *      signed value; per kernel position the maximum (mode 0) or the sum
+ *      (mode 1; the division of an average has been done by the truncation
+ *      before) of r over the kernel's elements inside the image.  Padding
+ *      adds nothing to a sum and cannot win a maximum of non-negative values.
+ *                                                          -> yplain [planes*Ho*Wo]
+ *   3. every party: out_i = y * betainv_i                  -> out [n][planes*Ho*Wo]
+ * Requires kh*kw * |x| * beta < p/2. */
+void orc_relu_pool(const u64 *x, const u64 *sh_b, const u64 *sh_bi, size_t planes, int H, int W, int kh, int kw,
+                   int sh, int sw, int ph, int pw, int mode, int n, int t, u64 p, u64 *msg, u64 *yplain, u64 *out)
+{
+    orc_pool_geom g = pool_geom(H, W, kh, kw, sh, sw, ph, pw);
+    size_t cin = planes * (size_t)H * W, cout = planes * (size_t)g.Ho * g.Wo;
+    int nr = 2 * t + 1;
+    int ids[ORC_MAXN];
+    for (int i = 0; i < nr; i++) ids[i] = i + 1;
+    u64 *m = (u64 *)calloc((size_t)n * cin, sizeof(u64));
+    u64 *v = (u64 *)malloc(sizeof(u64) * cin);
+    u64 *y = (u64 *)malloc(sizeof(u64) * cout);
+    for (int i = 0; i < nr; i++)
+        for (size_t e = 0; e < cin; e++) {
+            m[(size_t)i * cin + e] = orc_mul(x[(size_t)i * cin + e], sh_b[(size_t)i * cin + e], p);
+            if (msg) msg[(size_t)i * cin + e] = m[(size_t)i * cin + e];
+        }
+    orc_reconstruct(m, cin, ids, nr, p, v);
+    for (size_t e = 0; e < cin; e++) {
+        i64 s = orc_lift1(v[e], p);
+        v[e] = s > 0 ? (u64)s : 0;
+    }
+    for (size_t pl = 0; pl < planes; pl++)
+        for (int oh = 0; oh < g.Ho; oh++)
+            for (int ow = 0; ow < g.Wo; ow++) {
+                u64 acc = 0;
+                for (int i = 0; i < kh; i++)
+                    for (int j = 0; j < kw; j++) {
+                        int h = oh * sh - ph + i, w = ow * sw - pw + j;
+                        if (h < 0 || h >= H || w < 0 || w >= W) continue;
+                        u64 r = v[(pl * H + h) * W + w];
+                        if (mode == 0) acc = r > acc ? r : acc;
+                        else acc += r;
+                    }
+                y[(pl * g.Ho + oh) * g.Wo + ow] = acc % p;
+            }
+    if (yplain) memcpy(yplain, y, sizeof(u64) * cout);
+    for (int i = 0; i < n; i++)
+        for (size_t e = 0; e < cout; e++)
+            out[(size_t)i * cout + e] = orc_mul(y[e], sh_bi[(size_t)i * cout + e], p);
+    free(m); free(v); free(y);
 }

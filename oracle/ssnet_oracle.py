@@ -272,3 +272,63 @@ def relu(x, sh_b, sh_bi, n, t, p, full=False):
     out = np.empty(x.shape, np.uint64)
     _relu(_p(x), _p(sh_b), _p(sh_bi), count, n, t, p, _p(msg), _p(y), _p(out))
     return (out, msg, y) if full else out
+
+
+# ---- truncation with the rounding division of an average pooling (Sec. VI-C, App. C) ----
+_trd_explicit = _sig("orc_truncate_div_explicit", None, P, P, P, P, P, sz, C.c_int, C.c_int, C.c_int, C.c_int, u64,
+                     P, P, P)
+_trd = _sig("orc_truncate_div", None, P, sz, P, C.c_int, C.c_int, C.c_int, C.c_int, u64, u64, u64, P, P, P)
+
+
+def truncate_div_explicit(x, evals, ca, cat, cw, n, t, f, kdiv, p, full=False):
+    x, evals, ca, cat, cw = _a(x), _a(evals), _a(ca), _a(cat), _a(cw)
+    count = x[0].size
+    u = np.empty((t + 1, count), np.uint64)
+    wsh = np.empty((n, count), np.uint64)
+    out = np.empty((n,) + x.shape[1:], np.uint64)
+    _trd_explicit(_p(x), _p(evals), _p(ca), _p(cat), _p(cw), count, n, t, f, kdiv, p, _p(u), _p(wsh), _p(out))
+    return (out, u, wsh) if full else out
+
+
+def truncate_div(x, n, t, f, kdiv, p, seed, stream_id, eidx=None, full=False):
+    x = _a(x)
+    eidx = None if eidx is None else _a(eidx)
+    count = x[0].size
+    u = np.empty((t + 1, count), np.uint64) if full else None
+    wsh = np.empty((n, count), np.uint64) if full else None
+    out = np.empty((n,) + x.shape[1:], np.uint64)
+    _trd(_p(x), count, _p(eidx), n, t, f, kdiv, p, seed, stream_id, _p(u), _p(wsh), _p(out))
+    return (out, u, wsh) if full else out
+
+
+# ---- SSS-NonLinear with pooling ----
+_pool_out = _sig("orc_pool_out_size", C.c_int, C.c_int, C.c_int, C.c_int, C.c_int)
+_pool_masks = _sig("orc_pool_masks", None, sz, *([C.c_int] * 8), C.c_int, C.c_int, C.c_int, u64, u64, u64, P, P)
+_relu_pool = _sig("orc_relu_pool", None, P, P, P, sz, *([C.c_int] * 8), C.c_int, C.c_int, C.c_int, u64, P, P, P)
+
+POOL_MAX, POOL_SUM = 0, 1
+
+
+def pool_out_size(H, k, s, pad):
+    return _pool_out(H, k, s, pad)
+
+
+def pool_masks(planes, H, W, kh, kw, sh, sw, ph, pw, n, t, bbits, p, seed, stream_id):
+    """-> (shares of beta [n, planes*H*W], shares of beta^-1 [n, planes*Ho*Wo])"""
+    Ho, Wo = _pool_out(H, kh, sh, ph), _pool_out(W, kw, sw, pw)
+    sb, sbi = np.empty((n, planes * H * W), np.uint64), np.empty((n, planes * Ho * Wo), np.uint64)
+    _pool_masks(planes, H, W, kh, kw, sh, sw, ph, pw, n, t, bbits, p, seed, stream_id, _p(sb), _p(sbi))
+    return sb, sbi
+
+
+def relu_pool(x, sh_b, sh_bi, planes, H, W, kh, kw, sh, sw, ph, pw, mode, n, t, p, full=False):
+    """x [n, planes*H*W] -> out [n, planes*Ho*Wo] (with full: the masked products and the plain result)"""
+    x, sh_b, sh_bi = _a(x), _a(sh_b), _a(sh_bi)
+    Ho, Wo = _pool_out(H, kh, sh, ph), _pool_out(W, kw, sw, pw)
+    cin, cout = planes * H * W, planes * Ho * Wo
+    assert x.size == n * cin and sh_b.size == n * cin and sh_bi.size == n * cout
+    msg = np.empty((2 * t + 1, cin), np.uint64) if full else None
+    y = np.empty(cout, np.uint64) if full else None
+    out = np.empty((n, cout), np.uint64)
+    _relu_pool(_p(x), _p(sh_b), _p(sh_bi), planes, H, W, kh, kw, sh, sw, ph, pw, mode, n, t, p, _p(msg), _p(y), _p(out))
+    return (out, msg, y) if full else out

@@ -572,3 +572,119 @@ def test_relu_seeded_masks_mersenne61():
         assert np.array_equal(orc.reconstruct(out, ids, P61).astype(np.int64), np.maximum(xs, 0))
     # degree of the result stays t: k = 3 shares determine the other two
     assert np.array_equal(orc.reconstruct(out, [1, 2, 3], P61), orc.reconstruct(out, [3, 4, 5], P61))
+
+
+# ----------------------------------------------------------------- truncation with rounding division (Sec. VI-C, App. C)
+def _round_half_up(a, b):
+    """nearest integer to a/b for b > 0, halves going up, with Python's exact rationals"""
+    fr = Fraction(a, b)
+    lo = fr.numerator // fr.denominator
+    return lo + 1 if fr - lo >= Fraction(1, 2) else lo
+
+
+@pytest.mark.parametrize("n,t", [(3, 1), (5, 2)])
+def test_truncate_div_is_rounding_division_whatever_the_mask(n, t):
+    """y = [floor(x / 2^f) / kdiv] for every x of a signed range, every kdiv of the usual pooling
+    kernels and several e: the opened result never depends on e, and kdiv = 1 is the plain truncation."""
+    p, f = P61, 3
+    rng = random.Random(3)
+    xs = list(range(-700, 701))
+    count = len(xs)
+    x_sh = orc.share(np.array([x % p for x in xs], np.uint64), n, t, p, 5, 1)
+    coefs = [np.array([[rng.randrange(p) for _ in range(count)] for _ in range(t)], np.uint64) for _ in range(3)]
+    for kdiv in (1, 4, 9, 49):
+        want = [_round_half_up(x >> f, kdiv) for x in xs]
+        for evals in ([1] * count, [rng.randrange(1, 1 << 19) for _ in range(count)]):
+            out, u, wsh = orc.truncate_div_explicit(x_sh, np.array(evals, np.uint64), *coefs, n, t, f, kdiv, p, full=True)
+            for ids in ([1, 2, 3][:t + 1], list(range(n - t, n + 1))):
+                got = orc.lift(orc.reconstruct(out, ids, p), p)
+                assert [int(v) for v in got] == want, (kdiv, ids)
+            # what the elite party opens is x + e * 2^f * kdiv, what it re-shares is the result + e
+            opened = orc.reconstruct(np.vstack([u, np.zeros((n - t - 1, count), np.uint64)]), list(range(1, t + 2)), p)
+            assert [int(v) for v in opened] == [(x + e * (1 << f) * kdiv) % p for x, e in zip(xs, evals)]
+            shared = orc.reconstruct(wsh, list(range(1, t + 2)), p)
+            assert [int(v) for v in shared] == [(w + e) % p for w, e in zip(want, evals)]
+        if kdiv == 1:
+            assert np.array_equal(out, orc.truncate_explicit(x_sh, np.array(evals, np.uint64), *coefs, n, t, f, p))
+    # seeded form: kdiv = 1 draws the same masks as the plain truncation
+    assert np.array_equal(orc.truncate_div(x_sh, n, t, f, 1, p, 5, 2), orc.truncate(x_sh, n, t, f, p, 5, 2))
+    got = orc.lift(orc.reconstruct(orc.truncate_div(x_sh, n, t, f, 4, p, 5, 2), [1, 2, 3][:t + 1], p), p)
+    assert [int(v) for v in got] == [_round_half_up(x >> f, 4) for x in xs]
+
+
+def test_avgpool_fold_worst_case_and_bound_appendix_c():
+    """App. C: with every element of a 2x2 kernel equal to g*4 + 2 the folded form gives (g+1)*4
+    against the true 4g + 2: off by exactly 2; and over every 2x2 kernel of a small range the
+    sum of rounded quarters is never further than 2 from the rounded mean.  Run through the
+    oracle: truncation with kdiv = 4 (f = 0 keeps the values), then ReLU + sum pooling."""
+    n, t, p = 3, 1, P61
+    vals = list(range(-3, 10))
+    kernels = list(itertools.product(vals, repeat=4))
+    kernels += [(g * 4 + 2,) * 4 for g in range(0, 50)]            # the printed worst case
+    planes = len(kernels)
+    x = np.array([[v % p for v in ker] for ker in kernels], np.uint64)          # [planes, 2*2]
+    x_sh = orc.share(x.reshape(-1), n, t, p, 9, 1)
+    q_sh = orc.truncate_div(x_sh, n, t, 0, 4, p, 9, 2)
+    sb, sbi = orc.pool_masks(planes, 2, 2, 2, 2, 2, 2, 0, 0, n, t, 28, p, 9, 3)
+    out = orc.relu_pool(q_sh, sb, sbi, planes, 2, 2, 2, 2, 2, 2, 0, 0, orc.POOL_SUM, n, t, p)
+    folded = [int(v) for v in orc.lift(orc.reconstruct(out, [2, 3], p), p)]
+    worst = 0
+    for ker, got in zip(kernels, folded):
+        true = _round_half_up(sum(max(v, 0) for v in ker), 4)
+        assert got == sum(max(_round_half_up(v, 4), 0) for v in ker)
+        worst = max(worst, abs(got - true))
+        if len(set(ker)) == 1 and ker[0] % 4 == 2 and ker[0] > 0:
+            assert got - ker[0] == 2 and true == ker[0]
+    assert worst == 2
+
+
+# ----------------------------------------------------------------- SSS-NonLinear with pooling (Sec. VI-C)
+@pytest.mark.parametrize("geom", [
+    (6, 6, 2, 2, 2, 2, 0, 0),      # 2x2 / 2: kernels tile the image
+    (7, 5, 2, 2, 2, 2, 0, 0),      # ragged right and bottom edges
+    (9, 9, 3, 3, 2, 2, 1, 1),      # 3x3 / 2, padding 1: overlapping kernels (the ResNet stem)
+    (7, 7, 7, 7, 7, 7, 0, 0),      # global pooling
+    (8, 6, 3, 2, 1, 2, 0, 1),      # unequal kernel, stride and padding per axis
+])
+@pytest.mark.parametrize("n,t", [(3, 1), (5, 2)])
+def test_relu_pool_against_torch_and_mask_constancy(geom, n, t):
+    import torch
+    H, W, kh, kw, sh, sw, ph, pw = geom
+    p, planes, seed = P61, 5, 21
+    Ho, Wo = (H + 2 * ph - kh) // sh + 1, (W + 2 * pw - kw) // sw + 1
+    assert (orc.pool_out_size(H, kh, sh, ph), orc.pool_out_size(W, kw, sw, pw)) == (Ho, Wo)
+    rng = np.random.default_rng(4)
+    xs = rng.integers(-(1 << 20), 1 << 20, (planes, H, W), dtype=np.int64)
+    xs[0, 0, :3] = [0, -1, 1]
+    x_sh = orc.share(np.where(xs < 0, xs + p, xs).astype(np.uint64).reshape(-1), n, t, p, seed, 1)
+    sb, sbi = orc.pool_masks(planes, H, W, kh, kw, sh, sw, ph, pw, n, t, 28, p, seed, 2)
+    # the masks: beta in [1, 2^28], equal inside every pooling kernel, and the pooled element's
+    # beta^-1 inverts the beta of its kernel
+    beta = np.array([int(v) for v in orc.reconstruct(sb, list(range(1, t + 2)), p)], object).reshape(planes, H, W)
+    binv = np.array([int(v) for v in orc.reconstruct(sbi, list(range(n - t, n + 1)), p)], object).reshape(planes, Ho, Wo)
+    assert beta.min() >= 1 and beta.max() <= 1 << 28
+    for pl in range(planes):
+        for oh in range(Ho):
+            for ow in range(Wo):
+                win = [beta[pl, h, w] for h in range(oh * sh - ph, oh * sh - ph + kh)
+                       for w in range(ow * sw - pw, ow * sw - pw + kw) if 0 <= h < H and 0 <= w < W]
+                assert len(set(win)) == 1 and win[0] * binv[pl, oh, ow] % p == 1
+    tiled = (sh, sw, ph, pw) == (kh, kw, 0, 0)
+    distinct = len(set(beta.reshape(-1)))
+    assert distinct == (planes * Ho * Wo if tiled else planes)          # no coarser than needed
+    # the share polynomials differ from element to element even where beta is equal
+    assert len(set(int(v) for v in sb[0])) == planes * H * W
+    xt = torch.from_numpy(xs).clamp(min=0).to(torch.float64)[None]
+    want_max = torch.nn.functional.max_pool2d(xt, (kh, kw), (sh, sw), (ph, pw))[0].to(torch.int64).numpy()
+    want_sum = (torch.nn.functional.avg_pool2d(xt, (kh, kw), (sh, sw), (ph, pw), count_include_pad=True)[0]
+                * (kh * kw)).round().to(torch.int64).numpy()
+    for mode, want in ((orc.POOL_MAX, want_max), (orc.POOL_SUM, want_sum)):
+        out, msg, y = orc.relu_pool(x_sh, sb, sbi, planes, H, W, kh, kw, sh, sw, ph, pw, mode, n, t, p, full=True)
+        for ids in (list(range(1, t + 2)), list(range(n - t, n + 1))):
+            got = orc.lift(orc.reconstruct(out, ids, p), p).reshape(planes, Ho, Wo)
+            assert np.array_equal(got, want), (mode, ids)
+        # messages: products of the shares; the plain result is the pooled value times its kernel's beta
+        assert all(int(msg[i, e]) == int(x_sh[i, e]) * int(sb[i, e]) % p
+                   for i in range(2 * t + 1) for e in range(0, planes * H * W, 7))
+        b_out = np.array([pow(int(v), -1, p) for v in binv.reshape(-1)], object)
+        assert [int(v) for v in y] == [int(w) * int(b) for w, b in zip(want.reshape(-1), b_out)]
