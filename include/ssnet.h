@@ -182,6 +182,18 @@ int ssnet_degree_reduce(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint6
  * d_out may alias d_x. */
 int ssnet_truncate(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, uint64_t stream_id, uint64_t *d_out);
 
+/* SSS-Truncation followed by the rounding division that average pooling moves
+ * into it (Sec. VI-C, extra step for AvgPooling; App. C): shares of
+ * [floor(x / 2^f) / kdiv], kdiv = kh*kw of the pooling kernel that follows, so
+ * that the pooling itself is a sum.  The mask becomes alpha = e*2^f*kdiv with
+ * the same e and the same draws as ssnet_truncate; [.] rounds to the nearest
+ * integer, a remainder of ceil(kdiv/2) or more going up, on the signed value.
+ * 1 <= kdiv <= SSNET_MAX_KDIV; kdiv = 1 is ssnet_truncate.  Requires
+ * |x| + 2^32 * kdiv <= (p-1)/2.  Everything else as ssnet_truncate. */
+#define SSNET_MAX_KDIV 4096
+int ssnet_truncate_div(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, int kdiv, uint64_t stream_id,
+                       uint64_t *d_out);
+
 /* SSS-Linear's reduction followed at once by SSS-Truncation (the default layer
  * order Linear - Truncation of Sec. VII-A): the result, every message and every
  * random draw are those of ssnet_degree_reduce(stream_id) followed by
@@ -190,6 +202,11 @@ int ssnet_truncate(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, uint64_t s
  * (truncation).  d_out may alias d_c. */
 int ssnet_degree_reduce_truncate(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id,
                                  uint64_t *d_out);
+
+/* ssnet_degree_reduce(stream_id) followed by ssnet_truncate_div(kdiv, stream_id)
+ * in one launch; workspace as for ssnet_degree_reduce_truncate. */
+int ssnet_degree_reduce_truncate_div(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, int kdiv, uint64_t stream_id,
+                                     uint64_t *d_out);
 
 /* The same launch followed, per element, by REC (Eq. 2) of the truncated shares
  * of the parties party_ids[0..m) (distinct IDs in 1..n, m >= t+1): d_out
@@ -233,6 +250,42 @@ int ssnet_reduce_truncate_direct(ssnet_ctx *ctx, const uint64_t *d_c, size_t cou
 int ssnet_nonlinear_masks(ssnet_ctx *ctx, size_t count, uint64_t stream_id, uint64_t *d_beta, uint64_t *d_betainv);
 int ssnet_relu(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_beta, const uint64_t *d_betainv, size_t count,
                uint64_t *d_out);
+
+/* SSS-NonLinear with ReLU followed by pooling (Sec. VI-C).  A tensor is `planes`
+ * images of H x W (planes = batch * channels, [n][planes][H][W]); the pooling
+ * kernel is kh x kw, moved by (sh, sw) over the image padded by ph / pw zeros
+ * on each side, Ho = (H + 2*ph - kh) / sh + 1 = ssnet_pool_out_size(H, kh, sh,
+ * ph) (0 for sizes that do not fit), Wo likewise.  Accepted: ph < kh, pw < kw,
+ * kh <= H + 2*ph, kw <= W + 2*pw, H, W <= 2^15, kh*kw <= SSNET_MAX_KDIV.
+ *   ssnet_pool_masks: the trusted source's masks.  beta is equal inside one
+ *     pooling kernel: where the kernels partition the image (stride = kernel, no
+ *     padding) one beta per kernel position, drawn at counter (plane*Ho + oh)*Wo
+ *     + ow (elements beyond the last full kernel join the last one); where they
+ *     overlap, one beta per plane, drawn at counter = plane (shared kernels link
+ *     every element of a plane to every other).  The sharing coefficients are
+ *     drawn per element.  d_beta [n][planes*H*W]; d_betainv [n][planes*Ho*Wo]
+ *     shares beta^-1 of the pooled element's kernel.  Domains as
+ *     ssnet_nonlinear_masks.
+ *   ssnet_relu_pool: 1. parties 1..2t+1 multiply their shares of x and beta;
+ *     2. the elite party reconstructs x*beta elementwise, applies max(., 0), and
+ *     pools in the clear: mode SSNET_POOL_MAX the maximum, SSNET_POOL_SUM the sum
+ *     over the kernel's elements inside the image (the division of an average is
+ *     done before, by ssnet_truncate_div with kdiv = kh*kw); 3. every party
+ *     multiplies the pooled plain value by its share of beta^-1.  d_out
+ *     [n][planes*Ho*Wo] is a degree-t sharing of the pooled max(x, 0).
+ *     Requires kh*kw * |x| * 2^SSNET_BETA_BITS < p/2 for the sum, |x| < 2^32 for
+ *     the maximum.  Workspace behind the header: the products [2t+1][planes*H*W],
+ *     the rectified plain values [planes*H*W], the pooled plain values
+ *     [planes*Ho*Wo]; ssnet_workspace_bytes_stream(max of the two counts) covers
+ *     it.  d_out may not alias d_x. */
+#define SSNET_POOL_MAX 0
+#define SSNET_POOL_SUM 1
+int ssnet_pool_out_size(int H, int k, int s, int pad);
+int ssnet_pool_masks(ssnet_ctx *ctx, size_t planes, int H, int W, int kh, int kw, int sh, int sw, int ph, int pw,
+                     uint64_t stream_id, uint64_t *d_beta, uint64_t *d_betainv);
+int ssnet_relu_pool(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_beta, const uint64_t *d_betainv,
+                    size_t planes, int H, int W, int kh, int kw, int sh, int sw, int ph, int pw, int mode,
+                    uint64_t *d_out);
 
 /* The tail of a convolution layer in the default order Linear - Truncation -
  * NonLinear (Sec. VII-A) in one launch: ssnet_degree_reduce_truncate(stream_id)

@@ -57,6 +57,11 @@ SIGNATURES = {
     "ssnet_reduce_truncate_relu": (_int, [_ptr, _ptr, _int, _int, _int, _u64, _ptr, _ptr, _ptr, _ptr]),
     "ssnet_nonlinear_masks": (_int, [_ptr, _sz, _u64, _ptr, _ptr]),
     "ssnet_relu": (_int, [_ptr, _ptr, _ptr, _ptr, _sz, _ptr]),
+    "ssnet_truncate_div": (_int, [_ptr, _ptr, _sz, _int, _u64, _ptr]),
+    "ssnet_degree_reduce_truncate_div": (_int, [_ptr, _ptr, _sz, _int, _u64, _ptr]),
+    "ssnet_pool_out_size": (_int, [_int, _int, _int, _int]),
+    "ssnet_pool_masks": (_int, [_ptr, _sz] + [_int] * 8 + [_u64, _ptr, _ptr]),
+    "ssnet_relu_pool": (_int, [_ptr, _ptr, _ptr, _ptr, _sz] + [_int] * 9 + [_ptr]),
     "ssnet_rng_key": (_u64, [_u64] * 5),
     "ssnet_rng_draw": (_u64, [_u64, _u64]),
     "ssnet_rng_field": (_u64, [_u64, _u64]),
@@ -379,6 +384,26 @@ class SSNet:
                  "ssnet_degree_reduce_truncate")
         return out
 
+    def truncate_div(self, x: torch.Tensor, kdiv: int, stream_id: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        _check_i64(x, "x")
+        count = x[0].numel()
+        self.reserve(self.workspace_bytes_stream(count))
+        if out is None:
+            out = torch.empty_like(x)
+        self._ok(self.lib.ssnet_truncate_div(self._ctx, _dptr(x), count, kdiv, stream_id, _dptr(out)), "ssnet_truncate_div")
+        return out
+
+    def degree_reduce_truncate_div(self, c: torch.Tensor, kdiv: int, stream_id: int,
+                                   out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        _check_i64(c, "c")
+        count = c[0].numel()
+        self.reserve(self.workspace_bytes_stream(count))
+        if out is None:
+            out = torch.empty_like(c)
+        self._ok(self.lib.ssnet_degree_reduce_truncate_div(self._ctx, _dptr(c), count, kdiv, stream_id, _dptr(out)),
+                 "ssnet_degree_reduce_truncate_div")
+        return out
+
     def degree_reduce_truncate_reconstruct(self, c: torch.Tensor, stream_id: int, ids: Sequence[int],
                                            out: Optional[torch.Tensor] = None,
                                            secret: Optional[torch.Tensor] = None):
@@ -457,6 +482,45 @@ class SSNet:
         if out is None:
             out = torch.empty_like(x)
         self._ok(self.lib.ssnet_relu(self._ctx, _dptr(x), _dptr(beta), _dptr(betainv), count, _dptr(out)), "ssnet_relu")
+        return out
+
+    POOL_MAX, POOL_SUM = 0, 1
+
+    def pool_out_size(self, H: int, k: int, s: int, pad: int) -> int:
+        return self.lib.ssnet_pool_out_size(H, k, s, pad)
+
+    def pool_masks(self, planes: int, H: int, W: int, kernel, stride, pad, stream_id: int, device=None):
+        """-> (shares of beta [n, planes, H, W], shares of beta^-1 [n, planes, Ho, Wo]); offline preprocessing"""
+        (kh, kw), (sh, sw), (ph, pw) = kernel, stride, pad
+        Ho, Wo = self.pool_out_size(H, kh, sh, ph), self.pool_out_size(W, kw, sw, pw)
+        if Ho < 1 or Wo < 1:
+            raise SSNetError(EINVAL, "pool_masks: the pooling kernel does not fit the image")
+        device = device or self.device or "cuda"
+        b = torch.empty((self.n, planes, H, W), dtype=torch.int64, device=device)
+        bi = torch.empty((self.n, planes, Ho, Wo), dtype=torch.int64, device=device)
+        self._ok(self.lib.ssnet_pool_masks(self._ctx, planes, H, W, kh, kw, sh, sw, ph, pw, stream_id, _dptr(b), _dptr(bi)),
+                 "ssnet_pool_masks")
+        return b, bi
+
+    def relu_pool(self, x: torch.Tensor, beta: torch.Tensor, betainv: torch.Tensor, kernel, stride, pad, mode: int,
+                  out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """x [n, ..., H, W] -> shares of the pooled max(x, 0), [n, ..., Ho, Wo]"""
+        _check_i64(x, "x")
+        _check_i64(beta, "beta")
+        _check_i64(betainv, "betainv")
+        (kh, kw), (sh, sw), (ph, pw) = kernel, stride, pad
+        H, W = x.shape[-2], x.shape[-1]
+        planes = x[0].numel() // (H * W)
+        Ho, Wo = self.pool_out_size(H, kh, sh, ph), self.pool_out_size(W, kw, sw, pw)
+        if Ho < 1 or Wo < 1 or beta.numel() != x.numel() or betainv.numel() != self.n * planes * Ho * Wo:
+            raise SSNetError(EINVAL, "relu_pool: mask shares do not fit x and the pooling kernel")
+        self.reserve(self.workspace_bytes_stream(max(planes * H * W, planes * Ho * Wo)))
+        if out is None:
+            out = torch.empty(tuple(x.shape[:-2]) + (Ho, Wo), dtype=torch.int64, device=x.device)
+        elif out.numel() != self.n * planes * Ho * Wo:
+            raise SSNetError(EINVAL, "relu_pool: out has the wrong size")
+        self._ok(self.lib.ssnet_relu_pool(self._ctx, _dptr(x), _dptr(beta), _dptr(betainv), planes, H, W, kh, kw, sh, sw,
+                                          ph, pw, mode, _dptr(out)), "ssnet_relu_pool")
         return out
 
     PROF_CLASSES = ("share", "reconstruct", "pack_w", "pack_x", "gemm", "degree_reduce", "truncate", "nonlinear")

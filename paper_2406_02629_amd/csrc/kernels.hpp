@@ -32,6 +32,7 @@ struct ss_dr_params {             // RED + RERAND constants
 
 struct ss_tr_params {             // truncation constants
     int n, t, f;
+    int kdiv;                     // > 1: rounding division by kdiv after the shift (average pooling, Sec. VI-C)
     u64 e_key;
     u64 alpha_key[SS_MAXT], alphat_key[SS_MAXT], gen_key[SS_MAXT];
     int ilambda[SS_MAXK];
@@ -48,6 +49,14 @@ struct ss_nl_params {             // SSS-NonLinear
     u64 bgen_key[SS_MAXT], bigen_key[SS_MAXT];   // coefficients of [[beta]], [[beta^-1]]
     int ilambda[2 * SS_MAXT + 1]; // REC from the IDs 1..2t+1 (integers: (-1)^(i-1) C(2t+1, i))
     u64 dinv;
+};
+
+// Pooling kernel kh x kw moved by (sh, sw) over planes of H x W padded by ph / pw zeros (Sec. VI-C).
+// tiled: the kernels partition the plane, one beta per kernel position; otherwise one beta per plane.
+struct ss_pool_geom {
+    int H, W, kh, kw, sh, sw, ph, pw, Ho, Wo;
+    int tiled;
+    int mode;                     // 0: maximum, 1: sum
 };
 
 // ---- streaming family (stream_kernels.hip) ----
@@ -72,6 +81,15 @@ hipError_t ss_launch_reduce_truncate_direct(const u64 *c, u64 *out, u64 *rec, si
 hipError_t ss_launch_nonlinear_masks(u64 *sh_b, u64 *sh_bi, size_t count, const ss_nl_params &np, hipStream_t stream);
 hipError_t ss_launch_relu(const u64 *x, const u64 *sh_b, const u64 *sh_bi, u64 *msg, u64 *yplain, u64 *out,
                           size_t count, const ss_nl_params &np, hipStream_t stream);
+
+// the same with pooling: masks equal inside a pooling kernel (sh_b [n][planes*H*W], sh_bi [n][planes*Ho*Wo]);
+// ReLU under the mask elementwise (msg [2t+1][planes*H*W], rplain [planes*H*W]), then pooling in the clear
+// and the mask-off (yplain [planes*Ho*Wo], out [n][planes*Ho*Wo])
+hipError_t ss_launch_pool_masks(u64 *sh_b, u64 *sh_bi, size_t planes, const ss_pool_geom &g, const ss_nl_params &np,
+                                hipStream_t stream);
+hipError_t ss_launch_relu_pool(const u64 *x, const u64 *sh_b, const u64 *sh_bi, u64 *msg, u64 *rplain, u64 *yplain,
+                               u64 *out, size_t planes, const ss_pool_geom &g, const ss_nl_params &np,
+                               hipStream_t stream);
 
 // reduction + RERAND + truncation + ReLU of c [n][B][C][HW] in one launch, result as shares and (planes !=
 // nullptr) as limb planes; schemes (3,1) and (5,2) only (hipErrorInvalidValue otherwise, nothing launched)

@@ -467,7 +467,7 @@ int ssnet_conv1x1_mod_prepacked(ssnet_ctx *ctx, const void *d_x_packed, const vo
 
 namespace {
 
-bool planes_shape_ok(long B, long C, long H, long W)
+static bool planes_shape_ok(long B, long C, long H, long W)
 {
     return B >= 1 && C >= 64 && C % 64 == 0 && H >= 1 && W >= 1 && H < 32768 && W < 32768 && B * H * W < (1L << 30) &&
            B * H * W * C < (1L << 35);
@@ -582,7 +582,7 @@ int ssnet_conv_mod(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_w, int
 
 namespace {
 
-ss_dr_params make_dr_params(const ssnet_ctx *ctx, uint64_t stream_id)
+static ss_dr_params make_dr_params(const ssnet_ctx *ctx, uint64_t stream_id)
 {
     const int t = ctx->t, k = t + 1, nr = 2 * t + 1, n = ctx->n;
     ss_dr_params dp = {};
@@ -601,13 +601,14 @@ ss_dr_params make_dr_params(const ssnet_ctx *ctx, uint64_t stream_id)
     return dp;
 }
 
-ss_tr_params make_tr_params(const ssnet_ctx *ctx, uint64_t stream_id)
+static ss_tr_params make_tr_params(const ssnet_ctx *ctx, uint64_t stream_id)
 {
     const int t = ctx->t;
     ss_tr_params tp = {};
     tp.n = ctx->n;
     tp.t = t;
     tp.f = ctx->f;
+    tp.kdiv = 1;
     tp.e_key = ss_key(ctx->seed, SSNET_DOM_MASK_E, stream_id, 0, 0);
     for (int j = 1; j <= t; j++) {
         tp.alpha_key[j - 1] = ss_key(ctx->seed, SSNET_DOM_MASK_ALPHA, stream_id, 0, (u64)j);
@@ -632,25 +633,44 @@ int ssnet_degree_reduce(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint6
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
 
-int ssnet_truncate(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, uint64_t stream_id, uint64_t *d_out)
+namespace {
+
+static int truncate_by(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, int kdiv, uint64_t stream_id, uint64_t *d_out)
 {
-    if (!ctx || !d_x || !d_out || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
+    if (!ctx || !d_x || !d_out || count == 0 || count > MAX_COUNT || kdiv < 1 || kdiv > SSNET_MAX_KDIV)
+        return SSNET_EINVAL;
     const int k = ctx->t + 1, n = ctx->n;
     const size_t need = ((size_t)k + n) * count * 8;
     if (!ws_fits(ctx, need)) return SSNET_EWORKSPACE;
     u64 *u = (u64 *)ws_scratch(ctx), *wsh = u + (size_t)k * count;
+    ss_tr_params tp = make_tr_params(ctx, stream_id);
+    tp.kdiv = kdiv;
     timed tm(ctx, SSNET_PROF_TRUNCATE);
-    hipError_t e = ss_launch_truncate(d_x, u, wsh, d_out, count, make_tr_params(ctx, stream_id), ctx->stream);
+    hipError_t e = ss_launch_truncate(d_x, u, wsh, d_out, count, tp, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+}  // namespace
+
+int ssnet_truncate(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, uint64_t stream_id, uint64_t *d_out)
+{
+    return truncate_by(ctx, d_x, count, 1, stream_id, d_out);
+}
+
+int ssnet_truncate_div(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, int kdiv, uint64_t stream_id,
+                       uint64_t *d_out)
+{
+    return truncate_by(ctx, d_x, count, kdiv, stream_id, d_out);
 }
 
 namespace {
 
 // shared by the two fused entry points; d_rec == nullptr: no reconstruction
-int degree_reduce_truncate(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id, uint64_t *d_out,
-                           const int *party_ids, int m, uint64_t *d_rec)
+static int degree_reduce_truncate(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id, uint64_t *d_out,
+                           const int *party_ids, int m, uint64_t *d_rec, int kdiv = 1)
 {
-    if (!ctx || !d_c || !d_out || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
+    if (!ctx || !d_c || !d_out || count == 0 || count > MAX_COUNT || kdiv < 1 || kdiv > SSNET_MAX_KDIV)
+        return SSNET_EINVAL;
     ss_recf_params rf = {};
     if (d_rec) {
         if (!party_ids || m < 1 || m > ctx->n) return SSNET_EINVAL;
@@ -669,10 +689,11 @@ int degree_reduce_truncate(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, ui
     if (!ws_fits(ctx, need)) return SSNET_EWORKSPACE;
     u64 *msg1 = (u64 *)ws_scratch(ctx), *msg2 = msg1 + (size_t)nr * k * count;
     u64 *u = msg2 + (size_t)k * n * count, *wsh = u + (size_t)k * count;
+    ss_tr_params tp = make_tr_params(ctx, stream_id);
+    tp.kdiv = kdiv;
     timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
     hipError_t e = ss_launch_degree_reduce_truncate(d_c, msg1, msg2, u, wsh, d_out, d_rec, count,
-                                                    make_dr_params(ctx, stream_id), make_tr_params(ctx, stream_id), rf,
-                                                    ctx->stream);
+                                                    make_dr_params(ctx, stream_id), tp, rf, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
 
@@ -684,6 +705,12 @@ int ssnet_degree_reduce_truncate(ssnet_ctx *ctx, const uint64_t *d_c, size_t cou
     return degree_reduce_truncate(ctx, d_c, count, stream_id, d_out, nullptr, 0, nullptr);
 }
 
+int ssnet_degree_reduce_truncate_div(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, int kdiv, uint64_t stream_id,
+                                     uint64_t *d_out)
+{
+    return degree_reduce_truncate(ctx, d_c, count, stream_id, d_out, nullptr, 0, nullptr, kdiv);
+}
+
 int ssnet_degree_reduce_truncate_reconstruct(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id,
                                              uint64_t *d_out, const int *party_ids, int m, uint64_t *d_secret)
 {
@@ -693,7 +720,7 @@ int ssnet_degree_reduce_truncate_reconstruct(ssnet_ctx *ctx, const uint64_t *d_c
 
 namespace {
 
-bool make_nl_params(const ssnet_ctx *ctx, uint64_t stream_id, ss_nl_params *np)
+static bool make_nl_params(const ssnet_ctx *ctx, uint64_t stream_id, ss_nl_params *np)
 {
     *np = {};
     np->n = ctx->n;
@@ -740,7 +767,7 @@ namespace {
 
 // positions per message plane of the layer-tail call: the threads of its one-launch kernel (blocks of 16
 // pixels x 16 channels), or the elements themselves where the separate kernels run
-size_t tail_plane(const ssnet_ctx *ctx, int B, int C, int HW)
+static size_t tail_plane(const ssnet_ctx *ctx, int B, int C, int HW)
 {
     const bool fused = (ctx->n == 5 && ctx->t == 2) || (ctx->n == 3 && ctx->t == 1);
     return fused ? (size_t)((B * HW + 15) / 16) * ((C + 15) / 16) * 256 : (size_t)B * C * HW;
@@ -824,6 +851,61 @@ int ssnet_relu(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_beta, cons
     u64 *msg = (u64 *)ws_scratch(ctx), *yplain = msg + (size_t)nr * count;
     timed tm(ctx, SSNET_PROF_NONLINEAR);
     hipError_t e = ss_launch_relu(d_x, d_beta, d_betainv, msg, yplain, d_out, count, np, ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+namespace {
+
+// 0 if the pooling geometry is not acceptable
+static bool make_pool_geom(size_t planes, int H, int W, int kh, int kw, int sh, int sw, int ph, int pw, int mode,
+                    ss_pool_geom *g)
+{
+    if (planes < 1 || H < 1 || W < 1 || kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0) return false;
+    if (ph >= kh || pw >= kw || kh > H + 2 * ph || kw > W + 2 * pw) return false;   // every kernel meets the plane
+    if (H > (1 << 15) || W > (1 << 15) || (long)kh * kw > SSNET_MAX_KDIV || (mode != 0 && mode != 1)) return false;
+    *g = {H, W, kh, kw, sh, sw, ph, pw, (H + 2 * ph - kh) / sh + 1, (W + 2 * pw - kw) / sw + 1,
+          (sh == kh && sw == kw && ph == 0 && pw == 0) ? 1 : 0, mode};
+    const size_t cin = (size_t)H * W, cout = (size_t)g->Ho * g->Wo;
+    return planes <= MAX_COUNT / cin && planes <= MAX_COUNT / cout;
+}
+
+}  // namespace
+
+int ssnet_pool_out_size(int H, int k, int s, int pad)
+{
+    if (H < 1 || k < 1 || s < 1 || pad < 0 || k > H + 2 * pad) return 0;
+    return (H + 2 * pad - k) / s + 1;
+}
+
+int ssnet_pool_masks(ssnet_ctx *ctx, size_t planes, int H, int W, int kh, int kw, int sh, int sw, int ph, int pw,
+                     uint64_t stream_id, uint64_t *d_beta, uint64_t *d_betainv)
+{
+    ss_pool_geom g;
+    if (!ctx || !d_beta || !d_betainv || !make_pool_geom(planes, H, W, kh, kw, sh, sw, ph, pw, 0, &g))
+        return SSNET_EINVAL;
+    ss_nl_params np;
+    if (!make_nl_params(ctx, stream_id, &np)) return SSNET_EINVAL;
+    timed tm(ctx, SSNET_PROF_NONLINEAR);
+    hipError_t e = ss_launch_pool_masks(d_beta, d_betainv, planes, g, np, ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+int ssnet_relu_pool(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_beta, const uint64_t *d_betainv,
+                    size_t planes, int H, int W, int kh, int kw, int sh, int sw, int ph, int pw, int mode,
+                    uint64_t *d_out)
+{
+    ss_pool_geom g;
+    if (!ctx || !d_x || !d_beta || !d_betainv || !d_out ||
+        !make_pool_geom(planes, H, W, kh, kw, sh, sw, ph, pw, mode, &g))
+        return SSNET_EINVAL;
+    const int nr = 2 * ctx->t + 1;
+    const size_t cin = planes * H * W, cout = planes * g.Ho * g.Wo;
+    if (!ws_fits(ctx, ((size_t)(nr + 1) * cin + cout) * 8)) return SSNET_EWORKSPACE;
+    ss_nl_params np;
+    if (!make_nl_params(ctx, 0, &np)) return SSNET_EINVAL;
+    u64 *msg = (u64 *)ws_scratch(ctx), *rplain = msg + (size_t)nr * cin, *yplain = rplain + cin;
+    timed tm(ctx, SSNET_PROF_NONLINEAR);
+    hipError_t e = ss_launch_relu_pool(d_x, d_beta, d_betainv, msg, rplain, yplain, d_out, planes, g, np, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
 

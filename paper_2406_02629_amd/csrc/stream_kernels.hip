@@ -115,11 +115,23 @@ __device__ __forceinline__ u64 shift_signed(u64 v, int f)
     return qv >= 0 ? (u64)qv : SS_P - (u64)(-qv);
 }
 
+// The same followed by the rounding division that average pooling moves into the truncation (Sec. VI-C):
+// [q / kdiv] = floor((q + floor(kdiv/2)) / kdiv) on the signed quotient q, so that a remainder of
+// ceil(kdiv/2) or more goes up (the worst case of App. C) and [(q + e*kdiv) / kdiv] = [q / kdiv] + e.
+__device__ __forceinline__ u64 shift_round_div(u64 v, int f, int kdiv)
+{
+    const int64_t sv = (v <= (SS_P - 1) / 2) ? (int64_t)v : (int64_t)v - (int64_t)SS_P;
+    const int64_t a = (sv >> f) + kdiv / 2;
+    const u64 d = (u64)kdiv;
+    return a >= 0 ? (u64)a / d : SS_P - ((u64)(-a) + d - 1) / d;
+}
+
 // The three steps of masked truncation for the elements a thread owns, with
 // the same send-to-workspace / receive-from-registers convention as above:
 //   1. parties q = 1..k add their share of alpha = e * 2^f          -> umsg[q]
+//      (alpha = e * 2^f * kdiv with the rounding division)
 //   2. the elite party reconstructs x + alpha, divides by 2^f with floor on
-//      the signed value and shares the quotient                      -> wsh[m]
+//      the signed value (then by kdiv with rounding) and shares the quotient -> wsh[m]
 //   3. every party m adds its share of alpha~ = -e                   -> out[m]
 // x[q] holds the shares of parties q+1 = 1..k.  With rec != nullptr the new
 // shares are also reconstructed (REC, Eq. 2) with the multipliers rf   -> rec
@@ -143,7 +155,8 @@ __device__ __forceinline__ void truncate_steps(const pack_t<VEC> *x, u64 *__rest
             pack_t<VEC> s;
 #pragma unroll
             for (int u = 0; u < VEC; u++) {
-                s.v[u] = ss_add(x[q].v[u], ss_poly_eval<SS_MAXT>(ev[u] << tp.f, ca[u], tp.t, q + 1));
+                const u64 alpha = tp.kdiv > 1 ? (ev[u] * (u64)tp.kdiv) << tp.f : ev[u] << tp.f;   // < 2^47
+                s.v[u] = ss_add(x[q].v[u], ss_poly_eval<SS_MAXT>(alpha, ca[u], tp.t, q + 1));
                 acc[u].mac(s.v[u], tp.ilambda[q]);
             }
             s.store(umsg + (size_t)q * count + e0);
@@ -152,7 +165,7 @@ __device__ __forceinline__ void truncate_steps(const pack_t<VEC> *x, u64 *__rest
     u64 w[VEC], at[VEC], cw[VEC][SS_MAXT], cat[VEC][SS_MAXT];
 #pragma unroll
     for (int u = 0; u < VEC; u++) {
-        w[u] = shift_signed(acc[u].value(), tp.f);
+        w[u] = tp.kdiv > 1 ? shift_round_div(acc[u].value(), tp.f, tp.kdiv) : shift_signed(acc[u].value(), tp.f);
         at[u] = SS_P - ev[u];
         draw_coeffs<SS_MAXT>(cw[u], tp.gen_key, tp.t, e0 + u);
         draw_coeffs<SS_MAXT>(cat[u], tp.alphat_key, tp.t, e0 + u);
@@ -719,17 +732,27 @@ __global__ __launch_bounds__(BLOCK) void reduce_truncate_direct_kernel(const u64
 // What the trusted source prepares ahead of the inference (Sec. VII-B): a positive
 // mask beta per element, its inverse in F_p (Fermat: beta^(p-2), p - 2 = 2^61 - 3)
 // and a degree-t sharing of each.  One thread per element.
+__device__ __forceinline__ u64 mask_beta(const ss_nl_params &np, u64 counter)
+{
+    return 1 + ((ss_draw(np.beta_key, counter) >> 3) & ((1ULL << np.bbits) - 1));
+}
+
+__device__ __forceinline__ u64 field_inverse(u64 beta)
+{
+    // beta^(2^61 - 3): the exponent is 59 one bits, then 0, then 1
+    u64 inv = beta;
+    for (int i = 0; i < 58; i++) inv = ss_mul(ss_mul(inv, inv), beta);   // beta^(2^59 - 1)
+    inv = ss_mul(inv, inv);                                              // bit 1 of the exponent is 0
+    return ss_mul(ss_mul(inv, inv), beta);                               // bit 0 is 1
+}
+
 __global__ __launch_bounds__(BLOCK) void nonlinear_masks_kernel(u64 *__restrict__ sh_b, u64 *__restrict__ sh_bi,
                                                                 size_t count, ss_nl_params np)
 {
     const size_t e = (size_t)blockIdx.x * BLOCK + threadIdx.x;
     if (e >= count) return;
-    const u64 beta = 1 + ((ss_draw(np.beta_key, e) >> 3) & ((1ULL << np.bbits) - 1));
-    // beta^(2^61 - 3): the exponent is 59 one bits, then 0, then 1
-    u64 inv = beta;
-    for (int i = 0; i < 58; i++) inv = ss_mul(ss_mul(inv, inv), beta);   // beta^(2^59 - 1)
-    inv = ss_mul(inv, inv);                                              // bit 1 of the exponent is 0
-    inv = ss_mul(ss_mul(inv, inv), beta);                                // bit 0 is 1
+    const u64 beta = mask_beta(np, e);
+    const u64 inv = field_inverse(beta);
     u64 cb[SS_MAXT], cbi[SS_MAXT];
     draw_coeffs<SS_MAXT>(cb, np.bgen_key, np.t, e);
     draw_coeffs<SS_MAXT>(cbi, np.bigen_key, np.t, e);
@@ -748,7 +771,8 @@ __global__ __launch_bounds__(BLOCK) void nonlinear_masks_kernel(u64 *__restrict_
 //   2. elite party: REC of the 2t+1 products = x * beta; ReLU on the
 //      signed value, in the clear                                   -> yplain
 //   3. every party: out_i = y * betainv_i                            -> out[i]
-template <int VEC>
+// MASKOFF = false stops after step 2 (the pooled form continues from yplain in another kernel).
+template <int VEC, bool MASKOFF = true>
 __global__ __launch_bounds__(BLOCK) void relu_kernel(const u64 *x, const u64 *__restrict__ sh_b,
                                                      const u64 *__restrict__ sh_bi, u64 *__restrict__ msg,
                                                      u64 *__restrict__ yplain, u64 *out, size_t count,
@@ -768,7 +792,7 @@ __global__ __launch_bounds__(BLOCK) void relu_kernel(const u64 *x, const u64 *__
     }
 #pragma unroll
     for (int m = 0; m < SS_MAXN; m++)
-        if (m < np.n) binv[m].load(sh_bi + (size_t)m * count + e0);
+        if (MASKOFF && m < np.n) binv[m].load(sh_bi + (size_t)m * count + e0);
     ss_sacc acc[VEC];
 #pragma unroll
     for (int u = 0; u < VEC; u++) acc[u].clear();
@@ -793,13 +817,67 @@ __global__ __launch_bounds__(BLOCK) void relu_kernel(const u64 *x, const u64 *__
     y.store(yplain + e0);
 #pragma unroll
     for (int m = 0; m < SS_MAXN; m++) {
-        if (m < np.n) {
+        if (MASKOFF && m < np.n) {
             pack_t<VEC> o;
 #pragma unroll
             for (int u = 0; u < VEC; u++) o.v[u] = ss_mul(y.v[u], binv[m].v[u]);
             o.store(out + (size_t)m * count + e0);
         }
     }
+}
+
+// Masks for ReLU followed by pooling: beta has to be equal inside one pooling kernel.  Where the kernels
+// partition the plane a group is a kernel position (elements beyond the last full kernel join the last
+// one), otherwise the whole plane; beta is drawn at counter = group index.  The sharing coefficients are
+// drawn per element.  INV = false: one thread per input element, shares of beta; INV = true: one thread per
+// pooled element, shares of beta^-1 of its kernel's group.
+template <bool INV>
+__global__ __launch_bounds__(BLOCK) void pool_masks_kernel(u64 *__restrict__ sh, size_t count, ss_pool_geom g,
+                                                           ss_nl_params np)
+{
+    const size_t e = (size_t)blockIdx.x * BLOCK + threadIdx.x;
+    if (e >= count) return;
+    const int w = INV ? g.Wo : g.W, h = INV ? g.Ho : g.H;
+    const size_t plane = e / ((size_t)h * w);
+    const int r = (int)(e - plane * (size_t)h * w), row = r / w, col = r - row * w;
+    u64 group = plane;
+    if (g.tiled) {
+        const int oh = INV ? row : min(row / g.kh, g.Ho - 1), ow = INV ? col : min(col / g.kw, g.Wo - 1);
+        group = (plane * g.Ho + oh) * g.Wo + ow;
+    }
+    u64 secret = mask_beta(np, group);
+    if (INV) secret = field_inverse(secret);
+    u64 cf[SS_MAXT];
+    draw_coeffs<SS_MAXT>(cf, INV ? np.bigen_key : np.bgen_key, np.t, e);
+#pragma unroll
+    for (int m = 0; m < SS_MAXN; m++)
+        if (m < np.n) sh[(size_t)m * count + e] = ss_poly_eval<SS_MAXT>(secret, cf, np.t, m + 1);
+}
+
+// Pooling in the elite party's plain part of SSS-NonLinear and the mask-off (step 3), one thread per
+// pooled element: the maximum or the sum of the opened, rectified products r = max(x*beta, 0) over the
+// kernel's elements inside the plane (padding adds nothing to a sum and cannot win a maximum of
+// non-negative values), then y * betainv_m for every party.
+__global__ __launch_bounds__(BLOCK) void pool_maskoff_kernel(const u64 *__restrict__ rplain,
+                                                             const u64 *__restrict__ sh_bi, u64 *__restrict__ yplain,
+                                                             u64 *__restrict__ out, size_t count, ss_pool_geom g, int n)
+{
+    const size_t o = (size_t)blockIdx.x * BLOCK + threadIdx.x;
+    if (o >= count) return;
+    const size_t plane = o / ((size_t)g.Ho * g.Wo);
+    const int r = (int)(o - plane * (size_t)g.Ho * g.Wo), oh = r / g.Wo, ow = r - oh * g.Wo;
+    const u64 *src = rplain + plane * (size_t)g.H * g.W;
+    const int h0 = oh * g.sh - g.ph, w0 = ow * g.sw - g.pw;
+    u64 acc = 0;
+    for (int i = max(0, -h0); i < min(g.kh, g.H - h0); i++)
+        for (int j = max(0, -w0); j < min(g.kw, g.W - w0); j++) {
+            const u64 v = src[(size_t)(h0 + i) * g.W + (w0 + j)];
+            acc = g.mode == 0 ? (v > acc ? v : acc) : ss_add(acc, v);
+        }
+    yplain[o] = acc;
+#pragma unroll
+    for (int m = 0; m < SS_MAXN; m++)
+        if (m < n) out[(size_t)m * count + o] = ss_mul(acc, sh_bi[(size_t)m * count + o]);
 }
 
 // below this many elements one element per thread gives more waves to hide latency
@@ -883,7 +961,10 @@ hipError_t ss_launch_degree_reduce_truncate(const u64 *c, u64 *msg1, u64 *msg2, 
                                             const ss_recf_params &rf, hipStream_t stream)
 {
     const bool fixed = (dp.n == 5 && dp.t == 2) || (dp.n == 3 && dp.t == 1);
-    if (count < (fixed ? LANES_MAX_COUNT_FIXED : LANES_MAX_COUNT))
+    if (tp.kdiv > 1)   // the rounding division exists in the general kernel only
+        hipLaunchKernelGGL((degree_reduce_kernel<1, true>), dim3(blocks_for(count, 1)), dim3(BLOCK), 0, stream, c, msg1,
+                           msg2, u, wsh, out, rec, count, dp, tp, rf);
+    else if (count < (fixed ? LANES_MAX_COUNT_FIXED : LANES_MAX_COUNT))
         hipLaunchKernelGGL(degree_reduce_lanes_kernel<true>, dim3((unsigned)((count + 31) / 32)), dim3(BLOCK), 0, stream,
                            c, msg1, msg2, u, wsh, out, rec, count, dp, tp, rf);
     else if (dp.n == 5 && dp.t == 2)
@@ -922,6 +1003,27 @@ hipError_t ss_launch_relu(const u64 *x, const u64 *sh_b, const u64 *sh_bi, u64 *
                     aligned16(yplain) && aligned16(out) && count >= VEC2_MIN_COUNT;
     auto grid = [&](int vec) { return dim3(blocks_for(count, vec)); };
     SS_DISPATCH_VEC(v2, relu_kernel, grid, x, sh_b, sh_bi, msg, yplain, out, count, np);
+    return hipGetLastError();
+}
+
+hipError_t ss_launch_pool_masks(u64 *sh_b, u64 *sh_bi, size_t planes, const ss_pool_geom &g, const ss_nl_params &np,
+                                hipStream_t stream)
+{
+    const size_t cin = planes * g.H * g.W, cout = planes * g.Ho * g.Wo;
+    hipLaunchKernelGGL(pool_masks_kernel<false>, dim3(blocks_for(cin, 1)), dim3(BLOCK), 0, stream, sh_b, cin, g, np);
+    hipLaunchKernelGGL(pool_masks_kernel<true>, dim3(blocks_for(cout, 1)), dim3(BLOCK), 0, stream, sh_bi, cout, g, np);
+    return hipGetLastError();
+}
+
+hipError_t ss_launch_relu_pool(const u64 *x, const u64 *sh_b, const u64 *sh_bi, u64 *msg, u64 *rplain, u64 *yplain,
+                               u64 *out, size_t planes, const ss_pool_geom &g, const ss_nl_params &np,
+                               hipStream_t stream)
+{
+    const size_t cin = planes * g.H * g.W, cout = planes * g.Ho * g.Wo;
+    hipLaunchKernelGGL((relu_kernel<1, false>), dim3(blocks_for(cin, 1)), dim3(BLOCK), 0, stream, x, sh_b,
+                       (const u64 *)nullptr, msg, rplain, (u64 *)nullptr, cin, np);
+    hipLaunchKernelGGL(pool_maskoff_kernel, dim3(blocks_for(cout, 1)), dim3(BLOCK), 0, stream, rplain, sh_bi, yplain, out,
+                       cout, g, np.n);
     return hipGetLastError();
 }
 

@@ -476,3 +476,113 @@ def test_errors_surface_as_codes_not_crashes():
     with pytest.raises(SSNetError) as ei:
         s.reconstruct(x, [1, 4], degree=1)
     assert ei.value.code == binding.EID
+
+
+@pytest.mark.parametrize("n,t", SCHEMES)
+def test_truncate_div_parity(n, t):
+    """Truncation with the rounding division of average pooling (Sec. VI-C, App. C): result and
+    messages against the oracle, alone and fused behind the degree reduction."""
+    f = 13
+    s = SSNet(n, t, f=f, seed=31)
+    for count, kdiv in ((1, 4), (513, 1), (4099, 9), (65538, 49), (70001, 4096), (300001, 4), ((1 << 20) + 2, 49)):
+        say("truncate_div", n, t, count, kdiv)
+        rng = np.random.default_rng(count)
+        xs = rng.integers(-(1 << 57), 1 << 57, count, dtype=np.int64)
+        edge = [0, -1, 1, (kdiv << f) // 2 - 1, (kdiv << f) // 2, -((kdiv << f) // 2), -((kdiv << f) // 2) - 1]
+        xs[: min(count, 7)] = edge[: min(count, 7)]
+        xsh = orc.share(np.where(xs < 0, xs + P61, xs).astype(np.uint64), n, t, P61, 31, 1)
+        got = to_np(s.truncate_div(to_dev(xsh), kdiv, stream_id=count))
+        want, u, wsh = orc.truncate_div(xsh, n, t, f, kdiv, P61, 31, count, full=True)
+        ws = to_np(s.messages()[: (t + 1 + n) * count])
+        assert np.array_equal(ws[: (t + 1) * count].reshape(t + 1, count), u)
+        assert np.array_equal(ws[(t + 1) * count:].reshape(n, count), wsh)
+        assert np.array_equal(got, want)
+        rec = orc.lift(to_np(s.reconstruct(to_dev(got), list(range(n - t, n + 1)))), P61)
+        assert np.array_equal(rec, ((xs >> f) + kdiv // 2) // kdiv)
+        if count > 100000 and (n, t) not in ((3, 1), (5, 2)):
+            continue
+        # behind the reduction: product-degree shares in, one launch
+        c = orc.share(np.where(xs < 0, xs + P61, xs).astype(np.uint64), n, 2 * t, P61, 31, 2)
+        got2 = to_np(s.degree_reduce_truncate_div(to_dev(c), kdiv, stream_id=7))
+        want2 = orc.truncate_div(orc.degree_reduce(c, n, t, P61, 31, 7), n, t, f, kdiv, P61, 31, 7)
+        assert np.array_equal(got2, want2)
+
+
+POOL_GEOMS = [
+    # planes, H, W, kernel, stride, pad
+    (3, 6, 6, (2, 2), (2, 2), (0, 0)),
+    (5, 7, 5, (2, 2), (2, 2), (0, 0)),           # ragged edges
+    (4, 9, 9, (3, 3), (2, 2), (1, 1)),           # overlapping kernels
+    (70, 7, 7, (7, 7), (7, 7), (0, 0)),          # global pooling
+    (2, 8, 6, (3, 2), (1, 2), (0, 1)),           # unequal per axis
+    (1, 1, 1, (1, 1), (1, 1), (0, 0)),
+    (64, 33, 31, (3, 3), (2, 2), (1, 1)),        # several blocks, ragged
+    (16, 40, 40, (2, 2), (2, 2), (0, 0)),
+]
+
+
+@pytest.mark.parametrize("n,t", [(3, 1), (5, 2), (7, 3), (5, 1)])
+def test_relu_pool_parity_with_masks_and_messages(n, t):
+    """SSS-NonLinear with pooling: mask shares (beta equal inside a pooling kernel), masked
+    products, the elite party's rectified and pooled plain values, output shares; against the
+    oracle and, opened, against torch's pooling of the plain input."""
+    s = SSNet(n, t, seed=77)
+    nr = 2 * t + 1
+    for gi, (planes, H, W, kern, stride, pad) in enumerate(POOL_GEOMS):
+        say("relu_pool", n, t, planes, H, W, kern, stride, pad)
+        geo = (H, W) + kern + stride + pad
+        sb, sbi = s.pool_masks(planes, H, W, kern, stride, pad, stream_id=40 + gi)
+        osb, osbi = orc.pool_masks(planes, *geo, n, t, 28, P61, 77, 40 + gi)
+        assert np.array_equal(to_np(sb).reshape(n, -1), osb) and np.array_equal(to_np(sbi).reshape(n, -1), osbi)
+        Ho, Wo = sbi.shape[-2], sbi.shape[-1]
+        cin, cout = planes * H * W, planes * Ho * Wo
+        rng = np.random.default_rng(gi)
+        xs = rng.integers(-(1 << 25), 1 << 25, (planes, H, W), dtype=np.int64)
+        xs.reshape(-1)[: min(cin, 3)] = [0, 1, -1][: min(cin, 3)]
+        x = orc.share(np.where(xs < 0, xs + P61, xs).astype(np.uint64).reshape(-1), n, t, P61, 77, 13)
+        xt = torch.from_numpy(xs).clamp(min=0).to(torch.float64)[None]
+        for mode in (SSNet.POOL_MAX, SSNet.POOL_SUM):
+            want, msg, y = orc.relu_pool(x, osb, osbi, planes, *geo, mode, n, t, P61, full=True)
+            got = s.relu_pool(to_dev(x).view(n, planes, H, W), sb, sbi, kern, stride, pad, mode)
+            assert tuple(got.shape) == (n, planes, Ho, Wo)
+            ws = to_np(s.messages()[: (nr + 1) * cin + cout])
+            assert np.array_equal(ws[: nr * cin].reshape(nr, cin), msg)
+            # the rectified products before pooling: the elementwise protocol's plain value
+            _, _, r = orc.relu(x, osb, np.zeros_like(osb), n, t, P61, full=True)
+            assert np.array_equal(ws[nr * cin: (nr + 1) * cin], r)
+            assert np.array_equal(ws[(nr + 1) * cin:], y)
+            assert np.array_equal(to_np(got).reshape(n, -1), want)
+            if mode == SSNet.POOL_MAX:
+                ref = torch.nn.functional.max_pool2d(xt, kern, stride, pad)[0]
+            else:
+                ref = torch.nn.functional.avg_pool2d(xt, kern, stride, pad)[0] * (kern[0] * kern[1])
+            opened = orc.lift(to_np(s.reconstruct(got, list(range(n, n - t - 1, -1)))), P61)
+            assert np.array_equal(opened.reshape(planes, Ho, Wo), ref.round().to(torch.int64).numpy())
+
+
+def test_relu_pool_stem_size():
+    """The two pooling points of the ResNet stacks at full size (n = 5, t = 2): 3x3 / 2 padding 1 on
+    64 x 112 x 112 and the global sum on 2048 x 7 x 7 after the truncation with kdiv = 49."""
+    n, t, f = 5, 2, 13
+    s = SSNet(n, t, f=f, seed=8)
+    for planes, H, kern, stride, pad, mode, kdiv in ((64, 112, (3, 3), (2, 2), (1, 1), SSNet.POOL_MAX, 1),
+                                                     (2048, 7, (7, 7), (7, 7), (0, 0), SSNet.POOL_SUM, 49)):
+        say("relu_pool full size", planes, H, kern)
+        geo = (H, H) + kern + stride + pad
+        rng = np.random.default_rng(planes)
+        xs = rng.integers(-(1 << 39), 1 << 39, planes * H * H, dtype=np.int64)       # before truncation
+        c = orc.share(np.where(xs < 0, xs + P61, xs).astype(np.uint64), n, 2 * t, P61, 8, 1)
+        xt = s.degree_reduce_truncate_div(to_dev(c), kdiv, stream_id=2)
+        oxt = orc.truncate_div(orc.degree_reduce(c, n, t, P61, 8, 2), n, t, f, kdiv, P61, 8, 2)
+        assert np.array_equal(to_np(xt), oxt)
+        sb, sbi = s.pool_masks(planes, H, H, kern, stride, pad, stream_id=3)
+        osb, osbi = orc.pool_masks(planes, *geo, n, t, 28, P61, 8, 3)
+        assert np.array_equal(to_np(sb).reshape(n, -1), osb) and np.array_equal(to_np(sbi).reshape(n, -1), osbi)
+        got = s.relu_pool(xt.view(n, planes, H, H), sb, sbi, kern, stride, pad, mode)
+        want = orc.relu_pool(oxt, osb, osbi, planes, *geo, mode, n, t, P61)
+        assert np.array_equal(to_np(got).reshape(n, -1), want)
+        q = torch.from_numpy(((xs >> f) + kdiv // 2) // kdiv).clamp(min=0).to(torch.float64).view(1, planes, H, H)
+        ref = (torch.nn.functional.max_pool2d(q, kern, stride, pad) if mode == SSNet.POOL_MAX
+               else torch.nn.functional.avg_pool2d(q, kern, stride, pad) * (kern[0] * kern[1]))
+        opened = orc.lift(to_np(s.reconstruct(got, [1, 3, 5])), P61)
+        assert np.array_equal(opened.reshape(-1), ref.round().to(torch.int64).numpy().reshape(-1))

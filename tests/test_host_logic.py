@@ -142,3 +142,30 @@ def test_new_entry_points_check_their_arguments():
     assert s7.lib.ssnet_layer_tail_message_plane(s7._ctx, 1, 20, 17) == 20 * 17
     ids = (C.c_int * 3)(1, 1, 2)
     assert lib.ssnet_reduce_truncate_direct(ctx, 16, 8, 0, 16, ids, 3, 16) == binding.EID
+
+
+def test_pooling_entry_points_check_their_arguments():
+    lib = binding.load_library()
+    s = SSNet(5, 2, device=None)
+    ctx = s._ctx
+    assert lib.ssnet_pool_out_size(112, 3, 2, 1) == 56 and lib.ssnet_pool_out_size(7, 7, 7, 0) == 1
+    assert lib.ssnet_pool_out_size(5, 2, 2, 0) == 2 and lib.ssnet_pool_out_size(2, 3, 1, 0) == 0
+    geom = lambda H, W, kh, kw, sh, sw, ph, pw: (H, W, kh, kw, sh, sw, ph, pw)
+    bad = [geom(2, 2, 3, 3, 1, 1, 0, 0),      # kernel larger than the image
+           geom(8, 8, 2, 2, 2, 2, 2, 0),      # padding as large as the kernel
+           geom(8, 8, 2, 2, 0, 2, 0, 0),      # zero stride
+           geom(8, 8, 2, 2, 2, 2, -1, 0),
+           geom(1 << 16, 8, 2, 2, 2, 2, 0, 0),
+           geom(100, 100, 65, 64, 1, 1, 0, 0)]   # more than SSNET_MAX_KDIV kernel elements
+    for g in bad:
+        assert lib.ssnet_pool_masks(ctx, 1, *g, 0, 16, 16) == binding.EINVAL, g
+        assert lib.ssnet_relu_pool(ctx, 16, 16, 16, 1, *g, 0, 16) == binding.EINVAL, g
+    ok = geom(8, 8, 2, 2, 2, 2, 0, 0)
+    assert lib.ssnet_pool_masks(ctx, 0, *ok, 0, 16, 16) == binding.EINVAL
+    assert lib.ssnet_relu_pool(ctx, 16, 16, 16, 1, *ok, 2, 16) == binding.EINVAL         # unknown mode
+    assert lib.ssnet_relu_pool(ctx, 16, 16, None, 1, *ok, 0, 16) == binding.EINVAL
+    assert lib.ssnet_relu_pool(ctx, 16, 16, 16, 1, *ok, 0, 16) == binding.EWORKSPACE
+    for kdiv in (0, -1, 4097):
+        assert lib.ssnet_truncate_div(ctx, 16, 8, kdiv, 0, 16) == binding.EINVAL
+        assert lib.ssnet_degree_reduce_truncate_div(ctx, 16, 8, kdiv, 0, 16) == binding.EINVAL
+    assert lib.ssnet_truncate_div(ctx, 16, 8, 4, 0, 16) == binding.EWORKSPACE
