@@ -193,12 +193,13 @@ def measured_traffic_bytes(kernel):
     return None
 
 
-def secure_chain(chain, ss, steps, warmup, macs, out_elems):
+def secure_chain(chain, ss, steps, warmup, macs, out_elems, pool_on_shares=False):
     """The same stack with ReLU evaluated on the shares (SSS-NonLinear, Sec. VI-C): a layer's output
-    shares feed the next layer, nothing is opened except at the two pooling points.  Reported beside
-    the headline, not in it."""
+    shares feed the next layer, nothing is opened except at the two pooling points; with pool_on_shares
+    those stay on shares too (mask equal inside a pooling kernel, the average's division inside the
+    truncation) and only the logits are opened.  Reported beside the headline, not in it."""
     import torch
-    chain.secure_prepare()
+    chain.secure_prepare(pool_on_shares)
     torch.cuda.synchronize()
     for _ in range(warmup):
         chain.secure_timed()
@@ -212,13 +213,12 @@ def secure_chain(chain, ss, steps, warmup, macs, out_elems):
     chain.secure_timed()
     prof = ss.profile_end()
     relu_elems = sum(L.cout * L.M for L in chain.layers if L.post == "relu")
-    nr = 2 * ss.t + 1
-    relu_bytes = (3 * nr + (nr + 1) + 3 * ss.n) * 8 * relu_elems     # per party: operands in, message / result out
-    return {"workload": "same stack, Linear - Truncation - NonLinear per layer on shares; opened only at the "
-                        "max-pool, the global average and the logits",
+    opened = "the logits" if pool_on_shares else "the max-pool, the global average and the logits"
+    return {"workload": "same stack, Linear - Truncation - NonLinear per layer on shares; opened only at " + opened,
             "ms_per_step": ms, "field_MAC_per_s": macs / (ms * 1e-3),
             "kernel_ms_per_step": {k: {"ms": round(v[0], 4), "spans": int(v[1])} for k, v in prof.items() if v[1]},
-            "relu_GBps": relu_bytes / (prof["nonlinear"][0] * 1e-3) / 1e9 if prof["nonlinear"][1] else None,
+            # the ReLU of the plain layers runs inside the layer tail (class degree_reduce); class nonlinear
+            # holds the two ReLU + pooling calls
             "relu_elements_per_step": relu_elems}
 
 
@@ -341,6 +341,8 @@ def main():
                         "(bit-identical outputs, no messages: a simulation shortcut, not the protocol's work)",
             "ms_per_step": ms_direct, "field_MAC_per_s": macs / (ms_direct * 1e-3)}
         result["nonlinear_on_shares"] = secure_chain(chain, ss, args.steps, args.warmup, macs, out_elems)
+        result["nonlinear_and_pooling_on_shares"] = secure_chain(chain, ss, args.steps, args.warmup, macs, out_elems,
+                                                                 pool_on_shares=True)
     if not args.no_batch8:
         result["batch8"] = batch8_chain(chain, ss, layers, max(args.steps // 4, 2), 1)
     if args.copy_calibration:

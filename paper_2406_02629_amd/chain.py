@@ -5,9 +5,13 @@ Two ways through the stack:
     activation applied to the plain integers (see below);
   * `secure_prepare` / `secure_timed`: ReLU runs on the shares (SSS-NonLinear,
     Sec. VI-C, order Linear - Truncation - NonLinear of Sec. VII-A), so a layer's
-    output shares are the next layer's input and nothing is opened; only the two
+    output shares are the next layer's input and nothing is opened.  The two
     pooling points of the stack (max-pool after the stem, global average before
-    the classifier) still go through the plain route.
+    the classifier) go through the plain route, or, with
+    `secure_setup(pool_on_shares=True)`, stay on shares as well: ReLU and pooling
+    under a mask that is equal inside a pooling kernel, the division of the
+    average moved into the truncation before it (Sec. VI-C); then only the
+    logits are opened.
 
 Per layer, on the GPU library (Sec. VI, order Linear -> Truncation):
     share the layer input (GEN) -> conv / dense on shares -> degree reduction
@@ -29,6 +33,15 @@ from . import fixedpoint as fx
 from .binding import SSNet
 
 WEIGHT_STREAM_BASE = 1 << 20      # stream ids of the weight sharings, apart from the per-layer ones
+
+
+def pool_spec(L: Layer):
+    """-> (kernel, stride, pad, mode, kdiv) of the pooling that follows layer L, or None"""
+    if L.post == "relu+maxpool3s2":
+        return (3, 3), (2, 2), (1, 1), SSNet.POOL_MAX, 1
+    if L.post == "relu+gap":
+        return (L.hout, L.hout), (L.hout, L.hout), (0, 0), SSNet.POOL_SUM, L.hout * L.hout
+    return None
 
 
 def post_plain(y: torch.Tensor, post: Optional[str]) -> torch.Tensor:
@@ -176,12 +189,27 @@ class Chain:
     # ------------------------------------------------------------------ ReLU on shares
     MASK_STREAM_BASE = 1 << 21     # stream ids of the non-linear masks, apart from the others
 
-    def secure_setup(self):
+    def secure_setup(self, pool_on_shares: bool = False):
         """Offline part of SSS-NonLinear: the trusted source's mask shares for every layer whose
-        activation is a plain ReLU (Sec. VII-B)."""
+        activation is a plain ReLU (Sec. VII-B) and, with pool_on_shares, for the layers followed
+        by ReLU and pooling (masks equal inside a pooling kernel, Sec. VI-C)."""
         ss = self.ss
-        self.masks = [ss.nonlinear_masks(self._out_shape(L), stream_id=self.MASK_STREAM_BASE + l, device=ss.device or "cuda")
-                      if L.post == "relu" else None for l, L in enumerate(self.layers)]
+        dev = ss.device or "cuda"
+        self.pool_on_shares = pool_on_shares
+        self.masks, self.pooled = [], []
+        for l, L in enumerate(self.layers):
+            spec = pool_spec(L) if pool_on_shares else None
+            if L.post == "relu":
+                self.masks.append(ss.nonlinear_masks(self._out_shape(L), stream_id=self.MASK_STREAM_BASE + l, device=dev))
+            elif spec is not None:
+                kern, stride, pad, _, _ = spec
+                b, bi = ss.pool_masks(self.batch * L.cout, L.hout, L.hout, kern, stride, pad,
+                                      stream_id=self.MASK_STREAM_BASE + l, device=dev)
+                self.masks.append((b, bi))
+            else:
+                self.masks.append(None)
+            self.pooled.append(torch.empty((ss.n, self.batch, L.cout) + tuple(self.masks[l][1].shape[-2:]),
+                                           dtype=torch.int64, device=dev) if spec is not None else None)
         # here every convolution whose channel count allows it reads limb planes, 1x1 ones included: the
         # tail of the layer before writes them.  For a 1x1 kernel the tap-major tiles are the ordinary ones.
         self.sec_planes = [L.kind == "conv" and ss.planes_supported(self.batch, L.cin, L.hin, L.hin)
@@ -201,6 +229,8 @@ class Chain:
         y = self.y[l]
         if x_shares is None:
             x_shares = ss.share(x_plain, stream_id=l, out=self.x_shares[l])
+        elif L.kind == "fc":
+            x_shares = x_shares.view(ss.n, self.batch, -1)
         if self.sec_planes[l]:
             if not planes_ready:
                 ss.split_planes(x_shares, planes=self.x_planes)
@@ -217,14 +247,27 @@ class Chain:
             nxt = l + 1 < len(self.layers) and self.sec_planes[l + 1]
             ss.reduce_truncate_relu(y, l, b, bi, out=y, planes=self.x_planes if nxt else None)
             return y, None
+        if self.pooled[l] is not None:
+            # reduce + truncate (with the division of an average), then ReLU and pooling under the mask
+            kern, stride, pad, mode, kdiv = pool_spec(L)
+            b, bi = self.masks[l]
+            if kdiv > 1:
+                ss.degree_reduce_truncate_div(yv, kdiv, stream_id=l, out=yv)
+            else:
+                ss.degree_reduce_truncate(yv, stream_id=l, out=yv)
+            return ss.relu_pool(y, b, bi, kern, stride, pad, mode, out=self.pooled[l]), None
         ss.degree_reduce_truncate_reconstruct(yv, stream_id=l, ids=self.ids, out=yv, secret=self.rec[l])
         return None, self.rec[l]
 
-    def secure_prepare(self):
-        """One pass; records the plain inputs of the layers that follow a pooling point.
+    def _planes_ready(self, l: int, x_shares) -> bool:
+        """the tail of a layer with a plain ReLU has left the limb planes of layer l's input"""
+        return x_shares is not None and self.sec_planes[l] and l > 0 and self.layers[l - 1].post == "relu"
+
+    def secure_prepare(self, pool_on_shares: bool = False):
+        """One pass; records the plain inputs of the layers that follow an opened pooling point.
         Returns the last layer's opened output."""
-        if not hasattr(self, "masks"):
-            self.secure_setup()
+        if not hasattr(self, "masks") or self.pool_on_shares != pool_on_shares:
+            self.secure_setup(pool_on_shares)
         self.secure_plain: List[Optional[torch.Tensor]] = [None] * len(self.layers)
         x_plain, x_shares, out = self.image, None, None
         for l, L in enumerate(self.layers):
@@ -232,8 +275,7 @@ class Chain:
                 if L.kind == "fc":
                     x_plain = x_plain.reshape(self.batch, -1)
                 self.secure_plain[l] = x_plain.contiguous()
-            x_shares, out = self.secure_layer(l, self.secure_plain[l], x_shares,
-                                              planes_ready=x_shares is not None and self.sec_planes[l])
+            x_shares, out = self.secure_layer(l, self.secure_plain[l], x_shares, planes_ready=self._planes_ready(l, x_shares))
             if x_shares is None and L.post is not None:
                 x_plain = fx.from_signed(post_plain(fx.lift(out), L.post))
         return out
@@ -242,5 +284,4 @@ class Chain:
         """The share arithmetic of the whole stack, layer feeding layer."""
         x_shares = None
         for l in range(len(self.layers)):
-            x_shares, _ = self.secure_layer(l, self.secure_plain[l], x_shares,
-                                            planes_ready=x_shares is not None and self.sec_planes[l])
+            x_shares, _ = self.secure_layer(l, self.secure_plain[l], x_shares, planes_ready=self._planes_ready(l, x_shares))
