@@ -688,3 +688,60 @@ def test_relu_pool_against_torch_and_mask_constancy(geom, n, t):
                    for i in range(2 * t + 1) for e in range(0, planes * H * W, 7))
         b_out = np.array([pow(int(v), -1, p) for v in binv.reshape(-1)], object)
         assert [int(v) for v in y] == [int(w) * int(b) for w, b in zip(want.reshape(-1), b_out)]
+
+
+# ----------------------------------------------------------------- the paper's own prime, p = 2^45 - 55 (Sec. VII-A, App. D)
+P45 = (1 << 45) - 55
+
+
+def test_p45_split_product_of_appendix_d():
+    """App. D multiplies two 46-bit operands through 23-bit halves: C = (C_HH + hi(C_HL) + hi(C_LH)) 2^46 +
+    (lo(C_HL) + lo(C_LH)) 2^23 + C_LL with 2^46 = 110 (mod p).  (As printed the middle term has lost its
+    weight 2^23.)  Restated with Python integers, it agrees with the oracle's product."""
+    rng = random.Random(45)
+    ops = [(rng.randrange(P45), rng.randrange(P45)) for _ in range(2000)]
+    ops += [(P45 - 1, P45 - 1), (0, 5), (1, P45 - 1), ((1 << 44), (1 << 44) + 12345)]
+    for a, b in ops:
+        ah, al, bh, bl = a >> 23, a & 0x7FFFFF, b >> 23, b & 0x7FFFFF
+        chh, chl, clh, cll = ah * bh, ah * bl, al * bh, al * bl
+        c_h = chh + (chl >> 23) + (clh >> 23)
+        c_m = (chl & 0x7FFFFF) + (clh & 0x7FFFFF)
+        want = ((c_h % P45) * 110 + c_m * (1 << 23) + cll) % P45
+        assert orc.mul(a, b, P45) == want == a * b % P45
+
+
+def test_p45_bit_budget_of_a_layer():
+    """Sec. VII-A: 16-bit operands leave 13 bits for the accumulation of a dot product in a 45-bit
+    signed range.  A dot product of K = 2^13 - 1 worst-case 16-bit terms on shares over p = 2^45 - 55
+    reconstructs to the exact signed integer; one more doubling of K wraps."""
+    n, t, p = 3, 1, P45
+    for K, fits in ((1 << 13) - 1, True), (1 << 14, False):
+        x = np.full((1, K), -(1 << 15), np.int64)          # the extreme of the signed 16-bit range
+        w = np.full((K, 1), -(1 << 15), np.int64)
+        exact = int((x.astype(object) @ w.astype(object))[0, 0])
+        xs = orc.share(np.where(x < 0, x + p, x).astype(np.uint64), n, t, p, 3, 1)
+        ws = orc.share(np.where(w < 0, w + p, w).astype(np.uint64), n, t, p, 3, 2)
+        got = int(orc.lift(orc.reconstruct(orc.linear(xs, ws, p), [1, 2, 3], p), p)[0, 0])
+        assert (got == exact) == fits
+        assert (abs(exact) <= (p - 1) // 2) == fits
+
+
+def test_p45_tiny_secure_layer_with_relu_matches_float64():
+    """Linear - Truncation - NonLinear over the paper's prime with its mask ranges (alpha below 2^32,
+    beta below 2^28, Sec. VII-B): floor-truncated product, then max(., 0)."""
+    from ssnet_inputs import gaussian
+    n, t, f, p = 5, 2, 13, P45
+    M, K, N = 6, 48, 5
+    X, Wt = gaussian((M, K), 11), gaussian((K, N), 12) / np.sqrt(K)
+    xe, we = orc.encode(X, f, p), orc.encode(Wt, f, p)
+    y2 = orc.linear(orc.share(xe, n, t, p, 7, 1), orc.share(we, n, t, p, 7, 2), p)
+    exact = orc.decode(xe, f, p) @ orc.decode(we, f, p)
+    yt = orc.truncate(orc.degree_reduce(y2.reshape(n, -1), n, t, p, 7, 3), n, t, f, p, 7, 3)
+    sb, sbi = orc.nonlinear_masks(M * N, n, t, 28, p, 7, 4)
+    out = orc.relu(yt, sb, sbi, n, t, p)
+    for ids in ([1, 2, 3], [3, 4, 5], [1, 3, 5]):
+        tr = orc.decode(orc.reconstruct(yt, ids, p), f, p).reshape(M, N)
+        err = exact - tr
+        assert err.min() >= 0 and err.max() < 2.0 ** -f
+        got = orc.decode(orc.reconstruct(out, ids, p), f, p).reshape(M, N)
+        assert np.array_equal(got, np.maximum(tr, 0))
