@@ -7,6 +7,18 @@
  * the device inside a call.  The field is F_p with p = 2^61 - 1; a field
  * element is a uint64_t in [0, p-1] (canonical: the value p never appears).
  *
+ * The field is fixed when the library is compiled.  The same sources built
+ * with -DSS_FIELD_P45 give a second library with this same ABI over the prime
+ * of Sec. VII-A, p = 2^45 - 55 (16-bit operands, 13 bits of accumulation room):
+ * field elements have 6 int8 limbs instead of 8, so limb tiles and limb planes
+ * are three quarters the size (ask ssnet_packed_weight_bytes /
+ * ssnet_conv_planes_bytes of the library in use) and a product costs 36 int8
+ * multiply-adds instead of 64.  Wherever a comment below says 2^61 - 1, "61
+ * bits" or "eight limbs", read the library's own prime (ssnet_field_prime) and
+ * limb count.  Preconditions stated against p/2 scale with it: over the
+ * 45-bit prime truncation needs |x| + 2^32 <= (p-1)/2 and the ReLU mask
+ * |x| * 2^28 < p/2, i.e. |x| < 2^16, the paper's 16-bit budget (Sec. VII-B).
+ *
  * Conventions for every entry point below
  *   - `d_` pointers are DEVICE pointers owned by the caller (8-byte aligned;
  *     16-byte aligned buffers take the faster vector path).  The library never
@@ -35,7 +47,7 @@ extern "C" {
 
 #define SSNET_OK 0
 #define SSNET_EINVAL (-1)     /* null pointer, bad n/t/f/degree/shape                 */
-#define SSNET_EPRIME (-2)     /* p is not 2^61 - 1                                     */
+#define SSNET_EPRIME (-2)     /* p is not the prime this library was built for         */
 #define SSNET_ESHARES (-3)    /* fewer than degree+1 parties given to reconstruct      */
 #define SSNET_EID (-4)        /* party id outside [1, n] or repeated                   */
 #define SSNET_EWORKSPACE (-5) /* workspace missing or too small for this call          */
@@ -45,14 +57,18 @@ extern "C" {
 #define SSNET_MAX_T 3         /* t <= 3 (n >= 2t+1)                                    */
 #define SSNET_MAX_K 16383     /* contraction length of linear/conv (int32 exactness)   */
 
-#define SSNET_P61 0x1FFFFFFFFFFFFFFFULL
+#define SSNET_P61 0x1FFFFFFFFFFFFFFFULL /* 2^61 - 1                                    */
+#define SSNET_P45 0x1FFFFFFFFFC9ULL     /* 2^45 - 55 (Sec. VII-A)                      */
+
+/* The prime this library was built for: SSNET_P61 or SSNET_P45. */
+uint64_t ssnet_field_prime(void);
 
 typedef struct ssnet_ctx ssnet_ctx;
 
 /* Context: parameters of the scheme plus host-computed constant tables
  * (Lagrange multipliers of Eq. 2 for IDs 1..k, the factors of the reduction
  * matrix R = B^-1 P B of Eq. 3).  Requires n >= 2t+1 (Sec. III-B), 1 <= t <=
- * SSNET_MAX_T, n <= SSNET_MAX_PARTIES, p == 2^61-1, 1 <= f <= 31.
+ * SSNET_MAX_T, n <= SSNET_MAX_PARTIES, p == ssnet_field_prime(), 1 <= f <= 31.
  * `hip_stream` is a hipStream_t (NULL = the default stream).  Host-only work:
  * creating a context does not touch the GPU. */
 int ssnet_create(ssnet_ctx **out, int n, int t, uint64_t p, int f, uint64_t seed, void *hip_stream);

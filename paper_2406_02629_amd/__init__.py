@@ -4,5 +4,5 @@
 the plaintext-side encode/decode helpers of the harness; `chain` runs a
 sequential stack of linear layers on shares.
 """
-from .binding import (P61, SSNet, SSNetError, load_library, rng_draw, rng_field, rng_key)  # noqa: F401
+from .binding import (P45, P61, SSNet, SSNetError, load_library, rng_draw, rng_field, rng_key)  # noqa: F401
 from . import fixedpoint  # noqa: F401

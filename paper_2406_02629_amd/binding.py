@@ -15,6 +15,7 @@ import torch
 from . import build as _build
 
 P61 = (1 << 61) - 1
+P45 = (1 << 45) - 55          # the prime of Sec. VII-A; served by the second library
 
 WS_HEADER_BYTES = 65536      # SSNET_WS_HEADER_BYTES
 OK, EINVAL, EPRIME, ESHARES, EID, EWORKSPACE, EHIP = 0, -1, -2, -3, -4, -5, -6
@@ -62,6 +63,7 @@ SIGNATURES = {
     "ssnet_pool_out_size": (_int, [_int, _int, _int, _int]),
     "ssnet_pool_masks": (_int, [_ptr, _sz] + [_int] * 8 + [_u64, _ptr, _ptr]),
     "ssnet_relu_pool": (_int, [_ptr, _ptr, _ptr, _ptr, _sz] + [_int] * 9 + [_ptr]),
+    "ssnet_field_prime": (_u64, []),
     "ssnet_rng_key": (_u64, [_u64] * 5),
     "ssnet_rng_draw": (_u64, [_u64, _u64]),
     "ssnet_rng_field": (_u64, [_u64, _u64]),
@@ -73,22 +75,23 @@ SIGNATURES = {
     "ssnet_last_hip_error": (_int, [_ptr]),
 }
 
-_lib = None
+_libs = {}
 
 
-def load_library() -> C.CDLL:
-    """Load the built library; build it first only if no library is there.
+def load_library(p: int = P61) -> C.CDLL:
+    """Load the built library for the field F_p (any p other than P45 gets the default library, whose
+    ssnet_create then rejects it); build first only if no library is there.
     There is no fallback: without the HIP library nothing here works."""
-    global _lib
-    if _lib is None:
-        if not os.path.exists(_build.LIB):
+    path = _build.LIB_P45 if p == P45 else _build.LIB
+    if path not in _libs:
+        if not os.path.exists(path):
             _build.build(force=True)
-        lib = C.CDLL(_build.LIB)
+        lib = C.CDLL(path)
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(lib, name)
             fn.restype, fn.argtypes = res, args
-        _lib = lib
-    return _lib
+        _libs[path] = lib
+    return _libs[path]
 
 
 class SSNetError(RuntimeError):
@@ -109,11 +112,12 @@ def _check_i64(t: torch.Tensor, name: str) -> torch.Tensor:
 
 
 class SSNet:
-    """One (k = t+1, n) scheme over F_p, p = 2^61-1, fixed-point fraction bits f."""
+    """One (k = t+1, n) scheme over F_p, p = 2^61-1 (or P45, served by the second library), fixed-point
+    fraction bits f."""
 
     def __init__(self, n: int, t: int, f: int = 13, seed: int = 0, p: int = P61,
                  device: Optional[str] = "cuda:0", stream: Optional[int] = None):
-        self.lib = load_library()
+        self.lib = load_library(p)
         self.n, self.t, self.k, self.f, self.p, self.seed = n, t, t + 1, f, p, seed
         self.device = None if device is None else torch.device(device)
         if stream is None and self.device is not None:
@@ -557,5 +561,5 @@ def rng_draw(key, e) -> int:
     return load_library().ssnet_rng_draw(key, e)
 
 
-def rng_field(key, e) -> int:
-    return load_library().ssnet_rng_field(key, e)
+def rng_field(key, e, p: int = P61) -> int:
+    return load_library(p).ssnet_rng_field(key, e)

@@ -1,8 +1,10 @@
-"""Compile the HIP library for gfx950 into paper_2406_02629_amd/libssnet.so.
+"""Compile the HIP library for gfx950: paper_2406_02629_amd/libssnet.so over
+p = 2^61 - 1 and, from the same sources with -DSS_FIELD_P45, libssnet_p45.so
+over p = 2^45 - 55.
 
 hipcc cross-compiles without a GPU.  Each .hip file is compiled to an object
-and the objects are linked into one shared library that exports the C ABI of
-include/ssnet.h.
+and the objects are linked into one shared library per field that exports the
+C ABI of include/ssnet.h.
 """
 import os
 import subprocess
@@ -13,6 +15,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libssnet.so")
+LIB_P45 = os.path.join(HERE, "libssnet_p45.so")
+VARIANTS = {"p61": (LIB, []), "p45": (LIB_P45, ["-DSS_FIELD_P45"])}
 SOURCES = ["stream_kernels.hip", "gemm_kernels.hip", "ssnet_api.hip"]
 HEADERS = ["field.hpp", "kernels.hpp", "eval.hpp", "digits.hpp", os.path.join("..", "..", "include", "ssnet.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -26,33 +30,40 @@ def _newest_source() -> float:
 
 
 def is_current() -> bool:
-    return os.path.exists(LIB) and os.path.getmtime(LIB) >= _newest_source()
+    newest = _newest_source()
+    return all(os.path.exists(lib) and os.path.getmtime(lib) >= newest for lib, _ in VARIANTS.values())
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
+    """Build both libraries; returns the path of the default one."""
     if not force and is_current():
         return LIB
     os.makedirs(OBJ, exist_ok=True)
 
-    def compile_one(src):
-        obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-        cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    def compile_one(job):
+        tag, src = job
+        obj = os.path.join(OBJ, src.replace(".hip", f".{tag}.o"))
+        cmd = ["hipcc", *FLAGS, *VARIANTS[tag][1], "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
-            raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")
+            raise RuntimeError(f"hipcc failed on {src} ({tag}):\n{r.stdout}\n{r.stderr}")
         if verbose and r.stderr.strip():
             print(r.stderr, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
-        objs = list(ex.map(compile_one, SOURCES))
-    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB + ".tmp", *objs]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
-    os.replace(LIB + ".tmp", LIB)
+    jobs = [(tag, src) for tag in VARIANTS for src in SOURCES]
+    with ThreadPoolExecutor(max_workers=len(jobs)) as ex:
+        objs = list(ex.map(compile_one, jobs))
+    for v, tag in enumerate(VARIANTS):
+        lib = VARIANTS[tag][0]
+        cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib + ".tmp",
+               *objs[v * len(SOURCES):(v + 1) * len(SOURCES)]]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"link failed ({tag}):\n{r.stdout}\n{r.stderr}")
+        os.replace(lib + ".tmp", lib)
     return LIB
 
 

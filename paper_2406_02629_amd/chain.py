@@ -77,7 +77,7 @@ class Chain:
         for l, L in enumerate(layers if weights_of is None else []):
             shape = (L.cout, L.cin, L.ksize, L.ksize) if L.kind == "conv" else (L.cin, L.cout)
             w = he_normal(shape, L.K, weight_seed_base + l)
-            we = fx.encode(torch.from_numpy(w).to(dev), ss.f)
+            we = fx.encode(torch.from_numpy(w).to(dev), ss.f, ss.p)
             wsh = ss.share(we, stream_id=WEIGHT_STREAM_BASE + l)
             if self.on_planes[l]:
                 self.packed.append(ss.pack_weights_conv_taps(wsh))
@@ -86,7 +86,7 @@ class Chain:
             self.wshares.append(wsh if keep_weight_shares else None)
         L0 = layers[0]
         img = gaussian((batch, L0.cin, L0.hin, L0.hin), image_seed)
-        self.image = fx.encode(torch.from_numpy(img).to(dev), ss.f)
+        self.image = fx.encode(torch.from_numpy(img).to(dev), ss.f, ss.p)
         self.ids = list(range(1, ss.k + 1))
         # per-layer buffers so that the timed loop allocates nothing
         self.x_plain: List[Optional[torch.Tensor]] = [None] * len(layers)
@@ -175,7 +175,7 @@ class Chain:
             self.x_plain[l] = x.contiguous()
             out = self.run_layer(l, self.x_plain[l])
             if L.post is not None:
-                x = fx.from_signed(post_plain(fx.lift(out), L.post))
+                x = fx.from_signed(post_plain(fx.lift(out, self.ss.p), L.post), self.ss.p)
         return out
 
     def forward_timed(self, stages: str = "sgdtr"):
@@ -277,7 +277,7 @@ class Chain:
                 self.secure_plain[l] = x_plain.contiguous()
             x_shares, out = self.secure_layer(l, self.secure_plain[l], x_shares, planes_ready=self._planes_ready(l, x_shares))
             if x_shares is None and L.post is not None:
-                x_plain = fx.from_signed(post_plain(fx.lift(out), L.post))
+                x_plain = fx.from_signed(post_plain(fx.lift(out, self.ss.p), L.post), self.ss.p)
         return out
 
     def secure_timed(self):

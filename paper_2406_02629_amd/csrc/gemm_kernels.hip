@@ -11,6 +11,10 @@
 // C operand does the diagonal sum).  The epilogue turns the 15 sums of each
 // output into a 61-bit residue with 2^61 = 1 (mod p) and stores the canonical
 // field element.
+//
+// Built for p = 2^45 - 55 (Sec. VII-A) an element has 6 digits (x < 2^45 leaves
+// digits 6 and 7 zero): 36 products, 11 diagonal sums, tiles and limb planes
+// three quarters the size, and the epilogue folds with 2^45 = 55 (mod p).
 #include "kernels.hpp"
 #include "eval.hpp"
 #include "digits.hpp"
@@ -18,6 +22,11 @@
 typedef int v4i __attribute__((ext_vector_type(4)));
 
 namespace {
+
+// NL digits per field element (8 for p = 2^61 - 1, 6 for p = 2^45 - 55: the digits above are zero), hence
+// ND anti-diagonal sums; a packed tile (16 rows x 64 contraction indices) is NL limb slices of 64 lanes x
+// 16 bytes = TILE 16-byte words
+constexpr int NL = SS_NLIMB, ND = 2 * NL - 1, TILE = NL * 64;
 
 // Digit words of four consecutive contraction indices -> one dword per limb
 // (byte c of dword `limb` is digit `limb` of y[c]) and store them: the thread
@@ -27,7 +36,7 @@ __device__ __forceinline__ void store_digits(const u64 (&y)[4], v4i *tile, int r
 {
     u32 *base = reinterpret_cast<u32 *>(tile) + (row + 16 * (kq >> 2)) * 4 + (kq & 3);
 #pragma unroll
-    for (int limb = 0; limb < 8; limb++) {
+    for (int limb = 0; limb < NL; limb++) {
         const int i = limb & 3;
         const u32 a = limb < 4 ? (u32)y[0] : (u32)(y[0] >> 32), b = limb < 4 ? (u32)y[1] : (u32)(y[1] >> 32);
         const u32 c = limb < 4 ? (u32)y[2] : (u32)(y[2] >> 32), d = limb < 4 ? (u32)y[3] : (u32)(y[3] >> 32);
@@ -58,7 +67,7 @@ __global__ __launch_bounds__(256) void pack_matrix_kernel(const u64 *__restrict_
         const int k = k0 + c, ks = taps ? (k % C) * taps + k / C : k;
         y[c] = (row < rows && k < K) ? balanced_digits(s[(size_t)ks * stride_k]) : 0;
     }
-    store_digits(y, dst + (size_t)blockIdx.z * dst_party_stride + ((size_t)rb * Kb + kb) * 512, r16, kq);
+    store_digits(y, dst + (size_t)blockIdx.z * dst_party_stride + ((size_t)rb * Kb + kb) * TILE, r16, kq);
 }
 
 // rows = (b, ho, wo), k = (c, r, s) gathered from x [n][B][C][H][W]; zero padding
@@ -82,7 +91,7 @@ __global__ __launch_bounds__(256) void pack_im2col_kernel(const u64 *__restrict_
             if (++s == kw) { s = 0; if (++r == kh) { r = 0; ++c; } }
         }
     }
-    store_digits(y, dst + (size_t)blockIdx.z * dst_party_stride + ((size_t)rb * Kb + kb) * 512, r16, kq);
+    store_digits(y, dst + (size_t)blockIdx.z * dst_party_stride + ((size_t)rb * Kb + kb) * TILE, r16, kq);
 }
 
 // The two kernels below take one element per thread: lane l of a wave holds row (or pixel) l%16 and the
@@ -140,7 +149,7 @@ __global__ __launch_bounds__(256) void share_pack_kernel(const u64 *__restrict__
         const int b = row / HW, hw = row - b * HW;
         gen_digits<N, T>(secret, shares, (size_t)B * K * HW, ((size_t)b * K + k) * HW + hw, n, t, keys, dig);
     }
-    u32 *base = reinterpret_cast<u32 *>(dst + ((size_t)rb * Kb + kb) * 512) + (r16 + 16 * (kq >> 2)) * 4 + (kq & 3);
+    u32 *base = reinterpret_cast<u32 *>(dst + ((size_t)rb * Kb + kb) * TILE) + (r16 + 16 * (kq >> 2)) * 4 + (kq & 3);
 #pragma unroll
     for (int p = 0; p < MAXP; p++) {
         if (p < n) {
@@ -148,8 +157,10 @@ __global__ __launch_bounds__(256) void share_pack_kernel(const u64 *__restrict__
 #pragma unroll
             for (int q = 0; q < 4; q++) y[q] = __shfl(dig[p], r16 + 16 * q);
             u32 *bp = base + (size_t)p * dst_party_stride * 4;
-            bp[(2 * j) * 256] = limb_dword(y, 2 * j);
-            bp[(2 * j + 1) * 256] = limb_dword(y, 2 * j + 1);
+            if (2 * j < NL) {   // lane group j writes limbs 2j and 2j+1
+                bp[(2 * j) * 256] = limb_dword(y, 2 * j);
+                bp[(2 * j + 1) * 256] = limb_dword(y, 2 * j + 1);
+            }
         }
     }
 }
@@ -171,7 +182,7 @@ __global__ __launch_bounds__(256) void planes_kernel(const u64 *__restrict__ in,
     const int pix = blockIdx.x * 16 + r16, c0 = blockIdx.y * 16 + 4 * (threadIdx.x >> 6);
     const size_t plane = (size_t)B * HW * C;
     if (blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x < n)
-        *reinterpret_cast<v4i *>(planes + threadIdx.x * party_bytes + 8 * plane) = (v4i){0, 0, 0, 0};
+        *reinterpret_cast<v4i *>(planes + threadIdx.x * party_bytes + NL * plane) = (v4i){0, 0, 0, 0};
     u64 dig[MAXP];
 #pragma unroll
     for (int p = 0; p < MAXP; p++) dig[p] = 0;
@@ -193,7 +204,7 @@ __global__ __launch_bounds__(256) void planes_kernel(const u64 *__restrict__ in,
             u64 y[4];
 #pragma unroll
             for (int q = 0; q < 4; q++) y[q] = __shfl(dig[p], r16 + 16 * q);
-            if (live) {
+            if (live && 2 * j < NL) {
                 u32 *bp = reinterpret_cast<u32 *>(planes + p * party_bytes + (size_t)pix * C + c0);
                 bp[(2 * j) * (plane / 4)] = limb_dword(y, 2 * j);
                 bp[(2 * j + 1) * (plane / 4)] = limb_dword(y, 2 * j + 1);
@@ -214,7 +225,7 @@ __global__ __launch_bounds__(256) void planes4_kernel(const u64 *__restrict__ in
     const int pix = blockIdx.x * 16 + (threadIdx.x & 15), c0 = blockIdx.y * 64 + 4 * (threadIdx.x >> 4);
     const size_t plane = (size_t)B * HW * C, count = plane;
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < MAXP && (int)threadIdx.x < n)
-        *reinterpret_cast<v4i *>(planes + threadIdx.x * party_bytes + 8 * plane) = (v4i){0, 0, 0, 0};
+        *reinterpret_cast<v4i *>(planes + threadIdx.x * party_bytes + NL * plane) = (v4i){0, 0, 0, 0};
     if (pix >= B * HW) return;
     const int b = pix / HW, hw = pix - b * HW;
     u64 y[MAXP][4];
@@ -252,7 +263,7 @@ __global__ __launch_bounds__(256) void planes4_kernel(const u64 *__restrict__ in
         if (p < n) {
             u32 *dst = reinterpret_cast<u32 *>(planes + p * party_bytes + (size_t)pix * C + c0);
 #pragma unroll
-            for (int limb = 0; limb < 8; limb++) dst[limb * (plane / 4)] = limb_dword(y[p], limb);
+            for (int limb = 0; limb < NL; limb++) dst[limb * (plane / 4)] = limb_dword(y[p], limb);
         }
     }
 }
@@ -302,7 +313,24 @@ struct wave_src {
                      // pixel index of its image, -1 if the lane's column is past the matrix
 };
 
-// 15 diagonal sums of one output -> canonical field element
+// the ND diagonal sums of one output -> canonical field element
+#if defined(SS_FIELD_P45)
+__device__ __forceinline__ u64 fold_diagonals(const v4i (&acc)[ND], int r, u64 negbias)
+{
+    u32 U[ND];
+#pragma unroll
+    for (int s = 0; s < ND; s++) U[s] = (u32)acc[s][r] ^ 0x80000000u;   // D_s + 2^31, non-negative
+    const u64 g0 = (u64)U[0] + ((u64)U[1] << 8) + ((u64)U[2] << 16) + ((u64)U[3] << 24);   // < 2^57
+    const u64 g1 = (u64)U[4] + ((u64)U[5] << 8) + ((u64)U[6] << 16) + ((u64)U[7] << 24);
+    const u64 g2 = (u64)U[8] + ((u64)U[9] << 8) + ((u64)U[10] << 16);
+    // g0 + g1 2^32 + g2 2^64.  With g = a 2^13 + b: g 2^32 = a 2^45 + b 2^32 = 55 a + b 2^32, and
+    // 2^64 = 55 2^19 (mod p)
+    const u64 r1 = ss_reduce(g1), r2 = ss_reduce(g2);
+    const u64 t1 = SS_PC * (r1 >> 13) + ((r1 & 0x1FFFull) << 32);   // < 2^38 + 2^45
+    const u64 t2 = ss_mul(r2, SS_PC << 19);
+    return ss_reduce(ss_fold(g0) + t1 + t2 + negbias);   // minus the 2^31 offsets
+}
+#else
 __device__ __forceinline__ u64 fold_diagonals(const v4i (&acc)[15], int r, u64 negbias)
 {
     u32 U[15];
@@ -317,6 +345,7 @@ __device__ __forceinline__ u64 fold_diagonals(const v4i (&acc)[15], int r, u64 n
                     ((g3 & ((1ULL << 26) - 1)) << 35) + (g3 >> 26);
     return ss_reduce(ss_fold(tot) + negbias);   // minus the 2^31 offsets
 }
+#endif
 
 // The units are dealt to the workgroups by cost, not by count: a unit of a full
 // tile costs SS_UNIT_COST, a unit of the last column tile, where only some of
@@ -368,9 +397,9 @@ __device__ __forceinline__ wave_src tile_source(const gemm_args &g, unsigned til
     const int rt = (int)(rem % (unsigned)g.RT), party = (int)(rem / (unsigned)g.RT);
     wave_src ws = {nullptr, 0, 0};
     if (wave < 4) {
-        ws.p = g.A + (size_t)party * g.a_party_stride + (size_t)min(rt * 4 + wave, g.Rb - 1) * g.Kb * 512 + lane;
+        ws.p = g.A + (size_t)party * g.a_party_stride + (size_t)min(rt * 4 + wave, g.Rb - 1) * g.Kb * TILE + lane;
     } else if (!IMPLICIT) {
-        ws.p = g.B + (size_t)party * g.b_party_stride + (size_t)min(ct * 4 + wave - 4, g.Cb - 1) * g.Kb * 512 + lane;
+        ws.p = g.B + (size_t)party * g.b_party_stride + (size_t)min(ct * 4 + wave - 4, g.Cb - 1) * g.Kb * TILE + lane;
     } else {
         // lane l of a block holds column 16 cb + l%16 = output pixel (b, ho, wo)
         const int col = min(ct * 4 + wave - 4, g.Cb - 1) * 16 + (lane & 15);
@@ -389,7 +418,7 @@ __device__ __forceinline__ const v4i *unit_base(const gemm_args &g, const wave_s
 {
     if (!IMPLICIT || wave < 4) {
         qs = 64;
-        return ws.p + (size_t)kb * 512;
+        return ws.p + (size_t)kb * TILE;
     }
     // k block kb = channels [64 (kb % KbTap), +64) of tap kb / KbTap; this lane: 16 of them
     const int tap = kb / g.cvKbTap, c16 = (kb - tap * g.cvKbTap) * 4 + (lane >> 4);
@@ -425,7 +454,8 @@ __device__ __forceinline__ const v4i *unit_base(const gemm_args &g, const wave_s
 template <bool IMPLICIT>
 __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
 {
-    extern __shared__ v4i lds[];   // 2 stages x (4 A blocks + 4 B blocks) x 512
+    extern __shared__ v4i lds[];   // 2 stages x (4 A blocks + 4 B blocks) x TILE
+    constexpr int STAGE = 8 * TILE;
     __shared__ unsigned arrival;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wr = wave & 3, wc = wave >> 2;
     const unsigned G = gridDim.x;
@@ -445,7 +475,7 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
         u1 = (unsigned)g.Kb;
     }
     if (u0 >= u1) return;
-    v4i *mine = lds + wave * 512;   // wave-uniform LDS destination of this wave's block
+    v4i *mine = lds + wave * TILE;   // wave-uniform LDS destination of this wave's block
 
     unsigned tile = g.units ? u0 / (unsigned)g.Kb : slot;
     int kb = (int)(u0 - (g.units ? tile * (unsigned)g.Kb : 0));
@@ -454,7 +484,7 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
         unsigned qs;
         const v4i *ub = unit_base<IMPLICIT>(g, src, kb, wave, lane, qs);
 #pragma unroll
-        for (int q = 0; q < 8; q++) __builtin_amdgcn_global_load_lds(ub + (size_t)q * qs, mine + q * 64, 16, 0, 0);
+        for (int q = 0; q < NL; q++) __builtin_amdgcn_global_load_lds(ub + (size_t)q * qs, mine + q * 64, 16, 0, 0);
     }
     int st = 0;
 
@@ -470,11 +500,11 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
     while (u < u1) {
         const int nblk = valid_blocks(tile);
         const int kb_first = kb;
-        v4i acc[2][15];
+        v4i acc[2][ND];
 #pragma unroll
         for (int h = 0; h < 2; h++)
 #pragma unroll
-            for (int s = 0; s < 15; s++) acc[h][s] = (v4i){0, 0, 0, 0};
+            for (int s = 0; s < ND; s++) acc[h][s] = (v4i){0, 0, 0, 0};
 
         // units of this tile that belong to this workgroup
         const int kb_end = min(g.Kb, kb + (int)(u1 - u));
@@ -493,45 +523,45 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
                 }
                 if constexpr (!IMPLICIT) {
 #pragma unroll
-                    for (int q = 0; q < 8; q++)
-                        __builtin_amdgcn_global_load_lds(next_src.p + (size_t)nkb * 512 + q * 64,
-                                                         mine + (st ^ 1) * 4096 + q * 64, 16, 0, 0);
+                    for (int q = 0; q < NL; q++)
+                        __builtin_amdgcn_global_load_lds(next_src.p + (size_t)nkb * TILE + q * 64,
+                                                         mine + (st ^ 1) * STAGE + q * 64, 16, 0, 0);
                 } else {
                     unsigned qs;
                     const v4i *ub = unit_base<true>(g, next_src, nkb, wave, lane, qs);
 #pragma unroll
-                    for (int q = 0; q < 8; q++)
-                        __builtin_amdgcn_global_load_lds(ub + (size_t)q * qs, mine + (st ^ 1) * 4096 + q * 64, 16, 0, 0);
+                    for (int q = 0; q < NL; q++)
+                        __builtin_amdgcn_global_load_lds(ub + (size_t)q * qs, mine + (st ^ 1) * STAGE + q * 64, 16, 0, 0);
                 }
             }
-            const v4i *sa = lds + st * 4096 + wr * 512 + lane;
-            const v4i *sb = lds + st * 4096 + 2048 + wc * 1024 + lane;
+            const v4i *sa = lds + st * STAGE + wr * TILE + lane;
+            const v4i *sb = lds + st * STAGE + 4 * TILE + wc * 2 * TILE + lane;
             if (nblk == 2) {   // the usual case, kept free of branches so that loads and MFMAs interleave
-                v4i a[8];
+                v4i a[NL];
 #pragma unroll
-                for (int i = 0; i < 8; i++) a[i] = sa[i * 64];
+                for (int i = 0; i < NL; i++) a[i] = sa[i * 64];
 #pragma unroll
                 for (int h = 0; h < 2; h++) {
-                    v4i b[8];
+                    v4i b[NL];
 #pragma unroll
-                    for (int j = 0; j < 8; j++) b[j] = sb[h * 512 + j * 64];
+                    for (int j = 0; j < NL; j++) b[j] = sb[h * TILE + j * 64];
 #pragma unroll
-                    for (int i = 0; i < 8; i++)
+                    for (int i = 0; i < NL; i++)
 #pragma unroll
-                        for (int j = 0; j < 8; j++)
+                        for (int j = 0; j < NL; j++)
                             acc[h][i + j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[h][i + j], 0, 0, 0);
                 }
             } else if (nblk == 1) {   // ragged edge: only the first column block is inside the matrix
-                v4i a[8], b[8];
+                v4i a[NL], b[NL];
 #pragma unroll
-                for (int i = 0; i < 8; i++) {
+                for (int i = 0; i < NL; i++) {
                     a[i] = sa[i * 64];
                     b[i] = sb[i * 64];
                 }
 #pragma unroll
-                for (int i = 0; i < 8; i++)
+                for (int i = 0; i < NL; i++)
 #pragma unroll
-                    for (int j = 0; j < 8; j++)
+                    for (int j = 0; j < NL; j++)
                         acc[0][i + j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[0][i + j], 0, 0, 0);
             }
             st ^= 1;
@@ -615,11 +645,14 @@ __global__ void zero_words_kernel(unsigned *p, size_t nwords)
     if (i < nwords) p[i] = 0;
 }
 
-// residue of sum_{s<15} 2^31 2^(8s), negated
+// residue of sum_{s<ND} 2^31 2^(8s), negated
 u64 neg_bias()
 {
-    u64 b = 0;
-    for (int s = 0; s < 15; s++) b = ss_add(b, 1ULL << ((31 + 8 * s) % 61));
+    u64 b = 0, w = ss_reduce(1ULL << 31);
+    for (int s = 0; s < ND; s++) {
+        b = ss_add(b, w);
+        w = ss_mul(w, 256);
+    }
     return ss_neg(b);
 }
 
@@ -696,7 +729,7 @@ hipError_t ss_launch_zero_counters(unsigned *counters, hipStream_t stream)
 
 size_t ss_packed_bytes(int rows, int K)
 {
-    return (size_t)((rows + 15) / 16) * (size_t)((K + 63) / 64) * 8192;
+    return (size_t)((rows + 15) / 16) * (size_t)((K + 63) / 64) * (TILE * 16);
 }
 
 hipError_t ss_launch_pack_matrix(const u64 *src, void *dst, int n, int rows, int K, size_t party_stride,
@@ -733,7 +766,7 @@ hipError_t ss_launch_planes(const u64 *in, u64 *shares, void *planes, int n, int
     // million elements on, four per thread move the data with fewer instructions
     const bool big = (size_t)B * HW * C >= ((size_t)1 << 19);
     const dim3 grid((B * HW + 15) / 16, big ? C / 64 : C / 16), block(256);
-    const size_t party_bytes = (size_t)8 * B * HW * C + 256;
+    const size_t party_bytes = ss_planes_bytes(B, C, HW, 1);
 #define SS_PLANES(NC, TC, G)                                                                                        \
     do {                                                                                                            \
         if (big)                                                                                                    \
@@ -777,7 +810,7 @@ hipError_t launch_gemm(const void *packedA, const void *packedB, const conv_plan
                        unsigned *counters, u64 *partials, hipStream_t stream)
 {
     static bool lds_opt_in = false;
-    constexpr int LDS_BYTES = 2 * 4096 * 16;
+    constexpr int LDS_BYTES = 2 * 8 * TILE * 16;
     if (!lds_opt_in) {
         hipError_t e = hipFuncSetAttribute((const void *)gemm_limb_kernel<false>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
@@ -819,7 +852,7 @@ hipError_t launch_gemm(const void *packedA, const void *packedB, const conv_plan
         g.planes = (const v4i *)cv->planes;
         g.plane16 = (unsigned)(plane / 16);
         g.party16 = (unsigned)(ss_planes_bytes(cv->B, cv->C, cv->H, cv->W) / 16);
-        g.zero = g.planes + (size_t)8 * g.plane16;   // the pad behind the first party's planes
+        g.zero = g.planes + (size_t)NL * g.plane16;   // the pad behind the first party's planes
         g.cvH = cv->H, g.cvW = cv->W, g.cvC16 = cv->C / 16, g.cvKw = cv->kw, g.cvStride = cv->stride, g.cvPad = cv->pad;
         g.cvHoWo = cv->Ho * cv->Wo, g.cvWo = cv->Wo, g.cvKbTap = cv->C / 64;
     }
@@ -841,7 +874,7 @@ hipError_t launch_gemm(const void *packedA, const void *packedB, const conv_plan
 
 size_t ss_planes_bytes(int B, int C, int H, int W)
 {
-    return (size_t)8 * B * H * W * C + 256;   // eight limb planes and a pad that starts with 16 zero bytes
+    return (size_t)NL * B * H * W * C + 256;   // the limb planes and a pad that starts with 16 zero bytes
 }
 
 hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, int n, int rows, int cols, int K,

@@ -245,7 +245,7 @@ int ssnet_create(ssnet_ctx **out, int n, int t, uint64_t p, int f, uint64_t seed
 {
     if (!out) return SSNET_EINVAL;
     *out = nullptr;
-    if (p != SSNET_P61) return SSNET_EPRIME;
+    if (p != SS_P) return SSNET_EPRIME;
     if (t < 1 || t > SSNET_MAX_T || n < 2 * t + 1 || n > SSNET_MAX_PARTIES || f < 1 || f > 31) return SSNET_EINVAL;
     ssnet_ctx *c = new (std::nothrow) ssnet_ctx();
     if (!c) return SSNET_EINVAL;
@@ -871,6 +871,8 @@ static bool make_pool_geom(size_t planes, int H, int W, int kh, int kw, int sh, 
 
 }  // namespace
 
+uint64_t ssnet_field_prime(void) { return SS_P; }
+
 int ssnet_pool_out_size(int H, int k, int s, int pad)
 {
     if (H < 1 || k < 1 || s < 1 || pad < 0 || k > H + 2 * pad) return 0;
@@ -948,7 +950,7 @@ const char *ssnet_strerror(int code)
     switch (code) {
         case SSNET_OK: return "ok";
         case SSNET_EINVAL: return "invalid argument";
-        case SSNET_EPRIME: return "unsupported prime (only 2^61-1)";
+        case SSNET_EPRIME: return "this library was built for another prime (see ssnet_field_prime)";
         case SSNET_ESHARES: return "too few shares for this degree";
         case SSNET_EID: return "party id out of range or repeated";
         case SSNET_EWORKSPACE: return "workspace missing or too small";

@@ -332,7 +332,7 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_kernel(const u64 *c, u64 
 //  * sums stay unreduced ("lazy", any 64-bit word of the right residue) until
 //    a value is stored or multiplied.
 
-// sum of v * c over at most 8 terms, v canonical given as v = w0 + w1 2^31, |c| < 2^26
+// sum of v * c over at most 8 terms, v canonical given as v = w0 + w1 2^31 (w0 < 2^31), |c| < 2^26
 struct ss_sacc2 {
     long long lo, hi;
     __device__ __forceinline__ void clear() { lo = 0; hi = 0; }
@@ -343,9 +343,16 @@ struct ss_sacc2 {
     }
     __device__ __forceinline__ u64 value() const
     {
+#if defined(SS_FIELD_P45)
+        // here |hi| < 2^43 (w1 < 2^14).  Offsets that are multiples of p make both words positive;
+        // h 2^31 with h = a 2^14 + b: a 2^45 + b 2^31 = 55 a + b 2^31
+        const u64 l = (u64)(lo + (long long)(SS_P << 16)), h = (u64)(hi + (long long)SS_P);   // < 2^62, < 2^46
+        return ss_reduce(l + SS_PC * (h >> 14) + ((h & 0x3FFFull) << 31));
+#else
         const u64 l = (u64)(lo + (long long)SS_P), h = (u64)(hi + (long long)SS_P);   // in (2^60, 2^62)
         // h 2^31 with 2^61 = 1: low 30 bits of h shifted, the rest wraps to weight 1
         return ss_reduce(l + ((h & 0x3FFFFFFFull) << 31) + (h >> 30));
+#endif
     }
 };
 #define SS_SPLIT31(v, w0, w1) const u32 w0 = (u32)(v)&0x7FFFFFFFu, w1 = (u32)((v) >> 31)
@@ -511,7 +518,7 @@ __global__ __launch_bounds__(BLOCK) void layer_tail_kernel(const u64 *c, u64 *__
     const int pix = blockIdx.x * 16 + r16, c0 = blockIdx.y * 16 + 4 * (threadIdx.x >> 6);
     const size_t count = (size_t)B * HW * C;
     if (planes && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < N)
-        *reinterpret_cast<int4 *>(planes + threadIdx.x * party_bytes + 8 * count) = make_int4(0, 0, 0, 0);
+        *reinterpret_cast<int4 *>(planes + threadIdx.x * party_bytes + SS_NLIMB * count) = make_int4(0, 0, 0, 0);
     const bool live = pix < B * HW && c0 + j < C;
     u64 dig[N];
 #pragma unroll
@@ -536,7 +543,7 @@ __global__ __launch_bounds__(BLOCK) void layer_tail_kernel(const u64 *c, u64 *__
         u64 y[4];
 #pragma unroll
         for (int q = 0; q < 4; q++) y[q] = __shfl(dig[p], r16 + 16 * q);
-        if (live) {
+        if (live && 2 * j < SS_NLIMB) {
             u32 *bp = reinterpret_cast<u32 *>(planes + p * party_bytes + (size_t)pix * C + c0);
             bp[(2 * j) * (count / 4)] = limb_dword(y, 2 * j);
             bp[(2 * j + 1) * (count / 4)] = limb_dword(y, 2 * j + 1);
@@ -739,11 +746,21 @@ __device__ __forceinline__ u64 mask_beta(const ss_nl_params &np, u64 counter)
 
 __device__ __forceinline__ u64 field_inverse(u64 beta)
 {
+#if defined(SS_FIELD_P45)
+    // beta^(p - 2), p - 2 = 2^45 - 57: square and multiply from the top bit down
+    u64 inv = beta;
+    for (int bit = SS_PBITS - 2; bit >= 0; bit--) {
+        inv = ss_mul(inv, inv);
+        if (((SS_P - 2) >> bit) & 1) inv = ss_mul(inv, beta);
+    }
+    return inv;
+#else
     // beta^(2^61 - 3): the exponent is 59 one bits, then 0, then 1
     u64 inv = beta;
     for (int i = 0; i < 58; i++) inv = ss_mul(ss_mul(inv, inv), beta);   // beta^(2^59 - 1)
     inv = ss_mul(inv, inv);                                              // bit 1 of the exponent is 0
     return ss_mul(ss_mul(inv, inv), beta);                               // bit 0 is 1
+#endif
 }
 
 __global__ __launch_bounds__(BLOCK) void nonlinear_masks_kernel(u64 *__restrict__ sh_b, u64 *__restrict__ sh_bi,
@@ -1043,7 +1060,7 @@ hipError_t ss_launch_layer_tail(const u64 *c, u64 *msg1, u64 *msg2, u64 *umsg, u
                                 hipStream_t stream)
 {
     const dim3 grid((B * HW + 15) / 16, (C + 15) / 16), block(BLOCK);
-    const size_t party_bytes = (size_t)8 * B * HW * C + 256;
+    const size_t party_bytes = ss_planes_bytes(B, C, HW, 1);
     if (dp.n == 5 && dp.t == 2)
         hipLaunchKernelGGL((layer_tail_kernel<5, 2>), grid, block, 0, stream, c, msg1, msg2, umsg, wsh, rmsg, yplain, sh_b,
                            sh_bi, out, (signed char *)planes, B, C, HW, party_bytes, dp, tp, np);

@@ -56,8 +56,8 @@ def np_post(y, post):
     raise ValueError(post)
 
 
-def np_signed_to_field(v):
-    return np.where(v < 0, v + P61, v).astype(np.uint64)
+def np_signed_to_field(v, p=P61):
+    return np.where(v < 0, v + p, v).astype(np.uint64)
 
 
 def oracle_layer(L, l, x_plain, n, t, f, seed, wseed_base=100):
@@ -134,54 +134,58 @@ def run_chain_parity(depth, n, t, f, seed, full_every=1):
     return worst_float
 
 
-def run_secure_chain_parity(depth, n, t, f, seed, pool_on_shares=False):
+def run_secure_chain_parity(depth, n, t, f, seed, pool_on_shares=False, p=P61):
     """The stack with ReLU on shares (SSS-NonLinear): every layer's output shares against an
     oracle chain of its own, and the opened logits against the chain that opens every layer.
     With pool_on_shares the two pooling points stay on shares too (mask equal inside a pooling
     kernel, division of the average inside the truncation): nothing but the logits is opened."""
     layers = resnet_chain(depth)
-    ss = SSNet(n, t, f=f, seed=seed)
+    ss = SSNet(n, t, f=f, seed=seed, p=p)
     chain = Chain(ss, layers)
     chain.secure_setup(pool_on_shares)
     x_plain_g, x_sh_g = chain.image, None
-    x_plain_o, x_sh_o = orc.encode(gaussian((1, 3, 224, 224), 5), f, P61), None
+    x_plain_o, x_sh_o = orc.encode(gaussian((1, 3, 224, 224), 5), f, p), None
     t0 = time.time()
     rec_g = rec_o = None
     for l, L in enumerate(layers):
         shape = (L.cout, L.cin, L.ksize, L.ksize) if L.kind == "conv" else (L.cin, L.cout)
-        ws = orc.share(orc.encode(he_normal(shape, L.K, 100 + l), f, P61), n, t, P61, seed, WEIGHT_STREAM_BASE + l)
+        ws = orc.share(orc.encode(he_normal(shape, L.K, 100 + l), f, p), n, t, p, seed, WEIGHT_STREAM_BASE + l)
         if x_sh_o is None:
             if L.kind == "fc":
                 x_plain_g, x_plain_o = x_plain_g.reshape(1, -1), x_plain_o.reshape(1, -1)
             assert np.array_equal(to_np(x_plain_g), x_plain_o), f"layer {l}: plain input"
-            x_sh_o = orc.share(x_plain_o, n, t, P61, seed, l)
+            x_sh_o = orc.share(x_plain_o, n, t, p, seed, l)
         elif L.kind == "fc":
             x_sh_o = x_sh_o.reshape(n, 1, -1)
-        y2 = orc.conv(x_sh_o, ws, L.stride, L.pad, P61) if L.kind == "conv" else orc.linear(x_sh_o, ws, P61)
+        y2 = orc.conv(x_sh_o, ws, L.stride, L.pad, p) if L.kind == "conv" else orc.linear(x_sh_o, ws, p)
         pooled = pool_on_shares and L.post in ("relu+maxpool3s2", "relu+gap")
         kdiv = L.hout * L.hout if pooled and L.post == "relu+gap" else 1
-        yr = orc.degree_reduce(y2.reshape(n, -1), n, t, P61, seed, l)
-        yt = orc.truncate_div(yr, n, t, f, kdiv, P61, seed, l) if kdiv > 1 else orc.truncate(yr, n, t, f, P61, seed, l)
+        yr = orc.degree_reduce(y2.reshape(n, -1), n, t, p, seed, l)
+        yt = orc.truncate_div(yr, n, t, f, kdiv, p, seed, l) if kdiv > 1 else orc.truncate(yr, n, t, f, p, seed, l)
         x_sh_g, rec_g = chain.secure_layer(l, None if x_sh_g is not None else x_plain_g.contiguous(), x_sh_g)
+        if L.post is not None:
+            # the multiplicative mask must not wrap: (elements summed by the pooling) * |x| * 2^28 < p/2
+            peak = int(np.abs(orc.lift(orc.reconstruct(yt, list(range(1, t + 2)), p), p)).max())
+            assert peak * (kdiv << 28) < p // 2, f"layer {l}: activation {peak} outside the mask's range"
         if L.post == "relu":
-            sb, sbi = orc.nonlinear_masks(yt[0].size, n, t, 28, P61, seed, Chain.MASK_STREAM_BASE + l)
-            x_sh_o = orc.relu(yt, sb, sbi, n, t, P61).reshape(y2.shape)
+            sb, sbi = orc.nonlinear_masks(yt[0].size, n, t, 28, p, seed, Chain.MASK_STREAM_BASE + l)
+            x_sh_o = orc.relu(yt, sb, sbi, n, t, p).reshape(y2.shape)
             assert np.array_equal(to_np(x_sh_g), x_sh_o), f"layer {l}: shares after ReLU"
         elif pooled:
             geo = ((L.hout, L.hout, 3, 3, 2, 2, 1, 1, orc.POOL_MAX) if L.post == "relu+maxpool3s2"
                    else (L.hout, L.hout, L.hout, L.hout, L.hout, L.hout, 0, 0, orc.POOL_SUM))
-            sb, sbi = orc.pool_masks(L.cout, *geo[:8], n, t, 28, P61, seed, Chain.MASK_STREAM_BASE + l)
-            x_sh_o = orc.relu_pool(yt, sb, sbi, L.cout, *geo, n, t, P61)
+            sb, sbi = orc.pool_masks(L.cout, *geo[:8], n, t, 28, p, seed, Chain.MASK_STREAM_BASE + l)
+            x_sh_o = orc.relu_pool(yt, sb, sbi, L.cout, *geo, n, t, p)
             ho = orc.pool_out_size(L.hout, geo[2], geo[4], geo[6])
             x_sh_o = x_sh_o.reshape(n, 1, L.cout, ho, ho)
             assert np.array_equal(to_np(x_sh_g), x_sh_o), f"layer {l}: shares after ReLU and pooling"
         else:
-            rec_o = orc.reconstruct(yt, list(range(1, t + 2)), P61).reshape(y2.shape[1:])
+            rec_o = orc.reconstruct(yt, list(range(1, t + 2)), p).reshape(y2.shape[1:])
             assert x_sh_g is None and np.array_equal(to_np(rec_g), rec_o), f"layer {l}: opened result"
             x_sh_o = None
             if L.post is not None:
-                x_plain_g = fx.from_signed(post_plain(fx.lift(rec_g), L.post))
-                x_plain_o = np_signed_to_field(np_post(orc.lift(rec_o, P61), L.post))
+                x_plain_g = fx.from_signed(post_plain(fx.lift(rec_g, p), L.post), p)
+                x_plain_o = np_signed_to_field(np_post(orc.lift(rec_o, p), L.post), p)
         if l % 10 == 0:
             say(f"secure resnet{depth} layer {l}/{len(layers)} ok ({time.time() - t0:.0f} s)")
     logits = to_np(chain.secure_prepare(pool_on_shares)).copy()
@@ -197,7 +201,7 @@ def run_secure_chain_parity(depth, n, t, f, seed, pool_on_shares=False):
         # the average folded into the truncation rounds every element before the sum (App. C): each of
         # the 2048 pooled inputs of the classifier moves by a few units of 2^-f, the logits by little
         assert all(p is None for p in chain.secure_plain[1:])          # nothing was opened on the way
-        dev = np.abs(orc.decode(plain, f, P61) - orc.decode(logits, f, P61)).max()
+        dev = np.abs(orc.decode(plain, f, p) - orc.decode(logits, f, p)).max()
         say(f"resnet{depth} pooling on shares: max |logit - logit of the opened chain| = {dev:.3g}")
         assert dev < 2.0 ** -6
 
@@ -210,6 +214,13 @@ def test_resnet50_stack_with_relu_on_shares():
 @pytest.mark.timeout(900)
 def test_resnet50_stack_with_relu_and_pooling_on_shares():
     run_secure_chain_parity(50, 5, 2, 13, seed=20240602, pool_on_shares=True)
+
+
+@pytest.mark.timeout(900)
+def test_resnet50_stack_over_the_45_bit_prime():
+    """The library built for p = 2^45 - 55 (Sec. VII-A): the whole stack on shares, only the logits opened.
+    f = 12 keeps every activation inside the 16-bit budget the masks of Sec. VII-B assume."""
+    run_secure_chain_parity(50, 5, 2, 12, seed=20240602, pool_on_shares=True, p=(1 << 45) - 55)
 
 
 @pytest.mark.timeout(600)

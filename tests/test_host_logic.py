@@ -169,3 +169,37 @@ def test_pooling_entry_points_check_their_arguments():
         assert lib.ssnet_truncate_div(ctx, 16, 8, kdiv, 0, 16) == binding.EINVAL
         assert lib.ssnet_degree_reduce_truncate_div(ctx, 16, 8, kdiv, 0, 16) == binding.EINVAL
     assert lib.ssnet_truncate_div(ctx, 16, 8, 4, 0, 16) == binding.EWORKSPACE
+
+
+# ----------------------------------------------------------------- the second library, over p = 2^45 - 55
+P45 = (1 << 45) - 55
+
+
+def test_p45_library_exports_the_same_abi_and_knows_its_prime():
+    lib61, lib45 = binding.load_library(), binding.load_library(P45)
+    assert lib61 is not lib45
+    for name in binding.SIGNATURES:
+        assert hasattr(lib45, name), name
+    assert lib61.ssnet_field_prime() == P61 and lib45.ssnet_field_prime() == P45 == binding.P45
+    assert SSNet(5, 2, p=P45, device=None).lib is lib45
+    for lib, other in ((lib61, P45), (lib45, P61)):
+        ctx = C.c_void_p()
+        assert lib.ssnet_create(C.byref(ctx), 3, 1, other, 13, 0, None) == binding.EPRIME
+    # six limbs per element: tiles and planes are three quarters the size
+    assert lib45.ssnet_packed_weight_bytes(16, 64) == 6 * 1024 and lib61.ssnet_packed_weight_bytes(16, 64) == 8 * 1024
+    assert lib45.ssnet_conv_planes_bytes(1, 64, 8, 8) == 6 * 64 * 64 + 256
+
+
+@pytest.mark.parametrize("n,t", [(3, 1), (5, 2), (7, 3), (8, 2)])
+def test_p45_host_tables_and_generator_match_oracle(n, t):
+    import itertools
+    s = SSNet(n, t, p=P45, device=None)
+    assert s.host_reduction_matrix() == [[int(v) for v in r] for r in orc.red_matrix(n, t, P45)]
+    for m in (t + 1, 2 * t + 1):
+        for ids in list(itertools.combinations(range(1, n + 1), m))[:8]:
+            assert s.host_lagrange(ids) == [int(v) for v in orc.lagrange(list(ids), P45)]
+    # a field element is (draw >> 3) mod p
+    key = binding.rng_key(7, 1, 2, 3, 4)
+    for e in range(64):
+        d = binding.rng_draw(key, e)
+        assert binding.rng_field(key, e, P45) == (d >> 3) % P45 == orc.draw_field(key, e, P45)
