@@ -222,6 +222,39 @@ def secure_chain(chain, ss, steps, warmup, macs, out_elems, pool_on_shares=False
             "relu_elements_per_step": relu_elems}
 
 
+def p45_chain(layers, steps, warmup, batch=1):
+    """The headline step over the paper's own prime p = 2^45 - 55 (Sec. VII-A), on the second library: the same
+    shapes, scheme and steps; a field element has six int8 limbs, so a field multiply-add is 36 int8
+    multiply-adds instead of 64.  Another field, so another workload: reported beside the headline."""
+    import torch
+    from paper_2406_02629_amd import P45, SSNet
+    from paper_2406_02629_amd.chain import Chain
+    ss = SSNet(5, 2, f=13, seed=20240602, p=P45)
+    chain = Chain(ss, layers, batch=batch)
+    chain.forward_prepare()
+    torch.cuda.synchronize()
+    for _ in range(warmup):
+        chain.forward_timed()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        chain.forward_timed()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    ss.profile_begin()
+    chain.forward_timed()
+    prof = ss.profile_end()
+    macs = chain.total_field_macs()
+    ops = macs * 2 * 36
+    gemm_ms, gemm_launches = prof["gemm"]
+    return {"workload": f"headline stack over p = 2^45 - 55 (libssnet_p45.so), n=5 t=2 f=13 batch {batch}",
+            "ms_per_step": ms, "field_MAC_per_s": macs / (ms * 1e-3),
+            "kernel_ms_per_step": {k: {"ms": round(v[0], 4), "spans": int(v[1])} for k, v in prof.items() if v[1]},
+            "roofline": {"bound": "mfma", "kernel": "gemm_limb_kernel (6 limbs)", "achieved": ops / (gemm_ms * 1e-3) / 1e12,
+                         "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": ops / (gemm_ms * 1e-3) / 1e12 / INT8_PEAK_TOPS,
+                         "launches": int(gemm_launches), "int8_ops_per_step": ops}}
+
+
 def batch8_chain(chain, ss, layers, steps, warmup):
     """The headline step at batch 8 (the paper also reports batched inference): eight images through the same
     prepared weights.  M grows eightfold, so a launch has enough tiles to amortise its fixed cost."""
@@ -263,6 +296,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-secure", action="store_true", help="skip the pass with ReLU on shares")
     ap.add_argument("--no-batch8", action="store_true", help="skip the batch-8 pass of the same stack")
+    ap.add_argument("--no-p45", action="store_true", help="skip the passes over the prime 2^45 - 55")
     ap.add_argument("--cpu-layers", type=int, default=152)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale profiler counters)")
@@ -345,6 +379,10 @@ def main():
                                                                  pool_on_shares=True)
     if not args.no_batch8:
         result["batch8"] = batch8_chain(chain, ss, layers, max(args.steps // 4, 2), 1)
+    if not args.no_p45:
+        result["paper_prime_p45"] = p45_chain(layers, args.steps, args.warmup)
+        if not args.no_batch8:
+            result["paper_prime_p45_batch8"] = p45_chain(layers, max(args.steps // 4, 2), 1, batch=8)
     if args.copy_calibration:
         src = torch.zeros(1 << 27, dtype=torch.int64, device="cuda")
         dst = torch.empty_like(src)
