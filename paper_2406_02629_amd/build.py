@@ -58,7 +58,8 @@ def build(force: bool = True, verbose: bool = False) -> str:
         objs = list(ex.map(compile_one, jobs))
     for v, tag in enumerate(VARIANTS):
         lib = VARIANTS[tag][0]
-        cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib + ".tmp",
+        # -Bsymbolic: references inside a library bind to that library, also when both are loaded globally
+        cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-Wl,-Bsymbolic", "-o", lib + ".tmp",
                *objs[v * len(SOURCES):(v + 1) * len(SOURCES)]]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:

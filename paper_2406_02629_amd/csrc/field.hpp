@@ -32,6 +32,7 @@ SS_HD u64 ss_mulhi(u64 a, u64 b)
 #define SS_P 0x1FFFFFFFFFC9ULL   // 2^45 - 55 = 35184372088777, the prime of Sec. VII-A
 #define SS_PBITS 45
 #define SS_NLIMB 6             // balanced 8-bit digits of a field element
+#define SS_NS ss45             // namespace of this build's kernels and launchers
 #define SS_PC 55ULL            // 2^45 = 55 (mod p)
 #define SS_PMASK ((1ULL << 45) - 1)
 
@@ -100,6 +101,8 @@ SS_HD u64 ss_mul_small(u64 x, u32 c) { return ss_reduce(x * (u64)c); }
 #define SS_P 0x1FFFFFFFFFFFFFFFULL
 #define SS_PBITS 61
 #define SS_NLIMB 8   // balanced 8-bit digits of a field element
+#define SS_NS ss61   // namespace of this build's kernels and launchers
+
 // x < 2^64  ->  result < 2^61 + 8, same residue
 SS_HD u64 ss_fold(u64 x) { return (x & SS_P) + (x >> 61); }
 

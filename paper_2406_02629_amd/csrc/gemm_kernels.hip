@@ -19,6 +19,8 @@
 #include "eval.hpp"
 #include "digits.hpp"
 
+namespace SS_NS {
+
 typedef int v4i __attribute__((ext_vector_type(4)));
 
 namespace {
@@ -895,3 +897,5 @@ hipError_t ss_launch_gemm_conv(const void *packedW, const void *planes, u64 *out
     return launch_gemm(packedW, nullptr, &cv, out, n, Co, (int)(B * HW), C * kh * kw, (size_t)B * Co * HW, HW, (int)HW,
                        (size_t)Co * HW, counters, partials, stream);
 }
+
+}  // namespace SS_NS

@@ -3,6 +3,10 @@
 #pragma once
 #include "field.hpp"
 
+// Everything below lives in a namespace named after the field (ss61 / ss45), so that the two libraries built
+// from these sources never share a C++ symbol or a kernel name.
+namespace SS_NS {
+
 #define SS_MAXDEG (2 * SS_MAXT)   // highest polynomial degree ssnet_share accepts
 
 struct ss_keys {                  // generator keys, one per coefficient index j = 1..
@@ -134,3 +138,5 @@ hipError_t ss_launch_zero_counters(unsigned *counters, hipStream_t stream);
 hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, int n, int rows, int cols, int K,
                           size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb, unsigned *counters,
                           u64 *partials, hipStream_t stream);
+
+}  // namespace SS_NS

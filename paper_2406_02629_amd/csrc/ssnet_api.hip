@@ -9,6 +9,8 @@
 
 #include "kernels.hpp"
 
+using namespace SS_NS;
+
 struct ssnet_ctx {
     int n, t, f;
     u64 seed;

@@ -8,6 +8,8 @@
 #include "eval.hpp"
 #include "digits.hpp"
 
+namespace SS_NS {
+
 namespace {
 
 constexpr int BLOCK = 256;
@@ -1071,3 +1073,5 @@ hipError_t ss_launch_layer_tail(const u64 *c, u64 *msg1, u64 *msg2, u64 *umsg, u
         return hipErrorInvalidValue;   // the caller runs the separate kernels for other schemes
     return hipGetLastError();
 }
+
+}  // namespace SS_NS
