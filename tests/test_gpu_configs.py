@@ -134,17 +134,18 @@ def run_chain_parity(depth, n, t, f, seed, full_every=1):
     return worst_float
 
 
-def run_secure_chain_parity(depth, n, t, f, seed, pool_on_shares=False, p=P61):
+def run_secure_chain_parity(depth, n, t, f, seed, pool_on_shares=False, p=P61, layers=None, batch=1):
     """The stack with ReLU on shares (SSS-NonLinear): every layer's output shares against an
     oracle chain of its own, and the opened logits against the chain that opens every layer.
     With pool_on_shares the two pooling points stay on shares too (mask equal inside a pooling
     kernel, division of the average inside the truncation): nothing but the logits is opened."""
-    layers = resnet_chain(depth)
+    layers = resnet_chain(depth) if layers is None else layers
+    B = batch
     ss = SSNet(n, t, f=f, seed=seed, p=p)
-    chain = Chain(ss, layers)
+    chain = Chain(ss, layers, batch=B)
     chain.secure_setup(pool_on_shares)
     x_plain_g, x_sh_g = chain.image, None
-    x_plain_o, x_sh_o = orc.encode(gaussian((1, 3, 224, 224), 5), f, p), None
+    x_plain_o, x_sh_o = orc.encode(gaussian((B, layers[0].cin, layers[0].hin, layers[0].hin), 5), f, p), None
     t0 = time.time()
     rec_g = rec_o = None
     for l, L in enumerate(layers):
@@ -152,11 +153,11 @@ def run_secure_chain_parity(depth, n, t, f, seed, pool_on_shares=False, p=P61):
         ws = orc.share(orc.encode(he_normal(shape, L.K, 100 + l), f, p), n, t, p, seed, WEIGHT_STREAM_BASE + l)
         if x_sh_o is None:
             if L.kind == "fc":
-                x_plain_g, x_plain_o = x_plain_g.reshape(1, -1), x_plain_o.reshape(1, -1)
+                x_plain_g, x_plain_o = x_plain_g.reshape(B, -1), x_plain_o.reshape(B, -1)
             assert np.array_equal(to_np(x_plain_g), x_plain_o), f"layer {l}: plain input"
             x_sh_o = orc.share(x_plain_o, n, t, p, seed, l)
         elif L.kind == "fc":
-            x_sh_o = x_sh_o.reshape(n, 1, -1)
+            x_sh_o = x_sh_o.reshape(n, B, -1)
         y2 = orc.conv(x_sh_o, ws, L.stride, L.pad, p) if L.kind == "conv" else orc.linear(x_sh_o, ws, p)
         pooled = pool_on_shares and L.post in ("relu+maxpool3s2", "relu+gap")
         kdiv = L.hout * L.hout if pooled and L.post == "relu+gap" else 1
@@ -174,10 +175,10 @@ def run_secure_chain_parity(depth, n, t, f, seed, pool_on_shares=False, p=P61):
         elif pooled:
             geo = ((L.hout, L.hout, 3, 3, 2, 2, 1, 1, orc.POOL_MAX) if L.post == "relu+maxpool3s2"
                    else (L.hout, L.hout, L.hout, L.hout, L.hout, L.hout, 0, 0, orc.POOL_SUM))
-            sb, sbi = orc.pool_masks(L.cout, *geo[:8], n, t, 28, p, seed, Chain.MASK_STREAM_BASE + l)
-            x_sh_o = orc.relu_pool(yt, sb, sbi, L.cout, *geo, n, t, p)
+            sb, sbi = orc.pool_masks(B * L.cout, *geo[:8], n, t, 28, p, seed, Chain.MASK_STREAM_BASE + l)
+            x_sh_o = orc.relu_pool(yt, sb, sbi, B * L.cout, *geo, n, t, p)
             ho = orc.pool_out_size(L.hout, geo[2], geo[4], geo[6])
-            x_sh_o = x_sh_o.reshape(n, 1, L.cout, ho, ho)
+            x_sh_o = x_sh_o.reshape(n, B, L.cout, ho, ho)
             assert np.array_equal(to_np(x_sh_g), x_sh_o), f"layer {l}: shares after ReLU and pooling"
         else:
             rec_o = orc.reconstruct(yt, list(range(1, t + 2)), p).reshape(y2.shape[1:])
@@ -214,6 +215,17 @@ def test_resnet50_stack_with_relu_on_shares():
 @pytest.mark.timeout(900)
 def test_resnet50_stack_with_relu_and_pooling_on_shares():
     run_secure_chain_parity(50, 5, 2, 13, seed=20240602, pool_on_shares=True)
+
+
+@pytest.mark.parametrize("n,t,p", [(3, 1, P61), (5, 2, P61), (7, 3, P61), (5, 2, (1 << 45) - 55)])
+def test_small_stack_batch_3_with_pooling_on_shares(n, t, p):
+    """Three images through a short stack (stem with overlapping max-pool, 1x1 and 3x3 layers on limb planes,
+    global average, classifier), everything on shares: batched planes for masks and pooling, other schemes."""
+    from ssnet_inputs import Layer
+    layers = [Layer("conv", 3, 64, 7, 2, 3, 30, 15, "relu+maxpool3s2"), Layer("conv", 64, 64, 1, 1, 0, 8, 8, "relu"),
+              Layer("conv", 64, 128, 3, 2, 1, 8, 4, "relu"), Layer("conv", 128, 70, 1, 1, 0, 4, 4, "relu+gap"),
+              Layer("fc", 70, 10, 1, 1, 0, 1, 1, None)]
+    run_secure_chain_parity(0, n, t, 12, seed=77, pool_on_shares=True, p=p, layers=layers, batch=3)
 
 
 @pytest.mark.timeout(900)
