@@ -255,6 +255,35 @@ def p45_chain(layers, steps, warmup, batch=1):
                          "launches": int(gemm_launches), "int8_ops_per_step": ops}}
 
 
+def gemm_by_shape(chain, ss, reps=20):
+    """The product kernel of every distinct layer shape of the stack on its own: launch time (HIP events inside
+    the library), int8 rate, and the two bounds of a launch: MFMA time at the nominal rate, and the time to read
+    the operands (weight and activation limb tiles of all parties) once from HBM at 8 TB/s.  For the 7x7 maps
+    (49 output pixels) the weight read is within a small factor of the MFMA time."""
+    import torch
+    seen, rows = {}, []
+    for l, L in enumerate(chain.layers):
+        seen.setdefault((L.M * chain.batch, L.K, L.N, L.ksize), []).append(l)
+    for (M, K, N, ksize), ls in seen.items():
+        l = ls[0]
+        chain.run_layer(l, chain.x_plain[l], "sg")
+        torch.cuda.synchronize()
+        ss.profile_begin()
+        for _ in range(reps):
+            chain.run_layer(l, chain.x_plain[l], "sg")
+        prof = ss.profile_end()
+        us = prof["gemm"][0] * 1e3 / prof["gemm"][1]
+        ops = ss.n * M * K * N * OPS_PER_FIELD_MAC
+        operand_bytes = ss.n * 8 * (N * K + chain.layers[l].hin ** 2 * chain.batch * chain.layers[l].cin
+                                    if chain.layers[l].kind == "conv" and ksize > 1 and chain.on_planes[l]
+                                    else N * K + M * K)
+        rows.append({"M": M, "K": K, "N": N, "kernel": f"{ksize}x{ksize}", "layers": len(ls), "us": round(us, 2),
+                     "TOP/s": round(ops / us / 1e6, 1), "frac": round(ops / us / 1e6 / INT8_PEAK_TOPS, 3),
+                     "mfma_bound_us": round(ops / INT8_PEAK_TOPS / 1e6, 2),
+                     "operand_read_bound_us": round(operand_bytes / 8e12 * 1e6, 2)})
+    return rows
+
+
 def batch8_chain(chain, ss, layers, steps, warmup):
     """The headline step at batch 8 (the paper also reports batched inference): eight images through the same
     prepared weights.  M grows eightfold, so a launch has enough tiles to amortise its fixed cost."""
@@ -377,6 +406,7 @@ def main():
         result["nonlinear_on_shares"] = secure_chain(chain, ss, args.steps, args.warmup, macs, out_elems)
         result["nonlinear_and_pooling_on_shares"] = secure_chain(chain, ss, args.steps, args.warmup, macs, out_elems,
                                                                  pool_on_shares=True)
+    result["gemm_by_shape"] = gemm_by_shape(chain, ss)
     if not args.no_batch8:
         result["batch8"] = batch8_chain(chain, ss, layers, max(args.steps // 4, 2), 1)
     if not args.no_p45:
