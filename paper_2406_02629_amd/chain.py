@@ -39,6 +39,8 @@ def pool_spec(L: Layer):
     """-> (kernel, stride, pad, mode, kdiv) of the pooling that follows layer L, or None"""
     if L.post == "relu+maxpool3s2":
         return (3, 3), (2, 2), (1, 1), SSNet.POOL_MAX, 1
+    if L.post == "relu+maxpool2s2":
+        return (2, 2), (2, 2), (0, 0), SSNet.POOL_MAX, 1
     if L.post == "relu+gap":
         return (L.hout, L.hout), (L.hout, L.hout), (0, 0), SSNet.POOL_SUM, L.hout * L.hout
     return None
@@ -54,6 +56,9 @@ def post_plain(y: torch.Tensor, post: Optional[str]) -> torch.Tensor:
     if post == "relu+maxpool3s2":
         # values are below 2^53, so the float64 detour is exact
         z = torch.nn.functional.max_pool2d(y.to(torch.float64), kernel_size=3, stride=2, padding=1)
+        return z.to(torch.int64)
+    if post == "relu+maxpool2s2":
+        z = torch.nn.functional.max_pool2d(y.to(torch.float64), kernel_size=2, stride=2)
         return z.to(torch.int64)
     if post == "relu+gap":
         hw = y.shape[-1] * y.shape[-2]

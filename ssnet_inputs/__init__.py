@@ -42,7 +42,7 @@ class Layer:
     hin: int             # input spatial size (square); 1 for fc
     hout: int
     post: Optional[str]  # plaintext step applied by the harness after this layer:
-    #                      "relu", "relu+maxpool3s2", "relu+gap", or None (last layer)
+    #                      "relu", "relu+maxpool3s2", "relu+maxpool2s2", "relu+gap", or None (last layer)
 
     @property
     def M(self) -> int:
@@ -89,4 +89,22 @@ def resnet_chain(depth: int, image: int = 224, classes: int = 1000) -> List[Laye
                                 "relu+gap" if last else "relu"))
             cin = 4 * width
     layers.append(Layer("fc", cin, classes, 1, 1, 0, 1, 1, None))
+    return layers
+
+
+def vgg16_chain(image: int = 32, classes: int = 10, hidden: int = 4096) -> List[Layer]:
+    """Layers of a VGG16-shaped network for small images (the paper evaluates VGG16 on 32x32 and 64x64
+    inputs): thirteen 3x3 convolutions of widths 64,64 | 128,128 | 256x3 | 512x3 | 512x3, a 2x2 / 2 max-pool
+    after each group, then three dense layers.  No bias, no BatchNorm; 16 layers."""
+    layers: List[Layer] = []
+    h, cin = image, 3
+    for width, reps in ((64, 2), (128, 2), (256, 3), (512, 3), (512, 3)):
+        for r in range(reps):
+            layers.append(Layer("conv", cin, width, 3, 1, 1, h, h, "relu+maxpool2s2" if r == reps - 1 else "relu"))
+            cin = width
+        h //= 2
+    feat = cin * h * h
+    layers.append(Layer("fc", feat, hidden, 1, 1, 0, 1, 1, "relu"))
+    layers.append(Layer("fc", hidden, hidden, 1, 1, 0, 1, 1, "relu"))
+    layers.append(Layer("fc", hidden, classes, 1, 1, 0, 1, 1, None))
     return layers

@@ -17,7 +17,7 @@ import oracle as orc
 from paper_2406_02629_amd import SSNet
 from paper_2406_02629_amd import fixedpoint as fx
 from paper_2406_02629_amd.chain import WEIGHT_STREAM_BASE, Chain, post_plain
-from ssnet_inputs import gaussian, he_normal, resnet_chain, uniform_below
+from ssnet_inputs import gaussian, he_normal, resnet_chain, uniform_below, vgg16_chain
 from util import P61, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
@@ -51,6 +51,9 @@ def np_post(y, post):
             for s in range(3):
                 out = np.maximum(out, pad[:, :, r:r + 2 * Ho:2, s:s + 2 * Wo:2])
         return out
+    if post == "relu+maxpool2s2":
+        B, C, H, W = y.shape
+        return y[:, :, :H // 2 * 2, :W // 2 * 2].reshape(B, C, H // 2, 2, W // 2, 2).max(axis=(3, 5))
     if post == "relu+gap":
         return y.sum(axis=(-1, -2), keepdims=True) // (y.shape[-1] * y.shape[-2])
     raise ValueError(post)
@@ -159,7 +162,7 @@ def run_secure_chain_parity(depth, n, t, f, seed, pool_on_shares=False, p=P61, l
         elif L.kind == "fc":
             x_sh_o = x_sh_o.reshape(n, B, -1)
         y2 = orc.conv(x_sh_o, ws, L.stride, L.pad, p) if L.kind == "conv" else orc.linear(x_sh_o, ws, p)
-        pooled = pool_on_shares and L.post in ("relu+maxpool3s2", "relu+gap")
+        pooled = pool_on_shares and L.post in ("relu+maxpool3s2", "relu+maxpool2s2", "relu+gap")
         kdiv = L.hout * L.hout if pooled and L.post == "relu+gap" else 1
         yr = orc.degree_reduce(y2.reshape(n, -1), n, t, p, seed, l)
         yt = orc.truncate_div(yr, n, t, f, kdiv, p, seed, l) if kdiv > 1 else orc.truncate(yr, n, t, f, p, seed, l)
@@ -173,8 +176,9 @@ def run_secure_chain_parity(depth, n, t, f, seed, pool_on_shares=False, p=P61, l
             x_sh_o = orc.relu(yt, sb, sbi, n, t, p).reshape(y2.shape)
             assert np.array_equal(to_np(x_sh_g), x_sh_o), f"layer {l}: shares after ReLU"
         elif pooled:
-            geo = ((L.hout, L.hout, 3, 3, 2, 2, 1, 1, orc.POOL_MAX) if L.post == "relu+maxpool3s2"
-                   else (L.hout, L.hout, L.hout, L.hout, L.hout, L.hout, 0, 0, orc.POOL_SUM))
+            geo = {"relu+maxpool3s2": (L.hout, L.hout, 3, 3, 2, 2, 1, 1, orc.POOL_MAX),
+                   "relu+maxpool2s2": (L.hout, L.hout, 2, 2, 2, 2, 0, 0, orc.POOL_MAX),
+                   "relu+gap": (L.hout, L.hout, L.hout, L.hout, L.hout, L.hout, 0, 0, orc.POOL_SUM)}[L.post]
             sb, sbi = orc.pool_masks(B * L.cout, *geo[:8], n, t, 28, p, seed, Chain.MASK_STREAM_BASE + l)
             x_sh_o = orc.relu_pool(yt, sb, sbi, B * L.cout, *geo, n, t, p)
             ho = orc.pool_out_size(L.hout, geo[2], geo[4], geo[6])
@@ -226,6 +230,14 @@ def test_small_stack_batch_3_with_pooling_on_shares(n, t, p):
               Layer("conv", 64, 128, 3, 2, 1, 8, 4, "relu"), Layer("conv", 128, 70, 1, 1, 0, 4, 4, "relu+gap"),
               Layer("fc", 70, 10, 1, 1, 0, 1, 1, None)]
     run_secure_chain_parity(0, n, t, 12, seed=77, pool_on_shares=True, p=p, layers=layers, batch=3)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("batch,pool", [(1, True), (2, True), (1, False)])
+def test_vgg16_stack_three_parties(batch, pool):
+    """VGG16-shaped stack on 32 x 32 images, the paper's 3-party setting: 2 x 2 max-pools (one mask per kernel
+    position), dense layers with ReLU on share vectors."""
+    run_secure_chain_parity(0, 3, 1, 13, seed=16, pool_on_shares=pool, layers=vgg16_chain(32, 10, 512), batch=batch)
 
 
 @pytest.mark.timeout(900)
