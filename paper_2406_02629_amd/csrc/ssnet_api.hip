@@ -809,9 +809,19 @@ int ssnet_reduce_truncate_relu(ssnet_ctx *ctx, const uint64_t *d_c, int B, int C
     const ss_tr_params tp = make_tr_params(ctx, stream_id);
     hipError_t e;
     if ((n == 5 && ctx->t == 2) || (n == 3 && ctx->t == 1)) {
-        timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
-        e = ss_launch_layer_tail(d_c, msg1, msg2, u, wsh, rmsg, yplain, d_beta, d_betainv, d_out, d_planes, B, C, HW, dp,
-                                 tp, np, ctx->stream);
+        // from half a million elements on, the planes are written faster by the kernel that takes four
+        // channels per thread than by the tail's one-element threads
+        const bool planes_apart = d_planes && count >= ((size_t)1 << 19);
+        {
+            timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
+            e = ss_launch_layer_tail(d_c, msg1, msg2, u, wsh, rmsg, yplain, d_beta, d_betainv, d_out,
+                                     planes_apart ? nullptr : d_planes, B, C, HW, dp, tp, np, ctx->stream);
+        }
+        if (e == hipSuccess && planes_apart) {
+            const ss_keys none = {};
+            timed tm(ctx, SSNET_PROF_PACK_X);
+            e = ss_launch_planes(d_out, nullptr, d_planes, n, ctx->t, B, C, HW, false, none, ctx->stream);
+        }
     } else {   // other schemes: the same steps, messages and results in three launches
         const ss_recf_params norec = {};
         {
