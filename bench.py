@@ -284,7 +284,7 @@ def gemm_by_shape(chain, ss, reps=20):
     return rows
 
 
-def batch8_chain(chain, ss, layers, steps, warmup):
+def batch8_chain(chain, ss, layers, steps, warmup, secure=True):
     """The headline step at batch 8 (the paper also reports batched inference): eight images through the same
     prepared weights.  M grows eightfold, so a launch has enough tiles to amortise its fixed cost."""
     import torch
@@ -309,6 +309,11 @@ def batch8_chain(chain, ss, layers, steps, warmup):
            "gemm": {"ms": gemm_ms, "TOP/s": macs * OPS_PER_FIELD_MAC / (gemm_ms * 1e-3) / 1e12,
                     "frac": macs * OPS_PER_FIELD_MAC / (gemm_ms * 1e-3) / 1e12 / INT8_PEAK_TOPS},
            "kernel_ms_per_step": {k: {"ms": round(v[0], 4), "spans": int(v[1])} for k, v in prof.items() if v[1]}}
+    if secure:
+        # the eight images with ReLU and pooling on shares, only the logits opened
+        sec = secure_chain(c8, ss, steps, warmup, macs, 0, pool_on_shares=True)
+        res["nonlinear_and_pooling_on_shares"] = {"ms_per_step": sec["ms_per_step"], "field_MAC_per_s": sec["field_MAC_per_s"],
+                                                   "kernel_ms_per_step": sec["kernel_ms_per_step"]}
     del c8
     torch.cuda.empty_cache()
     return res
@@ -408,7 +413,7 @@ def main():
                                                                  pool_on_shares=True)
     result["gemm_by_shape"] = gemm_by_shape(chain, ss)
     if not args.no_batch8:
-        result["batch8"] = batch8_chain(chain, ss, layers, max(args.steps // 4, 2), 1)
+        result["batch8"] = batch8_chain(chain, ss, layers, max(args.steps // 4, 2), 1, secure=not args.no_secure)
     if not args.no_p45:
         result["paper_prime_p45"] = p45_chain(layers, args.steps, args.warmup)
         if not args.no_batch8:
