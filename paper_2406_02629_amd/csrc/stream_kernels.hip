@@ -375,6 +375,11 @@ __device__ __forceinline__ void reduce_truncate_fixed(size_t e, size_t count, si
         for (int j = 0; j < T; j++) r[j] = ss_draw_field_at(keys[j], counter);
     };
 
+    // all incoming shares are requested at once
+    u64 cin[NR];
+#pragma unroll
+    for (int i = 0; i < NR; i++) cin[i] = c[(size_t)i * count + e];
+
     // step 1, and of step 2 the sums coef[q][j] = sum_i msg1[i][q] * D binv[i][j]
     ss_sacc2 coef[K][K];
 #pragma unroll
@@ -383,7 +388,7 @@ __device__ __forceinline__ void reduce_truncate_fixed(size_t e, size_t count, si
         for (int j = 0; j < K; j++) coef[q][j].clear();
 #pragma unroll
     for (int i = 0; i < NR; i++) {
-        const u64 ci = c[(size_t)i * count + e];
+        const u64 ci = cin[i];
         u64 r[T];
         draw(dp.reshare_key[i], r);
         eval_points<T, K>(ci, r, [&](int q, u64 v) {
@@ -473,17 +478,11 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_fixed_kernel(const u64 *c
 // ReLU under the multiplicative mask for one element (the three steps of relu_kernel below), n and t
 // fixed: x[] the n shares, r[] the n output shares
 template <int N, int T>
-__device__ __forceinline__ void relu_fixed(const u64 (&x)[N], size_t e, size_t count, size_t em, size_t mcount,
-                                           const u64 *__restrict__ sh_b, const u64 *__restrict__ sh_bi,
-                                           u64 *__restrict__ msg, u64 *__restrict__ yplain, const ss_nl_params &np,
-                                           u64 (&r)[N])
+__device__ __forceinline__ void relu_fixed(const u64 (&x)[N], size_t em, size_t mcount, const u64 (&b)[2 * T + 1],
+                                           const u64 (&bi)[N], u64 *__restrict__ msg, u64 *__restrict__ yplain,
+                                           const ss_nl_params &np, u64 (&r)[N])
 {
     constexpr int NR = 2 * T + 1;
-    u64 b[NR], bi[N];
-#pragma unroll
-    for (int i = 0; i < NR; i++) b[i] = sh_b[(size_t)i * count + e];
-#pragma unroll
-    for (int m = 0; m < N; m++) bi[m] = sh_bi[(size_t)m * count + e];
     ss_sacc acc;
     acc.clear();
 #pragma unroll
@@ -531,8 +530,14 @@ __global__ __launch_bounds__(BLOCK) void layer_tail_kernel(const u64 *c, u64 *__
         const size_t mcount = (size_t)gridDim.x * gridDim.y * BLOCK;
         const size_t em = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * BLOCK + threadIdx.x;
         u64 o[N], r[N];
+        // the mask shares are requested before the reduction starts, so that they arrive while it computes
+        u64 mb[2 * T + 1], mbi[N];
+#pragma unroll
+        for (int i = 0; i < 2 * T + 1; i++) mb[i] = sh_b[(size_t)i * count + e];
+#pragma unroll
+        for (int m = 0; m < N; m++) mbi[m] = sh_bi[(size_t)m * count + e];
         reduce_truncate_fixed<N, T, true>(e, count, em, mcount, c, msg1, msg2, umsg, wsh, dp, tp, o);
-        relu_fixed<N, T>(o, e, count, em, mcount, sh_b, sh_bi, rmsg, yplain, np, r);
+        relu_fixed<N, T>(o, em, mcount, mb, mbi, rmsg, yplain, np, r);
 #pragma unroll
         for (int p = 0; p < N; p++) {
             out[(size_t)p * count + e] = r[p];
