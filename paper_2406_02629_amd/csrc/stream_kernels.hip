@@ -524,8 +524,13 @@ __global__ __launch_bounds__(BLOCK) void layer_tail_kernel(const u64 *c, u64 *__
     u64 dig[N];
 #pragma unroll
     for (int p = 0; p < N; p++) dig[p] = 0;
-    if (live) {
-        const int b = pix / HW, hw = pix - b * HW;
+    // A lane past the last pixel repeats the last pixel of its channel: it loads, computes and stores the very
+    // values of that element's own lane, which sits in the same wave (so also in place nothing is read after
+    // it was overwritten), and its messages go to its own, otherwise unused position.  Without this a wave is
+    // left with one or two lanes in each of its four rows, and such waves take twice as long here.
+    if (c0 + j < C) {
+        const int px = min(pix, B * HW - 1);
+        const int b = px / HW, hw = px - b * HW;
         const size_t e = ((size_t)b * C + (c0 + j)) * HW + hw;
         const size_t mcount = (size_t)gridDim.x * gridDim.y * BLOCK;
         const size_t em = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * BLOCK + threadIdx.x;
