@@ -221,7 +221,8 @@ def test_resnet50_stack_with_relu_and_pooling_on_shares():
     run_secure_chain_parity(50, 5, 2, 13, seed=20240602, pool_on_shares=True)
 
 
-@pytest.mark.parametrize("n,t,p", [(3, 1, P61), (5, 2, P61), (7, 3, P61), (5, 2, (1 << 45) - 55)])
+@pytest.mark.parametrize("n,t,p", [(3, 1, P61), (5, 2, P61), (7, 3, P61), (5, 1, P61), (8, 2, P61), (5, 2, (1 << 45) - 55),
+                                   (3, 1, (1 << 45) - 55), (6, 2, (1 << 45) - 55)])
 def test_small_stack_batch_3_with_pooling_on_shares(n, t, p):
     """Three images through a short stack (stem with overlapping max-pool, 1x1 and 3x3 layers on limb planes,
     global average, classifier), everything on shares: batched planes for masks and pooling, other schemes."""
