@@ -526,8 +526,9 @@ __global__ __launch_bounds__(BLOCK) void layer_tail_kernel(const u64 *c, u64 *__
     for (int p = 0; p < N; p++) dig[p] = 0;
     // A lane past the last pixel repeats the last pixel of its channel: it loads, computes and stores the very
     // values of that element's own lane, which sits in the same wave (so also in place nothing is read after
-    // it was overwritten), and its messages go to its own, otherwise unused position.  Without this a wave is
-    // left with one or two lanes in each of its four rows, and such waves take twice as long here.
+    // it was overwritten), and its messages go to its own, otherwise unused position.  Without this a block
+    // of one or two pixels leaves its waves with four or eight active lanes, and waves with so few lanes run
+    // their 64-bit integer arithmetic almost twice as slowly as full ones (measured on MI355X).
     if (c0 + j < C) {
         const int px = min(pix, B * HW - 1);
         const int b = px / HW, hw = px - b * HW;
