@@ -27,7 +27,7 @@ from typing import List, Optional
 
 import torch
 
-from ssnet_inputs import Layer, gaussian, he_normal
+from ssnet_inputs import Layer, gaussian, he_normal, pooling_of
 
 from . import fixedpoint as fx
 from .binding import SSNet
@@ -36,34 +36,32 @@ WEIGHT_STREAM_BASE = 1 << 20      # stream ids of the weight sharings, apart fro
 
 
 def pool_spec(L: Layer):
-    """-> (kernel, stride, pad, mode, kdiv) of the pooling that follows layer L, or None"""
-    if L.post == "relu+maxpool3s2":
-        return (3, 3), (2, 2), (1, 1), SSNet.POOL_MAX, 1
-    if L.post == "relu+maxpool2s2":
-        return (2, 2), (2, 2), (0, 0), SSNet.POOL_MAX, 1
-    if L.post == "relu+gap":
-        return (L.hout, L.hout), (L.hout, L.hout), (0, 0), SSNet.POOL_SUM, L.hout * L.hout
-    return None
+    """-> (kernel, stride, pad, mode, kdiv) of the pooling that follows layer L, or None.  An average is a sum
+    here: its division (kdiv = kernel elements) moves into the truncation before it (Sec. VI-C)."""
+    spec = pooling_of(L)
+    if spec is None:
+        return None
+    kind, k, s, pad = spec
+    if kind == "max":
+        return (k, k), (s, s), (pad, pad), SSNet.POOL_MAX, 1
+    return (k, k), (s, s), (pad, pad), SSNet.POOL_SUM, k * k
 
 
-def post_plain(y: torch.Tensor, post: Optional[str]) -> torch.Tensor:
-    """Plaintext step after a layer, on signed integers [B, C, H, W] (int64)."""
-    if post is None:
+def post_plain(y: torch.Tensor, L: Layer) -> torch.Tensor:
+    """Plaintext step after layer L, on signed integers [B, C, H, W] (int64): ReLU, then its pooling (an
+    average is the floor of sum / kernel elements)."""
+    if L.post is None:
         return y
     y = torch.clamp(y, min=0)
-    if post == "relu":
+    spec = pooling_of(L)
+    if spec is None:
         return y
-    if post == "relu+maxpool3s2":
-        # values are below 2^53, so the float64 detour is exact
-        z = torch.nn.functional.max_pool2d(y.to(torch.float64), kernel_size=3, stride=2, padding=1)
-        return z.to(torch.int64)
-    if post == "relu+maxpool2s2":
-        z = torch.nn.functional.max_pool2d(y.to(torch.float64), kernel_size=2, stride=2)
-        return z.to(torch.int64)
-    if post == "relu+gap":
-        hw = y.shape[-1] * y.shape[-2]
-        return torch.div(y.sum(dim=(-1, -2), keepdim=True), hw, rounding_mode="floor")
-    raise ValueError(post)
+    kind, k, s, pad = spec
+    z = y.to(torch.float64)      # values are below 2^53, so the float64 detour is exact
+    if kind == "max":
+        return torch.nn.functional.max_pool2d(z, kernel_size=k, stride=s, padding=pad).to(torch.int64)
+    sums = (torch.nn.functional.avg_pool2d(z, kernel_size=k, stride=s, padding=pad) * (k * k)).round().to(torch.int64)
+    return torch.div(sums, k * k, rounding_mode="floor")
 
 
 class Chain:
@@ -180,7 +178,7 @@ class Chain:
             self.x_plain[l] = x.contiguous()
             out = self.run_layer(l, self.x_plain[l])
             if L.post is not None:
-                x = fx.from_signed(post_plain(fx.lift(out, self.ss.p), L.post), self.ss.p)
+                x = fx.from_signed(post_plain(fx.lift(out, self.ss.p), L), self.ss.p)
         return out
 
     def forward_timed(self, stages: str = "sgdtr"):
@@ -282,7 +280,7 @@ class Chain:
                 self.secure_plain[l] = x_plain.contiguous()
             x_shares, out = self.secure_layer(l, self.secure_plain[l], x_shares, planes_ready=self._planes_ready(l, x_shares))
             if x_shares is None and L.post is not None:
-                x_plain = fx.from_signed(post_plain(fx.lift(out, self.ss.p), L.post), self.ss.p)
+                x_plain = fx.from_signed(post_plain(fx.lift(out, self.ss.p), L), self.ss.p)
         return out
 
     def secure_timed(self):

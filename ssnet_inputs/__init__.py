@@ -42,7 +42,8 @@ class Layer:
     hin: int             # input spatial size (square); 1 for fc
     hout: int
     post: Optional[str]  # plaintext step applied by the harness after this layer:
-    #                      "relu", "relu+maxpool3s2", "relu+maxpool2s2", "relu+gap", or None (last layer)
+    #                      "relu", "relu+gap" (global average), "relu+maxpool{k}s{s}[p{pad}]",
+    #                      "relu+avgpool{k}s{s}", or None (last layer); see pooling_of
 
     @property
     def M(self) -> int:
@@ -59,6 +60,23 @@ class Layer:
     @property
     def macs(self) -> int:
         return self.M * self.K * self.N
+
+
+def pooling_of(L: Layer):
+    """The pooling that follows layer L's ReLU: None, or (kind, kernel, stride, pad) with kind "max" or "avg"
+    (square kernels; "relu+maxpool3s2" is the ResNet stem's 3x3 / 2 with padding 1)."""
+    post = L.post
+    if post in (None, "relu"):
+        return None
+    if post == "relu+gap":
+        return ("avg", L.hout, L.hout, 0)
+    if post == "relu+maxpool3s2":
+        return ("max", 3, 2, 1)
+    import re
+    m = re.fullmatch(r"relu\+(max|avg)pool(\d+)s(\d+)(?:p(\d+))?", post)
+    if not m:
+        raise ValueError(post)
+    return (m.group(1), int(m.group(2)), int(m.group(3)), int(m.group(4) or 0))
 
 
 def resnet_chain(depth: int, image: int = 224, classes: int = 1000) -> List[Layer]:
@@ -108,3 +126,37 @@ def vgg16_chain(image: int = 32, classes: int = 10, hidden: int = 4096) -> List[
     layers.append(Layer("fc", hidden, hidden, 1, 1, 0, 1, 1, "relu"))
     layers.append(Layer("fc", hidden, classes, 1, 1, 0, 1, 1, None))
     return layers
+
+
+def resnet_basic_chain(depth: int = 18, image: int = 224, classes: int = 1000) -> List[Layer]:
+    """Main-path layers of a basic-block ResNet (18 or 34) as one sequential chain: conv1 7x7/2, 3x3/2
+    max-pool, stages of two 3x3 convolutions per block (stride 2 on the first convolution of stages 2-4),
+    global average, dense layer.  No shortcuts, as in resnet_chain."""
+    blocks = {18: (2, 2, 2, 2), 34: (3, 4, 6, 3)}[depth]
+    layers: List[Layer] = []
+    hout = (image + 2 * 3 - 7) // 2 + 1
+    layers.append(Layer("conv", 3, 64, 7, 2, 3, image, hout, "relu+maxpool3s2"))
+    h, cin = (hout + 2 - 3) // 2 + 1, 64
+    for stage, (nblocks, width) in enumerate(zip(blocks, (64, 128, 256, 512))):
+        for b in range(nblocks):
+            stride = 2 if (stage > 0 and b == 0) else 1
+            h2 = (h + 2 - 3) // stride + 1
+            layers.append(Layer("conv", cin, width, 3, stride, 1, h, h2, "relu"))
+            last = stage == 3 and b == nblocks - 1
+            layers.append(Layer("conv", width, width, 3, 1, 1, h2, h2, "relu+gap" if last else "relu"))
+            h, cin = h2, width
+    layers.append(Layer("fc", cin, classes, 1, 1, 0, 1, 1, None))
+    return layers
+
+
+def lenet_chain(image: int = 28, classes: int = 10) -> List[Layer]:
+    """LeNet-5-shaped stack for 28x28 one-channel images: 5x5 convolutions (1 -> 6, padding 2; 6 -> 16), each
+    followed by ReLU and a 2x2 / 2 average pool, then dense layers 120, 84, classes."""
+    h1 = image                      # 5x5, padding 2
+    h2 = h1 // 2 - 4                # after the pool, then 5x5 without padding
+    feat = 16 * (h2 // 2) * (h2 // 2)
+    return [Layer("conv", 1, 6, 5, 1, 2, image, h1, "relu+avgpool2s2"),
+            Layer("conv", 6, 16, 5, 1, 0, h1 // 2, h2, "relu+avgpool2s2"),
+            Layer("fc", feat, 120, 1, 1, 0, 1, 1, "relu"),
+            Layer("fc", 120, 84, 1, 1, 0, 1, 1, "relu"),
+            Layer("fc", 84, classes, 1, 1, 0, 1, 1, None)]

@@ -17,7 +17,8 @@ import oracle as orc
 from paper_2406_02629_amd import SSNet
 from paper_2406_02629_amd import fixedpoint as fx
 from paper_2406_02629_amd.chain import WEIGHT_STREAM_BASE, Chain, post_plain
-from ssnet_inputs import gaussian, he_normal, resnet_chain, uniform_below, vgg16_chain
+from ssnet_inputs import (gaussian, he_normal, lenet_chain, pooling_of, resnet_basic_chain, resnet_chain, uniform_below,
+                          vgg16_chain)
 from util import P61, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
@@ -34,29 +35,25 @@ def say(*a):
 
 
 # ------------------------------------------------------------------ oracle-side plaintext steps
-def np_post(y, post):
-    """y: signed int64 [B, C, H, W]"""
-    if post is None:
+def np_post(y, L):
+    """y: signed int64 [B, C, H, W] -> ReLU, then the layer's pooling (average = floor of sum / kernel elements)"""
+    if L.post is None:
         return y
     y = np.maximum(y, 0)
-    if post == "relu":
+    spec = pooling_of(L)
+    if spec is None:
         return y
-    if post == "relu+maxpool3s2":
-        B, C, H, W = y.shape
-        Ho, Wo = (H + 2 - 3) // 2 + 1, (W + 2 - 3) // 2 + 1
-        pad = np.zeros((B, C, H + 2, W + 2), np.int64)      # values are >= 0 after ReLU
-        pad[:, :, 1:-1, 1:-1] = y
-        out = np.zeros((B, C, Ho, Wo), np.int64)
-        for r in range(3):
-            for s in range(3):
-                out = np.maximum(out, pad[:, :, r:r + 2 * Ho:2, s:s + 2 * Wo:2])
-        return out
-    if post == "relu+maxpool2s2":
-        B, C, H, W = y.shape
-        return y[:, :, :H // 2 * 2, :W // 2 * 2].reshape(B, C, H // 2, 2, W // 2, 2).max(axis=(3, 5))
-    if post == "relu+gap":
-        return y.sum(axis=(-1, -2), keepdims=True) // (y.shape[-1] * y.shape[-2])
-    raise ValueError(post)
+    kind, k, s, pad = spec
+    B, C, H, W = y.shape
+    Ho, Wo = (H + 2 * pad - k) // s + 1, (W + 2 * pad - k) // s + 1
+    padded = np.zeros((B, C, H + 2 * pad, W + 2 * pad), np.int64)      # values are >= 0 after ReLU
+    padded[:, :, pad:pad + H, pad:pad + W] = y
+    out = np.zeros((B, C, Ho, Wo), np.int64)
+    for r in range(k):
+        for c in range(k):
+            win = padded[:, :, r:r + s * Ho:s, c:c + s * Wo:s]
+            out = np.maximum(out, win) if kind == "max" else out + win
+    return out if kind == "max" else out // (k * k)
 
 
 def np_signed_to_field(v, p=P61):
@@ -121,8 +118,8 @@ def run_chain_parity(depth, n, t, f, seed, full_every=1):
         assert int(np.abs(orc.lift(o["rec"], P61)).max()) < 1 << 40       # fixed-point range is respected
         # plaintext step between layers, on each side with its own code
         if L.post is not None:
-            x_gpu = fx.from_signed(post_plain(fx.lift(rec), L.post))
-            x_orc = np_signed_to_field(np_post(orc.lift(o["rec"], P61), L.post))
+            x_gpu = fx.from_signed(post_plain(fx.lift(rec), L))
+            x_orc = np_signed_to_field(np_post(orc.lift(o["rec"], P61), L))
             assert np.array_equal(to_np(x_gpu), x_orc), f"layer {l}: plaintext step"
         if l % 10 == 0:
             say(f"resnet{depth} layer {l}/{len(layers)} ok ({time.time() - t0:.0f} s)")
@@ -162,8 +159,9 @@ def run_secure_chain_parity(depth, n, t, f, seed, pool_on_shares=False, p=P61, l
         elif L.kind == "fc":
             x_sh_o = x_sh_o.reshape(n, B, -1)
         y2 = orc.conv(x_sh_o, ws, L.stride, L.pad, p) if L.kind == "conv" else orc.linear(x_sh_o, ws, p)
-        pooled = pool_on_shares and L.post in ("relu+maxpool3s2", "relu+maxpool2s2", "relu+gap")
-        kdiv = L.hout * L.hout if pooled and L.post == "relu+gap" else 1
+        spec = pooling_of(L) if pool_on_shares else None
+        pooled = spec is not None
+        kdiv = spec[1] * spec[1] if pooled and spec[0] == "avg" else 1
         yr = orc.degree_reduce(y2.reshape(n, -1), n, t, p, seed, l)
         yt = orc.truncate_div(yr, n, t, f, kdiv, p, seed, l) if kdiv > 1 else orc.truncate(yr, n, t, f, p, seed, l)
         x_sh_g, rec_g = chain.secure_layer(l, None if x_sh_g is not None else x_plain_g.contiguous(), x_sh_g)
@@ -176,9 +174,8 @@ def run_secure_chain_parity(depth, n, t, f, seed, pool_on_shares=False, p=P61, l
             x_sh_o = orc.relu(yt, sb, sbi, n, t, p).reshape(y2.shape)
             assert np.array_equal(to_np(x_sh_g), x_sh_o), f"layer {l}: shares after ReLU"
         elif pooled:
-            geo = {"relu+maxpool3s2": (L.hout, L.hout, 3, 3, 2, 2, 1, 1, orc.POOL_MAX),
-                   "relu+maxpool2s2": (L.hout, L.hout, 2, 2, 2, 2, 0, 0, orc.POOL_MAX),
-                   "relu+gap": (L.hout, L.hout, L.hout, L.hout, L.hout, L.hout, 0, 0, orc.POOL_SUM)}[L.post]
+            kind, pk, ps, pp = spec
+            geo = (L.hout, L.hout, pk, pk, ps, ps, pp, pp, orc.POOL_MAX if kind == "max" else orc.POOL_SUM)
             sb, sbi = orc.pool_masks(B * L.cout, *geo[:8], n, t, 28, p, seed, Chain.MASK_STREAM_BASE + l)
             x_sh_o = orc.relu_pool(yt, sb, sbi, B * L.cout, *geo, n, t, p)
             ho = orc.pool_out_size(L.hout, geo[2], geo[4], geo[6])
@@ -189,8 +186,8 @@ def run_secure_chain_parity(depth, n, t, f, seed, pool_on_shares=False, p=P61, l
             assert x_sh_g is None and np.array_equal(to_np(rec_g), rec_o), f"layer {l}: opened result"
             x_sh_o = None
             if L.post is not None:
-                x_plain_g = fx.from_signed(post_plain(fx.lift(rec_g, p), L.post), p)
-                x_plain_o = np_signed_to_field(np_post(orc.lift(rec_o, p), L.post), p)
+                x_plain_g = fx.from_signed(post_plain(fx.lift(rec_g, p), L), p)
+                x_plain_o = np_signed_to_field(np_post(orc.lift(rec_o, p), L), p)
         if l % 10 == 0:
             say(f"secure resnet{depth} layer {l}/{len(layers)} ok ({time.time() - t0:.0f} s)")
     logits = to_np(chain.secure_prepare(pool_on_shares)).copy()
@@ -239,6 +236,19 @@ def test_vgg16_stack_three_parties(batch, pool):
     """VGG16-shaped stack on 32 x 32 images, the paper's 3-party setting: 2 x 2 max-pools (one mask per kernel
     position), dense layers with ReLU on share vectors."""
     run_secure_chain_parity(0, 3, 1, 13, seed=16, pool_on_shares=pool, layers=vgg16_chain(32, 10, 512), batch=batch)
+
+
+@pytest.mark.parametrize("n,t,f,p,batch", [(3, 1, 13, P61, 1), (3, 1, 13, P61, 4), (5, 2, 12, (1 << 45) - 55, 2)])
+def test_lenet_stack_average_pools_on_shares(n, t, f, p, batch):
+    """LeNet-5-shaped stack on 28 x 28 images: 5 x 5 convolutions through the im2col matrix (6 and 16 channels),
+    2 x 2 average pools as sums behind a truncation with the rounding division by 4, dense layers with ReLU."""
+    run_secure_chain_parity(0, n, t, f, seed=5, pool_on_shares=True, p=p, layers=lenet_chain(), batch=batch)
+
+
+@pytest.mark.timeout(900)
+def test_resnet18_stack_on_shares():
+    """basic-block ResNet-18 shapes (3 x 3 convolutions on limb planes throughout), five parties"""
+    run_secure_chain_parity(18, 5, 2, 13, seed=18, pool_on_shares=True, layers=resnet_basic_chain(18))
 
 
 @pytest.mark.timeout(900)
