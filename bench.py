@@ -284,6 +284,33 @@ def gemm_by_shape(chain, ss, reps=20):
     return rows
 
 
+def paper_setting_3pc(steps, warmup):
+    """The setting of the paper's main table: three parties ((2,3) scheme), its prime 2^45 - 55, batch 1, the whole
+    inference on shares (Linear - Truncation - NonLinear per layer, pooling on shares, only the logits opened), for
+    the ResNet-50 / 101 / 152 main-path stacks.  Compute of all three parties on this one GPU, no network."""
+    import torch
+    from paper_2406_02629_amd import P45, SSNet
+    from paper_2406_02629_amd.chain import Chain
+    from ssnet_inputs import resnet_chain
+    out = {"workload": "n=3 t=1, p = 2^45 - 55, f=12, batch 1, ReLU and pooling on shares; ms per inference"}
+    for depth in (50, 101, 152):
+        ss = SSNet(3, 1, f=12, seed=20240602, p=P45)
+        chain = Chain(ss, resnet_chain(depth))
+        chain.secure_prepare(True)
+        torch.cuda.synchronize()
+        for _ in range(warmup):
+            chain.secure_timed()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            chain.secure_timed()
+        torch.cuda.synchronize()
+        out[f"resnet{depth}_ms"] = (time.perf_counter() - t0) * 1e3 / steps
+        del chain, ss
+        torch.cuda.empty_cache()
+    return out
+
+
 def batch8_chain(chain, ss, layers, steps, warmup, secure=True):
     """The headline step at batch 8 (the paper also reports batched inference): eight images through the same
     prepared weights.  M grows eightfold, so a launch has enough tiles to amortise its fixed cost."""
@@ -415,6 +442,8 @@ def main():
     if not args.no_batch8:
         result["batch8"] = batch8_chain(chain, ss, layers, max(args.steps // 4, 2), 1, secure=not args.no_secure)
     if not args.no_p45:
+        if not args.no_secure:
+            result["paper_setting_3pc_p45"] = paper_setting_3pc(max(args.steps // 2, 2), 2)
         result["paper_prime_p45"] = p45_chain(layers, args.steps, args.warmup)
         if not args.no_batch8:
             result["paper_prime_p45_batch8"] = p45_chain(layers, max(args.steps // 4, 2), 1, batch=8)

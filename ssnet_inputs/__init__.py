@@ -160,3 +160,23 @@ def lenet_chain(image: int = 28, classes: int = 10) -> List[Layer]:
             Layer("fc", feat, 120, 1, 1, 0, 1, 1, "relu"),
             Layer("fc", 120, 84, 1, 1, 0, 1, 1, "relu"),
             Layer("fc", 84, classes, 1, 1, 0, 1, 1, None)]
+
+
+def alexnet_chain(image: int = 227, classes: int = 1000, hidden: int = 4096) -> List[Layer]:
+    """AlexNet-shaped stack: 11x11 / 4 convolution (3 -> 96), 5x5 (96 -> 256, padding 2), 3x3 convolutions
+    384, 384, 256, overlapping 3x3 / 2 max-pools without padding after the first, second and fifth
+    convolution, then three dense layers."""
+    def pooled(h):
+        return (h - 3) // 2 + 1
+    h1 = (image - 11) // 4 + 1
+    p1 = pooled(h1)
+    p2 = pooled(p1)
+    p3 = pooled(p2)
+    return [Layer("conv", 3, 96, 11, 4, 0, image, h1, "relu+maxpool3s2p0"),
+            Layer("conv", 96, 256, 5, 1, 2, p1, p1, "relu+maxpool3s2p0"),
+            Layer("conv", 256, 384, 3, 1, 1, p2, p2, "relu"),
+            Layer("conv", 384, 384, 3, 1, 1, p2, p2, "relu"),
+            Layer("conv", 384, 256, 3, 1, 1, p2, p2, "relu+maxpool3s2p0"),
+            Layer("fc", 256 * p3 * p3, hidden, 1, 1, 0, 1, 1, "relu"),
+            Layer("fc", hidden, hidden, 1, 1, 0, 1, 1, "relu"),
+            Layer("fc", hidden, classes, 1, 1, 0, 1, 1, None)]

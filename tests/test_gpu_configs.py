@@ -17,7 +17,7 @@ import oracle as orc
 from paper_2406_02629_amd import SSNet
 from paper_2406_02629_amd import fixedpoint as fx
 from paper_2406_02629_amd.chain import WEIGHT_STREAM_BASE, Chain, post_plain
-from ssnet_inputs import (gaussian, he_normal, lenet_chain, pooling_of, resnet_basic_chain, resnet_chain, uniform_below,
+from ssnet_inputs import (alexnet_chain, gaussian, he_normal, lenet_chain, pooling_of, resnet_basic_chain, resnet_chain, uniform_below,
                           vgg16_chain)
 from util import P61, to_dev, to_np
 
@@ -243,6 +243,14 @@ def test_lenet_stack_average_pools_on_shares(n, t, f, p, batch):
     """LeNet-5-shaped stack on 28 x 28 images: 5 x 5 convolutions through the im2col matrix (6 and 16 channels),
     2 x 2 average pools as sums behind a truncation with the rounding division by 4, dense layers with ReLU."""
     run_secure_chain_parity(0, n, t, f, seed=5, pool_on_shares=True, p=p, layers=lenet_chain(), batch=batch)
+
+
+@pytest.mark.parametrize("n,t,batch", [(3, 1, 1), (5, 2, 2)])
+def test_alexnet_stack_on_shares(n, t, batch):
+    """AlexNet-shaped stack on 67 x 67 images: a strided 11 x 11 stem, a 5 x 5 layer with 96 input channels
+    (im2col route), 384-channel layers on limb planes, overlapping max-pools without padding (one mask per
+    plane), dense layers."""
+    run_secure_chain_parity(0, n, t, 13, seed=12, pool_on_shares=True, layers=alexnet_chain(67, 10, 512), batch=batch)
 
 
 @pytest.mark.timeout(900)
