@@ -293,7 +293,7 @@ int ssnet_relu(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_beta, cons
  *     the maximum.  Workspace behind the header: the products [2t+1][planes*H*W],
  *     the rectified plain values [planes*H*W], the pooled plain values
  *     [planes*Ho*Wo]; ssnet_workspace_bytes_stream(max of the two counts) covers
- *     it.  d_out may not alias d_x. */
+ *     it.  d_out must not overlap d_x (SSNET_EINVAL). */
 #define SSNET_POOL_MAX 0
 #define SSNET_POOL_SUM 1
 int ssnet_pool_out_size(int H, int k, int s, int pad);

@@ -914,6 +914,11 @@ int ssnet_relu_pool(ssnet_ctx *ctx, const uint64_t *d_x, const uint64_t *d_beta,
         return SSNET_EINVAL;
     const int nr = 2 * ctx->t + 1;
     const size_t cin = planes * H * W, cout = planes * g.Ho * g.Wo;
+    {   // the pooled shares are written while other threads still read the input: no overlap allowed
+        const uintptr_t x0 = (uintptr_t)d_x, x1 = x0 + (size_t)ctx->n * cin * 8, o0 = (uintptr_t)d_out,
+                        o1 = o0 + (size_t)ctx->n * cout * 8;
+        if (x0 < o1 && o0 < x1) return SSNET_EINVAL;
+    }
     if (!ws_fits(ctx, ((size_t)(nr + 1) * cin + cout) * 8)) return SSNET_EWORKSPACE;
     ss_nl_params np;
     if (!make_nl_params(ctx, 0, &np)) return SSNET_EINVAL;

@@ -164,7 +164,8 @@ def test_pooling_entry_points_check_their_arguments():
     assert lib.ssnet_pool_masks(ctx, 0, *ok, 0, 16, 16) == binding.EINVAL
     assert lib.ssnet_relu_pool(ctx, 16, 16, 16, 1, *ok, 2, 16) == binding.EINVAL         # unknown mode
     assert lib.ssnet_relu_pool(ctx, 16, 16, None, 1, *ok, 0, 16) == binding.EINVAL
-    assert lib.ssnet_relu_pool(ctx, 16, 16, 16, 1, *ok, 0, 16) == binding.EWORKSPACE
+    assert lib.ssnet_relu_pool(ctx, 16, 16, 16, 1, *ok, 0, 16) == binding.EINVAL        # output overlaps the input
+    assert lib.ssnet_relu_pool(ctx, 16, 16, 16, 1, *ok, 0, 1 << 20) == binding.EWORKSPACE
     for kdiv in (0, -1, 4097):
         assert lib.ssnet_truncate_div(ctx, 16, 8, kdiv, 0, 16) == binding.EINVAL
         assert lib.ssnet_degree_reduce_truncate_div(ctx, 16, 8, kdiv, 0, 16) == binding.EINVAL
