@@ -356,6 +356,9 @@ __device__ __forceinline__ u64 fold_diagonals(const v4i (&acc)[15], int r, u64 n
 // workgroup s of G owns the units with floor(s cost / G) <= cp(u) <
 // floor((s+1) cost / G).  cost / G >= SS_UNIT_COST, so no range is empty.
 constexpr unsigned SS_UNIT_COST = 9;
+// what one hand-over of a shared tile costs a workgroup, in the same scale: about 3.3 us, i.e. 1.3 units of
+// eight limbs (2.5 us each) or 2.2 units of six (1.6 us each)
+constexpr unsigned SS_HANDOVER_COST = SS_NLIMB == 8 ? 12 : 20;
 
 // cost position of unit j of tile `tile`
 __device__ __forceinline__ unsigned long long cost_before(const gemm_args &g, unsigned tile, unsigned j)
@@ -695,6 +698,23 @@ gemm_plan plan_gemm(int n, int rows, int cols, int K)
     p.wlast = unit_cost(Cb - 4 * (CT - 1));
     p.wrow = (unsigned)(CT - 1) * SS_UNIT_COST + p.wlast;
     p.cost = (unsigned long long)n * ((rows + 63) / 64) * p.Kb * p.wrow;
+    // Whole tiles or shared tiles?  Dealt by cost, a workgroup runs cost / G and hands over at both ends of its
+    // range (measured: each hand-over costs about SS_HANDOVER_COST / SS_UNIT_COST units).  With one whole tile
+    // per workgroup nothing is handed over and the launch lasts as many tiles as the fullest CU gets.  With a
+    // single k block tiles are never shared, so there is nothing to choose.
+    if (p.Kb > 1) {
+        const unsigned long long rounds = ((unsigned long long)p.tiles + SS_GEMM_CUS - 1) / SS_GEMM_CUS;
+        const unsigned long long whole = rounds * p.Kb * SS_UNIT_COST;
+        const unsigned long long g = p.cost / SS_UNIT_COST < SS_GEMM_CUS ? (p.cost / SS_UNIT_COST ? p.cost / SS_UNIT_COST : 1) : SS_GEMM_CUS;
+        const unsigned long long shared = p.cost / g + 2 * SS_HANDOVER_COST;
+        if (whole <= shared) {
+            p.G = (int)p.tiles;
+            p.slots = 0;
+            p.units = 0;
+            p.cost = 0;
+            return p;
+        }
+    }
     // every range must hold at least one unit start: cost / G >= SS_UNIT_COST
     const unsigned long long most = p.cost / SS_UNIT_COST;
     p.G = (int)(most < SS_GEMM_CUS ? (most ? most : 1) : SS_GEMM_CUS);
