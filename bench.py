@@ -358,6 +358,7 @@ def main():
     ap.add_argument("--no-secure", action="store_true", help="skip the pass with ReLU on shares")
     ap.add_argument("--no-batch8", action="store_true", help="skip the batch-8 pass of the same stack")
     ap.add_argument("--no-p45", action="store_true", help="skip the passes over the prime 2^45 - 55")
+    ap.add_argument("--no-shapes", action="store_true", help="skip the per-shape timing of the product kernel")
     ap.add_argument("--cpu-layers", type=int, default=152)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale profiler counters)")
@@ -438,7 +439,8 @@ def main():
         result["nonlinear_on_shares"] = secure_chain(chain, ss, args.steps, args.warmup, macs, out_elems)
         result["nonlinear_and_pooling_on_shares"] = secure_chain(chain, ss, args.steps, args.warmup, macs, out_elems,
                                                                  pool_on_shares=True)
-    result["gemm_by_shape"] = gemm_by_shape(chain, ss)
+    if not args.no_shapes:
+        result["gemm_by_shape"] = gemm_by_shape(chain, ss)
     if not args.no_batch8:
         result["batch8"] = batch8_chain(chain, ss, layers, max(args.steps // 4, 2), 1, secure=not args.no_secure)
     if not args.no_p45:
