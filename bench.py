@@ -287,15 +287,21 @@ def gemm_by_shape(chain, ss, reps=20):
 def paper_setting_3pc(steps, warmup):
     """The setting of the paper's main table: three parties ((2,3) scheme), its prime 2^45 - 55, batch 1, the whole
     inference on shares (Linear - Truncation - NonLinear per layer, pooling on shares, only the logits opened), for
-    the ResNet-50 / 101 / 152 main-path stacks.  Compute of all three parties on this one GPU, no network."""
+    the ResNet-50 / 101 / 152 main-path stacks and stacks shaped like the paper's other model families.  Compute
+    of all three parties on this one GPU, no network."""
     import torch
     from paper_2406_02629_amd import P45, SSNet
     from paper_2406_02629_amd.chain import Chain
     from ssnet_inputs import resnet_chain
+    from ssnet_inputs import alexnet_chain, lenet_chain, resnet_basic_chain, vgg16_chain
     out = {"workload": "n=3 t=1, p = 2^45 - 55, f=12, batch 1, ReLU and pooling on shares; ms per inference"}
-    for depth in (50, 101, 152):
+    stacks = [("resnet50", resnet_chain(50)), ("resnet101", resnet_chain(101)), ("resnet152", resnet_chain(152)),
+              ("resnet18", resnet_basic_chain(18)), ("vgg16_32x32", vgg16_chain(32, 10, 512)),
+              ("vgg16_64x64", vgg16_chain(64, 200, 512)), ("alexnet_227x227", alexnet_chain(227, 1000, 4096)),
+              ("lenet_28x28", lenet_chain())]
+    for name, stack in stacks:
         ss = SSNet(3, 1, f=12, seed=20240602, p=P45)
-        chain = Chain(ss, resnet_chain(depth))
+        chain = Chain(ss, stack)
         chain.secure_prepare(True)
         torch.cuda.synchronize()
         for _ in range(warmup):
@@ -305,7 +311,7 @@ def paper_setting_3pc(steps, warmup):
         for _ in range(steps):
             chain.secure_timed()
         torch.cuda.synchronize()
-        out[f"resnet{depth}_ms"] = (time.perf_counter() - t0) * 1e3 / steps
+        out[f"{name}_ms"] = (time.perf_counter() - t0) * 1e3 / steps
         del chain, ss
         torch.cuda.empty_cache()
     return out
