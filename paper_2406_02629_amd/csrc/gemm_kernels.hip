@@ -644,6 +644,146 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
 #endif
 }
 
+// The same contraction for a first operand of at most 16 rows (dense layers at a small batch, convolutions
+// with few output channels).  There the time goes into reading the second operand once, so a launch is as
+// fast as it keeps bytes in flight: a workgroup's tile is 16 rows x 128 columns, one row block and eight
+// column blocks per unit, twice the column blocks of the square tile in the same LDS, and no MFMA is spent on
+// row blocks that do not exist.  Wave w copies column block w and limb slice w of the row block, and owns
+// the 16 x 16 outputs of column block w.  Units, ranges, hand-over and epilogue are those of the kernel above
+// (a shared tile has 16 x 128 partial residues).
+constexpr int SKINNY_COLS = 128, SKINNY_PART = 16 * SKINNY_COLS;
+
+__global__ __launch_bounds__(512) void gemm_skinny_kernel(gemm_args g)
+{
+    extern __shared__ v4i lds[];   // 2 stages x (1 row block + 8 column blocks) x TILE
+    __shared__ unsigned arrival;
+    constexpr int STAGE = 9 * TILE;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const unsigned G = gridDim.x;
+    const unsigned slot = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
+    unsigned u0, u1;
+    if (g.units) {
+        u0 = unit_at(g, (unsigned long long)slot * g.cost / G);
+        u1 = unit_at(g, (unsigned long long)(slot + 1) * g.cost / G);
+    } else {
+        u0 = 0;
+        u1 = (unsigned)g.Kb;
+    }
+    if (u0 >= u1) return;
+
+    // this wave's column block of tile t (clamped past the edge: computed, never stored) and its limb slice
+    // of the party's row block
+    auto b_source = [&](unsigned t) {
+        const int ct = (int)(t % (unsigned)g.CT), party = (int)(t / (unsigned)g.CT);
+        return g.B + (size_t)party * g.b_party_stride + (size_t)min(ct * 8 + wave, g.Cb - 1) * g.Kb * TILE + lane;
+    };
+    auto a_source = [&](unsigned t) {
+        const int party = (int)(t / (unsigned)g.CT);
+        return g.A + (size_t)party * g.a_party_stride + min(wave, NL - 1) * 64 + lane;
+    };
+    auto copy_unit = [&](const v4i *as, const v4i *bs, int k, int stage) {
+        v4i *dst = lds + stage * STAGE;
+#pragma unroll
+        for (int q = 0; q < NL; q++)
+            __builtin_amdgcn_global_load_lds(bs + (size_t)k * TILE + q * 64, dst + (1 + wave) * TILE + q * 64, 16, 0, 0);
+        if (wave < NL) __builtin_amdgcn_global_load_lds(as + (size_t)k * TILE, dst + wave * 64, 16, 0, 0);
+    };
+
+    unsigned tile = g.units ? u0 / (unsigned)g.Kb : slot;
+    int kb = (int)(u0 - (g.units ? tile * (unsigned)g.Kb : 0));
+    const v4i *as = a_source(tile), *bs = b_source(tile);
+    copy_unit(as, bs, kb, 0);
+    int st = 0;
+
+    unsigned u = u0;
+    while (u < u1) {
+        const int ct = (int)(tile % (unsigned)g.CT), party = (int)(tile / (unsigned)g.CT);
+        const bool inside = ct * 8 + wave < g.Cb;   // this wave's column block lies inside the matrix
+        const int kb_first = kb;
+        v4i acc[ND];
+#pragma unroll
+        for (int s = 0; s < ND; s++) acc[s] = (v4i){0, 0, 0, 0};
+
+        const int kb_end = min(g.Kb, kb + (int)(u1 - u));
+        const v4i *next_as = as, *next_bs = bs;
+        for (; kb < kb_end; kb++, u++) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of the unit is in LDS
+            __syncthreads();                      // everyone's part is; stage st^1 is no longer read
+            if (u + 1 < u1) {
+                int nkb = kb + 1;
+                if (nkb == g.Kb) {
+                    nkb = 0;
+                    next_as = a_source(tile + 1);
+                    next_bs = b_source(tile + 1);
+                }
+                copy_unit(next_as, next_bs, nkb, st ^ 1);
+            }
+            if (inside) {
+                const v4i *sa = lds + st * STAGE + lane, *sb = lds + st * STAGE + (1 + wave) * TILE + lane;
+                v4i a[NL], b[NL];
+#pragma unroll
+                for (int i = 0; i < NL; i++) {
+                    a[i] = sa[i * 64];
+                    b[i] = sb[i * 64];
+                }
+#pragma unroll
+                for (int i = 0; i < NL; i++)
+#pragma unroll
+                    for (int j = 0; j < NL; j++)
+                        acc[i + j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[i + j], 0, 0, 0);
+            }
+            st ^= 1;
+        }
+
+        // lane holds column lane%16 of its block and rows 4*(lane/16)+r
+        u64 v[4];
+#pragma unroll
+        for (int r = 0; r < 4; r++) v[r] = fold_diagonals(acc, r, g.negbias);
+        const int lrow = 4 * (lane >> 4), lcol = wave * 16 + (lane & 15);   // within the 16 x 128 tile
+        bool finish = true;
+        if (kb_first != 0 || kb_end != g.Kb) {   // the tile is shared: uniform over the workgroup
+            const int first = owner_of(g, cost_before(g, tile, 0), G),
+                      last = owner_of(g, cost_before(g, tile, (unsigned)g.Kb - 1), G);
+            u64 *part = g.partials + (size_t)tile * g.slots * SKINNY_PART;
+            const int my = (int)slot - first;
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+                __hip_atomic_store(&part[(size_t)my * SKINNY_PART + (lrow + r) * SKINNY_COLS + lcol], v[r], __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the stores above are done
+            __syncthreads();
+            if (tid == 0)
+                arrival = __hip_atomic_fetch_add(&g.counters[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            finish = arrival == (unsigned)(last - first);
+            if (finish) {
+                if (tid == 0) __hip_atomic_store(&g.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int s = 0; s <= last - first; s++) {
+                    if (s == my) continue;
+#pragma unroll
+                    for (int r = 0; r < 4; r++)
+                        v[r] = ss_add(v[r], __hip_atomic_load(&part[(size_t)s * SKINNY_PART + (lrow + r) * SKINNY_COLS + lcol],
+                                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                }
+            }
+            __syncthreads();   // `arrival` may be rewritten by the next tile
+        }
+        if (finish) {
+            const int col = ct * SKINNY_COLS + lcol;
+            u64 *op = g.out + (size_t)party * g.out_party_stride + (size_t)(col / g.cdiv) * g.stride_cb + (col % g.cdiv);
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+                if (lrow + r < g.rows && col < g.cols) op[(size_t)(lrow + r) * g.stride_row] = v[r];
+        }
+        if (kb == g.Kb) {
+            kb = 0;
+            tile++;
+            as = next_as;
+            bs = next_bs;
+        }
+    }
+}
+
 __global__ void zero_words_kernel(unsigned *p, size_t nwords)
 {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -662,6 +802,7 @@ u64 neg_bias()
 }
 
 struct gemm_plan {
+    bool skinny;               // first operand of at most 16 rows: tiles of 16 x 128 (gemm_skinny_kernel)
     long tiles, units;
     int Kb, G, slots;
     unsigned wlast, wrow;
@@ -680,11 +821,13 @@ unsigned unit_cost(int vb)
 // How the units are dealt: one workgroup per CU unless there are fewer units
 // than CUs; slots = the most workgroups that can share one tile.  When there are
 // more tiles than arrival counters every workgroup gets whole tiles.
-gemm_plan plan_gemm(int n, int rows, int cols, int K)
+gemm_plan plan_gemm(int n, int rows, int cols, int K, bool allow_skinny)
 {
     gemm_plan p;
+    p.skinny = allow_skinny && rows <= 16;
     p.Kb = (K + 63) / 64;
-    p.tiles = (long)n * ((rows + 63) / 64) * ((cols + 63) / 64);
+    p.tiles = p.skinny ? (long)n * ((cols + SKINNY_COLS - 1) / SKINNY_COLS)
+                       : (long)n * ((rows + 63) / 64) * ((cols + 63) / 64);
     p.units = p.tiles * p.Kb;
     if (p.tiles > SS_GEMM_MAX_SPLIT_TILES || p.units >= (1L << 31)) {
         p.G = (int)(p.tiles < (1L << 30) ? p.tiles : 0);   // 0: not launchable, rejected by the caller
@@ -694,10 +837,17 @@ gemm_plan plan_gemm(int n, int rows, int cols, int K)
         p.cost = 0;
         return p;
     }
-    const int CT = (cols + 63) / 64, Cb = (cols + 15) / 16;
-    p.wlast = unit_cost(Cb - 4 * (CT - 1));
-    p.wrow = (unsigned)(CT - 1) * SS_UNIT_COST + p.wlast;
-    p.cost = (unsigned long long)n * ((rows + 63) / 64) * p.Kb * p.wrow;
+    if (p.skinny) {   // every unit copies the same nine blocks: one cost for all
+        const int CT = (cols + SKINNY_COLS - 1) / SKINNY_COLS;
+        p.wlast = SS_UNIT_COST;
+        p.wrow = (unsigned)CT * SS_UNIT_COST;
+        p.cost = (unsigned long long)n * p.Kb * p.wrow;
+    } else {
+        const int CT = (cols + 63) / 64, Cb = (cols + 15) / 16;
+        p.wlast = unit_cost(Cb - 4 * (CT - 1));
+        p.wrow = (unsigned)(CT - 1) * SS_UNIT_COST + p.wlast;
+        p.cost = (unsigned long long)n * ((rows + 63) / 64) * p.Kb * p.wrow;
+    }
     // Whole tiles or shared tiles?  Dealt by cost, a workgroup runs cost / G and hands over at both ends of its
     // range (measured: each hand-over costs about SS_HANDOVER_COST / SS_UNIT_COST units).  With one whole tile
     // per workgroup nothing is handed over and the launch lasts as many tiles as the fullest CU gets.  With a
@@ -738,8 +888,10 @@ extern "C" int ssnet_debug_trace_read(u64 *host, size_t n)
 
 size_t ss_gemm_scratch_bytes(int n, int rows, int cols, int K)
 {
-    const gemm_plan p = plan_gemm(n, rows, cols, K);
-    return (size_t)p.tiles * p.slots * 4096 * sizeof(u64);
+    // room for either form (an operand given as limb planes never takes the 16-row form)
+    const gemm_plan p = plan_gemm(n, rows, cols, K, false), q = plan_gemm(n, rows, cols, K, true);
+    const size_t a = (size_t)p.tiles * p.slots * 4096, b = q.skinny ? (size_t)q.tiles * q.slots * SKINNY_PART : 0;
+    return (a > b ? a : b) * sizeof(u64);
 }
 
 hipError_t ss_launch_zero_counters(unsigned *counters, hipStream_t stream)
@@ -832,17 +984,20 @@ hipError_t launch_gemm(const void *packedA, const void *packedB, const conv_plan
                        unsigned *counters, u64 *partials, hipStream_t stream)
 {
     static bool lds_opt_in = false;
-    constexpr int LDS_BYTES = 2 * 8 * TILE * 16;
+    constexpr int LDS_BYTES = 2 * 8 * TILE * 16, LDS_BYTES_SKINNY = 2 * 9 * TILE * 16;
     if (!lds_opt_in) {
         hipError_t e = hipFuncSetAttribute((const void *)gemm_limb_kernel<false>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e == hipSuccess)
             e = hipFuncSetAttribute((const void *)gemm_limb_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                     LDS_BYTES);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)gemm_skinny_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    LDS_BYTES_SKINNY);
         if (e != hipSuccess) return e;
         lds_opt_in = true;
     }
-    const gemm_plan p = plan_gemm(n, rows, cols, K);
+    const gemm_plan p = plan_gemm(n, rows, cols, K, cv == nullptr);
     if (p.G <= 0) return hipErrorInvalidValue;
     gemm_args g = {};
     g.A = (const v4i *)packedA;
@@ -855,8 +1010,8 @@ hipError_t launch_gemm(const void *packedA, const void *packedB, const conv_plan
     g.Rb = (rows + 15) / 16;
     g.Cb = (cols + 15) / 16;
     g.Kb = p.Kb;
-    g.RT = (rows + 63) / 64;
-    g.CT = (cols + 63) / 64;
+    g.RT = p.skinny ? 1 : (rows + 63) / 64;
+    g.CT = p.skinny ? (cols + SKINNY_COLS - 1) / SKINNY_COLS : (cols + 63) / 64;
     g.units = (unsigned)p.units;
     g.wlast = p.wlast;
     g.wrow = p.wrow;
@@ -885,7 +1040,9 @@ hipError_t launch_gemm(const void *packedA, const void *packedB, const conv_plan
     g.trace_block = getenv("SS_TRACE_BLOCK") ? atoi(getenv("SS_TRACE_BLOCK")) : 0;
     ss_debug_trace = trace_buf;
 #endif
-    if (cv)
+    if (p.skinny)
+        hipLaunchKernelGGL(gemm_skinny_kernel, dim3((unsigned)p.G), dim3(512), LDS_BYTES_SKINNY, stream, g);
+    else if (cv)
         hipLaunchKernelGGL(gemm_limb_kernel<true>, dim3((unsigned)p.G), dim3(512), LDS_BYTES, stream, g);
     else
         hipLaunchKernelGGL(gemm_limb_kernel<false>, dim3((unsigned)p.G), dim3(512), LDS_BYTES, stream, g);

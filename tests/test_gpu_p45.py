@@ -82,7 +82,7 @@ def test_p45_reduce_truncate_and_fused_forms(n, t):
 
 
 P45_LINEAR_SHAPES = [(1, 1, 1), (3, 5, 7), (17, 65, 33), (64, 256, 128), (100, 300, 70), (1, 2048, 100), (49, 700, 80),
-                     (130, 1000, 200), (256, 4608, 49)]
+                     (130, 1000, 200), (256, 4608, 49), (1, 9216, 300), (16, 1000, 257), (8, 64, 128), (2, 16383, 130)]
 
 
 @pytest.mark.parametrize("n,t", [(3, 1), (5, 2), (7, 3)])

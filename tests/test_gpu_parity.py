@@ -202,7 +202,9 @@ def test_truncate_parity(n, t, f):
 
 
 LINEAR_SHAPES = [(1, 1, 1), (3, 5, 7), (16, 64, 16), (17, 65, 33), (32, 128, 32), (33, 129, 31), (64, 256, 128),
-                 (100, 300, 70), (1, 2048, 100), (49, 700, 80)]
+                 (100, 300, 70), (1, 2048, 100), (49, 700, 80),
+                 # at most 16 rows: the 16 x 128 tile form, whole and shared tiles, ragged column tiles
+                 (1, 9216, 300), (16, 1000, 257), (8, 64, 128), (2, 16383, 130), (5, 130, 1000), (16, 4096, 4096)]
 
 
 @pytest.mark.parametrize("n,t", [(3, 1), (5, 2)])
