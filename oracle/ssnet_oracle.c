@@ -27,7 +27,9 @@
  * for the pooled form torch's max_pool2d / avg_pool2d on the plain values and
  * the constancy of beta inside a pooling kernel; for the truncation with the
  * rounding division of App. C the printed worst case (error 2 for a 2x2
- * kernel), its bound by brute force, and independence of the mask.
+ * kernel), its bound by brute force, and independence of the mask; over the
+ * paper's prime 2^45 - 55 the split product of App. D restated with integers,
+ * the 16-bit + 13-bit budget of Sec. VII-A, and a tiny layer end to end.
  * The choice of generator itself is not fixed by the paper ("randomly
  * generated", Sec. IV-A): parity unpinned for *which* random bits are drawn.
  */
