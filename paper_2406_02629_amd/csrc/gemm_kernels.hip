@@ -270,25 +270,7 @@ __global__ __launch_bounds__(256) void planes4_kernel(const u64 *__restrict__ in
     }
 }
 
-#ifdef SS_GEMM_TRACE
-// development aid: workgroup 0 records the shader clock at phase boundaries
-#define SS_TRACE(tag)                                                                 \
-    do {                                                                              \
-        if (g.trace && blockIdx.x == g.trace_block && tid == 0 && tn < 4000) {         \
-            g.trace[2 * tn] = tag;                                                    \
-            g.trace[2 * tn + 1] = __builtin_amdgcn_s_memtime();                       \
-            tn++;                                                                     \
-        }                                                                             \
-    } while (0)
-#else
-#define SS_TRACE(tag)
-#endif
-
 struct gemm_args {
-#ifdef SS_GEMM_TRACE
-    u64 *trace;
-    int trace_block;
-#endif
     const v4i *A, *B;          // packed operands, all parties
     u64 *out;
     u64 *partials;             // [tile][slot][64*64] residues of tiles shared between workgroups
@@ -464,10 +446,6 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
     __shared__ unsigned arrival;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wr = wave & 3, wc = wave >> 2;
     const unsigned G = gridDim.x;
-#ifdef SS_GEMM_TRACE
-    int tn = 0;
-#endif
-    SS_TRACE(1);
     // consecutive ranges go to workgroups of the same XCD (workgroups are dealt
     // round-robin to the 8 XCDs), so that neighbours in the list share an L2
     const unsigned slot = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
@@ -515,11 +493,8 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
         const int kb_end = min(g.Kb, kb + (int)(u1 - u));
         wave_src next_src = src;
         for (; kb < kb_end; kb++, u++) {
-            SS_TRACE(2);
             __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of the unit is in LDS
-            SS_TRACE(3);
             __syncthreads();                      // everyone's part is; stage st^1 is no longer read
-            SS_TRACE(4);
             if (u + 1 < u1) {
                 int nkb = kb + 1;
                 if (nkb == g.Kb) {
@@ -571,8 +546,6 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
             }
             st ^= 1;
         }
-
-        SS_TRACE(5);
         // lane holds, per column block h, column lane%16 and rows 4*(lane/16)+r
         u64 v[2][4];
 #pragma unroll
@@ -585,7 +558,6 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
         const int rt = (int)(rem % (unsigned)g.RT), party = (int)(rem / (unsigned)g.RT);
         const int lrow = wr * 16 + 4 * (lane >> 4), lcol = wc * 32 + (lane & 15);   // within the 64 x 64 tile
         bool finish = true;
-        SS_TRACE(6);
         if (kb_first != 0 || kb_end != g.Kb) {   // the tile is shared: uniform over the workgroup
             const int first = owner_of(g, cost_before(g, tile, 0), G),
                       last = owner_of(g, cost_before(g, tile, (unsigned)g.Kb - 1), G);
@@ -598,13 +570,11 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
                     __hip_atomic_store(&part[(size_t)my * 4096 + (lrow + r) * 64 + lcol + 16 * h], v[h][r],
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the stores above are done
-            SS_TRACE(7);
             __syncthreads();
             if (tid == 0)
                 arrival = __hip_atomic_fetch_add(&g.counters[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __syncthreads();
             finish = arrival == (unsigned)(last - first);
-            SS_TRACE(8);
             if (finish) {
                 if (tid == 0) __hip_atomic_store(&g.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 for (int s = 0; s <= last - first; s++) {
@@ -632,16 +602,12 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
                 }
             }
         }
-        SS_TRACE(9);
         if (kb == g.Kb) {
             kb = 0;
             tile++;
             src = next_src;
         }
     }
-#ifdef SS_GEMM_TRACE
-    if (g.trace && blockIdx.x == g.trace_block && tid == 0) g.trace[8190] = tn;
-#endif
 }
 
 // The same contraction for a first operand of at most 16 rows (dense layers at a small batch, convolutions
@@ -876,15 +842,6 @@ gemm_plan plan_gemm(int n, int rows, int cols, int K, bool allow_skinny)
 
 }  // namespace
 
-#ifdef SS_GEMM_TRACE
-#include <stdlib.h>
-static u64 *ss_debug_trace = nullptr;
-extern "C" int ssnet_debug_trace_read(u64 *host, size_t n)
-{
-    if (!ss_debug_trace) return -1;
-    return (int)hipMemcpy(host, ss_debug_trace, n * sizeof(u64), hipMemcpyDeviceToHost);
-}
-#endif
 
 size_t ss_gemm_scratch_bytes(int n, int rows, int cols, int K)
 {
@@ -1033,13 +990,6 @@ hipError_t launch_gemm(const void *packedA, const void *packedB, const conv_plan
         g.cvH = cv->H, g.cvW = cv->W, g.cvC16 = cv->C / 16, g.cvKw = cv->kw, g.cvStride = cv->stride, g.cvPad = cv->pad;
         g.cvHoWo = cv->Ho * cv->Wo, g.cvWo = cv->Wo, g.cvKbTap = cv->C / 64;
     }
-#ifdef SS_GEMM_TRACE
-    static u64 *trace_buf = nullptr;
-    if (!trace_buf && hipMalloc(&trace_buf, 8192 * sizeof(u64)) != hipSuccess) return hipErrorOutOfMemory;
-    g.trace = trace_buf;
-    g.trace_block = getenv("SS_TRACE_BLOCK") ? atoi(getenv("SS_TRACE_BLOCK")) : 0;
-    ss_debug_trace = trace_buf;
-#endif
     if (p.skinny)
         hipLaunchKernelGGL(gemm_skinny_kernel, dim3((unsigned)p.G), dim3(512), LDS_BYTES_SKINNY, stream, g);
     else if (cv)
