@@ -52,6 +52,7 @@ extern "C" {
 #define SSNET_EID (-4)        /* party id outside [1, n] or repeated                   */
 #define SSNET_EWORKSPACE (-5) /* workspace missing or too small for this call          */
 #define SSNET_EHIP (-6)       /* a HIP call failed; see ssnet_last_hip_error           */
+#define SSNET_ESCRATCH (-7)   /* count beyond the fixed scratch of ssnet_degree_reduce_static */
 
 #define SSNET_MAX_PARTIES 8   /* n <= 8                                                */
 #define SSNET_MAX_T 3         /* t <= 3 (n >= 2t+1)                                    */
@@ -185,6 +186,25 @@ int ssnet_conv_mod_planes(ssnet_ctx *ctx, const void *d_planes, const void *d_w_
  * steps 1 and 2 are materialised in the workspace ([2t+1][k][count] and
  * [k][n][count]).  d_out may alias d_c. */
 int ssnet_degree_reduce(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id, uint64_t *d_out);
+
+/* ssnet_degree_reduce for callers that cannot allocate device memory or hand a
+ * workspace over: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, same random draws, same d_out and the
+ * same two message arrays as ssnet_degree_reduce, but the messages go to a fixed
+ * array of SSNET_STATIC_SCRATCH_BYTES inside the library's device image (each
+ * GPU the library runs on holds it until the process ends) instead of the
+ * workspace; no workspace is needed and the call allocates and frees nothing.
+ * Limit: (2t+1)(t+1) + (t+1)n message words per element must fit, i.e. count <=
+ * SSNET_STATIC_SCRATCH_BYTES / 8 / ((2t+1)(t+1) + (t+1)n) (34952 elements for
+ * n = 5, t = 2), else SSNET_ESCRATCH and nothing is launched.  Every call on a
+ * GPU uses that GPU's one array (nothing in it needs clearing: a launch writes
+ * each message before it is read), so calls that overlap on one GPU, from any
+ * context or stream, race on it; calls on one stream are ordered and safe.
+ * The device current at the call must be the one the context's stream is on.
+ * d_out may alias d_c. */
+#define SSNET_STATIC_SCRATCH_BYTES (8u << 20)
+int ssnet_degree_reduce_static(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id,
+                               uint64_t *d_out);
 
 /* SSS-Truncation (Sec. VI-B) by r = 2^f: shares of floor(x / 2^f), x read as a
  * signed value in [-(p-1)/2, (p-1)/2].

@@ -18,7 +18,8 @@ P61 = (1 << 61) - 1
 P45 = (1 << 45) - 55          # the prime of Sec. VII-A; served by the second library
 
 WS_HEADER_BYTES = 65536      # SSNET_WS_HEADER_BYTES
-OK, EINVAL, EPRIME, ESHARES, EID, EWORKSPACE, EHIP = 0, -1, -2, -3, -4, -5, -6
+OK, EINVAL, EPRIME, ESHARES, EID, EWORKSPACE, EHIP, ESCRATCH = 0, -1, -2, -3, -4, -5, -6, -7
+STATIC_SCRATCH_BYTES = 8 << 20   # SSNET_STATIC_SCRATCH_BYTES
 DOM_SHARE, DOM_RESHARE, DOM_ZERO, DOM_MASK_E, DOM_MASK_ALPHA, DOM_MASK_ALPHAT, DOM_TRUNC_GEN = range(1, 8)
 
 _u64, _sz, _int, _ptr = C.c_uint64, C.c_size_t, C.c_int, C.c_void_p
@@ -49,6 +50,7 @@ SIGNATURES = {
     "ssnet_pack_weights_conv_taps": (_int, [_ptr, _ptr, _int, _int, _int, _int, _ptr]),
     "ssnet_conv_mod_planes": (_int, [_ptr, _ptr, _ptr] + [_int] * 9 + [_ptr]),
     "ssnet_degree_reduce": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
+    "ssnet_degree_reduce_static": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
     "ssnet_truncate": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
     "ssnet_degree_reduce_truncate": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
     "ssnet_degree_reduce_truncate_reconstruct": (_int, [_ptr, _ptr, _sz, _u64, _ptr, C.POINTER(_int), _int, _ptr]),
@@ -366,6 +368,15 @@ class SSNet:
             out = torch.empty_like(c)
         self._ok(self.lib.ssnet_degree_reduce(self._ctx, _dptr(c), count, stream_id, _dptr(out)),
                  "ssnet_degree_reduce")
+        return out
+
+    def degree_reduce_static(self, c: torch.Tensor, stream_id: int, out: torch.Tensor) -> torch.Tensor:
+        """ssnet_degree_reduce with the messages in the library's fixed device array: no workspace, and
+        nothing is allocated here either (the caller brings `out`)."""
+        _check_i64(c, "c")
+        _check_i64(out, "out")
+        self._ok(self.lib.ssnet_degree_reduce_static(self._ctx, _dptr(c), c[0].numel(), stream_id, _dptr(out)),
+                 "ssnet_degree_reduce_static")
         return out
 
     def truncate(self, x: torch.Tensor, stream_id: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:

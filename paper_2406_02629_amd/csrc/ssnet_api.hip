@@ -4,12 +4,18 @@
 #include "../../include/ssnet.h"
 
 #include <limits.h>
+#include <mutex>
 #include <new>
 #include <vector>
 
 #include "kernels.hpp"
 
 using namespace SS_NS;
+
+// Message buffer of ssnet_degree_reduce_static, the entry point that allocates nothing: a fixed array in
+// the library's device image.  Every GPU the library runs on holds its own copy at its own address until
+// the process ends; host code reaches it only through the per-device address taken below.
+static __device__ __align__(256) unsigned char scratch[SSNET_STATIC_SCRATCH_BYTES];
 
 struct ssnet_ctx {
     int n, t, f;
@@ -637,6 +643,47 @@ int ssnet_degree_reduce(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint6
 
 namespace {
 
+// device address of `scratch` on the current device, looked up once per device
+hipError_t static_scratch(void **out)
+{
+    constexpr int MAX_DEVICES = 64;
+    static void *ptr[MAX_DEVICES];   // zero-initialised
+    static std::mutex lock;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> guard(lock);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return hipSuccess;
+}
+
+}  // namespace
+
+int ssnet_degree_reduce_static(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id, uint64_t *d_out)
+{
+    if (!ctx || !d_c || !d_out || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
+    const int k = ctx->t + 1, nr = 2 * ctx->t + 1, n = ctx->n;
+    const size_t words = (size_t)nr * k + (size_t)k * n;
+    if (count > SSNET_STATIC_SCRATCH_BYTES / 8 / words) return SSNET_ESCRATCH;
+    void *base = nullptr;
+    hipError_t e = static_scratch(&base);
+    if (e != hipSuccess) return fail_hip(ctx, e);
+    // both message arrays are written in full by the launch before anything reads them: nothing to clear
+    u64 *msg1 = (u64 *)base, *msg2 = msg1 + (size_t)nr * k * count;
+    e = ss_launch_degree_reduce(d_c, msg1, msg2, d_out, count, make_dr_params(ctx, stream_id), ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+namespace {
+
 static int truncate_by(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, int kdiv, uint64_t stream_id, uint64_t *d_out)
 {
     if (!ctx || !d_x || !d_out || count == 0 || count > MAX_COUNT || kdiv < 1 || kdiv > SSNET_MAX_KDIV)
@@ -972,6 +1019,7 @@ const char *ssnet_strerror(int code)
         case SSNET_EID: return "party id out of range or repeated";
         case SSNET_EWORKSPACE: return "workspace missing or too small";
         case SSNET_EHIP: return "HIP error";
+        case SSNET_ESCRATCH: return "count exceeds the fixed scratch of the entry point that allocates nothing";
         default: return "unknown error";
     }
 }

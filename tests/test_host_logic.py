@@ -51,6 +51,10 @@ def test_null_and_range_checks_before_any_launch():
     assert lib.ssnet_reconstruct(ctx, 16, 8, (C.c_int * 3)(0, 1, 2), 3, 2, 16) == binding.EID
     assert lib.ssnet_degree_reduce(ctx, 16, 8, 0, 16) == binding.EWORKSPACE
     assert lib.ssnet_truncate(ctx, 16, 8, 0, 16) == binding.EWORKSPACE
+    # the entry point with the fixed message array: (8 MiB / 8) / 30 words per element at n = 5, t = 2
+    assert lib.ssnet_degree_reduce_static(ctx, 16, 34953, 0, 16) == binding.ESCRATCH
+    assert lib.ssnet_degree_reduce_static(ctx, None, 8, 0, 16) == binding.EINVAL
+    assert b"fixed scratch" in lib.ssnet_strerror(binding.ESCRATCH)
     assert lib.ssnet_linear_mod(ctx, 16, 16, 4, 4, 4, 16) == binding.EWORKSPACE
     assert lib.ssnet_linear_mod(ctx, 16, 16, 4, 16384, 4, 16) == binding.EINVAL   # K too long for int32
     assert lib.ssnet_linear_mod(ctx, 16, 16, 0, 4, 4, 16) == binding.EINVAL
