@@ -79,11 +79,10 @@ int ssnet_destroy(ssnet_ctx *ctx);
  * ssnet_truncate on `count` elements, and for the int8 limb tiles and split
  * partial sums of ssnet_linear_mod / ssnet_conv_mod.  Sizes are in bytes; a
  * workspace of the maximum over the calls that will be made serves all of them.
- * The first SSNET_WS_HEADER_BYTES of a workspace hold arrival counters that the
- * library zeroes in ssnet_set_workspace (one small kernel on the stream) and
- * keeps zero between calls; the messages of ssnet_degree_reduce ([2t+1][k][count]
- * then [k][n][count]) and of ssnet_truncate ([k][count] then [n][count]) start
- * right behind that header.  16-byte aligned. */
+ * The first SSNET_WS_HEADER_BYTES of a workspace are reserved; the messages of
+ * ssnet_degree_reduce ([2t+1][k][count] then [k][n][count]) and of
+ * ssnet_truncate ([k][count] then [n][count]) start right behind that header.
+ * 16-byte aligned. */
 #define SSNET_WS_HEADER_BYTES 65536
 size_t ssnet_workspace_bytes_stream(const ssnet_ctx *ctx, size_t count);
 size_t ssnet_workspace_bytes_linear(const ssnet_ctx *ctx, int M, int K, int N);
@@ -176,6 +175,37 @@ int ssnet_pack_weights_conv_taps(ssnet_ctx *ctx, const uint64_t *d_w, int Co, in
 int ssnet_conv_mod_planes(ssnet_ctx *ctx, const void *d_planes, const void *d_w_packed, int B, int C, int H, int W,
                           int Co, int kh, int kw, int stride, int pad, uint64_t *d_y);
 
+/* SSS-Linear step 1 (Sec. VI-A) with the product shares left inside the
+ * workspace for the reduction that follows (steps 2 and 3): the layers of a
+ * batch-1 network are small, a product kernel then has fewer output tiles than
+ * the chip has compute units and splits the contraction over them, and in this
+ * form it does not gather the pieces: every workgroup stores what it has, as
+ * planes whose sum mod p is the product, and the reduction adds the planes while
+ * it reads them.  Nothing is exchanged or waited for inside the product kernel.
+ *   ssnet_*_product_*: same operands, shapes and checks as ssnet_linear_mod_prepacked,
+ *     ssnet_conv1x1_mod_prepacked and ssnet_conv_mod_planes, but no d_y: the
+ *     product (count = M*N, resp. B*Co*Ho*Wo elements per party) becomes the
+ *     context's pending product, kept in the last ssnet_product_bytes_* bytes of
+ *     the workspace until the next ssnet_*_product_* or ssnet_set_workspace call.
+ *   Consuming it: ssnet_degree_reduce, ssnet_degree_reduce_truncate(_div,
+ *     _reconstruct), ssnet_reduce_truncate_direct and ssnet_reduce_truncate_relu
+ *     take d_c = NULL for "the pending product" (count, resp. B*C*HW, must equal
+ *     its element count, else SSNET_EINVAL; SSNET_EINVAL too if there is none).
+ *     Results, messages and random draws are those of the same call on the d_y
+ *     that the corresponding ssnet_*_mod_* call writes.  The call's messages
+ *     start behind the workspace header as always, so the workspace must hold
+ *     ssnet_workspace_bytes_stream(count) (ssnet_workspace_bytes_layer_tail for
+ *     ssnet_reduce_truncate_relu) plus ssnet_product_bytes_*(...) bytes, else
+ *     SSNET_EWORKSPACE. */
+size_t ssnet_product_bytes_linear(const ssnet_ctx *ctx, int M, int K, int N);
+size_t ssnet_product_bytes_conv(const ssnet_ctx *ctx, int B, int C, int H, int W, int Co, int kh, int kw, int stride,
+                                int pad);
+int ssnet_linear_product_prepacked(ssnet_ctx *ctx, const void *d_x_packed, const void *d_w_packed, int M, int K, int N);
+int ssnet_conv1x1_product_prepacked(ssnet_ctx *ctx, const void *d_x_packed, const void *d_w_packed, int B, int C, int HW,
+                                    int Co);
+int ssnet_conv_product_planes(ssnet_ctx *ctx, const void *d_planes, const void *d_w_packed, int B, int C, int H, int W,
+                              int Co, int kh, int kw, int stride, int pad);
+
 /* RED by resharing (Sec. IV-B, the three protocol steps with the matrix of
  * Eq. 3) followed by RERAND (Sec. IV-C), all n parties:
  *   1. parties 1..2t+1: GEN(c_i, k, k) towards parties 1..k   (domain RESHARE, party i)
@@ -184,7 +214,7 @@ int ssnet_conv_mod_planes(ssnet_ctx *ctx, const void *d_planes, const void *d_w_
  *      of a fresh degree-t sharing of zero                     (domain ZERO)
  * d_c [n][count] (degree 2t) -> d_out [n][count] (degree t).  The messages of
  * steps 1 and 2 are materialised in the workspace ([2t+1][k][count] and
- * [k][n][count]).  d_out may alias d_c. */
+ * [k][n][count]).  d_out may alias d_c.  d_c = NULL: the pending product. */
 int ssnet_degree_reduce(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id, uint64_t *d_out);
 
 /* ssnet_degree_reduce for callers that cannot allocate device memory or hand a
@@ -374,8 +404,9 @@ int ssnet_host_reduction_matrix(const ssnet_ctx *ctx, uint64_t *out);
  * events recorded on the context's stream.  ssnet_profile_end waits for those
  * events and writes, per class, the summed elapsed milliseconds and the number
  * of bracketed spans into two HOST arrays of SSNET_PROF_CLASSES entries.  A
- * span is one kernel, except DEGREE_REDUCE and TRUNCATE (three kernels each).
- * Not for use under stream capture. */
+ * span is what one entry-point call launches of that class: one kernel, two
+ * where a call is documented as two launches.  Not for use under stream
+ * capture. */
 #define SSNET_PROF_SHARE 0
 #define SSNET_PROF_RECONSTRUCT 1
 #define SSNET_PROF_PACK_W 2

@@ -49,6 +49,11 @@ SIGNATURES = {
     "ssnet_split_planes": (_int, [_ptr, _ptr, _int, _int, _int, _int, _ptr]),
     "ssnet_pack_weights_conv_taps": (_int, [_ptr, _ptr, _int, _int, _int, _int, _ptr]),
     "ssnet_conv_mod_planes": (_int, [_ptr, _ptr, _ptr] + [_int] * 9 + [_ptr]),
+    "ssnet_product_bytes_linear": (_sz, [_ptr, _int, _int, _int]),
+    "ssnet_product_bytes_conv": (_sz, [_ptr] + [_int] * 9),
+    "ssnet_linear_product_prepacked": (_int, [_ptr, _ptr, _ptr, _int, _int, _int]),
+    "ssnet_conv1x1_product_prepacked": (_int, [_ptr, _ptr, _ptr, _int, _int, _int, _int]),
+    "ssnet_conv_product_planes": (_int, [_ptr, _ptr, _ptr] + [_int] * 9),
     "ssnet_degree_reduce": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
     "ssnet_degree_reduce_static": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
     "ssnet_truncate": (_int, [_ptr, _ptr, _sz, _u64, _ptr]),
@@ -344,6 +349,33 @@ class SSNet:
                                                 pad, _dptr(out)), "ssnet_conv_mod_planes")
         return out
 
+    # ---- products left in the workspace for the reduction that follows (d_c = NULL there) ----
+    def _reserve_product(self, product_bytes: int, B: int, C: int, HW: int):
+        """room for the pending product plus the messages of whichever call consumes it"""
+        if product_bytes == 0:
+            raise SSNetError(EINVAL, "ssnet_product_bytes")
+        msgs = max(self.workspace_bytes_stream(B * C * HW), self.lib.ssnet_workspace_bytes_layer_tail(self._ctx, B, C, HW))
+        self.reserve(msgs + product_bytes)
+
+    def linear_product_prepacked(self, x_packed: torch.Tensor, w_packed: torch.Tensor, M: int, K: int, N: int):
+        self._reserve_product(self.lib.ssnet_product_bytes_linear(self._ctx, M, K, N), M, N, 1)
+        self._ok(self.lib.ssnet_linear_product_prepacked(self._ctx, _dptr(x_packed), _dptr(w_packed), M, K, N),
+                 "ssnet_linear_product_prepacked")
+
+    def conv1x1_product_prepacked(self, x_packed: torch.Tensor, w_packed: torch.Tensor, B: int, C: int, H: int, W: int,
+                                  Co: int):
+        self._reserve_product(self.lib.ssnet_product_bytes_conv(self._ctx, B, C, H, W, Co, 1, 1, 1, 0), B, Co, H * W)
+        self._ok(self.lib.ssnet_conv1x1_product_prepacked(self._ctx, _dptr(x_packed), _dptr(w_packed), B, C, H * W, Co),
+                 "ssnet_conv1x1_product_prepacked")
+
+    def conv_product_planes(self, planes: torch.Tensor, w_packed: torch.Tensor, B: int, C: int, H: int, W: int, Co: int,
+                            kh: int, kw: int, stride: int, pad: int):
+        Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+        self._reserve_product(self.lib.ssnet_product_bytes_conv(self._ctx, B, C, H, W, Co, kh, kw, stride, pad), B, Co,
+                              Ho * Wo)
+        self._ok(self.lib.ssnet_conv_product_planes(self._ctx, _dptr(planes), _dptr(w_packed), B, C, H, W, Co, kh, kw,
+                                                    stride, pad), "ssnet_conv_product_planes")
+
     def conv_mod_packed(self, x: torch.Tensor, w_packed: torch.Tensor, Co: int, kh: int, kw: int, stride: int,
                         pad: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
         _check_i64(x, "x")
@@ -360,13 +392,23 @@ class SSNet:
         return out
 
     # ---- RED + RERAND, truncation ----
-    def degree_reduce(self, c: torch.Tensor, stream_id: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
-        _check_i64(c, "c")
+    @staticmethod
+    def _incoming(c: Optional[torch.Tensor], out: Optional[torch.Tensor]):
+        """c = None stands for the pending product (d_c = NULL); `out` then gives the shape.
+        -> (pointer or None, tensor of the shares' shape)"""
+        if c is None:
+            if out is None:
+                raise TypeError("the pending product needs `out` for its shape")
+            return None, _check_i64(out, "out")
+        return _dptr(_check_i64(c, "c")), c
+
+    def degree_reduce(self, c: Optional[torch.Tensor], stream_id: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        cp, c = self._incoming(c, out)
         count = c[0].numel()
         self.reserve(self.workspace_bytes_stream(count))
         if out is None:
             out = torch.empty_like(c)
-        self._ok(self.lib.ssnet_degree_reduce(self._ctx, _dptr(c), count, stream_id, _dptr(out)),
+        self._ok(self.lib.ssnet_degree_reduce(self._ctx, cp, count, stream_id, _dptr(out)),
                  "ssnet_degree_reduce")
         return out
 
@@ -388,14 +430,14 @@ class SSNet:
         self._ok(self.lib.ssnet_truncate(self._ctx, _dptr(x), count, stream_id, _dptr(out)), "ssnet_truncate")
         return out
 
-    def degree_reduce_truncate(self, c: torch.Tensor, stream_id: int,
+    def degree_reduce_truncate(self, c: Optional[torch.Tensor], stream_id: int,
                                out: Optional[torch.Tensor] = None) -> torch.Tensor:
-        _check_i64(c, "c")
+        cp, c = self._incoming(c, out)
         count = c[0].numel()
         self.reserve(self.workspace_bytes_stream(count))
         if out is None:
             out = torch.empty_like(c)
-        self._ok(self.lib.ssnet_degree_reduce_truncate(self._ctx, _dptr(c), count, stream_id, _dptr(out)),
+        self._ok(self.lib.ssnet_degree_reduce_truncate(self._ctx, cp, count, stream_id, _dptr(out)),
                  "ssnet_degree_reduce_truncate")
         return out
 
@@ -408,22 +450,22 @@ class SSNet:
         self._ok(self.lib.ssnet_truncate_div(self._ctx, _dptr(x), count, kdiv, stream_id, _dptr(out)), "ssnet_truncate_div")
         return out
 
-    def degree_reduce_truncate_div(self, c: torch.Tensor, kdiv: int, stream_id: int,
+    def degree_reduce_truncate_div(self, c: Optional[torch.Tensor], kdiv: int, stream_id: int,
                                    out: Optional[torch.Tensor] = None) -> torch.Tensor:
-        _check_i64(c, "c")
+        cp, c = self._incoming(c, out)
         count = c[0].numel()
         self.reserve(self.workspace_bytes_stream(count))
         if out is None:
             out = torch.empty_like(c)
-        self._ok(self.lib.ssnet_degree_reduce_truncate_div(self._ctx, _dptr(c), count, kdiv, stream_id, _dptr(out)),
+        self._ok(self.lib.ssnet_degree_reduce_truncate_div(self._ctx, cp, count, kdiv, stream_id, _dptr(out)),
                  "ssnet_degree_reduce_truncate_div")
         return out
 
-    def degree_reduce_truncate_reconstruct(self, c: torch.Tensor, stream_id: int, ids: Sequence[int],
+    def degree_reduce_truncate_reconstruct(self, c: Optional[torch.Tensor], stream_id: int, ids: Sequence[int],
                                            out: Optional[torch.Tensor] = None,
                                            secret: Optional[torch.Tensor] = None):
         """-> (truncated shares [n][...], their reconstruction from the parties `ids`)"""
-        _check_i64(c, "c")
+        cp, c = self._incoming(c, out)
         count = c[0].numel()
         self.reserve(self.workspace_bytes_stream(count))
         if out is None:
@@ -433,7 +475,7 @@ class SSNet:
         else:
             _check_i64(secret, "secret")
         arr = (_int * len(ids))(*ids)
-        self._ok(self.lib.ssnet_degree_reduce_truncate_reconstruct(self._ctx, _dptr(c), count, stream_id, _dptr(out),
+        self._ok(self.lib.ssnet_degree_reduce_truncate_reconstruct(self._ctx, cp, count, stream_id, _dptr(out),
                                                                    arr, len(ids), _dptr(secret)),
                  "ssnet_degree_reduce_truncate_reconstruct")
         return out, secret
@@ -442,14 +484,14 @@ class SSNet:
     def reduce_truncate_direct(self, c: torch.Tensor, stream_id: int, ids: Optional[Sequence[int]] = None,
                                out: Optional[torch.Tensor] = None, secret: Optional[torch.Tensor] = None):
         """-> (truncated shares, their reconstruction or None): the outputs of the protocol calls, no messages"""
-        _check_i64(c, "c")
+        cp, c = self._incoming(c, out)
         count = c[0].numel()
         if out is None:
             out = torch.empty_like(c)
         if ids is not None and secret is None:
             secret = torch.empty(c.shape[1:], dtype=torch.int64, device=c.device)
         arr = (_int * len(ids))(*ids) if ids is not None else None
-        self._ok(self.lib.ssnet_reduce_truncate_direct(self._ctx, _dptr(c), count, stream_id, _dptr(out), arr,
+        self._ok(self.lib.ssnet_reduce_truncate_direct(self._ctx, cp, count, stream_id, _dptr(out), arr,
                                                        len(ids) if ids is not None else 0,
                                                        _dptr(secret) if secret is not None else None),
                  "ssnet_reduce_truncate_direct")
@@ -459,7 +501,7 @@ class SSNet:
                              out: Optional[torch.Tensor] = None, planes: Optional[torch.Tensor] = None,
                              want_planes: bool = False):
         """c [n][B][C][H][W] (or [n][B][C]) product shares -> (shares of ReLU(trunc(.)), limb planes or None)"""
-        _check_i64(c, "c")
+        cp, c = self._incoming(c, out)
         n, B, C = c.shape[0], c.shape[1], c.shape[2]
         HW = c[0, 0, 0].numel()
         count = c[0].numel()
@@ -470,7 +512,7 @@ class SSNet:
             out = torch.empty_like(c)
         if want_planes and planes is None:
             planes = self._planes_buffer(B, C, HW, 1, None, c.device)
-        self._ok(self.lib.ssnet_reduce_truncate_relu(self._ctx, _dptr(c), B, C, HW, stream_id, _dptr(beta), _dptr(betainv),
+        self._ok(self.lib.ssnet_reduce_truncate_relu(self._ctx, cp, B, C, HW, stream_id, _dptr(beta), _dptr(betainv),
                                                      _dptr(out), _dptr(planes) if planes is not None else None),
                  "ssnet_reduce_truncate_relu")
         return out, planes

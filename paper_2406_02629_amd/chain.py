@@ -66,10 +66,13 @@ def post_plain(y: torch.Tensor, L: Layer) -> torch.Tensor:
 
 class Chain:
     def __init__(self, ss: SSNet, layers: List[Layer], batch: int = 1, image_seed: int = 5,
-                 weight_seed_base: int = 100, keep_weight_shares: bool = False, weights_of: "Optional[Chain]" = None):
+                 weight_seed_base: int = 100, keep_weight_shares: bool = False, weights_of: "Optional[Chain]" = None,
+                 deferred: bool = True):
         """weights_of: another harness over the same layers and context whose prepared weight tiles are
-        reused (they do not depend on the batch size)."""
-        self.ss, self.layers, self.batch = ss, layers, batch
+        reused (they do not depend on the batch size).
+        deferred: a layer's product shares stay in the workspace as a sum of planes and the reduction
+        that follows adds them up (ssnet_*_product_*); otherwise the product kernel writes them out whole."""
+        self.ss, self.layers, self.batch, self.deferred = ss, layers, batch, deferred
         dev = ss.device
         # k x k layers whose channel count allows it read their input from channel-innermost limb planes
         # instead of an im2col matrix; their weights are packed in (tap, channel) order
@@ -111,8 +114,16 @@ class Chain:
             if L.kind == "conv":
                 need = max(need, ss.workspace_bytes_conv(batch, L.cin, L.hin, L.hin, L.cout, L.ksize, L.ksize,
                                                          L.stride, L.pad))
+                tail = (batch, L.cout, L.M)
+                product = ss.lib.ssnet_product_bytes_conv(ss._ctx, batch, L.cin, L.hin, L.hin, L.cout, L.ksize, L.ksize,
+                                                          L.stride, L.pad)
             else:
                 need = max(need, ss.workspace_bytes_linear(batch, L.cin, L.cout))
+                tail = (batch, L.cout, 1)
+                product = ss.lib.ssnet_product_bytes_linear(ss._ctx, batch, L.cin, L.cout)
+            # a pending product sits behind the messages of the call that consumes it
+            need = max(need, product + max(ss.workspace_bytes_stream(count),
+                                           ss.lib.ssnet_workspace_bytes_layer_tail(ss._ctx, *tail)))
         ss.reserve(need)
 
     def _in_shape(self, L: Layer):
@@ -124,23 +135,37 @@ class Chain:
     def run_layer(self, l: int, x_plain: torch.Tensor, stages: str = "sgdtr") -> torch.Tensor:
         """All share arithmetic of layer l.  `stages` selects steps for timing
         breakdowns: s=share, g=gemm/conv, d=degree_reduce, t=truncate, r=reconstruct;
-        D = the outputs of d, t, r by the no-message shortcut (reported separately)."""
+        D = the outputs of d, t, r by the no-message shortcut (reported separately);
+        p = leave the product pending although no reduction is asked for (timing of the product alone)."""
         ss, L = self.ss, self.layers[l]
         xs, y = self.x_shares[l], self.y[l]
+        # the product stays in the workspace if a reduction follows in this call
+        defer = self.deferred and "g" in stages and any(c in stages for c in "dDp")
+        pending = False
         if self.pointwise[l] and "s" in stages and "g" in stages:
             ss.share_packed(x_plain, stream_id=l, out=xs, packed=self.x_tiles)
             if L.kind == "conv":
-                ss.conv1x1_mod_prepacked(self.x_tiles, self.packed[l], self.batch, L.cin, L.hin, L.hin, L.cout, out=y)
+                if defer:
+                    ss.conv1x1_product_prepacked(self.x_tiles, self.packed[l], self.batch, L.cin, L.hin, L.hin, L.cout)
+                else:
+                    ss.conv1x1_mod_prepacked(self.x_tiles, self.packed[l], self.batch, L.cin, L.hin, L.hin, L.cout, out=y)
+            elif defer:
+                ss.linear_product_prepacked(self.x_tiles, self.packed[l], self.batch, L.cin, L.cout)
             else:
                 ss.linear_mod_prepacked(self.x_tiles, self.packed[l], self.batch, L.cin, L.cout, out=y)
+            pending = defer
             stages = stages.replace("s", "").replace("g", "")
         if self.on_planes[l] and "g" in stages:
             if "s" in stages:
                 ss.share_planes(x_plain, stream_id=l, out=xs, planes=self.x_planes)
             else:
                 ss.split_planes(xs, planes=self.x_planes)
-            ss.conv_mod_planes(self.x_planes, self.packed[l], self.batch, L.cin, L.hin, L.hin, L.cout, L.ksize, L.ksize,
-                               L.stride, L.pad, out=y)
+            geom = (self.batch, L.cin, L.hin, L.hin, L.cout, L.ksize, L.ksize, L.stride, L.pad)
+            if defer:
+                ss.conv_product_planes(self.x_planes, self.packed[l], *geom)
+            else:
+                ss.conv_mod_planes(self.x_planes, self.packed[l], *geom, out=y)
+            pending = defer
             stages = stages.replace("s", "").replace("g", "")
         if "s" in stages:
             ss.share(x_plain, stream_id=l, out=xs)
@@ -150,16 +175,17 @@ class Chain:
             else:
                 ss.linear_mod_packed(xs, self.packed[l], L.cout, out=y)
         yv = y.view(ss.n, -1)
+        c = None if pending else yv    # None: the pending product
         if "D" in stages:   # the outputs of reduction, truncation and opening without the protocol's messages
-            ss.reduce_truncate_direct(yv, stream_id=l, ids=self.ids, out=yv, secret=self.rec[l])
+            ss.reduce_truncate_direct(c, stream_id=l, ids=self.ids, out=yv, secret=self.rec[l])
             return self.rec[l]
         if "d" in stages and "t" in stages and "r" in stages:   # one launch for the three steps
-            ss.degree_reduce_truncate_reconstruct(yv, stream_id=l, ids=self.ids, out=yv, secret=self.rec[l])
+            ss.degree_reduce_truncate_reconstruct(c, stream_id=l, ids=self.ids, out=yv, secret=self.rec[l])
             return self.rec[l]
         if "d" in stages and "t" in stages:
-            ss.degree_reduce_truncate(yv, stream_id=l, out=yv)
+            ss.degree_reduce_truncate(c, stream_id=l, out=yv)
         elif "d" in stages:
-            ss.degree_reduce(yv, stream_id=l, out=yv)
+            ss.degree_reduce(c, stream_id=l, out=yv)
         elif "t" in stages:
             ss.truncate(yv, stream_id=l, out=yv)
         if "r" in stages:
@@ -234,32 +260,38 @@ class Chain:
             x_shares = ss.share(x_plain, stream_id=l, out=self.x_shares[l])
         elif L.kind == "fc":
             x_shares = x_shares.view(ss.n, self.batch, -1)
+        pending = False
         if self.sec_planes[l]:
             if not planes_ready:
                 ss.split_planes(x_shares, planes=self.x_planes)
-            ss.conv_mod_planes(self.x_planes, self.sec_packed[l], self.batch, L.cin, L.hin, L.hin, L.cout, L.ksize,
-                               L.ksize, L.stride, L.pad, out=y)
+            geom = (self.batch, L.cin, L.hin, L.hin, L.cout, L.ksize, L.ksize, L.stride, L.pad)
+            if self.deferred:   # every branch below starts with a reduction, which adds the product's planes up
+                ss.conv_product_planes(self.x_planes, self.sec_packed[l], *geom)
+                pending = True
+            else:
+                ss.conv_mod_planes(self.x_planes, self.sec_packed[l], *geom, out=y)
         elif L.kind == "conv":
             ss.conv_mod_packed(x_shares, self.packed[l], L.cout, L.ksize, L.ksize, L.stride, L.pad, out=y)
         else:
             ss.linear_mod_packed(x_shares, self.packed[l], L.cout, out=y)
         yv = y.view(ss.n, -1)
+        c = None if pending else yv
         if L.post == "relu":
             # reduce + truncate + ReLU in one launch, which also leaves the next layer's limb planes
             b, bi = self.masks[l]
             nxt = l + 1 < len(self.layers) and self.sec_planes[l + 1]
-            ss.reduce_truncate_relu(y, l, b, bi, out=y, planes=self.x_planes if nxt else None)
+            ss.reduce_truncate_relu(None if pending else y, l, b, bi, out=y, planes=self.x_planes if nxt else None)
             return y, None
         if self.pooled[l] is not None:
             # reduce + truncate (with the division of an average), then ReLU and pooling under the mask
             kern, stride, pad, mode, kdiv = pool_spec(L)
             b, bi = self.masks[l]
             if kdiv > 1:
-                ss.degree_reduce_truncate_div(yv, kdiv, stream_id=l, out=yv)
+                ss.degree_reduce_truncate_div(c, kdiv, stream_id=l, out=yv)
             else:
-                ss.degree_reduce_truncate(yv, stream_id=l, out=yv)
+                ss.degree_reduce_truncate(c, stream_id=l, out=yv)
             return ss.relu_pool(y, b, bi, kern, stride, pad, mode, out=self.pooled[l]), None
-        ss.degree_reduce_truncate_reconstruct(yv, stream_id=l, ids=self.ids, out=yv, secret=self.rec[l])
+        ss.degree_reduce_truncate_reconstruct(c, stream_id=l, ids=self.ids, out=yv, secret=self.rec[l])
         return None, self.rec[l]
 
     def _planes_ready(self, l: int, x_shares) -> bool:

@@ -270,24 +270,35 @@ __global__ __launch_bounds__(256) void planes4_kernel(const u64 *__restrict__ in
     }
 }
 
+// x / d for x < 2^31 by a multiplication: (x * m) >> s with s = 31 + ceil(log2 d), m = ceil(2^s / d) < 2^32.
+// The index arithmetic of the product kernels runs on these (a 64-bit division is some two hundred
+// instructions on this machine, and a launch of a small layer lasts only a few thousand).
+struct fdiv {
+    u32 m, s;
+};
+
+__host__ __device__ __forceinline__ u32 fd_div(u32 x, fdiv d) { return (u32)(((u64)x * d.m) >> d.s); }
+
 struct gemm_args {
     const v4i *A, *B;          // packed operands, all parties
-    u64 *out;
-    u64 *partials;             // [tile][slot][64*64] residues of tiles shared between workgroups
-    unsigned *counters;        // [tile], zero between launches
+    u64 *out;                  // `slots` planes of the output's layout, part_stride elements apart
+    size_t part_stride;
     int rows, cols, Rb, Cb, Kb, RT, CT;
-    unsigned units;            // tiles * Kb (< 2^31), or 0: one whole tile per workgroup
-    unsigned wlast, wrow;      // cost of one unit of the last column tile; of one k block over a whole tile row
-    unsigned long long cost;   // of all units
-    int slots;                 // partial slots per tile
+    unsigned units;            // tiles * Kb, or 0: one whole tile per workgroup
+    unsigned wlast;            // cost of one unit of the last column tile (SS_UNIT_COST for the others)
+    unsigned tcost, tlast;     // cost of a whole tile, fold included: all column tiles but the last; the last
+    unsigned cost;             // of all tiles (< 2^31)
+    unsigned share, rest;      // cost / G and cost % G for the G workgroups of the launch
+    int slots;                 // planes: the most workgroups that can share a tile (>= 1)
+    fdiv dG, dKb, dCT, dRT, dRowcost, dTilecost, dWlast, dCdiv;
     size_t a_party_stride, b_party_stride, out_party_stride, stride_row, stride_cb;
     int cdiv;
-    u64 negbias;
     // second operand read straight from channel-innermost limb planes (convolution without a materialised
     // im2col): planes [party][limb][b][h][w][c] int8, contraction index (tap, channel), C a multiple of 64
     const v4i *planes, *zero;          // zero: 16 zero bytes, for taps that fall into the padding
     unsigned plane16, party16;         // strides of a limb plane and of a party, in 16-byte units
     int cvH, cvW, cvC16, cvKw, cvStride, cvPad, cvHoWo, cvWo, cvKbTap;   // C16 = C/16, KbTap = C/64
+    fdiv dHoWo, dWo, dKbTap, dKw;
 };
 
 // where one wave's block of a unit comes from: limb slice q is the 64 lanes x 16 bytes at base + q * qs
@@ -297,80 +308,98 @@ struct wave_src {
                      // pixel index of its image, -1 if the lane's column is past the matrix
 };
 
-// the ND diagonal sums of one output -> canonical field element
-#if defined(SS_FIELD_P45)
-__device__ __forceinline__ u64 fold_diagonals(const v4i (&acc)[ND], int r, u64 negbias)
+// a * b + c, one instruction (the compiler turns a multiplication by a power of two into a sign extension,
+// a 64-bit shift and a 64-bit addition)
+__device__ __forceinline__ long long mad_i64(int a, int b, long long c)
 {
-    u32 U[ND];
-#pragma unroll
-    for (int s = 0; s < ND; s++) U[s] = (u32)acc[s][r] ^ 0x80000000u;   // D_s + 2^31, non-negative
-    const u64 g0 = (u64)U[0] + ((u64)U[1] << 8) + ((u64)U[2] << 16) + ((u64)U[3] << 24);   // < 2^57
-    const u64 g1 = (u64)U[4] + ((u64)U[5] << 8) + ((u64)U[6] << 16) + ((u64)U[7] << 24);
-    const u64 g2 = (u64)U[8] + ((u64)U[9] << 8) + ((u64)U[10] << 16);
+    long long d;
+    asm("v_mad_i64_i32 %0, vcc, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c) : "vcc");
+    return d;
+}
+
+// D_0 + D_1 2^8 + D_2 2^16 (+ D_3 2^24): up to four of the signed 32-bit diagonal sums in one signed 64-bit
+// word, |result| < 2^31 (1 + 2^8 + 2^16 + 2^24) < 2^56
+__device__ __forceinline__ long long join4(int d0, int d1, int d2, int d3)
+{
+    return mad_i64(d3, 1 << 24, mad_i64(d2, 1 << 16, mad_i64(d1, 1 << 8, (long long)d0)));
+}
+__device__ __forceinline__ long long join3(int d0, int d1, int d2)
+{
+    return mad_i64(d2, 1 << 16, mad_i64(d1, 1 << 8, (long long)d0));
+}
+
+// The ND diagonal sums of one output -> canonical field element.  The sums are signed 32-bit numbers and
+// stay signed: four of them at a time go into one signed 64-bit word, the words are joined with the field's
+// reduction rule, and a multiple of p makes the total positive before it is reduced.
+#if defined(SS_FIELD_P45)
+__device__ __forceinline__ u64 fold_diagonals(const v4i (&acc)[ND], int r)
+{
+    const long long off = (long long)(SS_P << 12);   // a multiple of p above 2^56
+    const u64 g0 = (u64)(join4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]) + off);
+    const u64 g1 = (u64)(join4(acc[4][r], acc[5][r], acc[6][r], acc[7][r]) + off);
+    const u64 g2 = (u64)(join3(acc[8][r], acc[9][r], acc[10][r]) + off);
     // g0 + g1 2^32 + g2 2^64.  With g = a 2^13 + b: g 2^32 = a 2^45 + b 2^32 = 55 a + b 2^32, and
     // 2^64 = 55 2^19 (mod p)
     const u64 r1 = ss_reduce(g1), r2 = ss_reduce(g2);
     const u64 t1 = SS_PC * (r1 >> 13) + ((r1 & 0x1FFFull) << 32);   // < 2^38 + 2^45
     const u64 t2 = ss_mul(r2, SS_PC << 19);
-    return ss_reduce(ss_fold(g0) + t1 + t2 + negbias);   // minus the 2^31 offsets
+    return ss_reduce(ss_fold(g0) + t1 + t2);
 }
 #else
-__device__ __forceinline__ u64 fold_diagonals(const v4i (&acc)[15], int r, u64 negbias)
+__device__ __forceinline__ u64 fold_diagonals(const v4i (&acc)[15], int r)
 {
-    u32 U[15];
-#pragma unroll
-    for (int s = 0; s < 15; s++) U[s] = (u32)acc[s][r] ^ 0x80000000u;   // D_s + 2^31, non-negative
-    const u64 g0 = (u64)U[0] + ((u64)U[1] << 8) + ((u64)U[2] << 16) + ((u64)U[3] << 24);
-    const u64 g1 = (u64)U[4] + ((u64)U[5] << 8) + ((u64)U[6] << 16) + ((u64)U[7] << 24);
-    const u64 g2 = (u64)U[8] + ((u64)U[9] << 8) + ((u64)U[10] << 16) + ((u64)U[11] << 24);
-    const u64 g3 = (u64)U[12] + ((u64)U[13] << 8) + ((u64)U[14] << 16);
-    // g0 + g1 2^32 + g2 2^64 + g3 2^96 with 2^61 = 1: 2^64 = 2^3, 2^96 = 2^35
-    const u64 tot = g0 + ((g1 & ((1ULL << 29) - 1)) << 32) + (g1 >> 29) + (g2 << 3) +
-                    ((g3 & ((1ULL << 26) - 1)) << 35) + (g3 >> 26);
-    return ss_reduce(ss_fold(tot) + negbias);   // minus the 2^31 offsets
+    const long long g0 = join4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
+    const long long g1 = join4(acc[4][r], acc[5][r], acc[6][r], acc[7][r]);
+    const long long g2 = join4(acc[8][r], acc[9][r], acc[10][r], acc[11][r]);
+    const long long g3 = join3(acc[12][r], acc[13][r], acc[14][r]);
+    // g0 + g1 2^32 + g2 2^64 + g3 2^96 with 2^61 = 1: 2^64 = 2^3, 2^96 = 2^35 = 2^3 2^32
+    const long long lo = g0 + (g2 << 3), hi = g1 + (g3 << 3);   // |.| < 2^60
+    // hi 2^32 = (hi >> 29) 2^61 + (hi mod 2^29) 2^32 = (hi >> 29) + (hi mod 2^29) 2^32
+    const long long tot = lo + (hi >> 29) + (long long)(((u64)hi & ((1ULL << 29) - 1)) << 32) + (long long)(2 * SS_P);
+    return ss_reduce((u64)tot);   // 2^61 < tot < 2^63
 }
 #endif
 
-// The units are dealt to the workgroups by cost, not by count: a unit of a full
-// tile costs SS_UNIT_COST, a unit of the last column tile, where only some of
-// the four column blocks exist and the MFMAs of the others are skipped, costs
-// less (see unit_cost).  With cp(u) the summed cost of all units before u,
-// workgroup s of G owns the units with floor(s cost / G) <= cp(u) <
-// floor((s+1) cost / G).  cost / G >= SS_UNIT_COST, so no range is empty.
-constexpr unsigned SS_UNIT_COST = 9;
-// what one hand-over of a shared tile costs a workgroup, in the same scale: about 3.3 us, i.e. 1.3 units of
-// eight limbs (2.5 us each) or 2.2 units of six (1.6 us each)
-constexpr unsigned SS_HANDOVER_COST = SS_NLIMB == 8 ? 12 : 20;
+// The units are dealt to the workgroups by cost, not by count.  A unit of a full tile costs SS_UNIT_COST; a
+// unit of the last column tile, where only some of the four column blocks exist and the MFMAs of the others
+// are skipped, costs less (see unit_cost); and every tile ends with its fold and stores, which cost about as
+// much as a unit (SS_FOLD_COST; a workgroup whose range holds the ends of two tiles really is busy that much
+// longer than one whose range lies inside one tile).  On the cost axis a tile is its units followed by its
+// fold; with cp(u) the position of unit u, workgroup s of G owns the units with bound(s) <= cp(u) <
+// bound(s + 1), bound(s) = floor(s cost / G).  cost / G >= SS_UNIT_COST + SS_FOLD_COST, the largest step
+// between two unit starts, so no range is empty.
+constexpr unsigned SS_UNIT_COST = 18;
+constexpr unsigned SS_FOLD_COST = 16;
 
-// cost position of unit j of tile `tile`
-__device__ __forceinline__ unsigned long long cost_before(const gemm_args &g, unsigned tile, unsigned j)
+__device__ __forceinline__ unsigned range_bound(const gemm_args &g, unsigned s)
 {
-    const unsigned ct = tile % (unsigned)g.CT, rg = tile / (unsigned)g.CT;
-    return (unsigned long long)rg * ((unsigned)g.Kb * g.wrow) + ct * SS_UNIT_COST * (unsigned)g.Kb +
-           j * (ct == (unsigned)g.CT - 1 ? g.wlast : SS_UNIT_COST);
+    return s * g.share + fd_div(s * g.rest, g.dG);   // s <= G <= 256, rest < G
 }
 
-// first unit whose cost position is >= x
-__device__ __forceinline__ unsigned unit_at(const gemm_args &g, unsigned long long x)
+// first unit whose cost position is >= x (x <= cost); positions inside a tile's fold belong to the next tile
+__device__ __forceinline__ unsigned unit_at(const gemm_args &g, unsigned x)
 {
-    const unsigned rowcost = (unsigned)g.Kb * g.wrow, tilecost = SS_UNIT_COST * (unsigned)g.Kb;
-    const unsigned rg = (unsigned)(x / rowcost), rem = (unsigned)(x - (unsigned long long)rg * rowcost);
-    const unsigned full = ((unsigned)g.CT - 1) * tilecost;
+    const unsigned full = ((unsigned)g.CT - 1) * g.tcost, rowcost = full + g.tlast;
+    const unsigned rg = fd_div(x, g.dRowcost), rem = x - rg * rowcost;
     unsigned ct, j;
     if (rem < full) {
-        ct = rem / tilecost;
-        j = (rem - ct * tilecost + SS_UNIT_COST - 1) / SS_UNIT_COST;
+        ct = fd_div(rem, g.dTilecost);
+        j = (rem - ct * g.tcost + SS_UNIT_COST - 1) / SS_UNIT_COST;
     } else {
         ct = (unsigned)g.CT - 1;
-        j = (rem - full + g.wlast - 1) / g.wlast;
+        j = fd_div(rem - full + g.wlast - 1, g.dWlast);
     }
-    return (rg * (unsigned)g.CT + ct) * (unsigned)g.Kb + j;   // j == Kb: first unit of the next tile
+    j = min(j, (unsigned)g.Kb);   // j == Kb: first unit of the next tile
+    return (rg * (unsigned)g.CT + ct) * (unsigned)g.Kb + j;
 }
 
-// workgroup that owns the unit at cost position cp
-__device__ __forceinline__ int owner_of(const gemm_args &g, unsigned long long cp, unsigned G)
+// tile -> (column tile, row tile, party)
+__device__ __forceinline__ void tile_coords(const gemm_args &g, unsigned tile, int &ct, int &rt, int &party)
 {
-    return (int)(((cp + 1) * G - 1) / g.cost);
+    const unsigned rem = fd_div(tile, g.dCT);
+    ct = (int)(tile - rem * (unsigned)g.CT);
+    party = (int)fd_div(rem, g.dRT);
+    rt = (int)(rem - (unsigned)party * (unsigned)g.RT);
 }
 
 // this wave's source block of tile `tile`: block `wave` of A for waves 0..3, of
@@ -379,9 +408,8 @@ __device__ __forceinline__ int owner_of(const gemm_args &g, unsigned long long c
 template <bool IMPLICIT>
 __device__ __forceinline__ wave_src tile_source(const gemm_args &g, unsigned tile, int wave, int lane)
 {
-    const int ct = (int)(tile % (unsigned)g.CT);
-    const unsigned rem = tile / (unsigned)g.CT;
-    const int rt = (int)(rem % (unsigned)g.RT), party = (int)(rem / (unsigned)g.RT);
+    int ct, rt, party;
+    tile_coords(g, tile, ct, rt, party);
     wave_src ws = {nullptr, 0, 0};
     if (wave < 4) {
         ws.p = g.A + (size_t)party * g.a_party_stride + (size_t)min(rt * 4 + wave, g.Rb - 1) * g.Kb * TILE + lane;
@@ -390,7 +418,8 @@ __device__ __forceinline__ wave_src tile_source(const gemm_args &g, unsigned til
     } else {
         // lane l of a block holds column 16 cb + l%16 = output pixel (b, ho, wo)
         const int col = min(ct * 4 + wave - 4, g.Cb - 1) * 16 + (lane & 15);
-        const int cc = min(col, g.cols - 1), b = cc / g.cvHoWo, r = cc - b * g.cvHoWo, ho = r / g.cvWo, wo = r - ho * g.cvWo;
+        const int cc = min(col, g.cols - 1), b = (int)fd_div((u32)cc, g.dHoWo), r = cc - b * g.cvHoWo,
+                  ho = (int)fd_div((u32)r, g.dWo), wo = r - ho * g.cvWo;
         ws.p = g.planes + (size_t)party * g.party16;
         ws.hw = (int)((unsigned)(ho * g.cvStride - g.cvPad) << 16) | ((wo * g.cvStride - g.cvPad) & 0xffff);
         ws.bpix = col < g.cols ? b * g.cvH * g.cvW : -1;
@@ -408,21 +437,32 @@ __device__ __forceinline__ const v4i *unit_base(const gemm_args &g, const wave_s
         return ws.p + (size_t)kb * TILE;
     }
     // k block kb = channels [64 (kb % KbTap), +64) of tap kb / KbTap; this lane: 16 of them
-    const int tap = kb / g.cvKbTap, c16 = (kb - tap * g.cvKbTap) * 4 + (lane >> 4);
-    const int r = tap / g.cvKw, sx = tap - r * g.cvKw;
+    const int tap = (int)fd_div((u32)kb, g.dKbTap), c16 = (kb - tap * g.cvKbTap) * 4 + (lane >> 4);
+    const int r = (int)fd_div((u32)tap, g.dKw), sx = tap - r * g.cvKw;
     const int hi = (ws.hw >> 16) + r, wi = (int)(short)(ws.hw & 0xffff) + sx;
     const bool ok = ws.bpix >= 0 && (unsigned)hi < (unsigned)g.cvH && (unsigned)wi < (unsigned)g.cvW;
     qs = ok ? g.plane16 : 0;
     return ok ? ws.p + (size_t)(ws.bpix + hi * g.cvW + wi) * g.cvC16 + c16 : g.zero;
 }
 
+// Planes that get zeros from workgroup `slot`, whose range ends at unit u1.  A workgroup that starts a tile
+// sees to the planes that no part of the tile goes to.  For a tile it computes whole that is all planes but
+// its own; the only tile it can start and not finish is the one its range ends in, which has one more part
+// for every following workgroup whose range starts before the tile ends (at most slots parts in all).
+__device__ __forceinline__ int zero_planes_of_cut_tile(const gemm_args &g, unsigned u1, unsigned slot, unsigned G)
+{
+    const unsigned tile_end = (fd_div(u1, g.dKb) + 1) * (unsigned)g.Kb;
+    int nc = 1;
+    while (slot + nc < G && nc < g.slots && unit_at(g, range_bound(g, slot + nc)) < tile_end) nc++;
+    return g.slots - nc;
+}
+
 // Persistent kernel, one workgroup of 8 waves (4 x 2) per CU.  The work is the
 // flat list of units (output tile of 64 x 64, k block of 64), tile-major; each
 // workgroup takes one contiguous range of it, of equal cost, so every CU gets
-// the same amount of work whatever the layer shape, and a tile whose k range is
-// cut by a range boundary is finished by the hand-over below.  Wave (wr, wc) owns row block wr
-// and column blocks 2wc, 2wc+1 of the tile (2 x 15 accumulator tiles); the two
-// waves of a SIMD differ in wc.
+// the same amount of work whatever the layer shape.  Wave (wr, wc) owns row
+// block wr and column blocks 2wc, 2wc+1 of the tile (2 x 15 accumulator tiles);
+// the two waves of a SIMD differ in wc.
 //
 // Per unit the workgroup needs four row blocks of A and four column blocks of
 // B, 8 KB each and already in MFMA lane order, so wave w copies block w (A for
@@ -430,29 +470,31 @@ __device__ __forceinline__ const v4i *unit_base(const gemm_args &g, const wave_s
 // stages, the next unit's loads (also across a tile boundary) in flight during
 // the 128 MFMAs per wave of the current one.
 //
-// Hand-over of a tile shared by several workgroups (which may sit on different
-// XCDs with separate L2s): each contributor folds its partial sums to residues,
-// stores them with agent-scope atomic stores, waits for these stores and bumps
-// the tile's counter; the contributor that arrives last adds the others'
-// residues (agent-scope atomic loads) to its own and writes the output.  No
-// cache-wide fence is used: it would evict the operand tiles that all other
-// workgroups are reusing.  Integer sums are exact, so the result does not
-// depend on how the units were dealt or on arrival order.
+// A tile whose k range is cut by a range boundary is computed in parts by
+// consecutive workgroups, and nothing passes between them: the output is
+// `slots` planes, workgroup `slot` stores what it has of a tile (folded to a
+// field element) in plane slot % slots -- the workgroups that share a tile are
+// consecutive and at most `slots`, so they hit different planes -- and whoever
+// reads the product adds the planes mod p.  The workgroup that starts a tile
+// gives the planes nobody writes zeros, so every position of every plane is
+// written by exactly one workgroup in every launch.  Integer sums are exact, so
+// the sum of the planes does not depend on how the units were dealt.
+//
 template <bool IMPLICIT>
 __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
 {
     extern __shared__ v4i lds[];   // 2 stages x (4 A blocks + 4 B blocks) x TILE
     constexpr int STAGE = 8 * TILE;
-    __shared__ unsigned arrival;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wr = wave & 3, wc = wave >> 2;
     const unsigned G = gridDim.x;
     // consecutive ranges go to workgroups of the same XCD (workgroups are dealt
     // round-robin to the 8 XCDs), so that neighbours in the list share an L2
     const unsigned slot = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
+    const unsigned myplane = g.slots > 1 ? slot % (unsigned)g.slots : 0;
     unsigned u0, u1;
     if (g.units) {
-        u0 = unit_at(g, (unsigned long long)slot * g.cost / G);
-        u1 = unit_at(g, (unsigned long long)(slot + 1) * g.cost / G);
+        u0 = unit_at(g, range_bound(g, slot));
+        u1 = unit_at(g, range_bound(g, slot + 1));
     } else {   // one whole tile per workgroup; unit numbers are relative to it
         u0 = 0;
         u1 = (unsigned)g.Kb;
@@ -460,7 +502,7 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
     if (u0 >= u1) return;
     v4i *mine = lds + wave * TILE;   // wave-uniform LDS destination of this wave's block
 
-    unsigned tile = g.units ? u0 / (unsigned)g.Kb : slot;
+    unsigned tile = g.units ? fd_div(u0, g.dKb) : slot;
     int kb = (int)(u0 - (g.units ? tile * (unsigned)g.Kb : 0));
     wave_src src = tile_source<IMPLICIT>(g, tile, wave, lane);
     {
@@ -470,18 +512,17 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
         for (int q = 0; q < NL; q++) __builtin_amdgcn_global_load_lds(ub + (size_t)q * qs, mine + q * 64, 16, 0, 0);
     }
     int st = 0;
-
-    // column blocks of this wave that lie inside the matrix (0 if its row block lies outside): MFMAs of
-    // blocks past the edge are skipped, so a ragged last tile costs only its valid part
-    auto valid_blocks = [&](unsigned t) {
-        const int ct = (int)(t % (unsigned)g.CT), rt = (int)(t / (unsigned)g.CT % (unsigned)g.RT);
-        if (rt * 4 + wr >= g.Rb) return 0;
-        return max(0, min(2, g.Cb - (ct * 4 + 2 * wc)));
-    };
+    // (worked out while the first unit is on its way)
+    const int zero_cut = g.slots > 1 ? zero_planes_of_cut_tile(g, u1, slot, G) : 0;
+    bool stores_in_flight = false;   // the last thing issued were a part's stores, behind a wait for all loads
 
     unsigned u = u0;
     while (u < u1) {
-        const int nblk = valid_blocks(tile);
+        int ct, rt, party;
+        tile_coords(g, tile, ct, rt, party);
+        // column blocks of this wave that lie inside the matrix (0 if its row block lies outside): MFMAs of
+        // blocks past the edge are skipped, so a ragged last tile costs only its valid part
+        const int nblk = rt * 4 + wr >= g.Rb ? 0 : max(0, min(2, g.Cb - (ct * 4 + 2 * wc)));
         const int kb_first = kb;
         v4i acc[2][ND];
 #pragma unroll
@@ -493,8 +534,23 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
         const int kb_end = min(g.Kb, kb + (int)(u1 - u));
         wave_src next_src = src;
         for (; kb < kb_end; kb++, u++) {
-            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of the unit is in LDS
+            // vmcnt(0): this wave's part of the unit is in LDS.  Right after a part's stores that is known
+            // already, and waiting here would wait for the stores (the counter counts them too).
+            if (!stores_in_flight) __builtin_amdgcn_s_waitcnt(0x0F70);
+            stores_in_flight = false;
             __syncthreads();                      // everyone's part is; stage st^1 is no longer read
+            // first the LDS reads of this unit's first half, then the copies of the next unit: right behind
+            // the barrier both waves of a SIMD are reading and the MFMA pipe idles, so that stretch is kept short
+            const v4i *sa = lds + st * STAGE + wr * TILE + lane;
+            const v4i *sb = lds + st * STAGE + 4 * TILE + wc * 2 * TILE + lane;
+            v4i a[NL], b[NL];
+            if (nblk >= 1) {
+#pragma unroll
+                for (int i = 0; i < NL; i++) {
+                    a[i] = sa[i * 64];
+                    b[i] = sb[i * 64];
+                }
+            }
             if (u + 1 < u1) {
                 int nkb = kb + 1;
                 if (nkb == g.Kb) {
@@ -514,93 +570,65 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
                         __builtin_amdgcn_global_load_lds(ub + (size_t)q * qs, mine + (st ^ 1) * STAGE + q * 64, 16, 0, 0);
                 }
             }
-            const v4i *sa = lds + st * STAGE + wr * TILE + lane;
-            const v4i *sb = lds + st * STAGE + 4 * TILE + wc * 2 * TILE + lane;
-            if (nblk == 2) {   // the usual case, kept free of branches so that loads and MFMAs interleave
-                v4i a[NL];
-#pragma unroll
-                for (int i = 0; i < NL; i++) a[i] = sa[i * 64];
-#pragma unroll
-                for (int h = 0; h < 2; h++) {
-                    v4i b[NL];
-#pragma unroll
-                    for (int j = 0; j < NL; j++) b[j] = sb[h * TILE + j * 64];
-#pragma unroll
-                    for (int i = 0; i < NL; i++)
-#pragma unroll
-                        for (int j = 0; j < NL; j++)
-                            acc[h][i + j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[h][i + j], 0, 0, 0);
-                }
-            } else if (nblk == 1) {   // ragged edge: only the first column block is inside the matrix
-                v4i a[NL], b[NL];
-#pragma unroll
-                for (int i = 0; i < NL; i++) {
-                    a[i] = sa[i * 64];
-                    b[i] = sb[i * 64];
-                }
+            // MFMAs of column blocks past the matrix edge are skipped (nblk < 2; uniform over the wave)
+            if (nblk >= 1) {
 #pragma unroll
                 for (int i = 0; i < NL; i++)
 #pragma unroll
                     for (int j = 0; j < NL; j++)
                         acc[0][i + j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[0][i + j], 0, 0, 0);
             }
+            if (nblk == 2) {
+#pragma unroll
+                for (int j = 0; j < NL; j++) b[j] = sb[TILE + j * 64];
+#pragma unroll
+                for (int i = 0; i < NL; i++)
+#pragma unroll
+                    for (int j = 0; j < NL; j++)
+                        acc[1][i + j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[1][i + j], 0, 0, 0);
+            }
             st ^= 1;
         }
-        // lane holds, per column block h, column lane%16 and rows 4*(lane/16)+r
+
+        // The part is done.  Lane holds, per column block h, column lane%16 and rows 4*(lane/16)+r of its
+        // wave's 16 x 32 outputs.
+        const int lrow = rt * 64 + wr * 16 + 4 * (lane >> 4);
         u64 v[2][4];
+        size_t off[2];        // element offset inside a plane of this lane's first row, per column block
+        unsigned mask = 0;    // bit 4h + r: value (h, r) lies inside the matrix
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            const int col = ct * 64 + wc * 32 + (lane & 15) + 16 * h;
+            const u32 cq = fd_div((u32)col, g.dCdiv);
+            off[h] = (size_t)party * g.out_party_stride + (size_t)cq * g.stride_cb + ((u32)col - cq * (u32)g.cdiv) +
+                     (size_t)lrow * g.stride_row;
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                if (h < nblk) v[h][r] = fold_diagonals(acc[h], r);
+                if (h < nblk && col < g.cols && lrow + r < g.rows) mask |= 1u << (4 * h + r);
+            }
+        }
+        const int nzero = (g.slots > 1 && kb_first == 0) ? (kb_end == g.Kb ? g.slots - 1 : zero_cut) : 0;
+        // The stores go out behind a wait for the loads of the next unit, which were issued a unit ago, so
+        // that the loop can go on without waiting for them: stores issued just before the loop's own wait
+        // would put a full trip to memory on the workgroup's critical path at every part.
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        stores_in_flight = true;
+        u64 *o = g.out + (size_t)myplane * g.part_stride;
 #pragma unroll
         for (int h = 0; h < 2; h++)
 #pragma unroll
-            for (int r = 0; r < 4; r++) v[h][r] = fold_diagonals(acc[h], r, g.negbias);
-
-        const int ct = (int)(tile % (unsigned)g.CT);
-        const unsigned rem = tile / (unsigned)g.CT;
-        const int rt = (int)(rem % (unsigned)g.RT), party = (int)(rem / (unsigned)g.RT);
-        const int lrow = wr * 16 + 4 * (lane >> 4), lcol = wc * 32 + (lane & 15);   // within the 64 x 64 tile
-        bool finish = true;
-        if (kb_first != 0 || kb_end != g.Kb) {   // the tile is shared: uniform over the workgroup
-            const int first = owner_of(g, cost_before(g, tile, 0), G),
-                      last = owner_of(g, cost_before(g, tile, (unsigned)g.Kb - 1), G);
-            u64 *part = g.partials + (size_t)tile * g.slots * 4096;
-            const int my = (int)slot - first;
+            for (int r = 0; r < 4; r++)
+                if (mask >> (4 * h + r) & 1) o[off[h] + (size_t)r * g.stride_row] = v[h][r];
+        for (int z = 0; z < nzero; z++) {
+            unsigned zpl = myplane + (unsigned)(g.slots - nzero + z);
+            if (zpl >= (unsigned)g.slots) zpl -= (unsigned)g.slots;
+            u64 *zo = g.out + (size_t)zpl * g.part_stride;
 #pragma unroll
             for (int h = 0; h < 2; h++)
 #pragma unroll
                 for (int r = 0; r < 4; r++)
-                    __hip_atomic_store(&part[(size_t)my * 4096 + (lrow + r) * 64 + lcol + 16 * h], v[h][r],
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the stores above are done
-            __syncthreads();
-            if (tid == 0)
-                arrival = __hip_atomic_fetch_add(&g.counters[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __syncthreads();
-            finish = arrival == (unsigned)(last - first);
-            if (finish) {
-                if (tid == 0) __hip_atomic_store(&g.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                for (int s = 0; s <= last - first; s++) {
-                    if (s == my) continue;
-#pragma unroll
-                    for (int h = 0; h < 2; h++)
-#pragma unroll
-                        for (int r = 0; r < 4; r++)
-                            v[h][r] = ss_add(v[h][r],
-                                             __hip_atomic_load(&part[(size_t)s * 4096 + (lrow + r) * 64 + lcol + 16 * h],
-                                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-                }
-            }
-            __syncthreads();   // `arrival` may be rewritten by the next tile
-        }
-        if (finish) {
-#pragma unroll
-            for (int h = 0; h < 2; h++) {
-                const int col = ct * 64 + lcol + 16 * h;
-                u64 *op = g.out + (size_t)party * g.out_party_stride + (size_t)(col / g.cdiv) * g.stride_cb + (col % g.cdiv);
-#pragma unroll
-                for (int r = 0; r < 4; r++) {
-                    const int row = rt * 64 + lrow + r;
-                    if (row < g.rows && col < g.cols) op[(size_t)row * g.stride_row] = v[h][r];
-                }
-            }
+                    if (mask >> (4 * h + r) & 1) zo[off[h] + (size_t)r * g.stride_row] = 0;
         }
         if (kb == g.Kb) {
             kb = 0;
@@ -615,36 +643,35 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
 // fast as it keeps bytes in flight: a workgroup's tile is 16 rows x 128 columns, one row block and eight
 // column blocks per unit, twice the column blocks of the square tile in the same LDS, and no MFMA is spent on
 // row blocks that do not exist.  Wave w copies column block w and limb slice w of the row block, and owns
-// the 16 x 16 outputs of column block w.  Units, ranges, hand-over and epilogue are those of the kernel above
-// (a shared tile has 16 x 128 partial residues).
-constexpr int SKINNY_COLS = 128, SKINNY_PART = 16 * SKINNY_COLS;
+// the 16 x 16 outputs of column block w.  Units, ranges, planes and fold are those of the kernel above.
+constexpr int SKINNY_COLS = 128;
 
 __global__ __launch_bounds__(512) void gemm_skinny_kernel(gemm_args g)
 {
     extern __shared__ v4i lds[];   // 2 stages x (1 row block + 8 column blocks) x TILE
-    __shared__ unsigned arrival;
     constexpr int STAGE = 9 * TILE;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const unsigned G = gridDim.x;
     const unsigned slot = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
     unsigned u0, u1;
     if (g.units) {
-        u0 = unit_at(g, (unsigned long long)slot * g.cost / G);
-        u1 = unit_at(g, (unsigned long long)(slot + 1) * g.cost / G);
+        u0 = unit_at(g, range_bound(g, slot));
+        u1 = unit_at(g, range_bound(g, slot + 1));
     } else {
         u0 = 0;
         u1 = (unsigned)g.Kb;
     }
     if (u0 >= u1) return;
+    const int zero_cut = g.slots > 1 ? zero_planes_of_cut_tile(g, u1, slot, G) : 0;
 
     // this wave's column block of tile t (clamped past the edge: computed, never stored) and its limb slice
     // of the party's row block
     auto b_source = [&](unsigned t) {
-        const int ct = (int)(t % (unsigned)g.CT), party = (int)(t / (unsigned)g.CT);
-        return g.B + (size_t)party * g.b_party_stride + (size_t)min(ct * 8 + wave, g.Cb - 1) * g.Kb * TILE + lane;
+        const unsigned party = fd_div(t, g.dCT), ct = t - party * (unsigned)g.CT;
+        return g.B + (size_t)party * g.b_party_stride + (size_t)min((int)ct * 8 + wave, g.Cb - 1) * g.Kb * TILE + lane;
     };
     auto a_source = [&](unsigned t) {
-        const int party = (int)(t / (unsigned)g.CT);
+        const unsigned party = fd_div(t, g.dCT);
         return g.A + (size_t)party * g.a_party_stride + min(wave, NL - 1) * 64 + lane;
     };
     auto copy_unit = [&](const v4i *as, const v4i *bs, int k, int stage) {
@@ -655,7 +682,7 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(gemm_args g)
         if (wave < NL) __builtin_amdgcn_global_load_lds(as + (size_t)k * TILE, dst + wave * 64, 16, 0, 0);
     };
 
-    unsigned tile = g.units ? u0 / (unsigned)g.Kb : slot;
+    unsigned tile = g.units ? fd_div(u0, g.dKb) : slot;
     int kb = (int)(u0 - (g.units ? tile * (unsigned)g.Kb : 0));
     const v4i *as = a_source(tile), *bs = b_source(tile);
     copy_unit(as, bs, kb, 0);
@@ -663,7 +690,7 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(gemm_args g)
 
     unsigned u = u0;
     while (u < u1) {
-        const int ct = (int)(tile % (unsigned)g.CT), party = (int)(tile / (unsigned)g.CT);
+        const int party = (int)fd_div(tile, g.dCT), ct = (int)(tile - (unsigned)party * (unsigned)g.CT);
         const bool inside = ct * 8 + wave < g.Cb;   // this wave's column block lies inside the matrix
         const int kb_first = kb;
         v4i acc[ND];
@@ -702,44 +729,23 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(gemm_args g)
         }
 
         // lane holds column lane%16 of its block and rows 4*(lane/16)+r
-        u64 v[4];
+        const int lrow = 4 * (lane >> 4), col = ct * SKINNY_COLS + wave * 16 + (lane & 15);
+        const u32 cq = fd_div((u32)col, g.dCdiv);
+        const size_t opos = (size_t)party * g.out_party_stride + (size_t)cq * g.stride_cb + ((u32)col - cq * (u32)g.cdiv);
+        const unsigned plane = g.slots > 1 ? slot % (unsigned)g.slots : 0;
+        u64 *outp = g.out + (size_t)plane * g.part_stride;
 #pragma unroll
-        for (int r = 0; r < 4; r++) v[r] = fold_diagonals(acc, r, g.negbias);
-        const int lrow = 4 * (lane >> 4), lcol = wave * 16 + (lane & 15);   // within the 16 x 128 tile
-        bool finish = true;
-        if (kb_first != 0 || kb_end != g.Kb) {   // the tile is shared: uniform over the workgroup
-            const int first = owner_of(g, cost_before(g, tile, 0), G),
-                      last = owner_of(g, cost_before(g, tile, (unsigned)g.Kb - 1), G);
-            u64 *part = g.partials + (size_t)tile * g.slots * SKINNY_PART;
-            const int my = (int)slot - first;
-#pragma unroll
-            for (int r = 0; r < 4; r++)
-                __hip_atomic_store(&part[(size_t)my * SKINNY_PART + (lrow + r) * SKINNY_COLS + lcol], v[r], __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the stores above are done
-            __syncthreads();
-            if (tid == 0)
-                arrival = __hip_atomic_fetch_add(&g.counters[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __syncthreads();
-            finish = arrival == (unsigned)(last - first);
-            if (finish) {
-                if (tid == 0) __hip_atomic_store(&g.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                for (int s = 0; s <= last - first; s++) {
-                    if (s == my) continue;
-#pragma unroll
-                    for (int r = 0; r < 4; r++)
-                        v[r] = ss_add(v[r], __hip_atomic_load(&part[(size_t)s * SKINNY_PART + (lrow + r) * SKINNY_COLS + lcol],
-                                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-                }
-            }
-            __syncthreads();   // `arrival` may be rewritten by the next tile
-        }
-        if (finish) {
-            const int col = ct * SKINNY_COLS + lcol;
-            u64 *op = g.out + (size_t)party * g.out_party_stride + (size_t)(col / g.cdiv) * g.stride_cb + (col % g.cdiv);
+        for (int r = 0; r < 4; r++)
+            if (inside && lrow + r < g.rows && col < g.cols)
+                outp[opos + (size_t)(lrow + r) * g.stride_row] = fold_diagonals(acc, r);
+        const int nzero = (g.slots > 1 && kb_first == 0) ? (kb_end == g.Kb ? g.slots - 1 : zero_cut) : 0;
+        for (int z = 0; z < nzero; z++) {
+            unsigned zpl = plane + (unsigned)(g.slots - nzero + z);
+            if (zpl >= (unsigned)g.slots) zpl -= (unsigned)g.slots;
+            u64 *zp = g.out + (size_t)zpl * g.part_stride;
 #pragma unroll
             for (int r = 0; r < 4; r++)
-                if (lrow + r < g.rows && col < g.cols) op[(size_t)(lrow + r) * g.stride_row] = v[r];
+                if (inside && lrow + r < g.rows && col < g.cols) zp[opos + (size_t)(lrow + r) * g.stride_row] = 0;
         }
         if (kb == g.Kb) {
             kb = 0;
@@ -750,43 +756,34 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(gemm_args g)
     }
 }
 
-__global__ void zero_words_kernel(unsigned *p, size_t nwords)
+fdiv make_fdiv(u32 d)
 {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < nwords) p[i] = 0;
-}
-
-// residue of sum_{s<ND} 2^31 2^(8s), negated
-u64 neg_bias()
-{
-    u64 b = 0, w = ss_reduce(1ULL << 31);
-    for (int s = 0; s < ND; s++) {
-        b = ss_add(b, w);
-        w = ss_mul(w, 256);
-    }
-    return ss_neg(b);
+    int l = 0;
+    while ((1ull << l) < d) l++;
+    fdiv f;
+    f.s = 31 + (u32)l;
+    f.m = (u32)(((1ull << f.s) + d - 1) / d);   // d > 2^(l-1), so m < 2^32
+    return f;
 }
 
 struct gemm_plan {
     bool skinny;               // first operand of at most 16 rows: tiles of 16 x 128 (gemm_skinny_kernel)
-    long tiles, units;
+    long tiles, units;         // units == 0: one whole tile per workgroup
     int Kb, G, slots;
-    unsigned wlast, wrow;
-    unsigned long long cost;
+    unsigned wlast, tcost, tlast, cost;
 };
 
-// relative duration of a unit in which `vb` of the four column blocks exist:
-// a fixed part (copy, barrier, LDS reads) plus one part per column block, as
-// measured; the full unit is SS_UNIT_COST
+// Relative duration of a unit in which `vb` of the four column blocks exist: a fixed part (copy, barrier,
+// LDS reads) plus one part per column block.  Measured on MI355X: 3.1 us for a full unit, 1.55 us with one
+// column block.
 unsigned unit_cost(int vb)
 {
-    static const unsigned w[5] = {0, 4, 6, 7, SS_UNIT_COST};
+    static const unsigned w[5] = {0, 9, 12, 15, SS_UNIT_COST};
     return w[vb];
 }
 
-// How the units are dealt: one workgroup per CU unless there are fewer units
-// than CUs; slots = the most workgroups that can share one tile.  When there are
-// more tiles than arrival counters every workgroup gets whole tiles.
+// How the units are dealt: one workgroup per CU unless there is too little work for that; slots = the most
+// workgroups that can share one tile.
 gemm_plan plan_gemm(int n, int rows, int cols, int K, bool allow_skinny)
 {
     gemm_plan p;
@@ -795,67 +792,55 @@ gemm_plan plan_gemm(int n, int rows, int cols, int K, bool allow_skinny)
     p.tiles = p.skinny ? (long)n * ((cols + SKINNY_COLS - 1) / SKINNY_COLS)
                        : (long)n * ((rows + 63) / 64) * ((cols + 63) / 64);
     p.units = p.tiles * p.Kb;
-    if (p.tiles > SS_GEMM_MAX_SPLIT_TILES || p.units >= (1L << 31)) {
+    const int CT = p.skinny ? (cols + SKINNY_COLS - 1) / SKINNY_COLS : (cols + 63) / 64;
+    const int vb_last = p.skinny ? 4 : (cols + 15) / 16 - 4 * (CT - 1);
+    p.wlast = unit_cost(vb_last);   // (every unit of the 16-row kernel copies the same nine blocks: one cost for all)
+    p.tcost = (unsigned)p.Kb * SS_UNIT_COST + SS_FOLD_COST;
+    p.tlast = (unsigned)p.Kb * p.wlast + (vb_last == 1 ? SS_FOLD_COST / 2 : SS_FOLD_COST);   // one block per wave to fold
+    const unsigned long long cost = (unsigned long long)(p.tiles / CT) * ((unsigned long long)(CT - 1) * p.tcost + p.tlast);
+    // Whole tiles or tiles in parts?  Dealt by cost, a workgroup is busy for cost / G plus the fold of the
+    // tile its range ends in; with one whole tile per workgroup the launch lasts as many tiles as the fullest
+    // CU gets.  With a single k block tiles are never cut, so there is nothing to choose; launches too large
+    // for the 32-bit range arithmetic have tiles enough for every CU many times over.
+    const unsigned step = SS_UNIT_COST + SS_FOLD_COST;   // largest distance between two unit starts
+    bool whole = cost >= (1ull << 31) || p.units >= (1L << 31);
+    if (!whole && p.Kb > 1) {
+        const unsigned long long rounds = ((unsigned long long)p.tiles + SS_GEMM_CUS - 1) / SS_GEMM_CUS;
+        const unsigned long long g = cost / step < SS_GEMM_CUS ? (cost / step ? cost / step : 1) : SS_GEMM_CUS;
+        whole = rounds * p.tcost <= cost / g + SS_FOLD_COST;
+    }
+    if (whole) {
         p.G = (int)(p.tiles < (1L << 30) ? p.tiles : 0);   // 0: not launchable, rejected by the caller
-        p.slots = 0;
+        p.slots = 1;
         p.units = 0;
-        p.wlast = p.wrow = SS_UNIT_COST;
         p.cost = 0;
         return p;
     }
-    if (p.skinny) {   // every unit copies the same nine blocks: one cost for all
-        const int CT = (cols + SKINNY_COLS - 1) / SKINNY_COLS;
-        p.wlast = SS_UNIT_COST;
-        p.wrow = (unsigned)CT * SS_UNIT_COST;
-        p.cost = (unsigned long long)n * p.Kb * p.wrow;
-    } else {
-        const int CT = (cols + 63) / 64, Cb = (cols + 15) / 16;
-        p.wlast = unit_cost(Cb - 4 * (CT - 1));
-        p.wrow = (unsigned)(CT - 1) * SS_UNIT_COST + p.wlast;
-        p.cost = (unsigned long long)n * ((rows + 63) / 64) * p.Kb * p.wrow;
-    }
-    // Whole tiles or shared tiles?  Dealt by cost, a workgroup runs cost / G and hands over at both ends of its
-    // range (measured: each hand-over costs about SS_HANDOVER_COST / SS_UNIT_COST units).  With one whole tile
-    // per workgroup nothing is handed over and the launch lasts as many tiles as the fullest CU gets.  With a
-    // single k block tiles are never shared, so there is nothing to choose.
-    if (p.Kb > 1) {
-        const unsigned long long rounds = ((unsigned long long)p.tiles + SS_GEMM_CUS - 1) / SS_GEMM_CUS;
-        const unsigned long long whole = rounds * p.Kb * SS_UNIT_COST;
-        const unsigned long long g = p.cost / SS_UNIT_COST < SS_GEMM_CUS ? (p.cost / SS_UNIT_COST ? p.cost / SS_UNIT_COST : 1) : SS_GEMM_CUS;
-        const unsigned long long shared = p.cost / g + 2 * SS_HANDOVER_COST;
-        if (whole <= shared) {
-            p.G = (int)p.tiles;
-            p.slots = 0;
-            p.units = 0;
-            p.cost = 0;
-            return p;
-        }
-    }
-    // every range must hold at least one unit start: cost / G >= SS_UNIT_COST
-    const unsigned long long most = p.cost / SS_UNIT_COST;
+    p.cost = (unsigned)cost;
+    // every range must hold at least one unit start
+    const unsigned most = p.cost / step;
     p.G = (int)(most < SS_GEMM_CUS ? (most ? most : 1) : SS_GEMM_CUS);
-    // a tile of cost <= SS_UNIT_COST Kb meets at most this many ranges of length >= cost / G
-    const unsigned long long share = p.cost / p.G;
-    p.slots = (int)(((unsigned long long)SS_UNIT_COST * p.Kb + share - 1) / share) + 1;
+    // a tile of cost <= tcost meets at most this many ranges of length >= cost / G; ranges are cut between
+    // units, so a tile of Kb units has at most Kb parts
+    const unsigned share = p.cost / p.G;
+    p.slots = (int)((p.tcost + share - 1) / share) + 1;
+    if (p.slots > p.Kb) p.slots = p.Kb;
     return p;
 }
 
 }  // namespace
 
+int ss_gemm_planes(int n, int rows, int cols, int K, bool planes_operand)
+{
+    return plan_gemm(n, rows, cols, K, !planes_operand).slots;
+}
 
 size_t ss_gemm_scratch_bytes(int n, int rows, int cols, int K)
 {
-    // room for either form (an operand given as limb planes never takes the 16-row form)
-    const gemm_plan p = plan_gemm(n, rows, cols, K, false), q = plan_gemm(n, rows, cols, K, true);
-    const size_t a = (size_t)p.tiles * p.slots * 4096, b = q.skinny ? (size_t)q.tiles * q.slots * SKINNY_PART : 0;
-    return (a > b ? a : b) * sizeof(u64);
-}
-
-hipError_t ss_launch_zero_counters(unsigned *counters, hipStream_t stream)
-{
-    hipLaunchKernelGGL(zero_words_kernel, dim3((SS_GEMM_MAX_SPLIT_TILES + 255) / 256), dim3(256), 0, stream, counters,
-                       (size_t)SS_GEMM_MAX_SPLIT_TILES);
-    return hipGetLastError();
+    // room for either form of the second operand (tiles may take the 16-row kernel, limb planes never do)
+    const int a = plan_gemm(n, rows, cols, K, false).slots, b = plan_gemm(n, rows, cols, K, true).slots;
+    const int planes = a > b ? a : b;
+    return planes > 1 ? (size_t)planes * n * rows * cols * sizeof(u64) : 0;
 }
 
 size_t ss_packed_bytes(int rows, int K)
@@ -936,9 +921,9 @@ struct conv_planes {   // geometry of an operand given as channel-innermost limb
     int B, C, H, W, kh, kw, stride, pad, Ho, Wo;
 };
 
-hipError_t launch_gemm(const void *packedA, const void *packedB, const conv_planes *cv, u64 *out, int n, int rows,
-                       int cols, int K, size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb,
-                       unsigned *counters, u64 *partials, hipStream_t stream)
+hipError_t launch_gemm(const void *packedA, const void *packedB, const conv_planes *cv, u64 *out, size_t part_stride,
+                       int n, int rows, int cols, int K, size_t out_party_stride, size_t stride_row, int cdiv,
+                       size_t stride_cb, hipStream_t stream)
 {
     static bool lds_opt_in = false;
     constexpr int LDS_BYTES = 2 * 8 * TILE * 16, LDS_BYTES_SKINNY = 2 * 9 * TILE * 16;
@@ -960,8 +945,7 @@ hipError_t launch_gemm(const void *packedA, const void *packedB, const conv_plan
     g.A = (const v4i *)packedA;
     g.B = (const v4i *)packedB;
     g.out = out;
-    g.partials = partials;
-    g.counters = counters;
+    g.part_stride = part_stride;
     g.rows = rows;
     g.cols = cols;
     g.Rb = (rows + 15) / 16;
@@ -971,16 +955,27 @@ hipError_t launch_gemm(const void *packedA, const void *packedB, const conv_plan
     g.CT = p.skinny ? (cols + SKINNY_COLS - 1) / SKINNY_COLS : (cols + 63) / 64;
     g.units = (unsigned)p.units;
     g.wlast = p.wlast;
-    g.wrow = p.wrow;
+    g.tcost = p.tcost;
+    g.tlast = p.tlast;
     g.cost = p.cost;
+    g.share = p.cost / (unsigned)p.G;
+    g.rest = p.cost % (unsigned)p.G;
     g.slots = p.slots;
+    auto fdz = [](unsigned long long d) { return make_fdiv(d >= 1 && d < (1ull << 32) ? (u32)d : 1u); };
+    g.dG = fdz((unsigned)p.G);
+    g.dKb = fdz((unsigned)g.Kb);
+    g.dCT = fdz((unsigned)g.CT);
+    g.dRT = fdz((unsigned)g.RT);
+    g.dRowcost = fdz((unsigned long long)(g.CT - 1) * g.tcost + g.tlast);
+    g.dTilecost = fdz(g.tcost);
+    g.dWlast = fdz(g.wlast);
+    g.dCdiv = fdz((unsigned)cdiv);
     g.a_party_stride = ss_packed_bytes(rows, K) / 16;
     g.b_party_stride = ss_packed_bytes(cols, K) / 16;
     g.out_party_stride = out_party_stride;
     g.stride_row = stride_row;
     g.stride_cb = stride_cb;
     g.cdiv = cdiv;
-    g.negbias = neg_bias();
     if (cv) {
         const size_t plane = (size_t)cv->B * cv->H * cv->W * cv->C;   // bytes
         g.planes = (const v4i *)cv->planes;
@@ -989,6 +984,10 @@ hipError_t launch_gemm(const void *packedA, const void *packedB, const conv_plan
         g.zero = g.planes + (size_t)NL * g.plane16;   // the pad behind the first party's planes
         g.cvH = cv->H, g.cvW = cv->W, g.cvC16 = cv->C / 16, g.cvKw = cv->kw, g.cvStride = cv->stride, g.cvPad = cv->pad;
         g.cvHoWo = cv->Ho * cv->Wo, g.cvWo = cv->Wo, g.cvKbTap = cv->C / 64;
+        g.dHoWo = fdz((unsigned)g.cvHoWo);
+        g.dWo = fdz((unsigned)g.cvWo);
+        g.dKbTap = fdz((unsigned)g.cvKbTap);
+        g.dKw = fdz((unsigned)g.cvKw);
     }
     if (p.skinny)
         hipLaunchKernelGGL(gemm_skinny_kernel, dim3((unsigned)p.G), dim3(512), LDS_BYTES_SKINNY, stream, g);
@@ -1006,23 +1005,23 @@ size_t ss_planes_bytes(int B, int C, int H, int W)
     return (size_t)NL * B * H * W * C + 256;   // the limb planes and a pad that starts with 16 zero bytes
 }
 
-hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, int n, int rows, int cols, int K,
-                          size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb, unsigned *counters,
-                          u64 *partials, hipStream_t stream)
+hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, size_t part_stride, int n, int rows,
+                          int cols, int K, size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb,
+                          hipStream_t stream)
 {
-    return launch_gemm(packedA, packedB, nullptr, out, n, rows, cols, K, out_party_stride, stride_row, cdiv, stride_cb,
-                       counters, partials, stream);
+    return launch_gemm(packedA, packedB, nullptr, out, part_stride, n, rows, cols, K, out_party_stride, stride_row, cdiv,
+                       stride_cb, stream);
 }
 
-hipError_t ss_launch_gemm_conv(const void *packedW, const void *planes, u64 *out, int n, int B, int C, int H, int W,
-                               int Co, int kh, int kw, int stride, int pad, int Ho, int Wo, unsigned *counters,
-                               u64 *partials, hipStream_t stream)
+hipError_t ss_launch_gemm_conv(const void *packedW, const void *planes, u64 *out, size_t part_stride, int n, int B, int C,
+                               int H, int W, int Co, int kh, int kw, int stride, int pad, int Ho, int Wo,
+                               hipStream_t stream)
 {
     const conv_planes cv = {planes, B, C, H, W, kh, kw, stride, pad, Ho, Wo};
     const size_t HW = (size_t)Ho * Wo;
     // rows = output channel, cols = (b, ho, wo): y[b][co][hw]
-    return launch_gemm(packedW, nullptr, &cv, out, n, Co, (int)(B * HW), C * kh * kw, (size_t)B * Co * HW, HW, (int)HW,
-                       (size_t)Co * HW, counters, partials, stream);
+    return launch_gemm(packedW, nullptr, &cv, out, part_stride, n, Co, (int)(B * HW), C * kh * kw, (size_t)B * Co * HW, HW,
+                       (int)HW, (size_t)Co * HW, stream);
 }
 
 }  // namespace SS_NS

@@ -63,19 +63,29 @@ struct ss_pool_geom {
     int mode;                     // 0: maximum, 1: sum
 };
 
+// The incoming product shares of a reduction given as a sum of planes (the partial-sum form of the product
+// kernels): share i of element e is the sum mod p of c[s * stride + i * count + e] over s < planes.
+// planes <= 1: one plane, the plain tensor.
+struct ss_part_src {
+    int planes;
+    size_t stride;
+};
+
 // ---- streaming family (stream_kernels.hip) ----
 hipError_t ss_launch_share(const u64 *secret, u64 *shares, size_t count, int n, int degree,
                            const ss_keys &keys, hipStream_t stream);
 hipError_t ss_launch_reconstruct(const u64 *shares, u64 *secret, size_t count, const ss_rec_params &rp,
                                  hipStream_t stream);
 hipError_t ss_launch_degree_reduce(const u64 *c, u64 *msg1, u64 *msg2, u64 *out, size_t count,
-                                   const ss_dr_params &dp, hipStream_t stream);
+                                   const ss_dr_params &dp, const ss_part_src &ps, hipStream_t stream);
+// dst[i] = sum over the planes of c, i < total (dst may be c: for consumers that read one plane)
+hipError_t ss_launch_sum_planes(u64 *dst, const u64 *c, size_t total, const ss_part_src &ps, hipStream_t stream);
 hipError_t ss_launch_truncate(const u64 *x, u64 *u, u64 *wsh, u64 *out, size_t count, const ss_tr_params &tp,
                               hipStream_t stream);
 // rec != nullptr: also REC of the truncated shares with the multipliers rf (one more output, same launch)
 hipError_t ss_launch_degree_reduce_truncate(const u64 *c, u64 *msg1, u64 *msg2, u64 *u, u64 *wsh, u64 *out,
                                             u64 *rec, size_t count, const ss_dr_params &dp, const ss_tr_params &tp,
-                                            const ss_recf_params &rf, hipStream_t stream);
+                                            const ss_recf_params &rf, const ss_part_src &ps, hipStream_t stream);
 
 // outputs of reduction + truncation taken directly from the secret (no messages); open_all carries the
 // multipliers of REC from the IDs 1..2t+1
@@ -100,7 +110,7 @@ hipError_t ss_launch_relu_pool(const u64 *x, const u64 *sh_b, const u64 *sh_bi, 
 hipError_t ss_launch_layer_tail(const u64 *c, u64 *msg1, u64 *msg2, u64 *umsg, u64 *wsh, u64 *rmsg, u64 *yplain,
                                 const u64 *sh_b, const u64 *sh_bi, u64 *out, void *planes, int B, int C, int HW,
                                 const ss_dr_params &dp, const ss_tr_params &tp, const ss_nl_params &np,
-                                hipStream_t stream);
+                                const ss_part_src &ps, hipStream_t stream);
 
 // ---- int8-limb MFMA family (gemm_kernels.hip) ----
 // Packed operand: int8 tiles [row block of 16][k block of 64][limb 0..7][lane 0..63][16 bytes];
@@ -120,23 +130,25 @@ size_t ss_planes_bytes(int B, int C, int H, int W);   // per party
 // gen: `in` is the plaintext [B][C][HW] and the shares [n][B][C][HW] are written too; else `in` is the shares
 hipError_t ss_launch_planes(const u64 *in, u64 *shares, void *planes, int n, int t, int B, int C, int HW, bool gen,
                             const ss_keys &keys, hipStream_t stream);
-// convolution with the input given as planes and the weights packed with contraction index (tap, channel)
-hipError_t ss_launch_gemm_conv(const void *packedW, const void *planes, u64 *out, int n, int B, int C, int H, int W,
-                               int Co, int kh, int kw, int stride, int pad, int Ho, int Wo, unsigned *counters,
-                               u64 *partials, hipStream_t stream);
+// convolution with the input given as planes and the weights packed with contraction index (tap, channel);
+// out and part_stride as for ss_launch_gemm
+hipError_t ss_launch_gemm_conv(const void *packedW, const void *planes, u64 *out, size_t part_stride, int n, int B, int C,
+                               int H, int W, int Co, int kh, int kw, int stride, int pad, int Ho, int Wo,
+                               hipStream_t stream);
 // rows = (b, ho, wo), k = (c, r, s) of x [n][B][C][H][W]
 hipError_t ss_launch_pack_im2col(const u64 *x, void *dst, int n, int B, int C, int H, int W, int kh, int kw,
                                  int stride, int pad, int Ho, int Wo, hipStream_t stream);
-// out[i][row*stride_row + (col / cdiv)*stride_cb + col % cdiv] = sum_k A_i[row][k] * B_i[col][k] mod p.
-// An output tile may be shared by several workgroups; `partials` must hold
-// ss_gemm_scratch_bytes and `counters` SS_GEMM_MAX_SPLIT_TILES zeroed words
-// (they are left zeroed).
-#define SS_GEMM_MAX_SPLIT_TILES 16384
+// product[i][row*stride_row + (col / cdiv)*stride_cb + col % cdiv] = sum_k A_i[row][k] * B_i[col][k] mod p, left as
+// ss_gemm_planes(...) planes of that layout, part_stride elements apart, whose sum mod p is the product: a tile
+// of the output may be computed in parts by several workgroups, each of which stores its part in a plane of
+// its own; every position of every plane is written in every launch, nothing passes between workgroups.
+// With one plane `out` is the product itself.
 #define SS_GEMM_CUS 256
+int ss_gemm_planes(int n, int rows, int cols, int K, bool planes_operand);
+// bytes of the planes for either form of the second operand if there are several, else 0
 size_t ss_gemm_scratch_bytes(int n, int rows, int cols, int K);
-hipError_t ss_launch_zero_counters(unsigned *counters, hipStream_t stream);
-hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, int n, int rows, int cols, int K,
-                          size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb, unsigned *counters,
-                          u64 *partials, hipStream_t stream);
+hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, size_t part_stride, int n, int rows,
+                          int cols, int K, size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb,
+                          hipStream_t stream);
 
 }  // namespace SS_NS

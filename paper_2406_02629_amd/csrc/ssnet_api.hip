@@ -21,8 +21,15 @@ struct ssnet_ctx {
     int n, t, f;
     u64 seed;
     hipStream_t stream;
-    void *ws;                             // caller's workspace: [split counters][scratch]
+    void *ws;                             // caller's workspace: [reserved header][scratch ... pending product]
     size_t ws_bytes;
+    // product shares that a ssnet_*_product_* call left at the end of the workspace as a sum of planes
+    struct {
+        bool on;
+        size_t count;                     // per party
+        u64 *base;                        // [planes][n][count]
+        int planes;
+    } pending;
     int last_hip;
     u64 binv[2 * SS_MAXT + 1][SS_MAXK];   // first k columns of the inverse Vandermonde matrix (Eq. 3)
     u64 lambda_k[SS_MAXK];                // Lagrange multipliers of IDs 1..k (Eq. 2)
@@ -219,10 +226,9 @@ int conv_out(int H, int k, int stride, int pad) { return (H + 2 * pad - k) / str
 
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
-// The first bytes of the workspace hold the arrival counters of split
-// contractions (zeroed when the workspace is set, left zeroed by every launch);
-// everything else lives behind them.
-constexpr size_t WS_COUNTER_BYTES = (size_t)SS_GEMM_MAX_SPLIT_TILES * sizeof(unsigned);
+// The first bytes of the workspace are a reserved header (SSNET_WS_HEADER_BYTES); everything else lives
+// behind it.
+constexpr size_t WS_COUNTER_BYTES = SSNET_WS_HEADER_BYTES;
 
 char *ws_scratch(const ssnet_ctx *c) { return (char *)c->ws + WS_COUNTER_BYTES; }
 bool ws_fits(const ssnet_ctx *c, size_t scratch) { return c->ws && c->ws_bytes >= WS_COUNTER_BYTES + scratch; }
@@ -235,14 +241,65 @@ bool gemm_shape_ok(long rows, long cols, long K)
     return rows >= 1 && cols >= 1 && K >= 1 && K <= SSNET_MAX_K && rows <= 16L * 65535 * 2 && cols <= (1L << 30);
 }
 
-// partial residues of a split contraction go to the start of the scratch area
+// A product for a caller that wants the tensor itself: the kernel's planes go to the start of the scratch
+// area and one more launch adds them up into d_y; with a single plane the kernel writes d_y directly.
+// launch(out, part_stride) enqueues the product kernel.
+template <typename F>
+int run_product(ssnet_ctx *ctx, u64 *d_y, int rows, int cols, int K, bool planes_operand, F &&launch)
+{
+    const size_t total = (size_t)ctx->n * rows * cols;
+    const int planes = ss_gemm_planes(ctx->n, rows, cols, K, planes_operand);
+    timed tm(ctx, SSNET_PROF_GEMM);
+    hipError_t e = launch(planes > 1 ? (u64 *)ws_scratch(ctx) : d_y, total);
+    if (e == hipSuccess && planes > 1) e = ss_launch_sum_planes(d_y, (const u64 *)ws_scratch(ctx), total, {planes, total}, ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
 int run_gemm(ssnet_ctx *ctx, const void *pa, const void *pb, u64 *out, int rows, int cols, int K,
              size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb)
 {
-    timed tm(ctx, SSNET_PROF_GEMM);
-    hipError_t e = ss_launch_gemm(pa, pb, out, ctx->n, rows, cols, K, out_party_stride, stride_row, cdiv, stride_cb,
-                                  (unsigned *)ctx->ws, (u64 *)ws_scratch(ctx), ctx->stream);
-    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+    return run_product(ctx, out, rows, cols, K, false, [&](u64 *o, size_t part_stride) {
+        return ss_launch_gemm(pa, pb, o, part_stride, ctx->n, rows, cols, K, out_party_stride, stride_row, cdiv, stride_cb,
+                              ctx->stream);
+    });
+}
+
+size_t product_bytes(const ssnet_ctx *ctx, int rows, int cols, int K, bool planes_operand)
+{
+    return align256((size_t)ss_gemm_planes(ctx->n, rows, cols, K, planes_operand) * ctx->n * rows * cols * 8);
+}
+
+// Room for a product of `planes` planes at the very end of the workspace; the messages of the call that
+// consumes it grow from the front.  nullptr if the workspace is too small.
+u64 *reserve_pending(ssnet_ctx *ctx, int rows, int cols, int K, bool planes_operand)
+{
+    ctx->pending.on = false;
+    const size_t bytes = product_bytes(ctx, rows, cols, K, planes_operand);
+    if (!ctx->ws || ctx->ws_bytes < WS_COUNTER_BYTES + bytes + 256) return nullptr;
+    const uintptr_t end = ((uintptr_t)ctx->ws + ctx->ws_bytes) & ~(uintptr_t)255;
+    if (end - bytes < (uintptr_t)ws_scratch(ctx)) return nullptr;
+    ctx->pending.base = (u64 *)(end - bytes);
+    ctx->pending.count = (size_t)rows * cols;
+    ctx->pending.planes = ss_gemm_planes(ctx->n, rows, cols, K, planes_operand);
+    return ctx->pending.base;
+}
+
+// The product shares a reduction reads: the caller's tensor, or (d_c == nullptr) the pending product, which
+// must have `count` elements per party and leave `msg_bytes` of the workspace free in front of it.
+int incoming_product(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, size_t msg_bytes, const u64 **c, ss_part_src *ps)
+{
+    if (d_c) {
+        if (!ws_fits(ctx, msg_bytes)) return SSNET_EWORKSPACE;
+        // a tensor of the caller's may be the pending product's consumer's output: it stays valid
+        *c = d_c;
+        *ps = {1, 0};
+        return SSNET_OK;
+    }
+    if (!ctx->pending.on || ctx->pending.count != count) return SSNET_EINVAL;
+    if ((uintptr_t)ws_scratch(ctx) + msg_bytes > (uintptr_t)ctx->pending.base) return SSNET_EWORKSPACE;
+    *c = ctx->pending.base;
+    *ps = {ctx->pending.planes, (size_t)ctx->n * count};
+    return SSNET_OK;
 }
 
 }  // namespace
@@ -264,6 +321,7 @@ int ssnet_create(ssnet_ctx **out, int n, int t, uint64_t p, int f, uint64_t seed
     c->stream = (hipStream_t)hip_stream;
     c->ws = nullptr;
     c->ws_bytes = 0;
+    c->pending = {false, 0, nullptr, 0};
     c->last_hip = 0;
     c->prof = false;
     int ids[SS_MAXK];
@@ -363,10 +421,7 @@ int ssnet_set_workspace(ssnet_ctx *ctx, void *d_workspace, size_t bytes)
     if (!ctx || (!d_workspace && bytes) || ((uintptr_t)d_workspace & 15)) return SSNET_EINVAL;
     ctx->ws = d_workspace;
     ctx->ws_bytes = bytes;
-    if (d_workspace && bytes >= WS_COUNTER_BYTES) {
-        hipError_t e = ss_launch_zero_counters((unsigned *)d_workspace, ctx->stream);
-        if (e != hipSuccess) return fail_hip(ctx, e);
-    }
+    ctx->pending.on = false;
     return SSNET_OK;
 }
 
@@ -532,9 +587,74 @@ int ssnet_conv_mod_planes(ssnet_ctx *ctx, const void *d_planes, const void *d_w_
     const long M = (long)B * Ho * Wo, K = (long)C * kh * kw;
     if (!gemm_shape_ok(Co, M, K)) return SSNET_EINVAL;
     if (!ws_fits(ctx, align256(ss_gemm_scratch_bytes(ctx->n, Co, (int)M, (int)K)))) return SSNET_EWORKSPACE;
+    return run_product(ctx, d_y, Co, (int)M, (int)K, true, [&](u64 *o, size_t part_stride) {
+        return ss_launch_gemm_conv(d_w_packed, d_planes, o, part_stride, ctx->n, B, C, H, W, Co, kh, kw, stride, pad, Ho, Wo,
+                                   ctx->stream);
+    });
+}
+
+size_t ssnet_product_bytes_linear(const ssnet_ctx *ctx, int M, int K, int N)
+{
+    if (!ctx || !gemm_shape_ok(M, N, K)) return 0;
+    return product_bytes(ctx, M, N, K, false);
+}
+
+size_t ssnet_product_bytes_conv(const ssnet_ctx *ctx, int B, int C, int H, int W, int Co, int kh, int kw, int stride,
+                                int pad)
+{
+    if (!ctx || B < 1 || C < 1 || H < 1 || W < 1 || Co < 1 || kh < 1 || kw < 1 || stride < 1 || pad < 0) return 0;
+    const int Ho = conv_out(H, kh, stride, pad), Wo = conv_out(W, kw, stride, pad);
+    if (H + 2 * pad < kh || W + 2 * pad < kw || Ho < 1 || Wo < 1) return 0;
+    const long M = (long)B * Ho * Wo, K = (long)C * kh * kw;
+    if (!gemm_shape_ok(Co, M, K)) return 0;
+    const size_t a = product_bytes(ctx, Co, (int)M, (int)K, false), b = product_bytes(ctx, Co, (int)M, (int)K, true);
+    return a > b ? a : b;
+}
+
+int ssnet_linear_product_prepacked(ssnet_ctx *ctx, const void *d_x_packed, const void *d_w_packed, int M, int K, int N)
+{
+    if (!ctx || !d_x_packed || !d_w_packed || !gemm_shape_ok(M, N, K)) return SSNET_EINVAL;
+    u64 *parts = reserve_pending(ctx, M, N, K, false);
+    if (!parts) return SSNET_EWORKSPACE;
     timed tm(ctx, SSNET_PROF_GEMM);
-    hipError_t e = ss_launch_gemm_conv(d_w_packed, d_planes, d_y, ctx->n, B, C, H, W, Co, kh, kw, stride, pad, Ho, Wo,
-                                       (unsigned *)ctx->ws, (u64 *)ws_scratch(ctx), ctx->stream);
+    hipError_t e = ss_launch_gemm(d_x_packed, d_w_packed, parts, (size_t)ctx->n * M * N, ctx->n, M, N, K, (size_t)M * N,
+                                  (size_t)N, INT_MAX, 0, ctx->stream);
+    ctx->pending.on = e == hipSuccess;
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+int ssnet_conv1x1_product_prepacked(ssnet_ctx *ctx, const void *d_x_packed, const void *d_w_packed, int B, int C, int HW,
+                                    int Co)
+{
+    if (!ctx || !d_x_packed || !d_w_packed || B < 1 || HW < 1 || (long)B * HW > (1L << 30) ||
+        !gemm_shape_ok(Co, (long)B * HW, C))
+        return SSNET_EINVAL;
+    const int M = B * HW;
+    u64 *parts = reserve_pending(ctx, Co, M, C, false);
+    if (!parts) return SSNET_EWORKSPACE;
+    timed tm(ctx, SSNET_PROF_GEMM);
+    hipError_t e = ss_launch_gemm(d_w_packed, d_x_packed, parts, (size_t)ctx->n * Co * M, ctx->n, Co, M, C,
+                                  (size_t)B * Co * HW, (size_t)HW, HW, (size_t)Co * HW, ctx->stream);
+    ctx->pending.on = e == hipSuccess;
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
+int ssnet_conv_product_planes(ssnet_ctx *ctx, const void *d_planes, const void *d_w_packed, int B, int C, int H, int W,
+                              int Co, int kh, int kw, int stride, int pad)
+{
+    if (!ctx || !d_planes || !d_w_packed || !planes_shape_ok(B, C, H, W) || Co < 1 || kh < 1 || kw < 1 || stride < 1 ||
+        pad < 0 || pad >= 32768)
+        return SSNET_EINVAL;
+    const int Ho = conv_out(H, kh, stride, pad), Wo = conv_out(W, kw, stride, pad);
+    if (Ho < 1 || Wo < 1) return SSNET_EINVAL;
+    const long M = (long)B * Ho * Wo, K = (long)C * kh * kw;
+    if (!gemm_shape_ok(Co, M, K)) return SSNET_EINVAL;
+    u64 *parts = reserve_pending(ctx, Co, (int)M, (int)K, true);
+    if (!parts) return SSNET_EWORKSPACE;
+    timed tm(ctx, SSNET_PROF_GEMM);
+    hipError_t e = ss_launch_gemm_conv(d_w_packed, d_planes, parts, (size_t)ctx->n * Co * M, ctx->n, B, C, H, W, Co, kh, kw,
+                                       stride, pad, Ho, Wo, ctx->stream);
+    ctx->pending.on = e == hipSuccess;
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
 
@@ -631,13 +751,15 @@ static ss_tr_params make_tr_params(const ssnet_ctx *ctx, uint64_t stream_id)
 
 int ssnet_degree_reduce(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id, uint64_t *d_out)
 {
-    if (!ctx || !d_c || !d_out || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
+    if (!ctx || !d_out || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
     const int k = ctx->t + 1, nr = 2 * ctx->t + 1, n = ctx->n;
     const size_t need = ((size_t)nr * k + (size_t)k * n) * count * 8;
-    if (!ws_fits(ctx, need)) return SSNET_EWORKSPACE;
+    const u64 *c;
+    ss_part_src ps;
+    if (int rc = incoming_product(ctx, d_c, count, need, &c, &ps)) return rc;
     u64 *msg1 = (u64 *)ws_scratch(ctx), *msg2 = msg1 + (size_t)nr * k * count;
     timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
-    hipError_t e = ss_launch_degree_reduce(d_c, msg1, msg2, d_out, count, make_dr_params(ctx, stream_id), ctx->stream);
+    hipError_t e = ss_launch_degree_reduce(c, msg1, msg2, d_out, count, make_dr_params(ctx, stream_id), ps, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
 
@@ -678,7 +800,7 @@ int ssnet_degree_reduce_static(ssnet_ctx *ctx, const uint64_t *d_c, size_t count
     if (e != hipSuccess) return fail_hip(ctx, e);
     // both message arrays are written in full by the launch before anything reads them: nothing to clear
     u64 *msg1 = (u64 *)base, *msg2 = msg1 + (size_t)nr * k * count;
-    e = ss_launch_degree_reduce(d_c, msg1, msg2, d_out, count, make_dr_params(ctx, stream_id), ctx->stream);
+    e = ss_launch_degree_reduce(d_c, msg1, msg2, d_out, count, make_dr_params(ctx, stream_id), {1, 0}, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
 
@@ -718,7 +840,7 @@ namespace {
 static int degree_reduce_truncate(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id, uint64_t *d_out,
                            const int *party_ids, int m, uint64_t *d_rec, int kdiv = 1)
 {
-    if (!ctx || !d_c || !d_out || count == 0 || count > MAX_COUNT || kdiv < 1 || kdiv > SSNET_MAX_KDIV)
+    if (!ctx || !d_out || count == 0 || count > MAX_COUNT || kdiv < 1 || kdiv > SSNET_MAX_KDIV)
         return SSNET_EINVAL;
     ss_recf_params rf = {};
     if (d_rec) {
@@ -735,14 +857,16 @@ static int degree_reduce_truncate(ssnet_ctx *ctx, const uint64_t *d_c, size_t co
     }
     const int k = ctx->t + 1, nr = 2 * ctx->t + 1, n = ctx->n;
     const size_t need = ((size_t)nr * k + (size_t)k * n + k + n) * count * 8;
-    if (!ws_fits(ctx, need)) return SSNET_EWORKSPACE;
+    const u64 *c;
+    ss_part_src ps;
+    if (int rc = incoming_product(ctx, d_c, count, need, &c, &ps)) return rc;
     u64 *msg1 = (u64 *)ws_scratch(ctx), *msg2 = msg1 + (size_t)nr * k * count;
     u64 *u = msg2 + (size_t)k * n * count, *wsh = u + (size_t)k * count;
     ss_tr_params tp = make_tr_params(ctx, stream_id);
     tp.kdiv = kdiv;
     timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
-    hipError_t e = ss_launch_degree_reduce_truncate(d_c, msg1, msg2, u, wsh, d_out, d_rec, count,
-                                                    make_dr_params(ctx, stream_id), tp, rf, ctx->stream);
+    hipError_t e = ss_launch_degree_reduce_truncate(c, msg1, msg2, u, wsh, d_out, d_rec, count,
+                                                    make_dr_params(ctx, stream_id), tp, rf, ps, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
 
@@ -790,7 +914,7 @@ static bool make_nl_params(const ssnet_ctx *ctx, uint64_t stream_id, ss_nl_param
 int ssnet_reduce_truncate_direct(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id,
                                  uint64_t *d_out, const int *party_ids, int m, uint64_t *d_secret)
 {
-    if (!ctx || !d_c || !d_out || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
+    if (!ctx || !d_out || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;
     ss_recf_params rf = {};
     if (d_secret) {
         if (!party_ids || m < 1 || m > ctx->n) return SSNET_EINVAL;
@@ -806,8 +930,17 @@ int ssnet_reduce_truncate_direct(ssnet_ctx *ctx, const uint64_t *d_c, size_t cou
     }
     ss_nl_params open_all;
     if (!make_nl_params(ctx, 0, &open_all)) return SSNET_EINVAL;
+    const u64 *c = d_c;
+    if (!d_c) {   // the pending product: this kernel reads one plane, so the planes are summed first
+        ss_part_src ps;
+        if (int rc = incoming_product(ctx, nullptr, count, 0, &c, &ps)) return rc;
+        timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
+        hipError_t e = ss_launch_sum_planes(ctx->pending.base, ctx->pending.base, (size_t)ctx->n * count, ps, ctx->stream);
+        if (e != hipSuccess) return fail_hip(ctx, e);
+        ctx->pending.planes = 1;
+    }
     timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
-    hipError_t e = ss_launch_reduce_truncate_direct(d_c, d_out, d_secret, count, open_all, make_tr_params(ctx, stream_id),
+    hipError_t e = ss_launch_reduce_truncate_direct(c, d_out, d_secret, count, open_all, make_tr_params(ctx, stream_id),
                                                     rf, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
@@ -841,12 +974,15 @@ size_t ssnet_workspace_bytes_layer_tail(const ssnet_ctx *ctx, int B, int C, int 
 int ssnet_reduce_truncate_relu(ssnet_ctx *ctx, const uint64_t *d_c, int B, int C, int HW, uint64_t stream_id,
                                const uint64_t *d_beta, const uint64_t *d_betainv, uint64_t *d_out, void *d_planes)
 {
-    if (!ctx || !d_c || !d_beta || !d_betainv || !d_out || B < 1 || C < 1 || HW < 1) return SSNET_EINVAL;
+    if (!ctx || !d_beta || !d_betainv || !d_out || B < 1 || C < 1 || HW < 1) return SSNET_EINVAL;
     if ((long)B * HW >= (1L << 30) || (size_t)B * C * HW > MAX_COUNT) return SSNET_EINVAL;
     if (d_planes && (((uintptr_t)d_planes & 15) || C % 64 != 0)) return SSNET_EINVAL;
     const size_t count = (size_t)B * C * HW, plane = tail_plane(ctx, B, C, HW);
     const int k = ctx->t + 1, nr = 2 * ctx->t + 1, n = ctx->n;
-    if (!ws_fits(ctx, ((size_t)nr * k + (size_t)k * n + k + n + nr + 1) * plane * 8)) return SSNET_EWORKSPACE;
+    const u64 *c;
+    ss_part_src ps;
+    if (int rc = incoming_product(ctx, d_c, count, ((size_t)nr * k + (size_t)k * n + k + n + nr + 1) * plane * 8, &c, &ps))
+        return rc;
     u64 *msg1 = (u64 *)ws_scratch(ctx), *msg2 = msg1 + (size_t)nr * k * plane;
     u64 *u = msg2 + (size_t)k * n * plane, *wsh = u + (size_t)k * plane;
     u64 *rmsg = wsh + (size_t)n * plane, *yplain = rmsg + (size_t)nr * plane;
@@ -861,8 +997,8 @@ int ssnet_reduce_truncate_relu(ssnet_ctx *ctx, const uint64_t *d_c, int B, int C
         const bool planes_apart = d_planes && count >= ((size_t)1 << 19);
         {
             timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
-            e = ss_launch_layer_tail(d_c, msg1, msg2, u, wsh, rmsg, yplain, d_beta, d_betainv, d_out,
-                                     planes_apart ? nullptr : d_planes, B, C, HW, dp, tp, np, ctx->stream);
+            e = ss_launch_layer_tail(c, msg1, msg2, u, wsh, rmsg, yplain, d_beta, d_betainv, d_out,
+                                     planes_apart ? nullptr : d_planes, B, C, HW, dp, tp, np, ps, ctx->stream);
         }
         if (e == hipSuccess && planes_apart) {
             const ss_keys none = {};
@@ -873,7 +1009,7 @@ int ssnet_reduce_truncate_relu(ssnet_ctx *ctx, const uint64_t *d_c, int B, int C
         const ss_recf_params norec = {};
         {
             timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
-            e = ss_launch_degree_reduce_truncate(d_c, msg1, msg2, u, wsh, d_out, nullptr, count, dp, tp, norec,
+            e = ss_launch_degree_reduce_truncate(c, msg1, msg2, u, wsh, d_out, nullptr, count, dp, tp, norec, ps,
                                                  ctx->stream);
         }
         if (e == hipSuccess) {

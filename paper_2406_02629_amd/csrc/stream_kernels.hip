@@ -40,6 +40,15 @@ struct pack_t<2> {
     }
 };
 
+// share i of element e of the incoming product, which may be given as a sum of planes (the partial-sum form
+// of the product kernels): canonical sum of the planes' values
+__device__ __forceinline__ u64 load_product(const u64 *c, size_t idx, const ss_part_src &ps)
+{
+    u64 v = c[idx];
+    for (int s = 1; s < ps.planes; s++) v = ss_add(v, c[idx + (size_t)s * ps.stride]);
+    return v;
+}
+
 template <int MAXD>
 __device__ __forceinline__ void draw_coeffs(u64 (&c)[MAXD], const u64 *keys, int d, u64 e)
 {
@@ -232,7 +241,7 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_kernel(const u64 *c, u64 
                                                               u64 *__restrict__ msg2, u64 *__restrict__ umsg,
                                                               u64 *__restrict__ wsh, u64 *out, u64 *__restrict__ rec,
                                                               size_t count, ss_dr_params dp, ss_tr_params tp,
-                                                              ss_recf_params rf)
+                                                              ss_recf_params rf, ss_part_src ps)
 {
     const size_t e0 = ((size_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
     if (e0 >= count) return;
@@ -251,6 +260,12 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_kernel(const u64 *c, u64 
         if (i < nr) {
             pack_t<VEC> ci;
             ci.load(c + (size_t)i * count + e0);
+            for (int s = 1; s < ps.planes; s++) {
+                pack_t<VEC> more;
+                more.load(c + (size_t)s * ps.stride + (size_t)i * count + e0);
+#pragma unroll
+                for (int u = 0; u < VEC; u++) ci.v[u] = ss_add(ci.v[u], more.v[u]);
+            }
             u64 r[VEC][SS_MAXT];
 #pragma unroll
             for (int u = 0; u < VEC; u++) draw_coeffs<SS_MAXT>(r[u], dp.reshare_key[i], dp.t, e0 + u);
@@ -366,7 +381,8 @@ template <int N, int T, bool TRUNC>
 __device__ __forceinline__ void reduce_truncate_fixed(size_t e, size_t count, size_t em, size_t mcount, const u64 *c,
                                                       u64 *__restrict__ msg1, u64 *__restrict__ msg2,
                                                       u64 *__restrict__ umsg, u64 *__restrict__ wsh,
-                                                      const ss_dr_params &dp, const ss_tr_params &tp, u64 (&o)[N])
+                                                      const ss_dr_params &dp, const ss_tr_params &tp,
+                                                      const ss_part_src &ps, u64 (&o)[N])
 {
     constexpr int K = T + 1, NR = 2 * T + 1;
     const u64 counter = ss_counter(e);
@@ -379,6 +395,13 @@ __device__ __forceinline__ void reduce_truncate_fixed(size_t e, size_t count, si
     u64 cin[NR];
 #pragma unroll
     for (int i = 0; i < NR; i++) cin[i] = c[(size_t)i * count + e];
+    for (int s = 1; s < ps.planes; s++) {   // the product as a sum of planes: one more round of loads per plane
+        u64 more[NR];
+#pragma unroll
+        for (int i = 0; i < NR; i++) more[i] = c[(size_t)s * ps.stride + (size_t)i * count + e];
+#pragma unroll
+        for (int i = 0; i < NR; i++) cin[i] = ss_add(cin[i], more[i]);
+    }
 
     // step 1, and of step 2 the sums coef[q][j] = sum_i msg1[i][q] * D binv[i][j]
     ss_sacc2 coef[K][K];
@@ -456,12 +479,13 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_fixed_kernel(const u64 *c
                                                                     u64 *__restrict__ msg2, u64 *__restrict__ umsg,
                                                                     u64 *__restrict__ wsh, u64 *out,
                                                                     u64 *__restrict__ rec, size_t count,
-                                                                    ss_dr_params dp, ss_tr_params tp, ss_recf_params rf)
+                                                                    ss_dr_params dp, ss_tr_params tp, ss_recf_params rf,
+                                                                    ss_part_src ps)
 {
     const size_t e = (size_t)blockIdx.x * BLOCK + threadIdx.x;
     if (e >= count) return;
     u64 o[N];
-    reduce_truncate_fixed<N, T, TRUNC>(e, count, e, count, c, msg1, msg2, umsg, wsh, dp, tp, o);
+    reduce_truncate_fixed<N, T, TRUNC>(e, count, e, count, c, msg1, msg2, umsg, wsh, dp, tp, ps, o);
     ss_sacc2 racc;   // if asked for, REC of the result
     racc.clear();
 #pragma unroll
@@ -513,7 +537,7 @@ __global__ __launch_bounds__(BLOCK) void layer_tail_kernel(const u64 *c, u64 *__
                                                            const u64 *__restrict__ sh_b, const u64 *__restrict__ sh_bi,
                                                            u64 *out, signed char *__restrict__ planes, int B, int C, int HW,
                                                            size_t party_bytes, ss_dr_params dp, ss_tr_params tp,
-                                                           ss_nl_params np)
+                                                           ss_nl_params np, ss_part_src ps)
 {
     const int lane = threadIdx.x & 63, r16 = lane & 15, j = lane >> 4;
     const int pix = blockIdx.x * 16 + r16, c0 = blockIdx.y * 16 + 4 * (threadIdx.x >> 6);
@@ -542,7 +566,7 @@ __global__ __launch_bounds__(BLOCK) void layer_tail_kernel(const u64 *c, u64 *__
         for (int i = 0; i < 2 * T + 1; i++) mb[i] = sh_b[(size_t)i * count + e];
 #pragma unroll
         for (int m = 0; m < N; m++) mbi[m] = sh_bi[(size_t)m * count + e];
-        reduce_truncate_fixed<N, T, true>(e, count, em, mcount, c, msg1, msg2, umsg, wsh, dp, tp, o);
+        reduce_truncate_fixed<N, T, true>(e, count, em, mcount, c, msg1, msg2, umsg, wsh, dp, tp, ps, o);
         relu_fixed<N, T>(o, em, mcount, mb, mbi, rmsg, yplain, np, r);
 #pragma unroll
         for (int p = 0; p < N; p++) {
@@ -580,7 +604,8 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_lanes_kernel(const u64 *c
                                                                     u64 *__restrict__ msg2, u64 *__restrict__ umsg,
                                                                     u64 *__restrict__ wsh, u64 *out,
                                                                     u64 *__restrict__ rec, size_t count,
-                                                                    ss_dr_params dp, ss_tr_params tp, ss_recf_params rf)
+                                                                    ss_dr_params dp, ss_tr_params tp, ss_recf_params rf,
+                                                                    ss_part_src ps)
 {
     __shared__ u64 sub[2 * SS_MAXT + 1][SS_MAXK][32];
     // drawn once per element by the spare lanes: 0 zero sharing, 1 alpha, 2 elite re-sharing, 3 alpha~
@@ -593,7 +618,7 @@ __global__ __launch_bounds__(BLOCK) void degree_reduce_lanes_kernel(const u64 *c
     const bool live = e < count;
     const int k = dp.t + 1, nr = 2 * dp.t + 1;
     if (live && p < nr) {
-        const u64 ci = c[(size_t)p * count + e];
+        const u64 ci = load_product(c, (size_t)p * count + e, ps);
         u64 r[SS_MAXT];
         draw_coeffs<SS_MAXT>(r, dp.reshare_key[p], dp.t, e);
 #pragma unroll
@@ -965,47 +990,62 @@ hipError_t ss_launch_reconstruct(const u64 *shares, u64 *secret, size_t count, c
     return hipGetLastError();
 }
 
+// sum of the product's planes, written to dst (which may be the first plane: each thread reads its element
+// of every plane before it writes)
+__global__ __launch_bounds__(BLOCK) void sum_planes_kernel(u64 *dst, const u64 *c, size_t total, ss_part_src ps)
+{
+    const size_t i = (size_t)blockIdx.x * BLOCK + threadIdx.x;
+    if (i < total) dst[i] = load_product(c, i, ps);
+}
+
+hipError_t ss_launch_sum_planes(u64 *dst, const u64 *c, size_t total, const ss_part_src &ps, hipStream_t stream)
+{
+    if (ps.planes > 1 || dst != c)
+        hipLaunchKernelGGL(sum_planes_kernel, dim3(blocks_for(total, 1)), dim3(BLOCK), 0, stream, dst, c, total, ps);
+    return hipGetLastError();
+}
+
 hipError_t ss_launch_degree_reduce(const u64 *c, u64 *msg1, u64 *msg2, u64 *out, size_t count,
-                                   const ss_dr_params &dp, hipStream_t stream)
+                                   const ss_dr_params &dp, const ss_part_src &ps, hipStream_t stream)
 {
     const ss_tr_params none = {};
     const ss_recf_params norec = {};
     const bool fixed = (dp.n == 5 && dp.t == 2) || (dp.n == 3 && dp.t == 1);
     if (count < (fixed ? LANES_MAX_COUNT_FIXED : LANES_MAX_COUNT))
         hipLaunchKernelGGL(degree_reduce_lanes_kernel<false>, dim3((unsigned)((count + 31) / 32)), dim3(BLOCK), 0, stream,
-                           c, msg1, msg2, (u64 *)nullptr, (u64 *)nullptr, out, (u64 *)nullptr, count, dp, none, norec);
+                           c, msg1, msg2, (u64 *)nullptr, (u64 *)nullptr, out, (u64 *)nullptr, count, dp, none, norec, ps);
     else if (dp.n == 5 && dp.t == 2)
         hipLaunchKernelGGL((degree_reduce_fixed_kernel<5, 2, false>), dim3(blocks_for(count, 1)), dim3(BLOCK), 0, stream, c,
-                           msg1, msg2, (u64 *)nullptr, (u64 *)nullptr, out, (u64 *)nullptr, count, dp, none, norec);
+                           msg1, msg2, (u64 *)nullptr, (u64 *)nullptr, out, (u64 *)nullptr, count, dp, none, norec, ps);
     else if (dp.n == 3 && dp.t == 1)
         hipLaunchKernelGGL((degree_reduce_fixed_kernel<3, 1, false>), dim3(blocks_for(count, 1)), dim3(BLOCK), 0, stream, c,
-                           msg1, msg2, (u64 *)nullptr, (u64 *)nullptr, out, (u64 *)nullptr, count, dp, none, norec);
+                           msg1, msg2, (u64 *)nullptr, (u64 *)nullptr, out, (u64 *)nullptr, count, dp, none, norec, ps);
     else   // one element per thread: the k*k + n wide accumulators of two elements would not fit the register file
         hipLaunchKernelGGL((degree_reduce_kernel<1, false>), dim3(blocks_for(count, 1)), dim3(BLOCK), 0, stream, c, msg1,
-                           msg2, (u64 *)nullptr, (u64 *)nullptr, out, (u64 *)nullptr, count, dp, none, norec);
+                           msg2, (u64 *)nullptr, (u64 *)nullptr, out, (u64 *)nullptr, count, dp, none, norec, ps);
     return hipGetLastError();
 }
 
 hipError_t ss_launch_degree_reduce_truncate(const u64 *c, u64 *msg1, u64 *msg2, u64 *u, u64 *wsh, u64 *out,
                                             u64 *rec, size_t count, const ss_dr_params &dp, const ss_tr_params &tp,
-                                            const ss_recf_params &rf, hipStream_t stream)
+                                            const ss_recf_params &rf, const ss_part_src &ps, hipStream_t stream)
 {
     const bool fixed = (dp.n == 5 && dp.t == 2) || (dp.n == 3 && dp.t == 1);
     if (tp.kdiv > 1)   // the rounding division exists in the general kernel only
         hipLaunchKernelGGL((degree_reduce_kernel<1, true>), dim3(blocks_for(count, 1)), dim3(BLOCK), 0, stream, c, msg1,
-                           msg2, u, wsh, out, rec, count, dp, tp, rf);
+                           msg2, u, wsh, out, rec, count, dp, tp, rf, ps);
     else if (count < (fixed ? LANES_MAX_COUNT_FIXED : LANES_MAX_COUNT))
         hipLaunchKernelGGL(degree_reduce_lanes_kernel<true>, dim3((unsigned)((count + 31) / 32)), dim3(BLOCK), 0, stream,
-                           c, msg1, msg2, u, wsh, out, rec, count, dp, tp, rf);
+                           c, msg1, msg2, u, wsh, out, rec, count, dp, tp, rf, ps);
     else if (dp.n == 5 && dp.t == 2)
         hipLaunchKernelGGL((degree_reduce_fixed_kernel<5, 2, true>), dim3(blocks_for(count, 1)), dim3(BLOCK), 0, stream, c,
-                           msg1, msg2, u, wsh, out, rec, count, dp, tp, rf);
+                           msg1, msg2, u, wsh, out, rec, count, dp, tp, rf, ps);
     else if (dp.n == 3 && dp.t == 1)
         hipLaunchKernelGGL((degree_reduce_fixed_kernel<3, 1, true>), dim3(blocks_for(count, 1)), dim3(BLOCK), 0, stream, c,
-                           msg1, msg2, u, wsh, out, rec, count, dp, tp, rf);
+                           msg1, msg2, u, wsh, out, rec, count, dp, tp, rf, ps);
     else
         hipLaunchKernelGGL((degree_reduce_kernel<1, true>), dim3(blocks_for(count, 1)), dim3(BLOCK), 0, stream, c, msg1,
-                           msg2, u, wsh, out, rec, count, dp, tp, rf);
+                           msg2, u, wsh, out, rec, count, dp, tp, rf, ps);
     return hipGetLastError();
 }
 
@@ -1070,16 +1110,16 @@ hipError_t ss_launch_reduce_truncate_direct(const u64 *c, u64 *out, u64 *rec, si
 hipError_t ss_launch_layer_tail(const u64 *c, u64 *msg1, u64 *msg2, u64 *umsg, u64 *wsh, u64 *rmsg, u64 *yplain,
                                 const u64 *sh_b, const u64 *sh_bi, u64 *out, void *planes, int B, int C, int HW,
                                 const ss_dr_params &dp, const ss_tr_params &tp, const ss_nl_params &np,
-                                hipStream_t stream)
+                                const ss_part_src &ps, hipStream_t stream)
 {
     const dim3 grid((B * HW + 15) / 16, (C + 15) / 16), block(BLOCK);
     const size_t party_bytes = ss_planes_bytes(B, C, HW, 1);
     if (dp.n == 5 && dp.t == 2)
         hipLaunchKernelGGL((layer_tail_kernel<5, 2>), grid, block, 0, stream, c, msg1, msg2, umsg, wsh, rmsg, yplain, sh_b,
-                           sh_bi, out, (signed char *)planes, B, C, HW, party_bytes, dp, tp, np);
+                           sh_bi, out, (signed char *)planes, B, C, HW, party_bytes, dp, tp, np, ps);
     else if (dp.n == 3 && dp.t == 1)
         hipLaunchKernelGGL((layer_tail_kernel<3, 1>), grid, block, 0, stream, c, msg1, msg2, umsg, wsh, rmsg, yplain, sh_b,
-                           sh_bi, out, (signed char *)planes, B, C, HW, party_bytes, dp, tp, np);
+                           sh_bi, out, (signed char *)planes, B, C, HW, party_bytes, dp, tp, np, ps);
     else
         return hipErrorInvalidValue;   // the caller runs the separate kernels for other schemes
     return hipGetLastError();

@@ -148,6 +148,31 @@ def test_new_entry_points_check_their_arguments():
     assert lib.ssnet_reduce_truncate_direct(ctx, 16, 8, 0, 16, ids, 3, 16) == binding.EID
 
 
+def test_product_entry_points_check_their_arguments():
+    lib = binding.load_library()
+    s = SSNet(5, 2, device=None)
+    ctx = s._ctx
+    # a product that one workgroup per tile computes whole is one plane of n * count elements
+    assert lib.ssnet_product_bytes_linear(ctx, 64, 64, 64) == 5 * 64 * 64 * 8
+    # 196 x 2304 x 256: 80 tiles of 36 k blocks for 256 workgroups, so several planes
+    one = 5 * 196 * 256 * 8
+    assert lib.ssnet_product_bytes_conv(ctx, 1, 256, 14, 14, 256, 3, 3, 1, 1) % 256 == 0
+    assert 2 * one <= lib.ssnet_product_bytes_conv(ctx, 1, 256, 14, 14, 256, 3, 3, 1, 1) <= 8 * one
+    assert lib.ssnet_product_bytes_linear(ctx, 0, 4, 4) == 0 and lib.ssnet_product_bytes_linear(ctx, 4, 16384, 4) == 0
+    assert lib.ssnet_product_bytes_conv(ctx, 1, 3, 4, 4, 2, 5, 5, 1, 0) == 0                  # kernel > input
+    assert lib.ssnet_linear_product_prepacked(ctx, 16, 16, 4, 4, 4) == binding.EWORKSPACE
+    assert lib.ssnet_linear_product_prepacked(ctx, None, 16, 4, 4, 4) == binding.EINVAL
+    assert lib.ssnet_conv1x1_product_prepacked(ctx, 16, 16, 1, 4, 0, 4) == binding.EINVAL
+    assert lib.ssnet_conv1x1_product_prepacked(ctx, 16, 16, 1, 4, 9, 4) == binding.EWORKSPACE
+    assert lib.ssnet_conv_product_planes(ctx, 16, 16, 1, 3, 8, 8, 4, 3, 3, 1, 1) == binding.EINVAL   # C % 64 != 0
+    assert lib.ssnet_conv_product_planes(ctx, 16, 16, 1, 64, 8, 8, 4, 3, 3, 1, 1) == binding.EWORKSPACE
+    # d_c = NULL means the pending product; there is none
+    assert lib.ssnet_degree_reduce(ctx, None, 8, 0, 16) == binding.EINVAL
+    assert lib.ssnet_degree_reduce_truncate(ctx, None, 8, 0, 16) == binding.EINVAL
+    assert lib.ssnet_reduce_truncate_direct(ctx, None, 8, 0, 16, None, 0, None) == binding.EINVAL
+    assert lib.ssnet_reduce_truncate_relu(ctx, None, 1, 64, 16, 0, 16, 16, 16, None) == binding.EINVAL
+
+
 def test_pooling_entry_points_check_their_arguments():
     lib = binding.load_library()
     s = SSNet(5, 2, device=None)
