@@ -17,3 +17,21 @@ __device__ __forceinline__ u32 limb_dword(const u64 (&y)[4], int limb)
     const u32 sel = (u32)i | ((u32)(4 + i) << 8) | 0x0c0c0000u;
     return __builtin_amdgcn_perm(__builtin_amdgcn_perm(d, c, sel), __builtin_amdgcn_perm(b, a, sel), 0x05040100u);
 }
+
+// Limb dwords of a block of 16 pixels x 16 channels, staged in LDS as [party][limb][pixel][group of four
+// channels], to channel-innermost limb planes (per party [limb][pixel][C channels], int8): thread t of the 256
+// takes limb t/16 % SS_NLIMB of pixel t%16 for the parties t/(16 SS_NLIMB), that + 2, ... and writes the 16
+// channels c0..c0+15 as one 16-byte store (a dword per wave would be a 4-byte store at a stride of C bytes).
+template <int MAXP>
+__device__ __forceinline__ void store_staged_planes(const u32 (&stage)[MAXP][SS_NLIMB][16][4],
+                                                    signed char *__restrict__ planes, size_t party_bytes, size_t plane,
+                                                    int pix0, int npix, int C, int c0, int n)
+{
+    constexpr int PSTEP = 256 / (16 * SS_NLIMB);   // parties in flight: 2
+    const int t = threadIdx.x, px = t & 15, limb = (t >> 4) % SS_NLIMB, p0 = t / (16 * SS_NLIMB);
+    if (pix0 + px >= npix || p0 >= PSTEP) return;
+    for (int p = p0; p < n; p += PSTEP) {
+        const int4 val = *reinterpret_cast<const int4 *>(&stage[p][limb][px][0]);
+        *reinterpret_cast<int4 *>(planes + p * party_bytes + (size_t)limb * plane + (size_t)(pix0 + px) * C + c0) = val;
+    }
+}

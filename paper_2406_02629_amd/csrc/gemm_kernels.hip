@@ -200,19 +200,25 @@ __global__ __launch_bounds__(256) void planes_kernel(const u64 *__restrict__ in,
                 if (p < n) dig[p] = balanced_digits(in[(size_t)p * plane + e]);
         }
     }
+    // The four lanes of a pixel swap their digit words, the limb dwords of the wave's four channels go through
+    // LDS, and the block's 16 channels of one pixel and limb leave as one 16-byte store (a dword per wave would
+    // be a 4-byte store at a stride of C bytes).
+    __shared__ __align__(16) u32 stage[MAXP][NL][16][4];   // [party][limb][pixel][wave]
+    const int w = threadIdx.x >> 6;
 #pragma unroll
     for (int p = 0; p < MAXP; p++) {
         if (p < n) {
             u64 y[4];
 #pragma unroll
             for (int q = 0; q < 4; q++) y[q] = __shfl(dig[p], r16 + 16 * q);
-            if (live && 2 * j < NL) {
-                u32 *bp = reinterpret_cast<u32 *>(planes + p * party_bytes + (size_t)pix * C + c0);
-                bp[(2 * j) * (plane / 4)] = limb_dword(y, 2 * j);
-                bp[(2 * j + 1) * (plane / 4)] = limb_dword(y, 2 * j + 1);
+            if (2 * j < NL) {
+                stage[p][2 * j][r16][w] = limb_dword(y, 2 * j);
+                stage[p][2 * j + 1][r16][w] = limb_dword(y, 2 * j + 1);
             }
         }
     }
+    __syncthreads();
+    store_staged_planes<MAXP>(stage, planes, party_bytes, plane, blockIdx.x * 16, B * HW, C, blockIdx.y * 16, n);
 }
 
 // The same with four channels per thread (thread t of block (pixel block, channel block of 64): pixel t%16,

@@ -544,7 +544,6 @@ __global__ __launch_bounds__(BLOCK) void layer_tail_kernel(const u64 *c, u64 *__
     const size_t count = (size_t)B * HW * C;
     if (planes && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < N)
         *reinterpret_cast<int4 *>(planes + threadIdx.x * party_bytes + SS_NLIMB * count) = make_int4(0, 0, 0, 0);
-    const bool live = pix < B * HW && c0 + j < C;
     u64 dig[N];
 #pragma unroll
     for (int p = 0; p < N; p++) dig[p] = 0;
@@ -575,17 +574,22 @@ __global__ __launch_bounds__(BLOCK) void layer_tail_kernel(const u64 *c, u64 *__
         }
     }
     if (!planes) return;   // uniform
+    // the four lanes of a pixel swap their digit words; the limb dwords go through LDS and leave as 16-byte
+    // stores of the block's 16 channels (see store_staged_planes)
+    __shared__ __align__(16) u32 stage[N][SS_NLIMB][16][4];   // [party][limb][pixel][wave]
+    const int w = threadIdx.x >> 6;
 #pragma unroll
     for (int p = 0; p < N; p++) {
         u64 y[4];
 #pragma unroll
         for (int q = 0; q < 4; q++) y[q] = __shfl(dig[p], r16 + 16 * q);
-        if (live && 2 * j < SS_NLIMB) {
-            u32 *bp = reinterpret_cast<u32 *>(planes + p * party_bytes + (size_t)pix * C + c0);
-            bp[(2 * j) * (count / 4)] = limb_dword(y, 2 * j);
-            bp[(2 * j + 1) * (count / 4)] = limb_dword(y, 2 * j + 1);
+        if (2 * j < SS_NLIMB) {
+            stage[p][2 * j][r16][w] = limb_dword(y, 2 * j);
+            stage[p][2 * j + 1][r16][w] = limb_dword(y, 2 * j + 1);
         }
     }
+    __syncthreads();
+    store_staged_planes<N>(stage, planes, party_bytes, count, blockIdx.x * 16, B * HW, C, blockIdx.y * 16, N);
 }
 
 // Same computation for small tensors, where the serial work of one thread per
