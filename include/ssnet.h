@@ -374,6 +374,20 @@ size_t ssnet_workspace_bytes_layer_tail(const ssnet_ctx *ctx, int B, int C, int 
 int ssnet_reduce_truncate_relu(ssnet_ctx *ctx, const uint64_t *d_c, int B, int C, int HW, uint64_t stream_id,
                                const uint64_t *d_beta, const uint64_t *d_betainv, uint64_t *d_out, void *d_planes);
 
+/* The outputs of ssnet_reduce_truncate_relu without the protocol, for all
+ * parties on one device (the companion of ssnet_reduce_truncate_direct for the
+ * order Linear - Truncation - NonLinear of Sec. VII-A): d_out and, if not NULL,
+ * d_planes hold the very residues the protocol entry point writes for any
+ * stream_id, because they do not depend on the reshare, zero and truncation
+ * randomness: the elite party of SSS-NonLinear (Sec. VI-C) sees floor(x / 2^f) *
+ * beta, x being the secret of the incoming degree-2t sharing, and every party's
+ * result is max(., 0) times its share of beta^-1.  One pass, no message, no
+ * workspace (beyond a pending product, d_c = NULL).  A simulation shortcut,
+ * reported beside the protocol path, never in its place.  Any scheme; shapes,
+ * masks and planes as for ssnet_reduce_truncate_relu.  d_out may alias d_c. */
+int ssnet_reduce_truncate_relu_direct(ssnet_ctx *ctx, const uint64_t *d_c, int B, int C, int HW, const uint64_t *d_beta,
+                                      const uint64_t *d_betainv, uint64_t *d_out, void *d_planes);
+
 /* Host-side generator, exposed so that its bits can be checked without a GPU.
  * key = absorb(seed, domain, stream_id, party, j) with h <- mix64((h ^ word) +
  * 0x9E3779B97F4A7C15) from h = 0, mix64 being the SplitMix64 output function;

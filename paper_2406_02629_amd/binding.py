@@ -63,6 +63,7 @@ SIGNATURES = {
     "ssnet_workspace_bytes_layer_tail": (_sz, [_ptr, _int, _int, _int]),
     "ssnet_layer_tail_message_plane": (_sz, [_ptr, _int, _int, _int]),
     "ssnet_reduce_truncate_relu": (_int, [_ptr, _ptr, _int, _int, _int, _u64, _ptr, _ptr, _ptr, _ptr]),
+    "ssnet_reduce_truncate_relu_direct": (_int, [_ptr, _ptr, _int, _int, _int, _ptr, _ptr, _ptr, _ptr]),
     "ssnet_nonlinear_masks": (_int, [_ptr, _sz, _u64, _ptr, _ptr]),
     "ssnet_relu": (_int, [_ptr, _ptr, _ptr, _ptr, _sz, _ptr]),
     "ssnet_truncate_div": (_int, [_ptr, _ptr, _sz, _int, _u64, _ptr]),
@@ -515,6 +516,24 @@ class SSNet:
         self._ok(self.lib.ssnet_reduce_truncate_relu(self._ctx, cp, B, C, HW, stream_id, _dptr(beta), _dptr(betainv),
                                                      _dptr(out), _dptr(planes) if planes is not None else None),
                  "ssnet_reduce_truncate_relu")
+        return out, planes
+
+    def reduce_truncate_relu_direct(self, c: Optional[torch.Tensor], beta: torch.Tensor, betainv: torch.Tensor,
+                                    out: Optional[torch.Tensor] = None, planes: Optional[torch.Tensor] = None,
+                                    want_planes: bool = False):
+        """the outputs of reduce_truncate_relu (shares, limb planes) in one pass without messages"""
+        cp, c = self._incoming(c, out)
+        B, C = c.shape[1], c.shape[2]
+        HW = c[0, 0, 0].numel()
+        if beta.numel() != c.numel() or betainv.numel() != c.numel():
+            raise SSNetError(EINVAL, "reduce_truncate_relu_direct: mask shares must have the shape of c")
+        if out is None:
+            out = torch.empty_like(c)
+        if want_planes and planes is None:
+            planes = self._planes_buffer(B, C, HW, 1, None, c.device)
+        self._ok(self.lib.ssnet_reduce_truncate_relu_direct(self._ctx, cp, B, C, HW, _dptr(beta), _dptr(betainv), _dptr(out),
+                                                            _dptr(planes) if planes is not None else None),
+                 "ssnet_reduce_truncate_relu_direct")
         return out, planes
 
     def nonlinear_masks(self, shape, stream_id: int, device=None):

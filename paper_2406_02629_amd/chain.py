@@ -250,7 +250,7 @@ class Chain:
             self.x_planes = torch.empty(need, dtype=torch.uint8, device=self.x_planes.device)
 
     def secure_layer(self, l: int, x_plain: Optional[torch.Tensor], x_shares: Optional[torch.Tensor],
-                     planes_ready: bool = False):
+                     planes_ready: bool = False, direct: bool = False):
         """Layer l from its plain input (shared here) or from the previous layer's output shares
         (planes_ready: their limb planes already are in self.x_planes).
         -> (output shares after the activation, or None; opened result, or None)"""
@@ -280,7 +280,10 @@ class Chain:
             # reduce + truncate + ReLU in one launch, which also leaves the next layer's limb planes
             b, bi = self.masks[l]
             nxt = l + 1 < len(self.layers) and self.sec_planes[l + 1]
-            ss.reduce_truncate_relu(None if pending else y, l, b, bi, out=y, planes=self.x_planes if nxt else None)
+            if direct:   # the same shares and planes in one pass without the protocol's messages
+                ss.reduce_truncate_relu_direct(None if pending else y, b, bi, out=y, planes=self.x_planes if nxt else None)
+            else:
+                ss.reduce_truncate_relu(None if pending else y, l, b, bi, out=y, planes=self.x_planes if nxt else None)
             return y, None
         if self.pooled[l] is not None:
             # reduce + truncate (with the division of an average), then ReLU and pooling under the mask
@@ -315,8 +318,10 @@ class Chain:
                 x_plain = fx.from_signed(post_plain(fx.lift(out, self.ss.p), L), self.ss.p)
         return out
 
-    def secure_timed(self):
-        """The share arithmetic of the whole stack, layer feeding layer."""
+    def secure_timed(self, direct: bool = False):
+        """The share arithmetic of the whole stack, layer feeding layer.  direct: the tails of the layers with
+        a plain ReLU in their one-pass form without messages (same shares)."""
         x_shares = None
         for l in range(len(self.layers)):
-            x_shares, _ = self.secure_layer(l, self.secure_plain[l], x_shares, planes_ready=self._planes_ready(l, x_shares))
+            x_shares, _ = self.secure_layer(l, self.secure_plain[l], x_shares,
+                                            planes_ready=self._planes_ready(l, x_shares), direct=direct)

@@ -520,7 +520,6 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
     int st = 0;
     // (worked out while the first unit is on its way)
     const int zero_cut = g.slots > 1 ? zero_planes_of_cut_tile(g, u1, slot, G) : 0;
-    bool stores_in_flight = false;   // the last thing issued were a part's stores, behind a wait for all loads
 
     unsigned u = u0;
     while (u < u1) {
@@ -540,10 +539,7 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
         const int kb_end = min(g.Kb, kb + (int)(u1 - u));
         wave_src next_src = src;
         for (; kb < kb_end; kb++, u++) {
-            // vmcnt(0): this wave's part of the unit is in LDS.  Right after a part's stores that is known
-            // already, and waiting here would wait for the stores (the counter counts them too).
-            if (!stores_in_flight) __builtin_amdgcn_s_waitcnt(0x0F70);
-            stores_in_flight = false;
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of the unit is in LDS
             __syncthreads();                      // everyone's part is; stage st^1 is no longer read
             // first the LDS reads of this unit's first half, then the copies of the next unit: right behind
             // the barrier both waves of a SIMD are reading and the MFMA pipe idles, so that stretch is kept short
@@ -615,11 +611,6 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
             }
         }
         const int nzero = (g.slots > 1 && kb_first == 0) ? (kb_end == g.Kb ? g.slots - 1 : zero_cut) : 0;
-        // The stores go out behind a wait for the loads of the next unit, which were issued a unit ago, so
-        // that the loop can go on without waiting for them: stores issued just before the loop's own wait
-        // would put a full trip to memory on the workgroup's critical path at every part.
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        stores_in_flight = true;
         u64 *o = g.out + (size_t)myplane * g.part_stride;
 #pragma unroll
         for (int h = 0; h < 2; h++)

@@ -112,6 +112,12 @@ hipError_t ss_launch_layer_tail(const u64 *c, u64 *msg1, u64 *msg2, u64 *umsg, u
                                 const ss_dr_params &dp, const ss_tr_params &tp, const ss_nl_params &np,
                                 const ss_part_src &ps, hipStream_t stream);
 
+// the tail's outputs (shares and, planes != nullptr, limb planes) taken directly from the secret: no messages;
+// open_all carries the multipliers of REC from the IDs 1..2t+1, tp those of the IDs 1..k; any scheme
+hipError_t ss_launch_tail_direct(const u64 *c, const u64 *sh_b, const u64 *sh_bi, u64 *out, void *planes, int B, int C,
+                                 int HW, const ss_nl_params &open_all, const ss_tr_params &tp, const ss_part_src &ps,
+                                 hipStream_t stream);
+
 // ---- int8-limb MFMA family (gemm_kernels.hip) ----
 // Packed operand: int8 tiles [row block of 16][k block of 64][limb 0..7][lane 0..63][16 bytes];
 // byte b of lane l is limb `limb` of element (row = 16*rb + l%16, k = 64*kb + 16*(l/16) + b).

@@ -1025,6 +1025,29 @@ int ssnet_reduce_truncate_relu(ssnet_ctx *ctx, const uint64_t *d_c, int B, int C
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
 
+int ssnet_reduce_truncate_relu_direct(ssnet_ctx *ctx, const uint64_t *d_c, int B, int C, int HW, const uint64_t *d_beta,
+                                      const uint64_t *d_betainv, uint64_t *d_out, void *d_planes)
+{
+    if (!ctx || !d_beta || !d_betainv || !d_out || B < 1 || C < 1 || HW < 1) return SSNET_EINVAL;
+    if ((long)B * HW >= (1L << 30) || (size_t)B * C * HW > MAX_COUNT) return SSNET_EINVAL;
+    if (d_planes && (((uintptr_t)d_planes & 15) || C % 64 != 0)) return SSNET_EINVAL;
+    const size_t count = (size_t)B * C * HW;
+    const u64 *c;
+    ss_part_src ps;
+    if (d_c) {
+        c = d_c;
+        ps = {1, 0};
+    } else if (int rc = incoming_product(ctx, nullptr, count, 0, &c, &ps)) {
+        return rc;
+    }
+    ss_nl_params open_all;
+    if (!make_nl_params(ctx, 0, &open_all)) return SSNET_EINVAL;
+    timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
+    hipError_t e = ss_launch_tail_direct(c, d_beta, d_betainv, d_out, d_planes, B, C, HW, open_all, make_tr_params(ctx, 0),
+                                         ps, ctx->stream);
+    return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
+}
+
 int ssnet_nonlinear_masks(ssnet_ctx *ctx, size_t count, uint64_t stream_id, uint64_t *d_beta, uint64_t *d_betainv)
 {
     if (!ctx || !d_beta || !d_betainv || count == 0 || count > MAX_COUNT) return SSNET_EINVAL;

@@ -592,6 +592,71 @@ __global__ __launch_bounds__(BLOCK) void layer_tail_kernel(const u64 *c, u64 *__
     store_staged_planes<N>(stage, planes, party_bytes, count, blockIdx.x * 16, B * HW, C, blockIdx.y * 16, N);
 }
 
+// The outputs of the layer tail without the protocol (all parties on one device): as for
+// reduce_truncate_direct_kernel, what the parties end up with follows from the secret of the incoming
+// degree-2t sharing.  x = REC of the 2t+1 product shares; the truncated value is floor(x / 2^f) on the signed
+// value whatever the mask was; the elite party of the ReLU sees floor(x / 2^f) * beta, beta = REC of its k
+// shares; every party's output is max(., 0) times its share of beta^-1.  Same residues in `out` and in the limb
+// planes as layer_tail_kernel; no message is formed.  Lanes as in that kernel (pixel l%16, channel 4 g + l/16),
+// so that the planes leave through the same staged 16-byte stores.
+__global__ __launch_bounds__(BLOCK) void tail_direct_kernel(const u64 *c, const u64 *__restrict__ sh_b,
+                                                            const u64 *__restrict__ sh_bi, u64 *out,
+                                                            signed char *__restrict__ planes, int B, int C, int HW,
+                                                            size_t party_bytes, ss_nl_params open_all, ss_tr_params tp,
+                                                            ss_part_src ps)
+{
+    const int lane = threadIdx.x & 63, r16 = lane & 15, j = lane >> 4;
+    const int pix = blockIdx.x * 16 + r16, c0 = blockIdx.y * 16 + 4 * (threadIdx.x >> 6);
+    const size_t count = (size_t)B * HW * C;
+    const int n = tp.n, k = tp.t + 1, nr = 2 * tp.t + 1;
+    if (planes && blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x < n)
+        *reinterpret_cast<int4 *>(planes + threadIdx.x * party_bytes + SS_NLIMB * count) = make_int4(0, 0, 0, 0);
+    u64 dig[SS_MAXN];
+#pragma unroll
+    for (int p = 0; p < SS_MAXN; p++) dig[p] = 0;
+    if (pix < B * HW && c0 + j < C) {
+        const int b = pix / HW, hw = pix - b * HW;
+        const size_t e = ((size_t)b * C + (c0 + j)) * HW + hw;
+        ss_sacc acc, bacc;
+        acc.clear();
+        bacc.clear();
+#pragma unroll
+        for (int i = 0; i < 2 * SS_MAXT + 1; i++)
+            if (i < nr) acc.mac(load_product(c, (size_t)i * count + e, ps), open_all.ilambda[i]);
+#pragma unroll
+        for (int q = 0; q < SS_MAXK; q++)
+            if (q < k) bacc.mac(sh_b[(size_t)q * count + e], tp.ilambda[q]);
+        const u64 x = open_all.dinv == 1 ? acc.value() : ss_mul(acc.value(), open_all.dinv);
+        const u64 v = ss_mul(shift_signed(x, tp.f), bacc.value());   // the multipliers of IDs 1..k are integers
+        const u64 y = v <= (SS_P - 1) / 2 ? v : 0;
+#pragma unroll
+        for (int m = 0; m < SS_MAXN; m++) {
+            if (m < n) {
+                const u64 r = ss_mul(y, sh_bi[(size_t)m * count + e]);
+                out[(size_t)m * count + e] = r;
+                dig[m] = balanced_digits(r);
+            }
+        }
+    }
+    if (!planes) return;   // uniform
+    __shared__ __align__(16) u32 stage[SS_MAXN][SS_NLIMB][16][4];   // [party][limb][pixel][wave]
+    const int w = threadIdx.x >> 6;
+#pragma unroll
+    for (int p = 0; p < SS_MAXN; p++) {
+        if (p < n) {
+            u64 y4[4];
+#pragma unroll
+            for (int q = 0; q < 4; q++) y4[q] = __shfl(dig[p], r16 + 16 * q);
+            if (2 * j < SS_NLIMB) {
+                stage[p][2 * j][r16][w] = limb_dword(y4, 2 * j);
+                stage[p][2 * j + 1][r16][w] = limb_dword(y4, 2 * j + 1);
+            }
+        }
+    }
+    __syncthreads();
+    store_staged_planes<SS_MAXN>(stage, planes, party_bytes, count, blockIdx.x * 16, B * HW, C, blockIdx.y * 16, n);
+}
+
 // Same computation for small tensors, where the serial work of one thread per
 // element leaves most of the chip idle: a workgroup takes 32 elements and eight
 // party lanes per element.  Lane p first plays reducing party p+1 (step 1),
@@ -1108,6 +1173,16 @@ hipError_t ss_launch_reduce_truncate_direct(const u64 *c, u64 *out, u64 *rec, si
                     count >= VEC2_MIN_COUNT;
     auto grid = [&](int vec) { return dim3(blocks_for(count, vec)); };
     SS_DISPATCH_VEC(v2, reduce_truncate_direct_kernel, grid, c, out, rec, count, open_all, tp, rf);
+    return hipGetLastError();
+}
+
+hipError_t ss_launch_tail_direct(const u64 *c, const u64 *sh_b, const u64 *sh_bi, u64 *out, void *planes, int B, int C,
+                                 int HW, const ss_nl_params &open_all, const ss_tr_params &tp, const ss_part_src &ps,
+                                 hipStream_t stream)
+{
+    const dim3 grid((B * HW + 15) / 16, (C + 15) / 16), block(BLOCK);
+    hipLaunchKernelGGL(tail_direct_kernel, grid, block, 0, stream, c, sh_b, sh_bi, out, (signed char *)planes, B, C, HW,
+                       ss_planes_bytes(B, C, HW, 1), open_all, tp, ps);
     return hipGetLastError();
 }
 

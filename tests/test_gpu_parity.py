@@ -431,6 +431,14 @@ def test_layer_tail_in_one_launch(n, t):
             w = orc.share(field_uniform(9 * C * 9, 4).reshape(9, C, 3, 3), n, t, P61, 63, 6)
             y = s.conv_mod_planes(planes, s.pack_weights_conv_taps(to_dev(w)), B, C, H, W, 9, 3, 3, 1, 1)
             assert np.array_equal(to_np(y), orc.conv(want.reshape(n, B, C, H, W), w, 1, 1, P61))
+        # the one-pass form without messages gives the protocol's residues, in place as well
+        d2 = to_dev(c.reshape(n, B, C, H, W))
+        out2, planes2 = s.reduce_truncate_relu_direct(d2, sb, sbi, out=d2, want_planes=(C % 64 == 0))
+        assert np.array_equal(to_np(out2).reshape(n, -1), want)
+        if planes is not None:
+            data = 8 * count + 16
+            per = planes.numel() // n
+            assert bool(torch.equal(planes2.view(n, per)[:, :data], planes.view(n, per)[:, :data]))
 
 
 def test_config1_tiny_secure_gemm_end_to_end():

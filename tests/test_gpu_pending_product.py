@@ -79,6 +79,14 @@ def check_consumers(s, p, y, shape, leave_product, f=12, seed=0):
         ref = s.split_planes(to_dev(want.reshape(n, B, C, H, W)))
         assert bool(torch.equal(planes.view(n, per)[:, :data], ref.view(n, per)[:, :data]))
 
+    # the same tail in one pass without messages: the protocol's residues, shares and planes
+    leave_product()
+    out6 = torch.empty_like(out5)
+    _, planes6 = s.reduce_truncate_relu_direct(None, sb, sbi, out=out6, want_planes=(C % 64 == 0))
+    assert np.array_equal(to_np(out6).reshape(n, -1), want)
+    if planes6 is not None:
+        assert bool(torch.equal(planes6.view(n, per)[:, :data], ref.view(n, per)[:, :data]))
+
 
 CONV_CASES = [
     # B, C, H, W, Co, k, stride, pad

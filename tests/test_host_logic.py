@@ -171,6 +171,9 @@ def test_product_entry_points_check_their_arguments():
     assert lib.ssnet_degree_reduce_truncate(ctx, None, 8, 0, 16) == binding.EINVAL
     assert lib.ssnet_reduce_truncate_direct(ctx, None, 8, 0, 16, None, 0, None) == binding.EINVAL
     assert lib.ssnet_reduce_truncate_relu(ctx, None, 1, 64, 16, 0, 16, 16, 16, None) == binding.EINVAL
+    assert lib.ssnet_reduce_truncate_relu_direct(ctx, None, 1, 64, 16, 16, 16, 16, None) == binding.EINVAL
+    assert lib.ssnet_reduce_truncate_relu_direct(ctx, 16, 1, 32, 16, 16, 16, 16, 16) == binding.EINVAL    # planes need C % 64 == 0
+    assert lib.ssnet_reduce_truncate_relu_direct(ctx, 16, 1, 64, 16, None, 16, 16, None) == binding.EINVAL
 
 
 def test_pooling_entry_points_check_their_arguments():

@@ -99,6 +99,46 @@ def test_generator_core_is_splitmix64():
     assert [orc.draw(0, e) for e in range(3)] == want
 
 
+def test_generator_second_published_stream():
+    """draw(key, e) is output e of the SplitMix64 stream started at state `key`: checked on the published
+    vector for state 1234567, so the counter stepping and the key entering as the state are pinned too."""
+    want = [int(l) for l in open(os.path.join(GOLD, "splitmix64.txt")) if l.strip().isdigit()]
+    assert len(want) == 5 and [orc.draw(1234567, e) for e in range(5)] == want
+
+
+def test_key_is_a_chain_of_first_outputs_and_field_draw_is_the_top_bits():
+    """The key absorbs its five words one by one, h <- first output of the stream at state (h ^ word), from
+    h = 0 (draw(s, 0) is that first output, pinned above); the field element is (draw >> 3) mod p."""
+    for words in [(0, 1, 0, 0, 1), (7, 2, 151, 3, 2), (2 ** 64 - 1, 10, 2 ** 40, 5, 0)]:
+        h = 0
+        for w in words:
+            h = orc.draw(h ^ w, 0)
+        assert orc.key(*words) == h
+    k = orc.key(5, orc.DOM_ZERO, 9, 0, 2)
+    for e in (0, 1, 2 ** 33 + 5):
+        for p in (P61, P45, 11, 97):
+            assert orc.draw_field(k, e, p) == (orc.draw(k, e) >> 3) % p
+
+
+def test_oracle_generator_matches_the_golden_vectors():
+    """tests/golden/rng_vectors.txt pins both implementations of the generator: the library's host code
+    (tests/test_host_logic.py) and, here, the oracle that wrote it."""
+    nkeys = ndraws = 0
+    for line in open(os.path.join(GOLD, "rng_vectors.txt")):
+        parts = line.split()
+        if not parts or parts[0].startswith("#"):
+            continue
+        if parts[0] == "key":
+            vals = [int(v) for v in parts[1:]]
+            assert orc.key(*vals[:5]) == vals[5]
+            nkeys += 1
+        else:
+            key, e, out, fld = (int(v) for v in parts[1:])
+            assert orc.draw(key, e) == out and orc.draw_field(key, e, P61) == fld
+            ndraws += 1
+    assert nkeys == 8 and ndraws == 32
+
+
 def test_keys_separate_streams_and_field_range():
     keys = {orc.key(s, d, sid, pty, j) for s in (0, 1) for d in range(1, 8) for sid in (0, 1, 2)
             for pty in range(0, 6) for j in range(0, 3)}
