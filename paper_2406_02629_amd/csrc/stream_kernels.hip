@@ -21,6 +21,7 @@ struct pack_t<1> {
     u64 v[1];
     __device__ __forceinline__ void load(const u64 *p) { v[0] = *p; }
     __device__ __forceinline__ void store(u64 *p) const { *p = v[0]; }
+    __device__ __forceinline__ void store_streaming(u64 *p) const { __builtin_nontemporal_store(v[0], p); }
 };
 template <>
 struct pack_t<2> {
@@ -37,6 +38,13 @@ struct pack_t<2> {
         q.x = v[0];
         q.y = v[1];
         *reinterpret_cast<ulonglong2 *>(p) = q;
+    }
+    // for output that nothing in the same launch reads again
+    __device__ __forceinline__ void store_streaming(u64 *p) const
+    {
+        typedef unsigned long long v2u __attribute__((ext_vector_type(2)));
+        v2u q = {v[0], v[1]};
+        __builtin_nontemporal_store(q, reinterpret_cast<v2u *>(p));
     }
 };
 
@@ -81,7 +89,7 @@ __global__ __launch_bounds__(BLOCK) void share_kernel(const u64 *__restrict__ se
             pack_t<VEC> s;
 #pragma unroll
             for (int u = 0; u < VEC; u++) s.v[u] = ss_poly_eval<MAXD>(a0.v[u], c[u], degree, i);
-            s.store(shares + (size_t)(i - 1) * count + e0);
+            s.store_streaming(shares + (size_t)(i - 1) * count + e0);   // five planes written, none read again
         }
     }
 }
