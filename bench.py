@@ -13,6 +13,15 @@ Prints ONE JSON line: throughput in field multiply-accumulates per second over
 all parties, the roofline of the dominant kernel (the MFMA GEMM), the bulk
 share/reconstruct roofline (2^28 elements, HBM-bound) and the CPU oracle timed
 on a bounded sample of the same workload.
+
+--legs selects what runs beside the headline step (default: everything), so
+that a profiler run can cover one workload at a time:
+  chain   the headline step                        shapes  product kernel per layer shape
+  direct  step with the no-message shortcuts       secure  ReLU (and pooling) on shares
+  batch8  the same stack at batch 8                p45     passes over the prime 2^45 - 55
+  bulk    configs[1], 2^28 elements                conv    configs[2], one conv layer
+  stream  reduction / ReLU at 2^24 elements        peaks   measured copy / MFMA ceilings
+  cpu     the oracle on the host cores             copycal one 1 GiB device copy (counter scaling)
 """
 import argparse
 import json
@@ -103,9 +112,12 @@ def bulk_streaming_steps(log2_count, reps):
     torch.cuda.synchronize()
     t_relu = event_ms(lambda: ss.relu(x, b, bi, out=out), stream, reps)
     b_relu = (3 * nr + nr + 1 + 3 * n) * 8 * count
+    m_red = (n + (2 * t + 1) * k + k * n + k + n + n + 1) * 8 * count   # shares in, messages out once, shares + opened value out
     res = {"workload": f"n=5 t=2, 2^{log2_count} elements",
            "degree_reduce+truncate+reconstruct": {"ms": t_red, "GB/s": b_red / t_red / 1e6,
-                                                  "bytes_per_element": b_red // count},
+                                                  "bytes_per_element": b_red // count,
+                                                  "moved_GB/s": m_red / t_red / 1e6,
+                                                  "moved_bytes_per_element": m_red // count},
            "relu": {"ms": t_relu, "GB/s": b_relu / t_relu / 1e6, "bytes_per_element": b_relu // count},
            "bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     del c, out, rec, x, b, bi
@@ -179,18 +191,67 @@ def cpu_baseline(nlayers):
                       f"in {secs:.1f} s (OpenMP over output rows / elements)"}
 
 
+TRAFFIC_SUMMARY = os.path.join("profiles", "resnet152_chain_pmc_traffic.txt")
+
+
 def measured_traffic_bytes(kernel):
     """HBM bytes per launch of `kernel` (fetch + write, scaled) from the committed summary of the
-    rocprofv3 --pmc runs of this same benchmark; None if the summary is not there."""
-    path = os.path.join(ROOT, "profiles", "bench_resnet152_chain_pmc_traffic.txt")
+    rocprofv3 --pmc runs of this benchmark's headline leg; None if the summary is not there."""
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, TRAFFIC_SUMMARY)):
             parts = line.split()
             if parts and parts[0] == kernel and len(parts) >= 5:
                 return float(parts[-1]) * 1024 * 1024
     except OSError:
         pass
     return None
+
+
+def stats(xs):
+    xs = sorted(xs)
+    return {"median": xs[len(xs) // 2] if len(xs) % 2 else 0.5 * (xs[len(xs) // 2 - 1] + xs[len(xs) // 2]),
+            "min": xs[0], "max": xs[-1], "n": len(xs)}
+
+
+def timed_steps(step, steps, warmup):
+    """EXACTLY `steps` passes of step() bracketed by synchronize -> (wall ms per step, per-step HIP-event ms)"""
+    import torch
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        step()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev[0].record(stream)
+    for i in range(steps):
+        step()
+        ev[i + 1].record(stream)
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    return wall, [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
+
+
+def profiled_passes(ss, step, passes=5):
+    """per kernel class: median over `passes` passes of the summed HIP-event time of its launches (ms), and the
+    launches per pass"""
+    per = {}
+    for _ in range(passes):
+        ss.profile_begin()
+        step()
+        for k, v in ss.profile_end().items():
+            if v[1]:
+                per.setdefault(k, []).append(v)
+    return {k: (stats([x[0] for x in v])["median"], int(v[0][1])) for k, v in per.items()}
+
+
+def measured_peaks():
+    """what this GPU reaches on a plain device copy, on the write pattern of GEN (one plane read, five written)
+    and on a register-resident int8 MFMA loop: the ceilings the published peaks are to be read against"""
+    from paper_2406_02629_amd import binding
+    return {"copy_GBps": binding.probe_planes(1 << 30, 1), "gen_pattern_1_read_5_writes_GBps": binding.probe_planes(1 << 28, 5),
+            "mfma_int8_TOPs_random_operands": binding.probe_mfma_int8(True),
+            "mfma_int8_TOPs_constant_operands": binding.probe_mfma_int8(False),
+            "kernels": "ssnet_probe_planes, ssnet_probe_mfma_int8 (csrc/probes.hip)"}
 
 
 def secure_chain(chain, ss, steps, warmup, macs, out_elems, pool_on_shares=False):
@@ -201,22 +262,13 @@ def secure_chain(chain, ss, steps, warmup, macs, out_elems, pool_on_shares=False
     import torch
     chain.secure_prepare(pool_on_shares)
     torch.cuda.synchronize()
-    for _ in range(warmup):
-        chain.secure_timed()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        chain.secure_timed()
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / steps
-    ss.profile_begin()
-    chain.secure_timed()
-    prof = ss.profile_end()
+    ms, _ = timed_steps(chain.secure_timed, steps, warmup)
+    prof = profiled_passes(ss, chain.secure_timed, 3)
     relu_elems = sum(L.cout * L.M for L in chain.layers if L.post == "relu")
     opened = "the logits" if pool_on_shares else "the max-pool, the global average and the logits"
     return {"workload": "same stack, Linear - Truncation - NonLinear per layer on shares; opened only at " + opened,
             "ms_per_step": ms, "field_MAC_per_s": macs / (ms * 1e-3),
-            "kernel_ms_per_step": {k: {"ms": round(v[0], 4), "spans": int(v[1])} for k, v in prof.items() if v[1]},
+            "kernel_ms_per_step": {k: {"ms": round(v[0], 4), "spans": v[1]} for k, v in prof.items()},
             # the ReLU of the plain layers runs inside the layer tail (class degree_reduce); class nonlinear
             # holds the two ReLU + pooling calls
             "relu_elements_per_step": relu_elems}
@@ -233,26 +285,17 @@ def p45_chain(layers, steps, warmup, batch=1):
     chain = Chain(ss, layers, batch=batch)
     chain.forward_prepare()
     torch.cuda.synchronize()
-    for _ in range(warmup):
-        chain.forward_timed()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        chain.forward_timed()
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / steps
-    ss.profile_begin()
-    chain.forward_timed()
-    prof = ss.profile_end()
+    ms, _ = timed_steps(chain.forward_timed, steps, warmup)
+    prof = profiled_passes(ss, chain.forward_timed, 3)
     macs = chain.total_field_macs()
     ops = macs * 2 * 36
     gemm_ms, gemm_launches = prof["gemm"]
     return {"workload": f"headline stack over p = 2^45 - 55 (libssnet_p45.so), n=5 t=2 f=13 batch {batch}",
             "ms_per_step": ms, "field_MAC_per_s": macs / (ms * 1e-3),
-            "kernel_ms_per_step": {k: {"ms": round(v[0], 4), "spans": int(v[1])} for k, v in prof.items() if v[1]},
+            "kernel_ms_per_step": {k: {"ms": round(v[0], 4), "spans": v[1]} for k, v in prof.items()},
             "roofline": {"bound": "mfma", "kernel": "gemm_limb_kernel (6 limbs)", "achieved": ops / (gemm_ms * 1e-3) / 1e12,
                          "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": ops / (gemm_ms * 1e-3) / 1e12 / INT8_PEAK_TOPS,
-                         "launches": int(gemm_launches), "int8_ops_per_step": ops}}
+                         "launches": gemm_launches, "int8_ops_per_step": ops}}
 
 
 def gemm_by_shape(chain, ss, reps=20):
@@ -266,11 +309,11 @@ def gemm_by_shape(chain, ss, reps=20):
         seen.setdefault((L.M * chain.batch, L.K, L.N, L.ksize), []).append(l)
     for (M, K, N, ksize), ls in seen.items():
         l = ls[0]
-        chain.run_layer(l, chain.x_plain[l], "sg")
+        chain.run_layer(l, chain.x_plain[l], "sgp")
         torch.cuda.synchronize()
         ss.profile_begin()
         for _ in range(reps):
-            chain.run_layer(l, chain.x_plain[l], "sg")
+            chain.run_layer(l, chain.x_plain[l], "sgp")
         prof = ss.profile_end()
         us = prof["gemm"][0] * 1e3 / prof["gemm"][1]
         ops = ss.n * M * K * N * OPS_PER_FIELD_MAC
@@ -287,31 +330,20 @@ def gemm_by_shape(chain, ss, reps=20):
 def paper_setting_3pc(steps, warmup):
     """The setting of the paper's main table: three parties ((2,3) scheme), its prime 2^45 - 55, batch 1, the whole
     inference on shares (Linear - Truncation - NonLinear per layer, pooling on shares, only the logits opened), for
-    the ResNet-50 / 101 / 152 main-path stacks and stacks shaped like the paper's other model families.  Compute
+    the ResNet-50 / 101 / 152 main-path stacks.  Compute
     of all three parties on this one GPU, no network."""
     import torch
     from paper_2406_02629_amd import P45, SSNet
     from paper_2406_02629_amd.chain import Chain
     from ssnet_inputs import resnet_chain
-    from ssnet_inputs import alexnet_chain, lenet_chain, resnet_basic_chain, vgg16_chain
     out = {"workload": "n=3 t=1, p = 2^45 - 55, f=12, batch 1, ReLU and pooling on shares; ms per inference"}
-    stacks = [("resnet50", resnet_chain(50)), ("resnet101", resnet_chain(101)), ("resnet152", resnet_chain(152)),
-              ("resnet18", resnet_basic_chain(18)), ("vgg16_32x32", vgg16_chain(32, 10, 512)),
-              ("vgg16_64x64", vgg16_chain(64, 200, 512)), ("alexnet_227x227", alexnet_chain(227, 1000, 4096)),
-              ("lenet_28x28", lenet_chain())]
+    stacks = [("resnet50", resnet_chain(50)), ("resnet101", resnet_chain(101)), ("resnet152", resnet_chain(152))]
     for name, stack in stacks:
         ss = SSNet(3, 1, f=12, seed=20240602, p=P45)
         chain = Chain(ss, stack)
         chain.secure_prepare(True)
         torch.cuda.synchronize()
-        for _ in range(warmup):
-            chain.secure_timed()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            chain.secure_timed()
-        torch.cuda.synchronize()
-        out[f"{name}_ms"] = (time.perf_counter() - t0) * 1e3 / steps
+        out[f"{name}_ms"] = timed_steps(chain.secure_timed, steps, warmup)[0]
         del chain, ss
         torch.cuda.empty_cache()
     return out
@@ -325,23 +357,14 @@ def batch8_chain(chain, ss, layers, steps, warmup, secure=True):
     c8 = Chain(ss, layers, batch=8, weights_of=chain)
     c8.forward_prepare()
     torch.cuda.synchronize()
-    for _ in range(warmup):
-        c8.forward_timed()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        c8.forward_timed()
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / steps
-    ss.profile_begin()
-    c8.forward_timed()
-    prof = ss.profile_end()
+    ms, _ = timed_steps(c8.forward_timed, steps, warmup)
+    prof = profiled_passes(ss, c8.forward_timed, 3)
     macs = c8.total_field_macs()
     gemm_ms = prof["gemm"][0]
     res = {"workload": "same stack and weights, batch 8", "ms_per_step": ms, "field_MAC_per_s": macs / (ms * 1e-3),
            "gemm": {"ms": gemm_ms, "TOP/s": macs * OPS_PER_FIELD_MAC / (gemm_ms * 1e-3) / 1e12,
                     "frac": macs * OPS_PER_FIELD_MAC / (gemm_ms * 1e-3) / 1e12 / INT8_PEAK_TOPS},
-           "kernel_ms_per_step": {k: {"ms": round(v[0], 4), "spans": int(v[1])} for k, v in prof.items() if v[1]}}
+           "kernel_ms_per_step": {k: {"ms": round(v[0], 4), "spans": v[1]} for k, v in prof.items()}}
     if secure:
         # the eight images with ReLU and pooling on shares, only the logits opened
         sec = secure_chain(c8, ss, steps, warmup, macs, 0, pool_on_shares=True)
@@ -352,6 +375,56 @@ def batch8_chain(chain, ss, layers, steps, warmup, secure=True):
     return res
 
 
+LEGS = ("chain", "direct", "secure", "shapes", "batch8", "p45", "bulk", "conv", "stream", "peaks", "cpu", "copycal")
+
+
+def chain_stream_bytes(chain, ss):
+    """Bytes of the two streaming passes of one headline step.  Algorithmic: GEN reads an element and writes n
+    shares; reduction + re-randomisation + truncation + opening read the n product shares, exchange every
+    message once each way and write the n shares and the opened value.  Moved: what the launches really read
+    and write: GEN also leaves the limb tiles / planes for the product kernel; the reduction reads the product
+    as the planes its kernel left (one per workgroup that had a part in a tile), writes every message once and
+    reads none back (one thread plays every party of its element)."""
+    n, k, t = ss.n, ss.k, ss.t
+    share_alg = share_moved = red_alg = red_moved = 0
+    for l, L in enumerate(chain.layers):
+        cin = chain.batch * L.cin * (L.hin * L.hin if L.kind == "conv" else 1)
+        cout = chain.batch * L.cout * L.M
+        share_alg += (1 + n) * 8 * cin
+        share_moved += (1 + 2 * n) * 8 * cin if (chain.pointwise[l] or chain.on_planes[l]) else (1 + n) * 8 * cin
+        if L.kind == "conv":
+            pb = ss.lib.ssnet_product_bytes_conv(ss._ctx, chain.batch, L.cin, L.hin, L.hin, L.cout, L.ksize, L.ksize,
+                                                 L.stride, L.pad)
+        else:
+            pb = ss.lib.ssnet_product_bytes_linear(ss._ctx, chain.batch, L.cin, L.cout)
+        planes = max(1, round(pb / (n * cout * 8)))
+        per_elem = n * ((1 + k) + 2 * k + (k + 1)) + (3 * k + 3 * n) + (k + 1)
+        red_alg += per_elem * 8 * cout
+        # the launch keeps the messages in registers for its own use and writes each once for the receiver
+        red_moved += (n * planes + (2 * t + 1) * k + k * n + k + n + n + 1) * 8 * cout
+    return {"share": (share_alg, share_moved), "degree_reduce": (red_alg, red_moved)}
+
+
+def cpu_baselines(nlayers):
+    """the oracle on every host core this process may use, and on one (a third of the sample: it is ~cores times
+    slower); the thread count is set through the OpenMP runtime the oracle's library already uses"""
+    import ctypes
+    res = cpu_baseline(nlayers)
+    try:
+        gomp = ctypes.CDLL("libgomp.so.1")
+        gomp.omp_get_max_threads.restype = ctypes.c_int
+        had = gomp.omp_get_max_threads()
+        gomp.omp_set_num_threads(1)
+        one = cpu_baseline(max(nlayers // 8, 4))
+        gomp.omp_set_num_threads(had)
+        res["cores"] = had
+        one["cores"] = 1
+        res["single_thread"] = one
+    except OSError:
+        pass
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -359,19 +432,16 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--depth", type=int, default=152, help="ResNet depth of the stack (152 is the benchmark)")
     ap.add_argument("--bulk-log2", type=int, default=28)
-    ap.add_argument("--no-bulk", action="store_true")
-    ap.add_argument("--no-cpu", action="store_true")
-    ap.add_argument("--no-secure", action="store_true", help="skip the pass with ReLU on shares")
-    ap.add_argument("--no-batch8", action="store_true", help="skip the batch-8 pass of the same stack")
-    ap.add_argument("--no-p45", action="store_true", help="skip the passes over the prime 2^45 - 55")
-    ap.add_argument("--no-shapes", action="store_true", help="skip the per-shape timing of the product kernel")
+    ap.add_argument("--legs", default="all", help="comma-separated subset of: " + ", ".join(LEGS) +
+                    " (all = everything but copycal)")
     ap.add_argument("--cpu-layers", type=int, default=152)
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run one 1 GiB device copy (a kernel of known traffic, to scale profiler counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (all parties are a batch dimension on it); "
                  "use --gpus 1")
+    legs = set(LEGS) - {"copycal"} if args.legs == "all" else set(x for x in args.legs.split(",") if x)
+    if legs - set(LEGS):
+        sys.exit("bench.py: unknown leg(s) " + ", ".join(sorted(legs - set(LEGS))))
 
     import torch
     from paper_2406_02629_amd import SSNet
@@ -383,90 +453,98 @@ def main():
     n, t, f = 5, 2, 13
     ss = SSNet(n, t, f=f, seed=20240602)
     layers = resnet_chain(args.depth)
-    chain = Chain(ss, layers)
-    chain.forward_prepare()
-    torch.cuda.synchronize()
-    for _ in range(args.warmup):
-        chain.forward_timed()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        chain.forward_timed()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    macs = chain.total_field_macs()
+    chain = None
+    result = {"metric": METRIC, "value": None, "unit": "field-MAC/s", "n_gpus": 1, "data": "synthetic",
+              "note": "headline leg not selected: only the legs asked for ran"}
+    if legs & {"chain", "direct", "secure", "shapes", "batch8"}:
+        chain = Chain(ss, layers)
+        chain.forward_prepare()
+        torch.cuda.synchronize()
+        ms_per_step, per_step = timed_steps(chain.forward_timed, args.steps, args.warmup)
+        macs = chain.total_field_macs()
 
-    # live per-class kernel time over one more pass (HIP events on the library's stream)
-    ss.profile_begin()
-    chain.forward_timed()
-    prof = ss.profile_end()
-    gemm_ms, gemm_launches = prof["gemm"]
-    achieved = macs * OPS_PER_FIELD_MAC / (gemm_ms * 1e-3) / 1e12
-    breakdown = {k: {"ms": round(v[0], 4), "spans": int(v[1])} for k, v in prof.items() if v[1]}
-
-    out_elems = sum(L.cout * L.M for L in chain.layers)
-    dr_bytes = n * ((1 + ss.k) + 2 * ss.k + (ss.k + 1)) * 8 * out_elems      # three passes, messages once each way
-    tr_bytes = (3 * ss.k + 3 * n) * 8 * out_elems
-    result = {
-        "metric": METRIC, "value": macs / (ms_per_step * 1e-3), "unit": "field-MAC/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "u64 mod 2^61-1 (int8 limbs, int32 MFMA accumulate)",
-        "data": "synthetic",
-        "config": {"workload": f"resnet{args.depth}-shaped linear stack, n=5 t=2 f=13 batch 1 (configs[4])",
-                   "layers": len(chain.layers), "field_macs_per_step": macs,
-                   "steps_in_timed_region": "share (+limb split for dense/1x1 layers), conv/dense, "
-                                            "degree_reduce+rerand+truncate+reconstruct (one launch)"},
-        "roofline": {"bound": "mfma", "kernel": "gemm_limb_kernel", "achieved": achieved, "peak": INT8_PEAK_TOPS,
-                     "unit": "TOP/s", "frac": achieved / INT8_PEAK_TOPS,
-                     "traffic": measured_traffic_bytes("gemm_limb_kernel"), "traffic_unit": "bytes per launch (HBM)",
-                     "launches": int(gemm_launches), "avg_launch_us": gemm_ms * 1e3 / max(gemm_launches, 1),
-                     "int8_ops_per_step": macs * OPS_PER_FIELD_MAC},
-        "kernel_ms_per_step": breakdown,
-        # the chain calls ssnet_degree_reduce_truncate_reconstruct: the three protocols' algorithmic bytes over
-        # one launch per layer
-        "stream_GBps_in_chain": {
-            "degree_reduce+truncate+reconstruct":
-                (dr_bytes + tr_bytes + (ss.k + 1) * 8 * out_elems) / (prof["degree_reduce"][0] * 1e-3) / 1e9},
-    }
-    if not args.no_secure:
+        # live per-class kernel time (HIP events on the library's stream): median over five more passes
+        prof = profiled_passes(ss, chain.forward_timed)
+        gemm_ms, gemm_launches = prof["gemm"]
+        achieved = macs * OPS_PER_FIELD_MAC / (gemm_ms * 1e-3) / 1e12
+        breakdown = {k: {"ms": round(v[0], 4), "spans": v[1]} for k, v in prof.items()}
+        traffic = measured_traffic_bytes("gemm_limb_kernel")
+        sb = chain_stream_bytes(chain, ss)
+        out_elems = sum(L.cout * L.M for L in chain.layers)
+        result = {
+            "metric": METRIC, "value": macs / (ms_per_step * 1e-3), "unit": "field-MAC/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "u64 mod 2^61-1 (int8 limbs, int32 MFMA accumulate)",
+            "data": "synthetic",
+            "config": {"workload": f"resnet{args.depth}-shaped linear stack, n=5 t=2 f=13 batch 1 (configs[4])",
+                       "layers": len(chain.layers), "field_macs_per_step": macs,
+                       "steps_in_timed_region": "share (+limb split for dense/1x1 layers), conv/dense, "
+                                                "degree_reduce+rerand+truncate+reconstruct (one launch)"},
+            # ms_per_step is wall time over the K steps; these are the same K steps one by one (HIP events)
+            "ms_per_step_events": {k: round(v, 4) if k != "n" else v for k, v in stats(per_step).items()},
+            "roofline": {"bound": "mfma", "kernel": "gemm_limb_kernel (+ gemm_skinny_kernel on the 7x7 maps)",
+                         "achieved": achieved, "peak": INT8_PEAK_TOPS,
+                         "unit": "TOP/s", "frac": achieved / INT8_PEAK_TOPS,
+                         "traffic": traffic, "traffic_unit": "bytes per launch (HBM)",
+                         "traffic_source": TRAFFIC_SUMMARY if traffic is not None else None,
+                         "launches": gemm_launches, "avg_launch_us": gemm_ms * 1e3 / max(gemm_launches, 1),
+                         "int8_ops_per_step": macs * OPS_PER_FIELD_MAC,
+                         "timing": "median over 5 passes of the summed launch durations of class gemm"},
+            "kernel_ms_per_step": breakdown,
+            # algorithmic: the bytes the protocol steps need; moved: with the limb tiles / planes and the product's
+            # planes the launches really read and write
+            "stream_GBps_in_chain": {
+                k: {"ms": round(prof[k][0], 4), "algorithmic_GBps": round(a / (prof[k][0] * 1e-3) / 1e9, 1),
+                    "moved_GBps": round(m / (prof[k][0] * 1e-3) / 1e9, 1), "algorithmic_bytes": a, "moved_bytes": m}
+                for k, (a, m) in sb.items() if k in prof},
+        }
+    if "peaks" in legs:
+        result["peak_measured"] = measured_peaks()
+    if chain is None:
+        legs -= {"direct", "secure", "shapes", "batch8"}
+    if "direct" in legs:
         # same step with the outputs of reduction + truncation + opening taken without the protocol's messages
-        for _ in range(args.warmup):
-            chain.forward_timed("sgD")
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            chain.forward_timed("sgD")
-        torch.cuda.synchronize()
-        ms_direct = (time.perf_counter() - t0) * 1e3 / args.steps
+        ms_direct, _ = timed_steps(lambda: chain.forward_timed("sgD"), args.steps, args.warmup)
         result["cross_party_single_pass"] = {
             "workload": "headline step with ssnet_reduce_truncate_direct in place of the protocol kernels "
                         "(bit-identical outputs, no messages: a simulation shortcut, not the protocol's work)",
             "ms_per_step": ms_direct, "field_MAC_per_s": macs / (ms_direct * 1e-3)}
+    if "secure" in legs:
         result["nonlinear_on_shares"] = secure_chain(chain, ss, args.steps, args.warmup, macs, out_elems)
         result["nonlinear_and_pooling_on_shares"] = secure_chain(chain, ss, args.steps, args.warmup, macs, out_elems,
                                                                  pool_on_shares=True)
-    if not args.no_shapes:
+        if "direct" in legs:
+            ms_sd, _ = timed_steps(lambda: chain.secure_timed(direct=True), args.steps, args.warmup)
+            result["nonlinear_and_pooling_on_shares"]["layer_tails_single_pass"] = {
+                "workload": "the same, every reduce + truncate + ReLU tail by ssnet_reduce_truncate_relu_direct "
+                            "(same shares and limb planes, no messages: a simulation shortcut)",
+                "ms_per_step": ms_sd, "field_MAC_per_s": macs / (ms_sd * 1e-3)}
+    if "shapes" in legs:
         result["gemm_by_shape"] = gemm_by_shape(chain, ss)
-    if not args.no_batch8:
-        result["batch8"] = batch8_chain(chain, ss, layers, max(args.steps // 4, 2), 1, secure=not args.no_secure)
-    if not args.no_p45:
-        if not args.no_secure:
+    if "batch8" in legs:
+        result["batch8"] = batch8_chain(chain, ss, layers, max(args.steps // 4, 2), 1, secure="secure" in legs)
+    if "p45" in legs:
+        if "secure" in legs:
             result["paper_setting_3pc_p45"] = paper_setting_3pc(max(args.steps // 2, 2), 2)
         result["paper_prime_p45"] = p45_chain(layers, args.steps, args.warmup)
-        if not args.no_batch8:
+        if "batch8" in legs:
             result["paper_prime_p45_batch8"] = p45_chain(layers, max(args.steps // 4, 2), 1, batch=8)
-    if args.copy_calibration:
+    del chain
+    torch.cuda.empty_cache()
+    if "copycal" in legs:
         src = torch.zeros(1 << 27, dtype=torch.int64, device="cuda")
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    if not args.no_bulk:
+    if "bulk" in legs:
         result["roofline_hbm"] = bulk_share_reconstruct(args.bulk_log2, reps=5)
+    if "conv" in legs:
         result["roofline_conv_layer"] = conv_layer_roofline(reps=10)
+    if "stream" in legs:
         result["roofline_hbm_other_steps"] = bulk_streaming_steps(24, reps=5)
-    if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(args.cpu_layers)
+    if "cpu" in legs:
+        result["cpu_baseline"] = cpu_baselines(args.cpu_layers)
     print(json.dumps(result))
 
 

@@ -433,6 +433,22 @@ int ssnet_host_reduction_matrix(const ssnet_ctx *ctx, uint64_t *out);
 int ssnet_profile_begin(ssnet_ctx *ctx);
 int ssnet_profile_end(ssnet_ctx *ctx, double *ms_by_class, uint64_t *spans_by_class);
 
+/* Measured ceilings of the machine, for roofline reports beside the published
+ * peaks (bench support, not part of the share arithmetic; each call runs its
+ * kernel reps + 1 times on the stream and waits for it):
+ *   ssnet_probe_planes: `planes` copies of the `bytes` at d_src to d_dst
+ *     (planes * bytes large), 16 bytes per lane, streaming stores: planes = 1 is
+ *     a device copy, planes = n the traffic pattern of GEN (Eq. 1).  Result:
+ *     moved gigabytes, (1 + planes) * bytes per run, per second.
+ *   ssnet_probe_mfma_int8: a register-resident loop of v_mfma_i32_16x16x64_i8, two
+ *     waves per SIMD with the operand and accumulator registers of the product
+ *     kernel, on operand bytes from the generator (random_operands != 0: the clock
+ *     this part holds under MFMA load depends on the data) or on constants.
+ *     Result: int8 tera-operations per second.  d_sink: 4 device bytes. */
+int ssnet_probe_planes(void *hip_stream, void *d_dst, const void *d_src, size_t bytes, int planes, int reps,
+                       double *gb_per_s);
+int ssnet_probe_mfma_int8(void *hip_stream, void *d_sink, int random_operands, int reps, double *tera_ops_per_s);
+
 const char *ssnet_strerror(int code);
 int ssnet_last_hip_error(const ssnet_ctx *ctx); /* hipError_t of the last failed HIP call, 0 if none */
 

@@ -79,6 +79,8 @@ SIGNATURES = {
     "ssnet_host_reduction_matrix": (_int, [_ptr, C.POINTER(_u64)]),
     "ssnet_profile_begin": (_int, [_ptr]),
     "ssnet_profile_end": (_int, [_ptr, C.POINTER(C.c_double), C.POINTER(_u64)]),
+    "ssnet_probe_planes": (_int, [_ptr, _ptr, _ptr, _sz, _int, _int, C.POINTER(C.c_double)]),
+    "ssnet_probe_mfma_int8": (_int, [_ptr, _ptr, _int, _int, C.POINTER(C.c_double)]),
     "ssnet_strerror": (C.c_char_p, [_int]),
     "ssnet_last_hip_error": (_int, [_ptr]),
 }
@@ -623,6 +625,31 @@ class SSNet:
         out = (_u64 * (nr * self.n))()
         self._ok(self.lib.ssnet_host_reduction_matrix(self._ctx, out), "ssnet_host_reduction_matrix")
         return [[out[i * self.n + m] for m in range(self.n)] for i in range(nr)]
+
+
+def probe_planes(nbytes: int, planes: int, reps: int = 5, p: int = P61) -> float:
+    """GB/s moved by `planes` streaming copies of nbytes (1: device copy; n: the traffic of GEN)"""
+    lib = load_library(p)
+    src = torch.zeros(nbytes // 8, dtype=torch.int64, device="cuda")
+    dst = torch.empty(planes * (nbytes // 8), dtype=torch.int64, device="cuda")
+    out = C.c_double()
+    rc = lib.ssnet_probe_planes(_ptr(torch.cuda.current_stream().cuda_stream), _dptr(dst), _dptr(src), nbytes, planes, reps,
+                                C.byref(out))
+    if rc:
+        raise SSNetError(rc, "ssnet_probe_planes")
+    return out.value
+
+
+def probe_mfma_int8(random_operands: bool = True, reps: int = 5, p: int = P61) -> float:
+    """int8 TOP/s of a register-resident MFMA loop (two waves per SIMD)"""
+    lib = load_library(p)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = C.c_double()
+    rc = lib.ssnet_probe_mfma_int8(_ptr(torch.cuda.current_stream().cuda_stream), _dptr(sink), int(random_operands), reps,
+                                   C.byref(out))
+    if rc:
+        raise SSNetError(rc, "ssnet_probe_mfma_int8")
+    return out.value
 
 
 def rng_key(seed, domain, stream_id, party, j) -> int:

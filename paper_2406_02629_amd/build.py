@@ -17,7 +17,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libssnet.so")
 LIB_P45 = os.path.join(HERE, "libssnet_p45.so")
 VARIANTS = {"p61": (LIB, []), "p45": (LIB_P45, ["-DSS_FIELD_P45"])}
-SOURCES = ["stream_kernels.hip", "gemm_kernels.hip", "ssnet_api.hip"]
+SOURCES = ["stream_kernels.hip", "gemm_kernels.hip", "ssnet_api.hip", "probes.hip"]
 HEADERS = ["field.hpp", "kernels.hpp", "eval.hpp", "digits.hpp", os.path.join("..", "..", "include", "ssnet.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
