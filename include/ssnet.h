@@ -252,10 +252,13 @@ int ssnet_truncate(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, uint64_t s
  * into it (Sec. VI-C, extra step for AvgPooling; App. C): shares of
  * [floor(x / 2^f) / kdiv], kdiv = kh*kw of the pooling kernel that follows, so
  * that the pooling itself is a sum.  The mask becomes alpha = e*2^f*kdiv with
- * the same e and the same draws as ssnet_truncate; [.] rounds to the nearest
- * integer, a remainder of ceil(kdiv/2) or more going up, on the signed value.
- * 1 <= kdiv <= SSNET_MAX_KDIV; kdiv = 1 is ssnet_truncate.  Requires
- * |x| + 2^32 * kdiv <= (p-1)/2.  Everything else as ssnet_truncate. */
+ * e uniform in [1, floor(2^(32-f) / kdiv)] (the smaller sample space of
+ * Sec. VII-B, so that alpha stays in (0, 2^32]; the draw is that of
+ * ssnet_truncate, reduced modulo the range instead of masked); [.] rounds to
+ * the nearest integer, a remainder of ceil(kdiv/2) or more going up, on the
+ * signed value.  1 <= kdiv <= min(SSNET_MAX_KDIV, 2^(32-f)), else
+ * SSNET_EINVAL; kdiv = 1 is ssnet_truncate.  Requires |x| + 2^32 <= (p-1)/2,
+ * as ssnet_truncate does.  Everything else as ssnet_truncate. */
 #define SSNET_MAX_KDIV 4096
 int ssnet_truncate_div(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, int kdiv, uint64_t stream_id,
                        uint64_t *d_out);

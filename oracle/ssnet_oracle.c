@@ -634,7 +634,9 @@ void orc_relu(const u64 *x, const u64 *sh_b, const u64 *sh_bi, size_t count, int
 /* Truncation followed by a rounding division (Sec. VI-C, the extra     */
 /* step for average pooling; App. C): y = [ floor(x / 2^f) / kdiv ],    */
 /* kdiv = kh*kw of the pooling kernel that follows.  The mask becomes   */
-/* alpha = e * 2^f * kdiv, alpha~ = -e stays.  [.] rounds to the        */
+/* alpha = e * 2^f * kdiv, alpha~ = -e stays; the sample space of e     */
+/* shrinks to [1, floor(2^(32-f) / kdiv)] so that alpha stays in        */
+/* (0, 2^32] (Sec. VII-B).  [.] rounds to the                           */
 /* nearest integer, a remainder of ceil(kdiv/2) or more going up (the   */
 /* worst case of App. C), i.e. [v/kdiv] = floor((v + floor(kdiv/2)) /   */
 /* kdiv) on the signed value, so that [(v + e*kdiv)/kdiv] = [v/kdiv]+e. */
@@ -692,7 +694,8 @@ void orc_truncate_div_explicit(const u64 *x, const u64 *eval, const u64 *ca, con
     if (!wsh) free(ww);
 }
 
-/* same draws as orc_truncate: e uniform in [1, 2^(32-f)], the three coefficient domains */
+/* same draws as orc_truncate; e uniform in [1, floor(2^(32-f) / kdiv)] (Sec. VII-B: the cardinality of the mask */
+/* generation before a pooling kernel of kh*kw elements), the three coefficient domains                          */
 void orc_truncate_div(const u64 *x, size_t count, const u64 *eidx, int n, int t, int f, int kdiv, u64 p, u64 seed,
                       u64 stream_id, u64 *u, u64 *wsh, u64 *out)
 {
@@ -702,7 +705,7 @@ void orc_truncate_div(const u64 *x, size_t count, const u64 *eidx, int n, int t,
     u64 *cw = (u64 *)malloc(sizeof(u64) * (size_t)t * count);
     u64 key = orc_key(seed, ORC_DOM_MASK_E, stream_id, 0, 0);
     for (size_t e = 0; e < count; e++)
-        eval[e] = 1 + (orc_draw(key, eidx ? eidx[e] : (u64)e) >> 3) % ((u64)1 << (32 - f));
+        eval[e] = 1 + (orc_draw(key, eidx ? eidx[e] : (u64)e) >> 3) % (((u64)1 << (32 - f)) / (u64)kdiv);
     orc_draw_coeffs(seed, ORC_DOM_MASK_ALPHA, stream_id, 0, t, count, eidx, p, ca);
     orc_draw_coeffs(seed, ORC_DOM_MASK_ALPHAT, stream_id, 0, t, count, eidx, p, cat);
     orc_draw_coeffs(seed, ORC_DOM_TRUNC_GEN, stream_id, 0, t, count, eidx, p, cw);

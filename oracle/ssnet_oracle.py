@@ -12,7 +12,7 @@ import numpy as np
 
 from . import build as _build
 
-_lib = C.CDLL(_build.build())
+_lib = C.CDLL(_build.build_sanitized() if os.environ.get("SSNET_ORACLE_SANITIZED") == "1" else _build.build())
 
 u64 = C.c_uint64
 i64 = C.c_int64

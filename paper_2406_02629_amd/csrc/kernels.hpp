@@ -37,6 +37,8 @@ struct ss_dr_params {             // RED + RERAND constants
 struct ss_tr_params {             // truncation constants
     int n, t, f;
     int kdiv;                     // > 1: rounding division by kdiv after the shift (average pooling, Sec. VI-C)
+    unsigned e_range;             // e is uniform in [1, e_range], e_range = floor(2^(32-f) / kdiv), so that the mask
+                                  // alpha = e * 2^f * kdiv stays in (0, 2^32] (Sec. VII-B)
     u64 e_key;
     u64 alpha_key[SS_MAXT], alphat_key[SS_MAXT], gen_key[SS_MAXT];
     int ilambda[SS_MAXK];

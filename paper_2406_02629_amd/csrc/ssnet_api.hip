@@ -737,6 +737,7 @@ static ss_tr_params make_tr_params(const ssnet_ctx *ctx, uint64_t stream_id)
     tp.t = t;
     tp.f = ctx->f;
     tp.kdiv = 1;
+    tp.e_range = 1u << (32 - ctx->f);
     tp.e_key = ss_key(ctx->seed, SSNET_DOM_MASK_E, stream_id, 0, 0);
     for (int j = 1; j <= t; j++) {
         tp.alpha_key[j - 1] = ss_key(ctx->seed, SSNET_DOM_MASK_ALPHA, stream_id, 0, (u64)j);
@@ -806,16 +807,27 @@ int ssnet_degree_reduce_static(ssnet_ctx *ctx, const uint64_t *d_c, size_t count
 
 namespace {
 
+// the divisor of average pooling leaves at least one value of e: kdiv <= 2^(32-f) (Sec. VII-B)
+static bool kdiv_fits(const ssnet_ctx *ctx, int kdiv)
+{
+    return kdiv >= 1 && kdiv <= SSNET_MAX_KDIV && (unsigned)kdiv <= (1u << (32 - ctx->f));
+}
+
+static void set_kdiv(const ssnet_ctx *ctx, ss_tr_params &tp, int kdiv)
+{
+    tp.kdiv = kdiv;
+    tp.e_range = (1u << (32 - ctx->f)) / (unsigned)kdiv;
+}
+
 static int truncate_by(ssnet_ctx *ctx, const uint64_t *d_x, size_t count, int kdiv, uint64_t stream_id, uint64_t *d_out)
 {
-    if (!ctx || !d_x || !d_out || count == 0 || count > MAX_COUNT || kdiv < 1 || kdiv > SSNET_MAX_KDIV)
-        return SSNET_EINVAL;
+    if (!ctx || !d_x || !d_out || count == 0 || count > MAX_COUNT || !kdiv_fits(ctx, kdiv)) return SSNET_EINVAL;
     const int k = ctx->t + 1, n = ctx->n;
     const size_t need = ((size_t)k + n) * count * 8;
     if (!ws_fits(ctx, need)) return SSNET_EWORKSPACE;
     u64 *u = (u64 *)ws_scratch(ctx), *wsh = u + (size_t)k * count;
     ss_tr_params tp = make_tr_params(ctx, stream_id);
-    tp.kdiv = kdiv;
+    set_kdiv(ctx, tp, kdiv);
     timed tm(ctx, SSNET_PROF_TRUNCATE);
     hipError_t e = ss_launch_truncate(d_x, u, wsh, d_out, count, tp, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
@@ -840,8 +852,7 @@ namespace {
 static int degree_reduce_truncate(ssnet_ctx *ctx, const uint64_t *d_c, size_t count, uint64_t stream_id, uint64_t *d_out,
                            const int *party_ids, int m, uint64_t *d_rec, int kdiv = 1)
 {
-    if (!ctx || !d_out || count == 0 || count > MAX_COUNT || kdiv < 1 || kdiv > SSNET_MAX_KDIV)
-        return SSNET_EINVAL;
+    if (!ctx || !d_out || count == 0 || count > MAX_COUNT || !kdiv_fits(ctx, kdiv)) return SSNET_EINVAL;
     ss_recf_params rf = {};
     if (d_rec) {
         if (!party_ids || m < 1 || m > ctx->n) return SSNET_EINVAL;
@@ -863,7 +874,7 @@ static int degree_reduce_truncate(ssnet_ctx *ctx, const uint64_t *d_c, size_t co
     u64 *msg1 = (u64 *)ws_scratch(ctx), *msg2 = msg1 + (size_t)nr * k * count;
     u64 *u = msg2 + (size_t)k * n * count, *wsh = u + (size_t)k * count;
     ss_tr_params tp = make_tr_params(ctx, stream_id);
-    tp.kdiv = kdiv;
+    set_kdiv(ctx, tp, kdiv);
     timed tm(ctx, SSNET_PROF_DEGREE_REDUCE);
     hipError_t e = ss_launch_degree_reduce_truncate(c, msg1, msg2, u, wsh, d_out, d_rec, count,
                                                     make_dr_params(ctx, stream_id), tp, rf, ps, ctx->stream);

@@ -126,6 +126,13 @@ __device__ __forceinline__ u64 mask_e(u64 key, u64 e, int f)
     return 1 + ((ss_draw(key, e) >> 3) & ((1ULL << (32 - f)) - 1));
 }
 
+// the same before a division by kh*kw: the sample space of e shrinks to [1, floor(2^(32-f) / kdiv)], which keeps
+// alpha = e * 2^f * kdiv within (0, 2^32] (Sec. VII-B); range = 2^(32-f) gives mask_e
+__device__ __forceinline__ u64 mask_e_below(u64 key, u64 e, unsigned range)
+{
+    return 1 + (ss_draw(key, e) >> 3) % range;
+}
+
 // what the elite party does with the reconstructed x + alpha: floor division of the signed value by 2^f
 __device__ __forceinline__ u64 shift_signed(u64 v, int f)
 {
@@ -164,7 +171,7 @@ __device__ __forceinline__ void truncate_steps(const pack_t<VEC> *x, u64 *__rest
     ss_sacc acc[VEC];
 #pragma unroll
     for (int u = 0; u < VEC; u++) {
-        ev[u] = mask_e(tp.e_key, e0 + u, tp.f);
+        ev[u] = tp.kdiv > 1 ? mask_e_below(tp.e_key, e0 + u, tp.e_range) : mask_e(tp.e_key, e0 + u, tp.f);
         draw_coeffs<SS_MAXT>(ca[u], tp.alpha_key, tp.t, e0 + u);
         acc[u].clear();
     }
@@ -174,7 +181,7 @@ __device__ __forceinline__ void truncate_steps(const pack_t<VEC> *x, u64 *__rest
             pack_t<VEC> s;
 #pragma unroll
             for (int u = 0; u < VEC; u++) {
-                const u64 alpha = tp.kdiv > 1 ? (ev[u] * (u64)tp.kdiv) << tp.f : ev[u] << tp.f;   // < 2^47
+                const u64 alpha = tp.kdiv > 1 ? (ev[u] * (u64)tp.kdiv) << tp.f : ev[u] << tp.f;   // <= 2^32
                 s.v[u] = ss_add(x[q].v[u], ss_poly_eval<SS_MAXT>(alpha, ca[u], tp.t, q + 1));
                 acc[u].mac(s.v[u], tp.ilambda[q]);
             }
@@ -1177,6 +1184,7 @@ hipError_t ss_launch_relu_pool(const u64 *x, const u64 *sh_b, const u64 *sh_bi, 
 hipError_t ss_launch_reduce_truncate_direct(const u64 *c, u64 *out, u64 *rec, size_t count, const ss_nl_params &open_all,
                                             const ss_tr_params &tp, const ss_recf_params &rf, hipStream_t stream)
 {
+    if (tp.kdiv != 1) return hipErrorInvalidValue;   // no rounding division in this kernel
     const bool v2 = (count % 2 == 0) && aligned16(c) && aligned16(out) && (!rec || aligned16(rec)) &&
                     count >= VEC2_MIN_COUNT;
     auto grid = [&](int vec) { return dim3(blocks_for(count, vec)); };
@@ -1188,6 +1196,7 @@ hipError_t ss_launch_tail_direct(const u64 *c, const u64 *sh_b, const u64 *sh_bi
                                  int HW, const ss_nl_params &open_all, const ss_tr_params &tp, const ss_part_src &ps,
                                  hipStream_t stream)
 {
+    if (tp.kdiv != 1) return hipErrorInvalidValue;   // no rounding division in this kernel
     const dim3 grid((B * HW + 15) / 16, (C + 15) / 16), block(BLOCK);
     hipLaunchKernelGGL(tail_direct_kernel, grid, block, 0, stream, c, sh_b, sh_bi, out, (signed char *)planes, B, C, HW,
                        ss_planes_bytes(B, C, HW, 1), open_all, tp, ps);
@@ -1199,6 +1208,7 @@ hipError_t ss_launch_layer_tail(const u64 *c, u64 *msg1, u64 *msg2, u64 *umsg, u
                                 const ss_dr_params &dp, const ss_tr_params &tp, const ss_nl_params &np,
                                 const ss_part_src &ps, hipStream_t stream)
 {
+    if (tp.kdiv != 1) return hipErrorInvalidValue;   // no rounding division in this kernel
     const dim3 grid((B * HW + 15) / 16, (C + 15) / 16), block(BLOCK);
     const size_t party_bytes = ss_planes_bytes(B, C, HW, 1);
     if (dp.n == 5 && dp.t == 2)

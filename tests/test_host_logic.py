@@ -202,6 +202,12 @@ def test_pooling_entry_points_check_their_arguments():
         assert lib.ssnet_truncate_div(ctx, 16, 8, kdiv, 0, 16) == binding.EINVAL
         assert lib.ssnet_degree_reduce_truncate_div(ctx, 16, 8, kdiv, 0, 16) == binding.EINVAL
     assert lib.ssnet_truncate_div(ctx, 16, 8, 4, 0, 16) == binding.EWORKSPACE
+    # the divisor must leave a value of e: kdiv <= 2^(32-f) (Sec. VII-B)
+    keep = SSNet(3, 1, f=24, device=None)
+    wide = keep._ctx
+    assert lib.ssnet_truncate_div(wide, 16, 8, 257, 0, 16) == binding.EINVAL
+    assert lib.ssnet_degree_reduce_truncate_div(wide, 16, 8, 257, 0, 16) == binding.EINVAL
+    assert lib.ssnet_truncate_div(wide, 16, 8, 256, 0, 16) == binding.EWORKSPACE
 
 
 # ----------------------------------------------------------------- the second library, over p = 2^45 - 55

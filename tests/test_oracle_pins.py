@@ -652,6 +652,26 @@ def test_truncate_div_is_rounding_division_whatever_the_mask(n, t):
     assert [int(v) for v in got] == [_round_half_up(x >> f, 4) for x in xs]
 
 
+def test_truncation_mask_range_with_pooling_divisor_sec_vii_b():
+    """Sec. VII-B: before a pooling kernel of kh*kw elements the mask is a multiple of 2^f * kh*kw and still lies in
+    (0, 2^32], i.e. e comes from [1, floor(2^32 / 2^f / (kh*kw))].  The mask is read off what the elite party opens
+    (x + alpha with x = 0); without a divisor the range is that of the plain truncation."""
+    for p, n, t, f in ((P61, 5, 2, 13), (P45, 3, 1, 12), (P61, 3, 1, 24)):
+        count = 4096
+        zeros = orc.share(np.zeros(count, np.uint64), n, t, p, 3, 1)
+        for kdiv in (1, 4, 9, 49, 255, 4096):
+            if kdiv > (1 << (32 - f)):
+                continue
+            _, u, _ = orc.truncate_div(zeros, n, t, f, kdiv, p, 77, kdiv, full=True)
+            alpha = orc.reconstruct(u[:t + 1], list(range(1, t + 2)), p)
+            step = kdiv << f
+            e = alpha // np.uint64(step)
+            assert np.all(alpha % np.uint64(step) == 0) and int(alpha.min()) > 0 and int(alpha.max()) <= 1 << 32, (p, kdiv)
+            assert int(e.max()) <= (1 << (32 - f)) // kdiv
+            if (1 << (32 - f)) // kdiv >= 64:   # the whole range is used, not a corner of it
+                assert int(e.max()) > 0.9 * ((1 << (32 - f)) // kdiv) and int(e.min()) < 0.1 * ((1 << (32 - f)) // kdiv) + 2
+
+
 def test_avgpool_fold_worst_case_and_bound_appendix_c():
     """App. C: with every element of a 2x2 kernel equal to g*4 + 2 the folded form gives (g+1)*4
     against the true 4g + 2: off by exactly 2; and over every 2x2 kernel of a small range the
