@@ -83,13 +83,22 @@ __global__ __launch_bounds__(BLOCK) void share_kernel(const u64 *__restrict__ se
     u64 c[VEC][MAXD];
 #pragma unroll
     for (int u = 0; u < VEC; u++) draw_coeffs<MAXD>(c[u], keys.k, degree, e0 + u);
+    if constexpr (NC != 0 && (DC == 1 || DC == 2)) {
+        // consecutive party IDs: forward differences, two additions per point instead of Horner's multiplications
+        pack_t<VEC> s[NC];
 #pragma unroll
-    for (int i = 1; i <= MAXP; i++) {
-        if (i <= n) {
-            pack_t<VEC> s;
+        for (int u = 0; u < VEC; u++) eval_points<DC, NC>(a0.v[u], c[u], [&](int p, u64 v) { s[p].v[u] = v; });
 #pragma unroll
-            for (int u = 0; u < VEC; u++) s.v[u] = ss_poly_eval<MAXD>(a0.v[u], c[u], degree, i);
-            s.store_streaming(shares + (size_t)(i - 1) * count + e0);   // five planes written, none read again
+        for (int p = 0; p < NC; p++) s[p].store_streaming(shares + (size_t)p * count + e0);   // written, not read again
+    } else {
+#pragma unroll
+        for (int i = 1; i <= MAXP; i++) {
+            if (i <= n) {
+                pack_t<VEC> s;
+#pragma unroll
+                for (int u = 0; u < VEC; u++) s.v[u] = ss_poly_eval<MAXD>(a0.v[u], c[u], degree, i);
+                s.store_streaming(shares + (size_t)(i - 1) * count + e0);
+            }
         }
     }
 }
