@@ -19,8 +19,11 @@ LIB_P45 = os.path.join(HERE, "libssnet_p45.so")
 VARIANTS = {"p61": (LIB, []), "p45": (LIB_P45, ["-DSS_FIELD_P45"])}
 SOURCES = ["stream_kernels.hip", "gemm_kernels.hip", "ssnet_api.hip", "probes.hip"]
 HEADERS = ["field.hpp", "kernels.hpp", "eval.hpp", "digits.hpp", os.path.join("..", "..", "include", "ssnet.h")]
+# kernarg preload: the first kernel arguments arrive in scalar registers with the wave instead of by a load at its
+# start, which is worth about half a microsecond on each of the short streaming launches of a batch-1 layer
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-kernarg-preload-count=16",
          "-Wall", "-Wno-unused-command-line-argument"]
 
 
