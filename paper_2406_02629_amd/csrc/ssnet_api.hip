@@ -228,10 +228,10 @@ size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 // The first bytes of the workspace are a reserved header (SSNET_WS_HEADER_BYTES); everything else lives
 // behind it.
-constexpr size_t WS_COUNTER_BYTES = SSNET_WS_HEADER_BYTES;
+constexpr size_t WS_HEADER_BYTES = SSNET_WS_HEADER_BYTES;
 
-char *ws_scratch(const ssnet_ctx *c) { return (char *)c->ws + WS_COUNTER_BYTES; }
-bool ws_fits(const ssnet_ctx *c, size_t scratch) { return c->ws && c->ws_bytes >= WS_COUNTER_BYTES + scratch; }
+char *ws_scratch(const ssnet_ctx *c) { return (char *)c->ws + WS_HEADER_BYTES; }
+bool ws_fits(const ssnet_ctx *c, size_t scratch) { return c->ws && c->ws_bytes >= WS_HEADER_BYTES + scratch; }
 
 // largest element count whose 1-D grid fits
 constexpr size_t MAX_COUNT = (size_t)1 << 38;
@@ -275,7 +275,7 @@ u64 *reserve_pending(ssnet_ctx *ctx, int rows, int cols, int K, bool planes_oper
 {
     ctx->pending.on = false;
     const size_t bytes = product_bytes(ctx, rows, cols, K, planes_operand);
-    if (!ctx->ws || ctx->ws_bytes < WS_COUNTER_BYTES + bytes + 256) return nullptr;
+    if (!ctx->ws || ctx->ws_bytes < WS_HEADER_BYTES + bytes + 256) return nullptr;
     const uintptr_t end = ((uintptr_t)ctx->ws + ctx->ws_bytes) & ~(uintptr_t)255;
     if (end - bytes < (uintptr_t)ws_scratch(ctx)) return nullptr;
     ctx->pending.base = (u64 *)(end - bytes);
@@ -394,13 +394,13 @@ size_t ssnet_workspace_bytes_stream(const ssnet_ctx *ctx, size_t count)
     if (!ctx) return 0;
     const size_t k = ctx->t + 1, nr = 2 * ctx->t + 1, n = ctx->n;
     // the fused call keeps the messages of both protocols at once
-    return WS_COUNTER_BYTES + align256((nr * k + k * n + k + n) * count * 8);
+    return WS_HEADER_BYTES + align256((nr * k + k * n + k + n) * count * 8);
 }
 
 size_t ssnet_workspace_bytes_linear(const ssnet_ctx *ctx, int M, int K, int N)
 {
     if (!ctx || M < 1 || K < 1 || N < 1) return 0;
-    return WS_COUNTER_BYTES + align256(ss_gemm_scratch_bytes(ctx->n, M, N, K)) +
+    return WS_HEADER_BYTES + align256(ss_gemm_scratch_bytes(ctx->n, M, N, K)) +
            (size_t)ctx->n * (ss_packed_bytes(M, K) + ss_packed_bytes(N, K));
 }
 
@@ -412,7 +412,7 @@ size_t ssnet_workspace_bytes_conv(const ssnet_ctx *ctx, int B, int C, int H, int
     if (Ho < 1 || Wo < 1) return 0;
     const long M = (long)B * Ho * Wo, K = (long)C * kh * kw;
     if (M > INT_MAX || K > INT_MAX) return 0;
-    return WS_COUNTER_BYTES + align256(ss_gemm_scratch_bytes(ctx->n, Co, (int)M, (int)K)) +
+    return WS_HEADER_BYTES + align256(ss_gemm_scratch_bytes(ctx->n, Co, (int)M, (int)K)) +
            (size_t)ctx->n * (ss_packed_bytes((int)M, (int)K) + ss_packed_bytes(Co, (int)K));
 }
 
@@ -979,7 +979,7 @@ size_t ssnet_workspace_bytes_layer_tail(const ssnet_ctx *ctx, int B, int C, int 
     const size_t plane = ssnet_layer_tail_message_plane(ctx, B, C, HW);
     if (!plane) return 0;
     const size_t k = ctx->t + 1, nr = 2 * ctx->t + 1, n = ctx->n;
-    return WS_COUNTER_BYTES + align256((nr * k + k * n + k + n + nr + 1) * plane * 8);
+    return WS_HEADER_BYTES + align256((nr * k + k * n + k + n + nr + 1) * plane * 8);
 }
 
 int ssnet_reduce_truncate_relu(ssnet_ctx *ctx, const uint64_t *d_c, int B, int C, int HW, uint64_t stream_id,

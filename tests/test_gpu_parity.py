@@ -235,8 +235,8 @@ def test_linear_random_shapes_cover_the_unit_dealing():
         assert np.array_equal(to_np(y), orc.linear(x, w, P61)), (n, t, M, K, N)
 
 
-def test_linear_more_tiles_than_arrival_counters():
-    # 3 * 130 * 130 output tiles: every workgroup takes one whole tile, nothing is handed over
+def test_linear_many_tiles_one_whole_tile_per_workgroup():
+    # 3 * 130 * 130 output tiles: many more than compute units, so every workgroup takes one whole tile (one plane)
     n, t = 3, 1
     s = SSNet(n, t, seed=1)
     M, K, N = 8320, 64, 8320
