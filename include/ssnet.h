@@ -422,8 +422,16 @@ int ssnet_host_reduction_matrix(const ssnet_ctx *ctx, uint64_t *out);
  * events and writes, per class, the summed elapsed milliseconds and the number
  * of bracketed spans into two HOST arrays of SSNET_PROF_CLASSES entries.  A
  * span is what one entry-point call launches of that class: one kernel, two
- * where a call is documented as two launches.  Not for use under stream
- * capture. */
+ * where a call is documented as two launches.  An event recorded in front of a
+ * launch is stamped when the queue reaches it, so a span contains the few
+ * microseconds between that and the kernel's first wave.  Class
+ * SSNET_PROF_GEMM_KERNEL has none of that: after ssnet_profile_begin_kernels
+ * (instead of ssnet_profile_begin) it holds, for every product kernel (the
+ * kernels of class SSNET_PROF_GEMM without the pass that adds planes up), the
+ * time between the kernel's own start and end on the GPU, which is what a
+ * profiler's kernel trace reports as its duration; the launches that take these
+ * time stamps are slower to enqueue, so the bracketed spans of the same pass
+ * are wider than after ssnet_profile_begin.  Not for use under stream capture. */
 #define SSNET_PROF_SHARE 0
 #define SSNET_PROF_RECONSTRUCT 1
 #define SSNET_PROF_PACK_W 2
@@ -432,8 +440,10 @@ int ssnet_host_reduction_matrix(const ssnet_ctx *ctx, uint64_t *out);
 #define SSNET_PROF_DEGREE_REDUCE 5
 #define SSNET_PROF_TRUNCATE 6
 #define SSNET_PROF_NONLINEAR 7
-#define SSNET_PROF_CLASSES 8
+#define SSNET_PROF_GEMM_KERNEL 8
+#define SSNET_PROF_CLASSES 9
 int ssnet_profile_begin(ssnet_ctx *ctx);
+int ssnet_profile_begin_kernels(ssnet_ctx *ctx);
 int ssnet_profile_end(ssnet_ctx *ctx, double *ms_by_class, uint64_t *spans_by_class);
 
 /* Measured ceilings of the machine, for roofline reports beside the published

@@ -78,6 +78,7 @@ SIGNATURES = {
     "ssnet_host_lagrange": (_int, [_ptr, C.POINTER(_int), _int, C.POINTER(_u64)]),
     "ssnet_host_reduction_matrix": (_int, [_ptr, C.POINTER(_u64)]),
     "ssnet_profile_begin": (_int, [_ptr]),
+    "ssnet_profile_begin_kernels": (_int, [_ptr]),
     "ssnet_profile_end": (_int, [_ptr, C.POINTER(C.c_double), C.POINTER(_u64)]),
     "ssnet_probe_planes": (_int, [_ptr, _ptr, _ptr, _sz, _int, _int, C.POINTER(C.c_double)]),
     "ssnet_probe_mfma_int8": (_int, [_ptr, _ptr, _int, _int, C.POINTER(C.c_double)]),
@@ -601,10 +602,15 @@ class SSNet:
                                           ph, pw, mode, _dptr(out)), "ssnet_relu_pool")
         return out
 
-    PROF_CLASSES = ("share", "reconstruct", "pack_w", "pack_x", "gemm", "degree_reduce", "truncate", "nonlinear")
+    PROF_CLASSES = ("share", "reconstruct", "pack_w", "pack_x", "gemm", "degree_reduce", "truncate", "nonlinear",
+                    "gemm_kernel")   # gemm_kernel: the product kernels from their own start to their own end
 
-    def profile_begin(self):
-        self._ok(self.lib.ssnet_profile_begin(self._ctx), "ssnet_profile_begin")
+    def profile_begin(self, kernels: bool = False):
+        """kernels: also time every product kernel from its own start to its own end (class gemm_kernel)"""
+        if kernels:
+            self._ok(self.lib.ssnet_profile_begin_kernels(self._ctx), "ssnet_profile_begin_kernels")
+        else:
+            self._ok(self.lib.ssnet_profile_begin(self._ctx), "ssnet_profile_begin")
 
     def profile_end(self):
         """-> {class: (total_ms, spans)} for the calls since profile_begin"""

@@ -19,6 +19,8 @@
 #include "eval.hpp"
 #include "digits.hpp"
 
+#include <hip/hip_ext.h>
+
 namespace SS_NS {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -920,7 +922,7 @@ struct conv_planes {   // geometry of an operand given as channel-innermost limb
 
 hipError_t launch_gemm(const void *packedA, const void *packedB, const conv_planes *cv, u64 *out, size_t part_stride,
                        int n, int rows, int cols, int K, size_t out_party_stride, size_t stride_row, int cdiv,
-                       size_t stride_cb, hipStream_t stream)
+                       size_t stride_cb, hipStream_t stream, hipEvent_t started, hipEvent_t stopped)
 {
     static bool lds_opt_in = false;
     constexpr int LDS_BYTES = 2 * 8 * TILE * 16, LDS_BYTES_SKINNY = 2 * 9 * TILE * 16;
@@ -986,12 +988,22 @@ hipError_t launch_gemm(const void *packedA, const void *packedB, const conv_plan
         g.dKbTap = fdz((unsigned)g.cvKbTap);
         g.dKw = fdz((unsigned)g.cvKw);
     }
+    // with an event pair the launch goes through the entry point that stamps the events with the kernel's own
+    // start and end (profiling only)
+#define SS_LAUNCH_PRODUCT(KERNEL, LDS)                                                                            \
+    do {                                                                                                          \
+        if (started && stopped)                                                                                   \
+            hipExtLaunchKernelGGL(KERNEL, dim3((unsigned)p.G), dim3(512), LDS, stream, started, stopped, 0, g);   \
+        else                                                                                                      \
+            hipLaunchKernelGGL(KERNEL, dim3((unsigned)p.G), dim3(512), LDS, stream, g);                           \
+    } while (0)
     if (p.skinny)
-        hipLaunchKernelGGL(gemm_skinny_kernel, dim3((unsigned)p.G), dim3(512), LDS_BYTES_SKINNY, stream, g);
+        SS_LAUNCH_PRODUCT(gemm_skinny_kernel, LDS_BYTES_SKINNY);
     else if (cv)
-        hipLaunchKernelGGL(gemm_limb_kernel<true>, dim3((unsigned)p.G), dim3(512), LDS_BYTES, stream, g);
+        SS_LAUNCH_PRODUCT(gemm_limb_kernel<true>, LDS_BYTES);
     else
-        hipLaunchKernelGGL(gemm_limb_kernel<false>, dim3((unsigned)p.G), dim3(512), LDS_BYTES, stream, g);
+        SS_LAUNCH_PRODUCT(gemm_limb_kernel<false>, LDS_BYTES);
+#undef SS_LAUNCH_PRODUCT
     return hipGetLastError();
 }
 
@@ -1004,21 +1016,21 @@ size_t ss_planes_bytes(int B, int C, int H, int W)
 
 hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, size_t part_stride, int n, int rows,
                           int cols, int K, size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb,
-                          hipStream_t stream)
+                          hipStream_t stream, hipEvent_t started, hipEvent_t stopped)
 {
     return launch_gemm(packedA, packedB, nullptr, out, part_stride, n, rows, cols, K, out_party_stride, stride_row, cdiv,
-                       stride_cb, stream);
+                       stride_cb, stream, started, stopped);
 }
 
 hipError_t ss_launch_gemm_conv(const void *packedW, const void *planes, u64 *out, size_t part_stride, int n, int B, int C,
                                int H, int W, int Co, int kh, int kw, int stride, int pad, int Ho, int Wo,
-                               hipStream_t stream)
+                               hipStream_t stream, hipEvent_t started, hipEvent_t stopped)
 {
     const conv_planes cv = {planes, B, C, H, W, kh, kw, stride, pad, Ho, Wo};
     const size_t HW = (size_t)Ho * Wo;
     // rows = output channel, cols = (b, ho, wo): y[b][co][hw]
     return launch_gemm(packedW, nullptr, &cv, out, part_stride, n, Co, (int)(B * HW), C * kh * kw, (size_t)B * Co * HW, HW,
-                       (int)HW, (size_t)Co * HW, stream);
+                       (int)HW, (size_t)Co * HW, stream, started, stopped);
 }
 
 }  // namespace SS_NS

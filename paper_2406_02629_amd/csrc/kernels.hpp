@@ -140,9 +140,10 @@ hipError_t ss_launch_planes(const u64 *in, u64 *shares, void *planes, int n, int
                             const ss_keys &keys, hipStream_t stream);
 // convolution with the input given as planes and the weights packed with contraction index (tap, channel);
 // out and part_stride as for ss_launch_gemm
+// (started, stopped: see ss_launch_gemm)
 hipError_t ss_launch_gemm_conv(const void *packedW, const void *planes, u64 *out, size_t part_stride, int n, int B, int C,
                                int H, int W, int Co, int kh, int kw, int stride, int pad, int Ho, int Wo,
-                               hipStream_t stream);
+                               hipStream_t stream, hipEvent_t started = nullptr, hipEvent_t stopped = nullptr);
 // rows = (b, ho, wo), k = (c, r, s) of x [n][B][C][H][W]
 hipError_t ss_launch_pack_im2col(const u64 *x, void *dst, int n, int B, int C, int H, int W, int kh, int kw,
                                  int stride, int pad, int Ho, int Wo, hipStream_t stream);
@@ -155,8 +156,10 @@ hipError_t ss_launch_pack_im2col(const u64 *x, void *dst, int n, int B, int C, i
 int ss_gemm_planes(int n, int rows, int cols, int K, bool planes_operand);
 // bytes of the planes for either form of the second operand if there are several, else 0
 size_t ss_gemm_scratch_bytes(int n, int rows, int cols, int K);
+// started / stopped, if given, take the times at which the product kernel itself starts and ends on the GPU (the
+// dispatch's own time stamps, without the gap between two launches that events recorded around a launch include)
 hipError_t ss_launch_gemm(const void *packedA, const void *packedB, u64 *out, size_t part_stride, int n, int rows,
                           int cols, int K, size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb,
-                          hipStream_t stream);
+                          hipStream_t stream, hipEvent_t started = nullptr, hipEvent_t stopped = nullptr);
 
 }  // namespace SS_NS

@@ -41,6 +41,7 @@ struct ssnet_ctx {
     // optional per-kernel-class timing with HIP events on the context's stream
     bool prof;
     struct span { hipEvent_t a, b; int cls; };
+    bool prof_kernels = false;            // also take the product kernels' own start and end (ssnet_profile_begin_kernels)
     std::vector<span> spans;              // recorded since ssnet_profile_begin
     std::vector<span> pool;               // events kept for reuse
 };
@@ -222,6 +223,40 @@ struct timed {
     }
 };
 
+// While profiling is on: an event pair for the product kernel's own start and end (class
+// SSNET_PROF_GEMM_KERNEL), handed to the launcher; a, b stay null otherwise.
+struct kernel_span {
+    ssnet_ctx *ctx;
+    ssnet_ctx::span sp;
+    bool on;
+    kernel_span(ssnet_ctx *c) : ctx(c), on(c->prof && c->prof_kernels)
+    {
+        sp.a = sp.b = nullptr;
+        if (!on) return;
+        if (!c->pool.empty()) {
+            sp = c->pool.back();
+            c->pool.pop_back();
+        } else if (hipEventCreate(&sp.a) != hipSuccess || hipEventCreate(&sp.b) != hipSuccess) {
+            on = false;
+            sp.a = sp.b = nullptr;
+            return;
+        }
+        sp.cls = SSNET_PROF_GEMM_KERNEL;
+    }
+    hipEvent_t started() const { return on ? sp.a : nullptr; }
+    hipEvent_t stopped() const { return on ? sp.b : nullptr; }
+    // after the launch: the pair counts only if the launch took it
+    void done(hipError_t e)
+    {
+        if (!on) return;
+        if (e == hipSuccess)
+            ctx->spans.push_back(sp);
+        else
+            ctx->pool.push_back(sp);
+        on = false;
+    }
+};
+
 int conv_out(int H, int k, int stride, int pad) { return (H + 2 * pad - k) / stride + 1; }
 
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
@@ -250,7 +285,9 @@ int run_product(ssnet_ctx *ctx, u64 *d_y, int rows, int cols, int K, bool planes
     const size_t total = (size_t)ctx->n * rows * cols;
     const int planes = ss_gemm_planes(ctx->n, rows, cols, K, planes_operand);
     timed tm(ctx, SSNET_PROF_GEMM);
-    hipError_t e = launch(planes > 1 ? (u64 *)ws_scratch(ctx) : d_y, total);
+    kernel_span ks(ctx);
+    hipError_t e = launch(planes > 1 ? (u64 *)ws_scratch(ctx) : d_y, total, ks.started(), ks.stopped());
+    ks.done(e);
     if (e == hipSuccess && planes > 1) e = ss_launch_sum_planes(d_y, (const u64 *)ws_scratch(ctx), total, {planes, total}, ctx->stream);
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
@@ -258,9 +295,9 @@ int run_product(ssnet_ctx *ctx, u64 *d_y, int rows, int cols, int K, bool planes
 int run_gemm(ssnet_ctx *ctx, const void *pa, const void *pb, u64 *out, int rows, int cols, int K,
              size_t out_party_stride, size_t stride_row, int cdiv, size_t stride_cb)
 {
-    return run_product(ctx, out, rows, cols, K, false, [&](u64 *o, size_t part_stride) {
+    return run_product(ctx, out, rows, cols, K, false, [&](u64 *o, size_t part_stride, hipEvent_t ea, hipEvent_t eb) {
         return ss_launch_gemm(pa, pb, o, part_stride, ctx->n, rows, cols, K, out_party_stride, stride_row, cdiv, stride_cb,
-                              ctx->stream);
+                              ctx->stream, ea, eb);
     });
 }
 
@@ -361,13 +398,22 @@ int ssnet_profile_begin(ssnet_ctx *ctx)
     for (auto &sp : ctx->spans) ctx->pool.push_back(sp);
     ctx->spans.clear();
     ctx->prof = true;
+    ctx->prof_kernels = false;
     return SSNET_OK;
+}
+
+int ssnet_profile_begin_kernels(ssnet_ctx *ctx)
+{
+    const int rc = ssnet_profile_begin(ctx);
+    if (rc == SSNET_OK) ctx->prof_kernels = true;
+    return rc;
 }
 
 int ssnet_profile_end(ssnet_ctx *ctx, double *ms_by_class, uint64_t *spans_by_class)
 {
     if (!ctx || !ms_by_class || !spans_by_class) return SSNET_EINVAL;
     ctx->prof = false;
+    ctx->prof_kernels = false;
     for (int c = 0; c < SSNET_PROF_CLASSES; c++) {
         ms_by_class[c] = 0.0;
         spans_by_class[c] = 0;
@@ -587,9 +633,9 @@ int ssnet_conv_mod_planes(ssnet_ctx *ctx, const void *d_planes, const void *d_w_
     const long M = (long)B * Ho * Wo, K = (long)C * kh * kw;
     if (!gemm_shape_ok(Co, M, K)) return SSNET_EINVAL;
     if (!ws_fits(ctx, align256(ss_gemm_scratch_bytes(ctx->n, Co, (int)M, (int)K)))) return SSNET_EWORKSPACE;
-    return run_product(ctx, d_y, Co, (int)M, (int)K, true, [&](u64 *o, size_t part_stride) {
+    return run_product(ctx, d_y, Co, (int)M, (int)K, true, [&](u64 *o, size_t part_stride, hipEvent_t ea, hipEvent_t eb) {
         return ss_launch_gemm_conv(d_w_packed, d_planes, o, part_stride, ctx->n, B, C, H, W, Co, kh, kw, stride, pad, Ho, Wo,
-                                   ctx->stream);
+                                   ctx->stream, ea, eb);
     });
 }
 
@@ -617,8 +663,10 @@ int ssnet_linear_product_prepacked(ssnet_ctx *ctx, const void *d_x_packed, const
     u64 *parts = reserve_pending(ctx, M, N, K, false);
     if (!parts) return SSNET_EWORKSPACE;
     timed tm(ctx, SSNET_PROF_GEMM);
+    kernel_span ks(ctx);
     hipError_t e = ss_launch_gemm(d_x_packed, d_w_packed, parts, (size_t)ctx->n * M * N, ctx->n, M, N, K, (size_t)M * N,
-                                  (size_t)N, INT_MAX, 0, ctx->stream);
+                                  (size_t)N, INT_MAX, 0, ctx->stream, ks.started(), ks.stopped());
+    ks.done(e);
     ctx->pending.on = e == hipSuccess;
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
@@ -633,8 +681,11 @@ int ssnet_conv1x1_product_prepacked(ssnet_ctx *ctx, const void *d_x_packed, cons
     u64 *parts = reserve_pending(ctx, Co, M, C, false);
     if (!parts) return SSNET_EWORKSPACE;
     timed tm(ctx, SSNET_PROF_GEMM);
+    kernel_span ks(ctx);
     hipError_t e = ss_launch_gemm(d_w_packed, d_x_packed, parts, (size_t)ctx->n * Co * M, ctx->n, Co, M, C,
-                                  (size_t)B * Co * HW, (size_t)HW, HW, (size_t)Co * HW, ctx->stream);
+                                  (size_t)B * Co * HW, (size_t)HW, HW, (size_t)Co * HW, ctx->stream, ks.started(),
+                                  ks.stopped());
+    ks.done(e);
     ctx->pending.on = e == hipSuccess;
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
@@ -652,8 +703,10 @@ int ssnet_conv_product_planes(ssnet_ctx *ctx, const void *d_planes, const void *
     u64 *parts = reserve_pending(ctx, Co, (int)M, (int)K, true);
     if (!parts) return SSNET_EWORKSPACE;
     timed tm(ctx, SSNET_PROF_GEMM);
+    kernel_span ks(ctx);
     hipError_t e = ss_launch_gemm_conv(d_w_packed, d_planes, parts, (size_t)ctx->n * Co * M, ctx->n, B, C, H, W, Co, kh, kw,
-                                       stride, pad, Ho, Wo, ctx->stream);
+                                       stride, pad, Ho, Wo, ctx->stream, ks.started(), ks.stopped());
+    ks.done(e);
     ctx->pending.on = e == hipSuccess;
     return e == hipSuccess ? SSNET_OK : fail_hip(ctx, e);
 }
