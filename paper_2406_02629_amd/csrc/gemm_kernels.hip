@@ -555,34 +555,29 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
                     b[i] = sb[i * 64];
                 }
             }
-            if (u + 1 < u1) {
+            // where the next unit's block comes from (nothing is loaded yet)
+            const bool more = u + 1 < u1;
+            const v4i *cp = nullptr;
+            unsigned cqs = 64;
+            if (more) {
                 int nkb = kb + 1;
                 if (nkb == g.Kb) {
                     nkb = 0;
                     next_src = tile_source<IMPLICIT>(g, tile + 1, wave, lane);
                 }
-                if constexpr (!IMPLICIT) {
-#pragma unroll
-                    for (int q = 0; q < NL; q++)
-                        __builtin_amdgcn_global_load_lds(next_src.p + (size_t)nkb * TILE + q * 64,
-                                                         mine + (st ^ 1) * STAGE + q * 64, 16, 0, 0);
-                } else {
-                    unsigned qs;
-                    const v4i *ub = unit_base<true>(g, next_src, nkb, wave, lane, qs);
-#pragma unroll
-                    for (int q = 0; q < NL; q++)
-                        __builtin_amdgcn_global_load_lds(ub + (size_t)q * qs, mine + (st ^ 1) * STAGE + q * 64, 16, 0, 0);
-                }
+                cp = unit_base<IMPLICIT>(g, next_src, nkb, wave, lane, cqs);
             }
-            // MFMAs of column blocks past the matrix edge are skipped (nblk < 2; uniform over the wave)
-            if (nblk >= 1) {
+            v4i *cdst = mine + (st ^ 1) * STAGE;
+            if (nblk == 2 && more) {
+                // the usual case in one run of instructions: the copies of the next unit go out one by one between
+                // the MFMAs of the first column block, so that their issue hides behind matrix work
 #pragma unroll
-                for (int i = 0; i < NL; i++)
+                for (int i = 0; i < NL; i++) {
 #pragma unroll
                     for (int j = 0; j < NL; j++)
                         acc[0][i + j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[0][i + j], 0, 0, 0);
-            }
-            if (nblk == 2) {
+                    __builtin_amdgcn_global_load_lds(cp + (size_t)i * cqs, cdst + i * 64, 16, 0, 0);
+                }
 #pragma unroll
                 for (int j = 0; j < NL; j++) b[j] = sb[TILE + j * 64];
 #pragma unroll
@@ -590,6 +585,33 @@ __global__ __launch_bounds__(512) void gemm_limb_kernel(gemm_args g)
 #pragma unroll
                     for (int j = 0; j < NL; j++)
                         acc[1][i + j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[1][i + j], 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < NL; i++) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, NL, 0);   // NL MFMAs
+                    __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);    // one copy
+                }
+            } else {
+                if (more) {
+#pragma unroll
+                    for (int q = 0; q < NL; q++) __builtin_amdgcn_global_load_lds(cp + (size_t)q * cqs, cdst + q * 64, 16, 0, 0);
+                }
+                // MFMAs of column blocks past the matrix edge are skipped (nblk < 2; uniform over the wave)
+                if (nblk >= 1) {
+#pragma unroll
+                    for (int i = 0; i < NL; i++)
+#pragma unroll
+                        for (int j = 0; j < NL; j++)
+                            acc[0][i + j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[0][i + j], 0, 0, 0);
+                }
+                if (nblk == 2) {
+#pragma unroll
+                    for (int j = 0; j < NL; j++) b[j] = sb[TILE + j * 64];
+#pragma unroll
+                    for (int i = 0; i < NL; i++)
+#pragma unroll
+                        for (int j = 0; j < NL; j++)
+                            acc[1][i + j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[1][i + j], 0, 0, 0);
+                }
             }
             st ^= 1;
         }
